@@ -1,0 +1,153 @@
+/*
+ * rampde.h -- C ABI of the MI355X (gfx950) mixed-precision neural-ODE time stepper.
+ *
+ * One library, two compute entry points:
+ *   rampde_odeint_fwd : explicit Runge-Kutta forward pass with low-precision velocity
+ *                       evaluations, fp32 solution accumulation and a low-precision
+ *                       state trajectory (paper Algorithm 1).
+ *   rampde_odeint_bwd : discrete adjoint of that forward pass: stage recomputation from the
+ *                       stored states, low-precision vector-Jacobian products, dynamic
+ *                       power-of-two adjoint scaling with overflow detection, fp32
+ *                       accumulation of the adjoint and of the parameter gradient
+ *                       (paper Algorithm 2 and eq. (vjp); update formulas of Sec. 3).
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) pointers owned by the caller; "host" pointers are
+ *     ordinary host memory.  The library allocates no device memory: all scratch comes
+ *     from the caller's workspace (size from rampde_workspace_bytes).
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*, may be NULL
+ *     for the default stream).  rampde_odeint_fwd never synchronises.  rampde_odeint_bwd
+ *     synchronises the stream once before returning (it must read the outcome of the
+ *     overflow detector) -- and once more per detected overflow, to retry from that step.
+ *   - Return value: 0 on success, otherwise a rampde_status code; rampde_strerror gives
+ *     a message.  No exceptions, no global state besides an immutable device-property cache.
+ *   - theta layout (flat fp32, also the layout of grad_theta):
+ *       MLP  : for each layer l: W_l[out_l][in_l] row-major, then b_l[out_l];
+ *              layer 1 has in_1 = d + 1 when time_input is set (time column LAST).
+ *       CONV2: W1[C][C+time_input][3][3], b1[C], W2[C][C+time_input][3][3], b2[C]
+ *              (time channel LAST); zero padding 1, stride 1.
+ *     Activation is tanh after every layer but the last.
+ *   - State layout at the boundary (y0, yN, grad_yN, grad_y0, grad_ys), fp32:
+ *       MLP [B][d];  CONV2 NCHW [B][C][H][W].
+ *   - Checkpoint layout (ckpt, written by fwd, read by bwd; element type = policy.low):
+ *       MLP [N+1][B][d];  CONV2 channels-last [N+1][B][H][W][C].
+ */
+#ifndef RAMPDE_H
+#define RAMPDE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { RAMPDE_F32 = 0, RAMPDE_F16 = 1, RAMPDE_BF16 = 2 } rampde_dtype;
+
+/* Backward variants (paper Sec. 5, "three backward pass implementations"). */
+typedef enum {
+  RAMPDE_SCALE_NONE = 0,      /* unscaled: S = 1, no overflow checks                       */
+  RAMPDE_SCALE_NONE_SAFE = 1, /* unscaled-safe: S = 1, overflow => gradients filled with +inf */
+  RAMPDE_SCALE_DYNAMIC = 2,   /* dynamic adjoint scaling, Algorithm 2                      */
+  RAMPDE_SCALE_AUTO = 3       /* F32/BF16 -> NONE, F16 -> DYNAMIC                          */
+} rampde_scaling;
+
+typedef enum { RAMPDE_VEL_MLP = 0, RAMPDE_VEL_CONV2 = 1 } rampde_vel_kind;
+
+typedef enum {
+  RAMPDE_OK = 0,
+  RAMPDE_EINVAL = 1,       /* null pointer, N < 1, non-increasing grid, tableau not strictly lower triangular, ... */
+  RAMPDE_EUNSUPPORTED = 2, /* dtype / velocity kind / shape not built                        */
+  RAMPDE_EWORKSPACE = 3,   /* workspace too small or misaligned (256 B)                      */
+  RAMPDE_ESCALE = 4,       /* dynamic adjoint scaling failed at step stats.failed_step (Alg. 2, error branch) */
+  RAMPDE_EHIP = 5          /* HIP runtime error                                              */
+} rampde_status;
+
+/* policy.flags */
+#define RAMPDE_ROUND_INCREMENT 1u /* round sum_j b_j k_j to `low` before the fp32 add (literal Alg. 1 line 4) */
+#define RAMPDE_GROW_RAW_NORM 2u   /* growth test on the unscaled norm ||a|| <= 1/(2 u_L) (literal Alg. 2)     */
+
+/* Explicit Butcher tableau, host memory, fp64.  A is s*s row-major; only the strictly
+ * lower triangle may be non-zero (checked).  Consistency (sum b = 1, ...) is not checked. */
+typedef struct {
+  int s;
+  const double *A;
+  const double *b;
+  const double *c;
+} rampde_tableau;
+
+/* Velocity network descriptor (host memory). */
+typedef struct {
+  rampde_vel_kind kind;
+  int n_layers;      /* MLP: number of linear layers (>= 1)                           */
+  const int *widths; /* MLP: n_layers + 1 entries, widths[0] = widths[n_layers] = d   */
+  int C, H, W;       /* CONV2: channels and spatial size; kernel 3x3, padding 1      */
+  int time_input;    /* 1: append t as last input column (MLP, layer 1) / channel (each conv) */
+} rampde_velocity;
+
+typedef struct {
+  rampde_dtype low;       /* precision of velocity evaluations, stage values and checkpoints */
+  rampde_scaling scaling;
+  int k_max;              /* max attempts per step under DYNAMIC (Alg. 2); <= 0 means 16     */
+  unsigned flags;
+} rampde_policy;
+
+typedef struct {
+  int status;        /* 0 ok; 1 = overflow under NONE_SAFE (gradients are +inf); 2 = scaling failed */
+  int failed_step;   /* step index i of the failure, -1 if none                                  */
+  int retries;       /* number of halvings over the whole pass                                   */
+  float s_first;     /* S_N                                                                      */
+  float s_last;      /* accepted S_0                                                             */
+  float s_min, s_max;
+} rampde_stats;
+
+/* Number of parameters P implied by a velocity descriptor (0 if invalid). */
+int64_t rampde_num_params(const rampde_velocity *vel);
+
+/* Bytes of device workspace needed by fwd (is_backward = 0) or bwd (= 1). 0 if invalid. */
+size_t rampde_workspace_bytes(const rampde_velocity *vel, int64_t B, int N,
+                              const rampde_tableau *tab, const rampde_policy *pol,
+                              int is_backward);
+
+/* Forward pass, Algorithm 1.
+ *   theta   dev, P fp32 (master weights; rounded to `low` once inside, Alg. 1 line 4)
+ *   y0      dev, B*d fp32
+ *   tgrid   host, N+1 strictly increasing fp64
+ *   ckpt    dev, (N+1)*B*d elements of `low`, written: ckpt[i] = Q_low(y_i)
+ *   yN      dev, B*d fp32, written: the fp32 accumulator after the last step
+ *   workspace dev, >= rampde_workspace_bytes(..., 0) bytes, 256-byte aligned
+ * Asynchronous on hip_stream. */
+int rampde_odeint_fwd(const rampde_velocity *vel, const float *theta, const float *y0,
+                      int64_t B, const double *tgrid, int N, const rampde_tableau *tab,
+                      const rampde_policy *pol, void *ckpt, float *yN, void *workspace,
+                      size_t workspace_bytes, void *hip_stream);
+
+/* Backward pass, Algorithm 2 (time-grid gradients are not formed).
+ *   ckpt       dev, read: the trajectory written by rampde_odeint_fwd with the same arguments
+ *   grad_yN    dev, B*d fp32: dL/dy_N (the terminal-cost gradient, formed by the caller)
+ *   grad_ys    dev or NULL: (N+1)*B*d fp32 per-step cotangents dL/dy_i of a running cost,
+ *              added to the adjoint in fp32 (entry N at initialisation, entry i after step i)
+ *   grad_y0    dev, B*d fp32, written: dL/dy_0
+ *   grad_theta dev, P fp32, ACCUMULATED into (Alg. 2 starts g at the caller's dL/dtheta):
+ *              zero it for a plain gradient
+ *   scale_hist host or NULL, N+1 floats: [N] = S_N, [i] = accepted S_i
+ *   stats      host or NULL
+ * Returns RAMPDE_ESCALE if no finite scale was found within k_max attempts at some step
+ * (outputs then undefined).  Under NONE_SAFE an overflow is not an error: grad_y0 and
+ * grad_theta are filled with +inf and stats.status = 1. */
+int rampde_odeint_bwd(const rampde_velocity *vel, const float *theta, int64_t B,
+                      const double *tgrid, int N, const rampde_tableau *tab,
+                      const rampde_policy *pol, const void *ckpt, const float *grad_yN,
+                      const float *grad_ys, float *grad_y0, float *grad_theta,
+                      float *scale_hist, rampde_stats *stats, void *workspace,
+                      size_t workspace_bytes, void *hip_stream);
+
+const char *rampde_strerror(int code);
+
+/* Library/ABI version, e.g. 100 = 1.0.0. */
+int rampde_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAMPDE_H */

@@ -1,0 +1,103 @@
+// Shared device-side definitions for the gfx950 neural-ODE time stepper.
+// Low-precision formats, rounding (the paper's Q16 operator, Sec. 2: round to
+// nearest even into fp16 or bfloat16), the MFMA wrappers and the device control
+// block of the dynamic adjoint scaling (paper Algorithm 2).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rampde {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxStages = 8;
+constexpr int kPad = 64;  // every internal feature dimension is padded to a multiple of this
+
+// Device control block: one per backward pass, lives in the workspace.
+struct Ctl {
+  float S;             // current adjoint scale (power of two)
+  int attempt;         // attempt number at the current step (1 = first)
+  int poison;          // non-zero: a VJP chain produced a non-finite value; all later kernels exit
+  int failed_step;     // step at which poison was raised (N for a non-finite dL/dy_N)
+  unsigned nonfinite;  // raised by the overflow detector of the cotangent chain
+  unsigned amax_bits;  // bit pattern of max |a| (non-negative floats order like unsigned ints)
+  int retries;         // number of halvings so far
+  float s_min, s_max;
+  int pad[7];
+};
+
+struct F16 {};
+struct BF16 {};
+
+template <class T>
+struct Low;
+
+template <>
+struct Low<F16> {
+  static constexpr int p_bits = 11;  // unit roundoff 2^-11
+  __device__ static inline uint16_t from_f32(float x) {
+    _Float16 h = (_Float16)x;  // v_cvt_f16_f32: round to nearest even, gradual underflow, overflow -> inf
+    return __builtin_bit_cast(uint16_t, h);
+  }
+  __device__ static inline float to_f32(uint16_t u) { return (float)__builtin_bit_cast(_Float16, u); }
+  __device__ static inline bool nonfinite(uint16_t u) { return (u & 0x7C00u) == 0x7C00u; }
+  __device__ static inline f32x16 mfma32(u16x8 a, u16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  }
+  __device__ static inline f32x4 mfma16(u16x8 a, u16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  }
+};
+
+template <>
+struct Low<BF16> {
+  static constexpr int p_bits = 8;  // unit roundoff 2^-8
+  __device__ static inline uint16_t from_f32(float x) {
+    uint32_t u = __builtin_bit_cast(uint32_t, x);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;  // NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);                       // ties to even; carries into inf on overflow
+    return (uint16_t)(u >> 16);
+  }
+  __device__ static inline float to_f32(uint16_t u) { return __builtin_bit_cast(float, (uint32_t)u << 16); }
+  __device__ static inline bool nonfinite(uint16_t u) { return (u & 0x7F80u) == 0x7F80u; }
+  __device__ static inline f32x16 mfma32(u16x8 a, u16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+  __device__ static inline f32x4 mfma16(u16x8 a, u16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+};
+
+// tanh of an fp32 pre-activation; the result is rounded to low precision by the caller.
+__device__ inline float act_tanh(float x) { return tanhf(x); }
+
+// Wavefront-level OR of a per-lane overflow flag, one atomic per wavefront that saw one.
+__device__ inline void raise_if_any(bool bad, Ctl* ctl) {
+  if (__any(bad ? 1 : 0)) {
+    if ((threadIdx.x & 63) == 0) atomicOr(&ctl->nonfinite, 1u);
+  }
+}
+
+// Block-wide max of |x| bit patterns, then one atomicMax per workgroup.
+__device__ inline void block_amax(unsigned bits, unsigned* dst) {
+  for (int o = 32; o > 0; o >>= 1) {
+    unsigned other = __shfl_xor(bits, o);
+    bits = bits > other ? bits : other;
+  }
+  __shared__ unsigned wmax[16];
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  if (lane == 0) wmax[w] = bits;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned m = 0;
+    int nw = (blockDim.x + 63) >> 6;
+    for (int i = 0; i < nw; ++i) m = wmax[i] > m ? wmax[i] : m;
+    if (m) atomicMax(dst, m);
+  }
+}
+
+}  // namespace rampde

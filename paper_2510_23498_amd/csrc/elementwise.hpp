@@ -1,0 +1,321 @@
+// Streaming kernels of the time stepper: weight rounding, stage inputs, the fp32
+// solution update with the low-precision checkpoint store (paper Algorithm 1), and the
+// adjoint-side kernels: scale-and-round, overflow detection, fp32 adjoint update and
+// the scale state machine (paper Algorithm 2).
+#pragma once
+#include "common.hpp"
+
+namespace rampde {
+
+struct Coefs {
+  float v[kMaxStages];
+};
+
+__device__ inline bool poisoned(const Ctl* ctl) { return ctl && ctl->poison; }
+
+// theta (fp32) -> padded low-precision operands of one dense layer:
+//   Wp [Npad][Kpad]  (W rounded, zero padded),  WTp [Kpad][Npad]  (its transpose),
+//   bias_f[Npad], wt_f[Npad]: rounded bias / time-column, kept as fp32 for the epilogue.
+template <class T>
+__global__ void cast_dense_layer(const float* __restrict__ W, const float* __restrict__ b, int out, int in,
+                                 int in_full, int has_time, uint16_t* Wp, uint16_t* WTp, float* bias_f,
+                                 float* wt_f, int Npad, int Kpad) {
+  int k = blockIdx.x * blockDim.x + threadIdx.x;
+  int n = blockIdx.y;
+  if (k >= Kpad) return;
+  uint16_t q = 0;
+  if (n < out && k < in) q = Low<T>::from_f32(W[(size_t)n * in_full + k]);
+  Wp[(size_t)n * Kpad + k] = q;
+  WTp[(size_t)k * Npad + n] = q;
+  if (k == 0) {
+    bias_f[n] = (n < out) ? Low<T>::to_f32(Low<T>::from_f32(b[n])) : 0.f;
+    wt_f[n] = (n < out && has_time) ? Low<T>::to_f32(Low<T>::from_f32(W[(size_t)n * in_full + in])) : 0.f;
+  }
+}
+
+// theta (fp32) -> padded low-precision operands of one 3x3 convolution, channels-last taps:
+//   Wp  [Cpad][9*Cpad] : Wp[co][tap*Cpad + ci]  = Q(W[co][ci][tap])          (forward)
+//   WTp [Cpad][9*Cpad] : WTp[ci][tap*Cpad + co] = Q(W[co][ci][8 - tap])      (input cotangent:
+//         the transposed convolution is a convolution with the flipped kernel)
+//   wt_f [9][Cpad] time-channel weights per tap, bias_f[Cpad].
+template <class T>
+__global__ void cast_conv_layer(const float* __restrict__ W, const float* __restrict__ b, int C, int Cin,
+                                int has_time, uint16_t* Wp, uint16_t* WTp, float* bias_f, float* wt_f, int Cpad) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;  // over Cpad * 9 * Cpad
+  int total = Cpad * 9 * Cpad;
+  if (idx >= total) return;
+  int ci = idx % Cpad, tap = (idx / Cpad) % 9, co = idx / (9 * Cpad);
+  uint16_t q = 0;
+  if (co < C && ci < C) q = Low<T>::from_f32(W[((size_t)co * Cin + ci) * 9 + tap]);
+  Wp[(size_t)co * 9 * Cpad + tap * Cpad + ci] = q;
+  WTp[(size_t)ci * 9 * Cpad + (8 - tap) * Cpad + co] = q;
+  if (ci == 0) {
+    float w = 0.f;
+    if (co < C && has_time) w = Low<T>::to_f32(Low<T>::from_f32(W[((size_t)co * Cin + C) * 9 + tap]));
+    wt_f[tap * Cpad + co] = w;
+    if (tap == 0) bias_f[co] = (co < C) ? Low<T>::to_f32(Low<T>::from_f32(b[co])) : 0.f;
+  }
+}
+
+// fp32 NCHW <-> channels-last [B*H*W][C]
+__global__ void nchw_to_rows(const float* __restrict__ src, float* __restrict__ dst, int64_t P, int C, int HW) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // index into dst
+  if (i >= P * C) return;
+  int64_t p = i / C;
+  int c = (int)(i % C);
+  int64_t bimg = p / HW, pix = p % HW;
+  dst[i] = src[(bimg * C + c) * HW + pix];
+}
+__global__ void rows_to_nchw(const float* __restrict__ src, float* __restrict__ dst, int64_t P, int C, int HW,
+                             const Ctl* ctl, int fill_inf) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // index into dst (NCHW)
+  if (i >= P * C) return;
+  int64_t pix = i % HW;
+  int c = (int)((i / HW) % C);
+  int64_t bimg = i / ((int64_t)HW * C);
+  float v = src[(bimg * HW + pix) * C + c];
+  if (fill_inf && ctl->poison) v = __builtin_inff();
+  dst[i] = v;
+}
+
+// y <- y0 (fp32), ckpt[0] <- Q(y0)     (paper Alg. 1: initialisation and first stored state)
+template <class T>
+__global__ void init_state(const float* __restrict__ y0, float* __restrict__ y, uint16_t* __restrict__ ck0,
+                           int64_t n, int copy_y) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float v = y0[i];
+  if (copy_y) y[i] = v;
+  ck0[i] = Low<T>::from_f32(v);
+}
+
+// Stage input  z_j = Q( yhat + h * sum_{l<j} a_jl k_l ),  yhat = stored checkpoint.
+// Output in the padded layout [R][ld]; pad columns are written as zero.
+template <class T>
+__global__ void stage_input(const uint16_t* __restrict__ ck, int d, const uint16_t* __restrict__ K,
+                            int64_t stage_stride, int j, Coefs arow, float h, uint16_t* __restrict__ z,
+                            int ld, int64_t R, const Ctl* ctl) {
+  if (poisoned(ctl)) return;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= R * ld) return;
+  int64_t r = i / ld;
+  int c = (int)(i % ld);
+  uint16_t q = 0;
+  if (c < d) {
+    q = ck[r * d + c];
+    if (j > 0) {
+      float incr = 0.f;
+      for (int l = 0; l < j; ++l)
+        if (arow.v[l] != 0.f) incr = fmaf(arow.v[l], Low<T>::to_f32(K[l * stage_stride + i]), incr);
+      q = Low<T>::from_f32(fmaf(h, incr, Low<T>::to_f32(q)));
+    }
+  }
+  z[i] = q;
+}
+
+// y <- y + h * sum_j b_j k_j  in fp32;  ckpt[i+1] <- Q(y)     (paper Alg. 1, accumulate + store)
+template <class T>
+__global__ void combine_store(float* __restrict__ y, const uint16_t* __restrict__ K, int64_t stage_stride, int s,
+                              Coefs b, float h, int round_incr, uint16_t* __restrict__ ck_next, int d, int ld,
+                              int64_t R) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= R * d) return;
+  int64_t r = i / d;
+  int c = (int)(i % d);
+  float incr = 0.f;
+  for (int j = 0; j < s; ++j) incr = fmaf(b.v[j], Low<T>::to_f32(K[j * stage_stride + r * ld + c]), incr);
+  if (round_incr) incr = Low<T>::to_f32(Low<T>::from_f32(incr));
+  float v = fmaf(h, incr, y[i]);
+  y[i] = v;
+  ck_next[i] = Low<T>::from_f32(v);
+}
+
+// ------------------------------------------------------------------------- backward
+__global__ void ctl_reset(Ctl* ctl) {
+  ctl->S = 1.f; ctl->attempt = 1; ctl->poison = 0; ctl->failed_step = -1; ctl->nonfinite = 0;
+  ctl->amax_bits = 0; ctl->retries = 0; ctl->s_min = 1.f; ctl->s_max = 1.f;
+}
+
+// a <- dL/dy_N (+ running-cost cotangent), max|a|   (paper Alg. 2, initialisation)
+__global__ void init_adjoint(const float* __restrict__ gyN, const float* __restrict__ gys_last,
+                             float* __restrict__ a, int64_t n, Ctl* ctl, int copy) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  unsigned bits = 0;
+  if (i < n) {
+    float v = gyN[i];
+    if (gys_last) v += gys_last[i];
+    if (copy || gys_last) a[i] = v;
+    bits = __builtin_bit_cast(unsigned, fabsf(v));
+  }
+  block_amax(bits, &ctl->amax_bits);
+}
+
+// S_N = 2^floor(-log2(u_L * max|a|)) from the exponent of max|a|; exact in integers.
+__global__ void scale_init(Ctl* ctl, float* scale_hist, int N, int p_bits, int dynamic) {
+  unsigned bits = ctl->amax_bits;
+  float S = 1.f;
+  if (bits >= 0x7F800000u) {  // non-finite dL/dy_N
+    ctl->poison = 1;
+    ctl->failed_step = N;
+  } else if (dynamic && bits != 0) {
+    int e;
+    float m = frexpf(__builtin_bit_cast(float, bits), &e);  // amax = m * 2^e, m in [0.5, 1)
+    int E = p_bits - e + (m == 0.5f ? 1 : 0);
+    E = E > 126 ? 126 : (E < -126 ? -126 : E);
+    S = ldexpf(1.f, E);
+  }
+  ctl->S = S;
+  ctl->s_min = S;
+  ctl->s_max = S;
+  ctl->amax_bits = 0;
+  scale_hist[N] = S;
+}
+
+// kbar_j = Q( b_j * Q(S a) + h * sum_{l>j} a_lj zbar_l )   (paper eq. (vjp): the cotangent
+// Q16(S a) pushed through the stage recursion of Phi).  Padded output layout.
+template <class T>
+__global__ void stage_cotangent(const float* __restrict__ a, int d, const uint16_t* __restrict__ zbar,
+                                int64_t stage_stride, int j, int s, float bj, Coefs acol, float h,
+                                uint16_t* __restrict__ kbar, int ld, int64_t R, Ctl* ctl, int detect) {
+  if (ctl->poison) return;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  bool bad = false;
+  if (i < R * ld) {
+    int64_t r = i / ld;
+    int c = (int)(i % ld);
+    uint16_t q = 0;
+    if (c < d) {
+      uint16_t lam = Low<T>::from_f32(ctl->S * a[r * d + c]);
+      float v = bj * Low<T>::to_f32(lam);
+      float acc = 0.f;
+      for (int l = j + 1; l < s; ++l)
+        if (acol.v[l] != 0.f) acc = fmaf(acol.v[l], Low<T>::to_f32(zbar[l * stage_stride + i]), acc);
+      v = fmaf(h, acc, v);
+      q = Low<T>::from_f32(v);
+      bad = Low<T>::nonfinite(lam) || Low<T>::nonfinite(q);
+    }
+    kbar[i] = q;
+  }
+  if (detect) raise_if_any(bad, ctl);
+}
+
+// after the cotangent chain of a step: accept or poison   (paper Alg. 2, finiteness test)
+__global__ void chain_decide(Ctl* ctl, int step) {
+  if (ctl->poison) return;
+  if (ctl->nonfinite) {
+    ctl->poison = 1;
+    ctl->failed_step = step;
+  }
+}
+
+// host-requested retry of the poisoned step with half the scale   (paper Alg. 2, halve and retry)
+__global__ void chain_retry(Ctl* ctl) {
+  ctl->S *= 0.5f;
+  ctl->attempt += 1;
+  ctl->retries += 1;
+  ctl->poison = 0;
+  ctl->nonfinite = 0;
+  ctl->failed_step = -1;
+}
+
+// a <- a + (h/S) * sum_j zbar_j (+ running-cost cotangent), fp32; new max|a|
+template <class T>
+__global__ void adjoint_update(float* __restrict__ a, int d, const uint16_t* __restrict__ zbar,
+                               int64_t stage_stride, int s, float h, const float* __restrict__ gys_i, int ld,
+                               int64_t R, Ctl* ctl) {
+  if (ctl->poison) return;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  unsigned bits = 0;
+  if (i < R * d) {
+    int64_t r = i / d;
+    int c = (int)(i % d);
+    float da = 0.f;
+    for (int j = 0; j < s; ++j) da += Low<T>::to_f32(zbar[j * stage_stride + r * ld + c]);
+    float v = fmaf(h / ctl->S, da, a[i]);
+    if (gys_i) v += gys_i[i];
+    a[i] = v;
+    bits = __builtin_bit_cast(unsigned, fabsf(v));
+  }
+  block_amax(bits, &ctl->amax_bits);
+}
+
+// end of a step: record S_i, decide growth   (paper Alg. 2, doubling rule)
+__global__ void scale_grow(Ctl* ctl, float* scale_hist, int step, int p_bits, int dynamic, int raw_norm) {
+  if (ctl->poison) return;
+  float S = ctl->S;
+  scale_hist[step] = S;
+  ctl->s_min = fminf(ctl->s_min, S);
+  ctl->s_max = fmaxf(ctl->s_max, S);
+  if (dynamic && ctl->attempt == 1) {
+    float amax = __builtin_bit_cast(float, ctl->amax_bits);
+    float test = raw_norm ? amax : S * amax;
+    if (test <= ldexpf(1.f, p_bits - 1) && S < ldexpf(1.f, 126)) ctl->S = 2.f * S;
+  }
+  ctl->attempt = 1;
+  ctl->amax_bits = 0;
+  ctl->nonfinite = 0;
+}
+
+// Column sums of the cotangents for bias and time-weight gradients:
+//   db[c]  += (h/S) * sum_rows delta[row][c]
+//   dwt[c] += (h/S) * sum_j tau_j sum_{rows of stage j} delta[row][c]          (dense layer 1)
+//   conv: dwt[c][tap] += (h/S) * sum_j tau_j sum_{pixels whose tap neighbour exists} delta
+// rows = stages * R; `taus` gives tau_j.  Grid: (column blocks of 64, row chunks).
+template <class T, bool CONV>
+__global__ __launch_bounds__(256) void column_sums(const uint16_t* __restrict__ delta, int ld, int64_t R, int s,
+                                                   int ncols, Coefs taus, float h, float* __restrict__ gb,
+                                                   float* __restrict__ gwt, int wt_stride, int H, int Wd,
+                                                   int rows_per_block, const Ctl* ctl) {
+  if (ctl->poison) return;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + tx;
+  const int64_t rows = (int64_t)s * R;
+  int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+  int64_t r1 = r0 + rows_per_block;
+  if (r1 > rows) r1 = rows;
+  constexpr int NT = CONV ? 9 : 1;
+  float sb = 0.f, st[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) st[t] = 0.f;
+  for (int64_t r = r0 + ty; r < r1; r += 4) {
+    float v = Low<T>::to_f32(delta[r * ld + c]);
+    float tau = taus.v[r / R];
+    sb += v;
+    if (CONV) {
+      int x = (int)(r % Wd), y = (int)((r / Wd) % H);
+#pragma unroll
+      for (int t = 0; t < 9; ++t) {
+        int yy = y + t / 3 - 1, xx = x + t % 3 - 1;
+        if (yy >= 0 && yy < H && xx >= 0 && xx < Wd) st[t] = fmaf(tau, v, st[t]);
+      }
+    } else {
+      st[0] = fmaf(tau, v, st[0]);
+    }
+  }
+  __shared__ float red[4][64][NT + 1];
+  red[ty][tx][0] = sb;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) red[ty][tx][1 + t] = st[t];
+  __syncthreads();
+  if (ty == 0 && c < ncols) {
+    const float scale = h / ctl->S;
+    float v = red[0][tx][0] + red[1][tx][0] + red[2][tx][0] + red[3][tx][0];
+    unsafeAtomicAdd(&gb[c], scale * v);
+    if (gwt) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        float w = red[0][tx][1 + t] + red[1][tx][1 + t] + red[2][tx][1 + t] + red[3][tx][1 + t];
+        unsafeAtomicAdd(&gwt[(size_t)c * wt_stride + t], scale * w);
+      }
+    }
+  }
+}
+
+// NONE_SAFE outcome: overflow => gradients are +inf
+__global__ void fill_inf_if_poisoned(float* p, int64_t n, const Ctl* ctl) {
+  if (!ctl->poison) return;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = __builtin_inff();
+}
+
+}  // namespace rampde

@@ -1,0 +1,323 @@
+// MFMA contractions of the velocity network and of its vector-Jacobian products.
+//
+//   gemm_nt : C[M, N] = epilogue( A[M, K] * W[N, K]^T )        (both operands K-contiguous)
+//             forward layers  (paper Alg. 1, the low-precision evaluation of Phi)  and the
+//             input-cotangent products  delta_{l-1} = (delta_l W_l) * tanh'  of eq. (vjp).
+//             With CONV the rows of A are pixels of a channels-last image and the K axis
+//             runs over (3x3 tap, channel): an implicit-GEMM convolution with zero padding.
+//   gemm_tn : G[Na, Nb] += scale * sum_k A[k, Na] * B[k, Nb]   (contraction over rows)
+//             the parameter-gradient products  dW_l = delta_l^T act_{l-1}, accumulated in
+//             fp32 straight into the gradient vector (paper Sec. 3, update of g).
+//
+// Tiles are built from v_mfma_f32_32x32x16_{f16,bf16}; a workgroup is 4 wavefronts (2x2).
+// Low-precision values travel as raw 16-bit patterns (uint16_t).
+#pragma once
+#include "common.hpp"
+
+namespace rampde {
+
+constexpr int BK = 64;        // K extent of one LDS tile
+constexpr int LDS_PITCH = BK + 8;  // elements; 144 B rows keep 16-byte reads conflict-light
+
+struct GemmNT {
+  const uint16_t* A; int lda;
+  const uint16_t* W; int ldw;
+  uint16_t* C; int ldc;
+  int M, N, K;                 // N, K multiples of 64 (padded)
+  const float* bias;           // [N] fp32 (already rounded to low) or null
+  const float* wt;             // time weights: MLP [N]; conv [9][N]; or null
+  float tau;                   // stage time, already rounded to low
+  int act_tanh;                // apply tanh before rounding
+  const uint16_t* dact; int ldd;  // stored activation for the factor (1 - act^2), or null
+  Ctl* ctl;                    // may be null (forward pass)
+  int detect;                  // raise ctl->nonfinite if any output is inf/nan
+  // conv geometry (CONV only)
+  int H, Wd, Cpad;
+};
+
+template <class T, int MI, int NI, bool CONV>
+__global__ __launch_bounds__(256) void gemm_nt(GemmNT g) {
+  if (g.ctl && g.ctl->poison) return;
+  constexpr int BM = 64 * MI, BN = 64 * NI;
+  __shared__ __attribute__((aligned(16))) uint16_t sA[BM * LDS_PITCH];
+  __shared__ __attribute__((aligned(16))) uint16_t sW[BN * LDS_PITCH];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+
+  constexpr int A_CHUNKS = BM * (BK / 8) / 256;  // 16-byte chunks per thread
+  constexpr int W_CHUNKS = BN * (BK / 8) / 256;
+  u16x8 ra[A_CHUNKS], rw[W_CHUNKS];
+
+  // per-chunk row bookkeeping (row index and, for conv, pixel coordinates)
+  int a_row[A_CHUNKS], a_kc[A_CHUNKS], a_x[A_CHUNKS], a_y[A_CHUNKS];
+#pragma unroll
+  for (int i = 0; i < A_CHUNKS; ++i) {
+    int id = tid + i * 256;
+    a_row[i] = m0 + (id >> 3);
+    a_kc[i] = (id & 7) * 8;
+    if (CONV) {
+      a_x[i] = a_row[i] % g.Wd;
+      a_y[i] = (a_row[i] / g.Wd) % g.H;
+    }
+  }
+
+  auto load_tiles = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) {
+      u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (a_row[i] < g.M) {
+        if (CONV) {
+          int per_tap = g.Cpad / BK;
+          int tap = kt / per_tap, c0 = (kt - tap * per_tap) * BK;
+          int dy = tap / 3 - 1, dx = tap % 3 - 1;
+          int yy = a_y[i] + dy, xx = a_x[i] + dx;
+          if (yy >= 0 && yy < g.H && xx >= 0 && xx < g.Wd) {
+            const uint16_t* p = g.A + (size_t)(a_row[i] + dy * g.Wd + dx) * g.lda + c0 + a_kc[i];
+            v = *reinterpret_cast<const u16x8*>(p);
+          }
+        } else {
+          const uint16_t* p = g.A + (size_t)a_row[i] * g.lda + kt * BK + a_kc[i];
+          v = *reinterpret_cast<const u16x8*>(p);
+        }
+      }
+      ra[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < W_CHUNKS; ++i) {
+      int id = tid + i * 256;
+      const uint16_t* p = g.W + (size_t)(n0 + (id >> 3)) * g.ldw + kt * BK + (id & 7) * 8;
+      rw[i] = *reinterpret_cast<const u16x8*>(p);
+    }
+  };
+  auto store_tiles = [&]() {
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) {
+      int id = tid + i * 256;
+      *reinterpret_cast<u16x8*>(&sA[(id >> 3) * LDS_PITCH + (id & 7) * 8]) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < W_CHUNKS; ++i) {
+      int id = tid + i * 256;
+      *reinterpret_cast<u16x8*>(&sW[(id >> 3) * LDS_PITCH + (id & 7) * 8]) = rw[i];
+    }
+  };
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int a = 0; a < MI; ++a)
+#pragma unroll
+    for (int b = 0; b < NI; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+  const int KT = g.K / BK;
+  load_tiles(0);
+  store_tiles();
+  __syncthreads();
+  const int frow = lane & 31, fk = (lane >> 5) * 8;
+  for (int kt = 0; kt < KT; ++kt) {
+    if (kt + 1 < KT) load_tiles(kt + 1);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      u16x8 fa[MI], fb[NI];
+#pragma unroll
+      for (int a = 0; a < MI; ++a)
+        fa[a] = *reinterpret_cast<const u16x8*>(&sA[(wm * 32 * MI + a * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
+#pragma unroll
+      for (int b = 0; b < NI; ++b)
+        fb[b] = *reinterpret_cast<const u16x8*>(&sW[(wn * 32 * NI + b * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
+#pragma unroll
+      for (int a = 0; a < MI; ++a)
+#pragma unroll
+        for (int b = 0; b < NI; ++b) acc[a][b] = Low<T>::mfma32(fa[a], fb[b], acc[a][b]);
+    }
+    __syncthreads();
+    if (kt + 1 < KT) {
+      store_tiles();
+      __syncthreads();
+    }
+  }
+
+  // ---- epilogue: accumulator lane layout of the 32x32 tile:
+  //      column = lane % 32, row = 8 * (r / 4) + 4 * (lane / 32) + r % 4
+  bool bad = false;
+#pragma unroll
+  for (int b = 0; b < NI; ++b) {
+    const int n = n0 + wn * 32 * NI + b * 32 + (lane & 31);
+    const float bv = g.bias ? g.bias[n] : 0.f;
+    float tv = 0.f;
+    float tw[9];
+    if (g.wt) {
+      if (CONV) {
+#pragma unroll
+        for (int t = 0; t < 9; ++t) tw[t] = g.wt[t * g.N + n] * g.tau;
+      } else {
+        tv = g.wt[n] * g.tau;
+      }
+    }
+#pragma unroll
+    for (int a = 0; a < MI; ++a) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * 32 * MI + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m < g.M) {
+          float v = acc[a][b][r] + bv;
+          if (g.wt) {
+            if (CONV) {
+              int x = m % g.Wd, y = (m / g.Wd) % g.H;
+              float s = 0.f;
+#pragma unroll
+              for (int t = 0; t < 9; ++t) {
+                int yy = y + t / 3 - 1, xx = x + t % 3 - 1;
+                if (yy >= 0 && yy < g.H && xx >= 0 && xx < g.Wd) s += tw[t];
+              }
+              v += s;
+            } else {
+              v += tv;
+            }
+          }
+          if (g.act_tanh) v = act_tanh(v);
+          if (g.dact) {
+            float av = Low<T>::to_f32(g.dact[(size_t)m * g.ldd + n]);
+            v = v * (1.f - av * av);
+          }
+          uint16_t q = Low<T>::from_f32(v);
+          bad = bad || Low<T>::nonfinite(q);
+          g.C[(size_t)m * g.ldc + n] = q;
+        }
+      }
+    }
+  }
+  if (g.detect) raise_if_any(bad, g.ctl);
+}
+
+// ------------------------------------------------------------------------------------
+struct GemmTN {
+  const uint16_t* A; int lda;   // [rows, >= Na] cotangents delta_l
+  const uint16_t* B; int ldb;   // [rows, >= Nb] layer inputs act_{l-1}
+  int64_t rows;                 // contraction length (stages * batch rows)
+  int rows_per_split;           // multiple of BK
+  float* G; int ldg;            // fp32 gradient block, row pitch ldg
+  int Na, Nb;                   // valid extents (unpadded)
+  int NaPad, NbPad;             // padded extents (multiples of 64): columns that exist in A / B
+  float h;                      // step size; scale = h / ctl->S
+  const Ctl* ctl;
+  // conv: B rows are gathered with a tap shift, G index = na*ldg + nb*9 + tap
+  int H, Wd, taps;              // taps = 1 (dense) or 9 (conv)
+};
+
+template <class T, bool CONV>
+__global__ __launch_bounds__(256) void gemm_tn(GemmTN g) {
+  if (g.ctl->poison) return;
+  constexpr int BM = 128, BN = 128;
+  __shared__ __attribute__((aligned(16))) uint16_t sA[BM * LDS_PITCH];  // [feature][k]
+  __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDS_PITCH];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int a0 = blockIdx.x * BM, b0 = blockIdx.y * BN;
+  int split = blockIdx.z, tap = 0;
+  if (CONV) { tap = split % 9; split /= 9; }
+  const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+  const int64_t k_begin = (int64_t)split * g.rows_per_split;
+  int64_t k_end = k_begin + g.rows_per_split;
+  if (k_end > g.rows) k_end = g.rows;
+
+  // each thread owns one 8(k) x 8(feature) block of A (threads 0..127) or B (128..255)
+  const bool isB = tid >= 128;
+  const int t7 = tid & 127;
+  const int fg = t7 & 15, kg = t7 >> 4;
+  u16x8 r[8];
+
+  auto load_block = [&](int64_t k0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int64_t k = k0 + kg * 8 + i;
+      u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (k < k_end) {
+        if (!isB) {
+          if (a0 + fg * 8 < g.NaPad) v = *reinterpret_cast<const u16x8*>(g.A + (size_t)k * g.lda + a0 + fg * 8);
+        } else if (b0 + fg * 8 >= g.NbPad) {
+          // column block beyond the padded width: stays zero
+        } else if (CONV) {
+          int x = (int)(k % g.Wd), y = (int)((k / g.Wd) % g.H);
+          int yy = y + dy, xx = x + dx;
+          if (yy >= 0 && yy < g.H && xx >= 0 && xx < g.Wd)
+            v = *reinterpret_cast<const u16x8*>(g.B + (size_t)(k + dy * g.Wd + dx) * g.ldb + b0 + fg * 8);
+        } else {
+          v = *reinterpret_cast<const u16x8*>(g.B + (size_t)k * g.ldb + b0 + fg * 8);
+        }
+      }
+      r[i] = v;
+    }
+  };
+  auto store_block = [&]() {
+    uint16_t* s = isB ? sB : sA;
+#pragma unroll
+    for (int f = 0; f < 8; ++f) {
+      u16x8 o;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = r[i][f];
+      *reinterpret_cast<u16x8*>(&s[(fg * 8 + f) * LDS_PITCH + kg * 8]) = o;
+    }
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.f;
+
+  const int frow = lane & 31, fk = (lane >> 5) * 8;
+  if (k_begin < k_end) {
+    load_block(k_begin);
+    store_block();
+    __syncthreads();
+    for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+      const bool more = k0 + BK < k_end;
+      if (more) load_block(k0 + BK);
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        u16x8 fa[2], fb[2];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+          fa[a] = *reinterpret_cast<const u16x8*>(&sA[(wm * 64 + a * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+          fb[b] = *reinterpret_cast<const u16x8*>(&sB[(wn * 64 + b * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int b = 0; b < 2; ++b) acc[a][b] = Low<T>::mfma32(fa[a], fb[b], acc[a][b]);
+      }
+      __syncthreads();
+      if (more) {
+        store_block();
+        __syncthreads();
+      }
+    }
+  }
+
+  const float scale = g.h / g.ctl->S;
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    const int nb = b0 + wn * 64 + b * 32 + (lane & 31);
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int na = a0 + wm * 64 + a * 32 + 8 * (q >> 2) + 4 * (lane >> 5) + (q & 3);
+        if (na < g.Na && nb < g.Nb) {
+          size_t idx = CONV ? ((size_t)na * g.ldg + (size_t)nb * 9 + tap) : ((size_t)na * g.ldg + nb);
+          unsafeAtomicAdd(&g.G[idx], scale * acc[a][b][q]);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace rampde

@@ -1,0 +1,86 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element
+in the norm-wise sense, on seeded inputs with the shapes of the five workloads.
+
+Tolerances: relative 2-norm error <= 1e-3 against the rounding-emulation oracle and
+<= 2e-2 (fp16) / 5e-2 (bf16) against the fp64 oracle, for y_N, the stored trajectory,
+dL/dy_0 and dL/dtheta (overall and per parameter tensor).  The adjoint scale history and
+the retry count are compared exactly: they are powers of two and integers.
+"""
+import numpy as np
+import pytest
+
+from paper_2510_23498_amd import workloads as wl
+
+import parity as par
+
+pytestmark = pytest.mark.gpu
+
+
+def _both(cfg, bias_std=0.0, scaling=None, tol_emul=par.TOL_EMUL):
+    theta, y0, target = par.make_inputs(cfg, bias_std=bias_std)
+    print(f"[case] {cfg.name} kind={cfg.kind} B={cfg.B} N={cfg.N} low={cfg.low} tab={cfg.tableau}", flush=True)
+    gpu = par.run_gpu(cfg, theta, y0, target, scaling=scaling)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul", scaling=scaling)
+    f64 = par.run_oracle(cfg, theta, y0, target, "f64")
+    e1 = par.compare(cfg, gpu, emu, tol_emul, "emulation oracle")
+    e2 = par.compare(cfg, gpu, f64, par.TOL_F64[cfg.low], "fp64 oracle", check_ckpt=False)
+    print("  vs emul:", {k: f"{v:.2e}" for k, v in e1.items()}, flush=True)
+    print("  vs f64 :", {k: f"{v:.2e}" for k, v in e2.items()}, flush=True)
+    assert gpu["status"] == 0 and emu["status"] == "ok"
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
+    assert gpu["retries"] == emu["retries"]
+    return gpu, emu, f64
+
+
+def test_cfg1_tiny_mlp_full_size():
+    _both(wl.CONFIGS["cfg1"])
+
+
+def test_cfg1_nonzero_bias_and_ragged_batch():
+    _both(wl.CONFIGS["cfg1"].with_(name="cfg1r", B=77, N=5), bias_std=0.3)
+
+
+@pytest.mark.parametrize("tab", ["euler", "heun", "rk4", "kutta3"])
+def test_small_mlp_all_tableaux(tab):
+    cfg = wl.CONFIGS["cfg1"].with_(name="tabs", B=130, N=6, widths=(5, 40, 24, 5), tableau=tab)
+    _both(cfg, bias_std=0.2)
+
+
+def test_cfg2_shape_reduced_batch():
+    # widths of the bf16 workload; batch spans two 128-row tiles and a ragged tail
+    _both(wl.CONFIGS["cfg2"].with_(name="cfg2s", B=300, N=6), bias_std=0.1)
+
+
+def test_cfg3_shape_reduced_needs_dynamic_scaling():
+    cfg = wl.CONFIGS["cfg3"].with_(name="cfg3s", B=200, N=6)
+    gpu, emu, f64 = _both(cfg)
+    assert gpu["scale_hist"][cfg.N] > 2.0 ** 20  # the 1e-6 loss gradient needs a large scale
+    # negative control: without scaling the fp16 cotangents underflow and the gradient is lost
+    theta, y0, target = par.make_inputs(cfg)
+    raw = par.run_gpu(cfg, theta, y0, target, scaling="none")
+    e_raw = par.rel_err(raw["grad_theta"], f64["grad_theta"])
+    e_dyn = par.rel_err(gpu["grad_theta"], f64["grad_theta"])
+    assert e_raw > par.TOL_F64["f16"] and e_raw > 10 * e_dyn, (e_raw, e_dyn)
+
+
+def test_cfg4_conv_shape_reduced():
+    _both(wl.CONFIGS["cfg4"].with_(name="cfg4s", B=3, N=3), bias_std=0.1)
+
+
+def test_conv_small_odd_geometry():
+    cfg = wl.CONFIGS["cfg4"].with_(name="convodd", B=2, N=2, C=5, H=7, W=6, tableau="kutta3")
+    _both(cfg, bias_std=0.1)
+
+
+@pytest.mark.parametrize("tab", ["rk4", "heun", "euler"])
+def test_cfg5_shape_reduced(tab):
+    _both(wl.CONFIGS["cfg5"].with_(name="cfg5s", B=96, N=5, tableau=tab))
+
+
+def test_running_cost_cotangents():
+    cfg = wl.CONFIGS["cfg1"].with_(name="run", B=64, N=4, widths=(6, 32, 6))
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    gys = wl.normals(3, "run.gys", (cfg.N + 1, cfg.B, 6), 0.1)
+    gpu = par.run_gpu(cfg, theta, y0, target, grad_ys=gys)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul", grad_ys=gys.astype(np.float64))
+    par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
