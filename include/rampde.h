@@ -147,6 +147,34 @@ const char *rampde_strerror(int code);
 /* Library/ABI version, e.g. 100 = 1.0.0. */
 int rampde_version(void);
 
+/* Optional per-kernel timing, a measurement aid for benchmarks (off by default).
+ * While enabled, every launch of the kernel classes below is bracketed by two HIP events on
+ * the caller's stream (this perturbs end-to-end time slightly: measure throughput with it off).
+ * Process-global and not thread safe.
+ *   rampde_timing_enable(on) : drops all recorded events, then switches recording on/off.
+ *   rampde_timing_read(cls, out) : waits for the recorded events of class cls and sums them:
+ *       out->ms       total elapsed milliseconds of the launches,
+ *       out->launches number of launches,
+ *       out->work     algorithmic work of those launches: floating-point operations
+ *                     (2 * M * N * K of the padded contraction) for the GEMM classes, bytes
+ *                     for the streaming classes (per state element: forward update reads y (4),
+ *                     s slopes (2 each), writes y (4) and the checkpoint (2); adjoint update
+ *                     reads a (4), s stage cotangents (2 each), writes a (4)).            */
+typedef enum {
+  RAMPDE_K_VELOCITY_GEMM = 0,  /* forward layers, recomputation and input-cotangent products (Alg. 1 line 4, eq. (vjp)) */
+  RAMPDE_K_WGRAD_GEMM = 1,     /* parameter-gradient contractions over the batch (update of g, Sec. 3) */
+  RAMPDE_K_COMBINE_STORE = 2,  /* fp32 solution update + low-precision checkpoint store (Alg. 1 lines 5-6) */
+  RAMPDE_K_ADJOINT_UPDATE = 3, /* fp32 adjoint update + max-norm (Alg. 2, update of a) */
+  RAMPDE_K_CLASSES = 4
+} rampde_kernel_class;
+typedef struct {
+  double ms;
+  int64_t launches;
+  double work;
+} rampde_kernel_time;
+int rampde_timing_enable(int on);
+int rampde_timing_read(int kernel_class, rampde_kernel_time *out);
+
 #ifdef __cplusplus
 }
 #endif

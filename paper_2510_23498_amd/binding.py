@@ -27,7 +27,9 @@ _SCALING = {"none": SCALE_NONE, "none_safe": SCALE_NONE_SAFE, "dynamic": SCALE_D
 _TORCH_LOW = {F16: torch.float16, BF16: torch.bfloat16}
 
 EXPORTS = ("rampde_num_params", "rampde_workspace_bytes", "rampde_odeint_fwd", "rampde_odeint_bwd",
-           "rampde_strerror", "rampde_version")
+           "rampde_strerror", "rampde_version", "rampde_timing_enable", "rampde_timing_read")
+
+K_VELOCITY_GEMM, K_WGRAD_GEMM, K_COMBINE_STORE, K_ADJOINT_UPDATE = 0, 1, 2, 3
 
 
 class _Tableau(C.Structure):
@@ -47,6 +49,10 @@ class _Policy(C.Structure):
 class _Stats(C.Structure):
     _fields_ = [("status", C.c_int), ("failed_step", C.c_int), ("retries", C.c_int),
                 ("s_first", C.c_float), ("s_last", C.c_float), ("s_min", C.c_float), ("s_max", C.c_float)]
+
+
+class _KernelTime(C.Structure):
+    _fields_ = [("ms", C.c_double), ("launches", C.c_int64), ("work", C.c_double)]
 
 
 class RampdeError(RuntimeError):
@@ -85,6 +91,10 @@ def load_library():
     lib.rampde_strerror.restype = C.c_char_p
     lib.rampde_strerror.argtypes = [C.c_int]
     lib.rampde_version.restype = C.c_int
+    lib.rampde_timing_enable.restype = C.c_int
+    lib.rampde_timing_enable.argtypes = [C.c_int]
+    lib.rampde_timing_read.restype = C.c_int
+    lib.rampde_timing_read.argtypes = [C.c_int, C.POINTER(_KernelTime)]
     _lib = lib
     return lib
 
@@ -189,6 +199,19 @@ def rampde_strerror(code: int) -> str:
 
 def rampde_version() -> int:
     return load_library().rampde_version()
+
+
+def rampde_timing_enable(on: bool) -> None:
+    load_library().rampde_timing_enable(1 if on else 0)
+
+
+def rampde_timing_read(kernel_class: int):
+    """(total ms, launches, algorithmic work) of the recorded launches of one kernel class."""
+    kt = _KernelTime()
+    rc = load_library().rampde_timing_read(kernel_class, C.byref(kt))
+    if rc != OK:
+        raise RampdeError(rc, rampde_strerror(rc))
+    return kt.ms, int(kt.launches), kt.work
 
 
 def rampde_num_params(vel: Velocity) -> int:

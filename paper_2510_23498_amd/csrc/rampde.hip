@@ -197,6 +197,39 @@ static int hip_fail(hipError_t e, const char* where) {
 
 static inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
+// ---------------------------------------------------------------- optional per-kernel timing
+// When enabled, launches of the kernel classes below are bracketed by HIP events on the
+// caller's stream; rampde_timing_read sums the elapsed times.  Process-global, not thread safe:
+// a measurement aid for the benchmark, off by default.
+struct TimedLaunch {
+  hipEvent_t e0, e1;
+  int cls;
+  double work;
+};
+static bool g_timing = false;
+static std::vector<TimedLaunch> g_timed;
+
+struct TimeScope {
+  bool on;
+  hipStream_t st;
+  TimedLaunch t;
+  TimeScope(int cls, double work, hipStream_t stream) : on(g_timing), st(stream) {
+    if (!on) return;
+    t.cls = cls;
+    t.work = work;
+    if (hipEventCreate(&t.e0) != hipSuccess || hipEventCreate(&t.e1) != hipSuccess) {
+      on = false;
+      return;
+    }
+    (void)hipEventRecord(t.e0, st);
+  }
+  ~TimeScope() {
+    if (!on) return;
+    (void)hipEventRecord(t.e1, st);
+    g_timed.push_back(t);
+  }
+};
+
 // ---------------------------------------------------------------- typed launch sequences
 template <class T>
 struct Runner {
@@ -226,6 +259,7 @@ struct Runner {
   }
 
   void launch_nt(const GemmNT& g) {
+    TimeScope ts(RAMPDE_K_VELOCITY_GEMM, 2.0 * g.M * (double)g.N * g.K, st);
     if (p.conv) {
       dim3 grid(blocks_for(g.M, 128), g.N / 64);
       gemm_nt<T, 2, 1, true><<<grid, 256, 0, st>>>(g);
@@ -305,6 +339,8 @@ struct Runner {
       const float h = (float)(tgrid[i + 1] - tgrid[i]);
       const uint16_t* ck = ckpt + (size_t)i * p.n;
       stages(ck, tgrid[i], h, tab, pol->low, 0, nullptr, nullptr);
+      // bytes per state element: read y (4) + s slopes (2 each) + write y (4) + write checkpoint (2)
+      TimeScope ts(RAMPDE_K_COMBINE_STORE, (double)p.n * (10.0 + 2.0 * p.s), st);
       combine_store<T><<<blocks_for(p.n, 256), 256, 0, st>>>(y, u16(p.K), p.stage_stride, p.s, bw, h,
                                                             (pol->flags & RAMPDE_ROUND_INCREMENT) ? 1 : 0,
                                                             ckpt + (size_t)(i + 1) * p.n, p.d, p.dpad, p.R);
@@ -397,10 +433,13 @@ struct Runner {
       g.Wd = p.Wd;
       g.taps = p.conv ? 9 : 1;
       dim3 grid((y.Npad + 127) / 128, (y.Kpad + 127) / 128, splits * g.taps);
-      if (p.conv)
-        gemm_tn<T, true><<<grid, 256, 0, st>>>(g);
-      else
-        gemm_tn<T, false><<<grid, 256, 0, st>>>(g);
+      {
+        TimeScope ts(RAMPDE_K_WGRAD_GEMM, 2.0 * rows * (double)y.Npad * y.Kpad * g.taps, st);
+        if (p.conv)
+          gemm_tn<T, true><<<grid, 256, 0, st>>>(g);
+        else
+          gemm_tn<T, false><<<grid, 256, 0, st>>>(g);
+      }
       // bias and time-weight gradients
       int rpb = (int)((rows + 255) / 256);
       if (rpb < 64) rpb = 64;
@@ -414,8 +453,12 @@ struct Runner {
         column_sums<T, false><<<cgrid, 256, 0, st>>>(g.A, y.Npad, p.R, s, y.out, taus, h, gb, gwt, y.in_full, p.H,
                                                      p.Wd, rpb, ctl);
     }
-    adjoint_update<T><<<blocks_for(p.n, 256), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, s, h, gys_i, p.dpad,
-                                                           p.R, ctl);
+    {
+      // bytes per state element: read a (4) + s stage cotangents (2 each) + write a (4)
+      TimeScope ts(RAMPDE_K_ADJOINT_UPDATE, (double)p.n * (8.0 + 2.0 * s), st);
+      adjoint_update<T><<<blocks_for(p.n, 256), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, s, h, gys_i, p.dpad,
+                                                             p.R, ctl);
+    }
     scale_grow<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), i, Low<T>::p_bits, dynamic,
                                 (pol->flags & RAMPDE_GROW_RAW_NORM) ? 1 : 0);
   }
@@ -584,5 +627,32 @@ const char* rampde_strerror(int code) {
 }
 
 int rampde_version(void) { return 100; }
+
+int rampde_timing_enable(int on) {
+  for (auto& t : g_timed) {
+    (void)hipEventDestroy(t.e0);
+    (void)hipEventDestroy(t.e1);
+  }
+  g_timed.clear();
+  g_timing = on != 0;
+  return RAMPDE_OK;
+}
+
+int rampde_timing_read(int kernel_class, rampde_kernel_time* out) {
+  if (!out || kernel_class < 0 || kernel_class >= RAMPDE_K_CLASSES) return RAMPDE_EINVAL;
+  out->ms = 0.0;
+  out->launches = 0;
+  out->work = 0.0;
+  for (auto& t : g_timed) {
+    if (t.cls != kernel_class) continue;
+    HIP_TRY(hipEventSynchronize(t.e1));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, t.e0, t.e1));
+    out->ms += ms;
+    out->launches += 1;
+    out->work += t.work;
+  }
+  return RAMPDE_OK;
+}
 
 }  // extern "C"
