@@ -101,13 +101,14 @@ def main():
         one_pass()
     torch.cuda.synchronize()
     classes = {"velocity_gemm": rb.K_VELOCITY_GEMM, "wgrad_gemm": rb.K_WGRAD_GEMM,
-               "combine_store": rb.K_COMBINE_STORE, "adjoint_update": rb.K_ADJOINT_UPDATE}
+               "combine_store": rb.K_COMBINE_STORE, "adjoint_update": rb.K_ADJOINT_UPDATE,
+               "fused_forward": rb.K_FUSED_FORWARD, "fused_adjoint_step": rb.K_FUSED_ADJOINT_STEP}
     timing = {}
     for name, cls in classes.items():
         ms, launches, work = rb.rampde_timing_read(cls)
         timing[name] = dict(ms=ms, launches=launches, work=work)
     rb.rampde_timing_enable(False)
-    dom = max(("velocity_gemm", "wgrad_gemm"), key=lambda k: timing[k]["ms"])
+    dom = max(("velocity_gemm", "wgrad_gemm", "fused_forward", "fused_adjoint_step"), key=lambda k: timing[k]["ms"])
     td = timing[dom]
     ach_tflops = td["work"] / (td["ms"] * 1e-3) / 1e12 if td["ms"] > 0 else 0.0
     roofline = {"bound": "mfma", "kernel": dom, "achieved": ach_tflops, "peak": PEAK_TFLOPS[cfg.low],

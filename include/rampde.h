@@ -66,6 +66,7 @@ typedef enum {
 /* policy.flags */
 #define RAMPDE_ROUND_INCREMENT 1u /* round sum_j b_j k_j to `low` before the fp32 add (literal Alg. 1 line 4) */
 #define RAMPDE_GROW_RAW_NORM 2u   /* growth test on the unscaled norm ||a|| <= 1/(2 u_L) (literal Alg. 2)     */
+#define RAMPDE_PER_LAYER_KERNELS 4u /* dense networks: use one kernel per layer instead of the row-tile-persistent kernels */
 
 /* Explicit Butcher tableau, host memory, fp64.  A is s*s row-major; only the strictly
  * lower triangle may be non-zero (checked).  Consistency (sum b = 1, ...) is not checked. */
@@ -165,7 +166,10 @@ typedef enum {
   RAMPDE_K_WGRAD_GEMM = 1,     /* parameter-gradient contractions over the batch (update of g, Sec. 3) */
   RAMPDE_K_COMBINE_STORE = 2,  /* fp32 solution update + low-precision checkpoint store (Alg. 1 lines 5-6) */
   RAMPDE_K_ADJOINT_UPDATE = 3, /* fp32 adjoint update + max-norm (Alg. 2, update of a) */
-  RAMPDE_K_CLASSES = 4
+  RAMPDE_K_FUSED_FORWARD = 4,  /* dense networks: whole forward pass of a row tile, all steps, one launch (Alg. 1);
+                                  work = flops of all its layer contractions */
+  RAMPDE_K_FUSED_ADJOINT_STEP = 5, /* dense networks: recomputation + cotangent chain + adjoint update of one step (Alg. 2) */
+  RAMPDE_K_CLASSES = 6
 } rampde_kernel_class;
 typedef struct {
   double ms;

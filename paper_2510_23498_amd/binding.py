@@ -20,8 +20,6 @@ F32, F16, BF16 = 0, 1, 2
 SCALE_NONE, SCALE_NONE_SAFE, SCALE_DYNAMIC, SCALE_AUTO = 0, 1, 2, 3
 VEL_MLP, VEL_CONV2 = 0, 1
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, ESCALE, EHIP = 0, 1, 2, 3, 4, 5
-ROUND_INCREMENT, GROW_RAW_NORM = 1, 2
-
 _LOW = {"f32": F32, "f16": F16, "bf16": BF16}
 _SCALING = {"none": SCALE_NONE, "none_safe": SCALE_NONE_SAFE, "dynamic": SCALE_DYNAMIC, "auto": SCALE_AUTO}
 _TORCH_LOW = {F16: torch.float16, BF16: torch.bfloat16}
@@ -29,7 +27,8 @@ _TORCH_LOW = {F16: torch.float16, BF16: torch.bfloat16}
 EXPORTS = ("rampde_num_params", "rampde_workspace_bytes", "rampde_odeint_fwd", "rampde_odeint_bwd",
            "rampde_strerror", "rampde_version", "rampde_timing_enable", "rampde_timing_read")
 
-K_VELOCITY_GEMM, K_WGRAD_GEMM, K_COMBINE_STORE, K_ADJOINT_UPDATE = 0, 1, 2, 3
+K_VELOCITY_GEMM, K_WGRAD_GEMM, K_COMBINE_STORE, K_ADJOINT_UPDATE, K_FUSED_FORWARD, K_FUSED_ADJOINT_STEP = range(6)
+ROUND_INCREMENT, GROW_RAW_NORM, PER_LAYER_KERNELS = 1, 2, 4
 
 
 class _Tableau(C.Structure):

@@ -27,8 +27,11 @@ struct Ctl {
   unsigned amax_bits;  // bit pattern of max |a| (non-negative floats order like unsigned ints)
   int retries;         // number of halvings so far
   float s_min, s_max;
-  int pad[7];
+  int done;            // workgroups of the current adjoint-step kernel that have finished
+  float S_step;        // scale of the most recently accepted step (used by its parameter-gradient kernels)
+  int pad[5];
 };
+static_assert(sizeof(Ctl) == 64, "control block layout");
 
 struct F16 {};
 struct BF16 {};
@@ -44,6 +47,14 @@ struct Low<F16> {
     return __builtin_bit_cast(uint16_t, h);
   }
   __device__ static inline float to_f32(uint16_t u) { return (float)__builtin_bit_cast(_Float16, u); }
+  // two values rounded and packed (first in the low half): one v_cvt_pkrtz-free RNE conversion pair
+  __device__ static inline uint32_t pack2(float a, float b) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    h2 v;
+    v[0] = (_Float16)a;
+    v[1] = (_Float16)b;
+    return __builtin_bit_cast(uint32_t, v);
+  }
   __device__ static inline bool nonfinite(uint16_t u) { return (u & 0x7C00u) == 0x7C00u; }
   __device__ static inline f32x16 mfma32(u16x8 a, u16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
@@ -63,6 +74,14 @@ struct Low<BF16> {
     return (uint16_t)(u >> 16);
   }
   __device__ static inline float to_f32(uint16_t u) { return __builtin_bit_cast(float, (uint32_t)u << 16); }
+  // two values rounded (nearest even, hardware conversion of gfx950) and packed, first in the low half
+  __device__ static inline uint32_t pack2(float a, float b) {
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    b2 v;
+    v[0] = (__bf16)a;
+    v[1] = (__bf16)b;
+    return __builtin_bit_cast(uint32_t, v);
+  }
   __device__ static inline bool nonfinite(uint16_t u) { return (u & 0x7F80u) == 0x7F80u; }
   __device__ static inline f32x16 mfma32(u16x8 a, u16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);

@@ -133,7 +133,7 @@ __global__ void combine_store(float* __restrict__ y, const uint16_t* __restrict_
 // ------------------------------------------------------------------------- backward
 __global__ void ctl_reset(Ctl* ctl) {
   ctl->S = 1.f; ctl->attempt = 1; ctl->poison = 0; ctl->failed_step = -1; ctl->nonfinite = 0;
-  ctl->amax_bits = 0; ctl->retries = 0; ctl->s_min = 1.f; ctl->s_max = 1.f;
+  ctl->amax_bits = 0; ctl->retries = 0; ctl->s_min = 1.f; ctl->s_max = 1.f; ctl->done = 0; ctl->S_step = 1.f;
 }
 
 // a <- dL/dy_N (+ running-cost cotangent), max|a|   (paper Alg. 2, initialisation)
@@ -200,11 +200,13 @@ __global__ void stage_cotangent(const float* __restrict__ a, int d, const uint16
 }
 
 // after the cotangent chain of a step: accept or poison   (paper Alg. 2, finiteness test)
-__global__ void chain_decide(Ctl* ctl, int step) {
+__global__ void chain_decide(Ctl* ctl, int step, int detect) {
   if (ctl->poison) return;
-  if (ctl->nonfinite) {
+  if (detect && ctl->nonfinite) {
     ctl->poison = 1;
     ctl->failed_step = step;
+  } else {
+    ctl->S_step = ctl->S;
   }
 }
 
@@ -298,7 +300,7 @@ __global__ __launch_bounds__(256) void column_sums(const uint16_t* __restrict__ 
   for (int t = 0; t < NT; ++t) red[ty][tx][1 + t] = st[t];
   __syncthreads();
   if (ty == 0 && c < ncols) {
-    const float scale = h / ctl->S;
+    const float scale = h / ctl->S_step;
     float v = red[0][tx][0] + red[1][tx][0] + red[2][tx][0] + red[3][tx][0];
     unsafeAtomicAdd(&gb[c], scale * v);
     if (gwt) {

@@ -1,0 +1,862 @@
+// Row-tile-persistent kernels for dense (MLP) velocity networks.
+//
+// Samples are independent in the forward recursion (paper Algorithm 1) and in the cotangent
+// chain of the adjoint (paper Algorithm 2, eq. (vjp)); only the parameter gradient and the
+// adjoint scale couple them.  So one workgroup owns TM = 16 * MT batch rows and carries them
+//   * mlp_forward_fused : through ALL time steps, stages and layers in one launch,
+//   * mlp_adjoint_step  : through one step of the adjoint: stage recomputation, the whole
+//                         cotangent chain, the fp32 adjoint update and the max-norm / overflow
+//                         bookkeeping of the dynamic scale (the last workgroup to finish takes
+//                         the accept / grow decision, so no extra launches are needed).
+//
+// Where things live
+//   * fp32 state (y forward, a backward): in registers, in the accumulator layout of the last
+//     contraction of a stage, so the Runge-Kutta combinations are lane-local;
+//   * slopes k_j / stage cotangents zbar_j: low precision, in LDS when they fit (else in the
+//     global workspace); every lane only ever reads back the elements it wrote itself;
+//   * activations of the current layer: LDS, two ping-pong tiles plus one tile for the stage
+//     input (so the epilogue of a stage's last contraction can already write the next stage's
+//     input while other wavefronts still read the ping-pong tiles);
+//   * biases and time-column weights: LDS (copied once per launch);
+//   * weights: streamed from L2 in a pre-swizzled "fragment-major" layout straight into MFMA
+//     operand registers (each wavefront reads a disjoint slice of the output columns, so
+//     staging weights in LDS would not save traffic), PD k-blocks ahead and across layer
+//     boundaries.
+//
+// MFMA shape: v_mfma_f32_16x16x32_{f16,bf16} with the WEIGHT tile as the first operand, so a
+// lane ends up with 4 consecutive output columns of one row: 8-byte stores, float4 bias loads.
+#pragma once
+#include "common.hpp"
+
+namespace rampde {
+
+// LDS pointers carry their address space in the type: a generic pointer would turn every LDS
+// access into a flat instruction, whose completion order is unknown to the wait-count logic, and
+// every wait in the software pipeline below would become a wait for ALL outstanding loads.
+#define RAMPDE_LDS __attribute__((address_space(3)))
+typedef RAMPDE_LDS uint16_t lds_u16;
+typedef RAMPDE_LDS float lds_f32;
+typedef RAMPDE_LDS u16x8 lds_u16x8;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ inline uint2 lds_load_u2(const lds_u16* p) {
+  const u32x2 v = *(const RAMPDE_LDS u32x2*)p;
+  return make_uint2(v[0], v[1]);
+}
+__device__ inline void lds_store_u2(lds_u16* p, uint2 q) {
+  u32x2 v;
+  v[0] = q.x;
+  v[1] = q.y;
+  *(RAMPDE_LDS u32x2*)p = v;
+}
+__device__ inline float4 lds_load_f4(const lds_f32* p) {
+  const f32x4 v = *(const RAMPDE_LDS f32x4*)p;
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+typedef __attribute__((address_space(1))) u16x8 glb_u16x8;  // weight fragments: always global memory
+
+constexpr int kMaxLayers = 8;
+constexpr int PD = 4;  // k-blocks (of 32) of weight fragments kept in flight per wavefront
+
+struct FusedLayer {
+  const u16x8* Wf;    // forward fragments  [Kpad/32][Npad/16][64 lanes]: lane -> W[nt*16 + lane%16][kb*32 + (lane/16)*8 + 0..7]
+  const u16x8* WTf;   // transposed frags   [Npad/32][Kpad/16][64 lanes]: lane -> W[nb*32 + (lane/16)*8 + 0..7][kt*16 + lane%16]
+  const float* bias;  // [Npad] fp32, already rounded to low precision
+  const float* wt;    // [Npad] time-column weights (layer 1 only) or null
+  int Kpad, Npad;
+  int bias_off;       // offset (floats) of this layer's bias in the LDS parameter block
+};
+
+struct FusedArgs {
+  FusedLayer layer[kMaxLayers];
+  int L, s, N, d, dpad, ldp;
+  int wt_off;            // offset (floats) of the time-column weights in the LDS parameter block
+  int nparam;            // floats in the LDS parameter block (multiple of 4)
+  int k_in_lds;          // slopes / stage cotangents of a step are kept in LDS
+  int64_t R;
+  int64_t stage_stride;  // R * dpad
+  float A[kMaxStages * kMaxStages];
+  float b[kMaxStages];
+  const float* steptab;  // [N][1 + s]: h_i, tau_{i,1..s} (tau already rounded to low precision)
+  // forward
+  const float* y0;
+  float* y;
+  uint16_t* ckpt;
+  int round_incr;
+  uint16_t* K;  // [s][R][dpad] slopes (used when they do not fit in LDS)
+  // one adjoint step
+  int step;
+  uint16_t* ACT[kMaxLayers];   // [s][R][Npad_l], l = 0..L-2: hidden activations (read back for tanh')
+  // feature-major copies for the parameter-gradient contraction: [feature][k], k = stage * Rp + row
+  uint16_t* ZT;                // [dpad][ldk] stage inputs
+  uint16_t* ACTT[kMaxLayers];  // [Npad_l][ldk] hidden activations
+  uint16_t* DELTAT[kMaxLayers];// [Npad_l][ldk] their cotangents
+  uint16_t* KBART;             // [dpad][ldk] cotangents of the slopes
+  int64_t ldk, Rp;
+  uint16_t* ZBAR;              // [s][R][dpad] (used when they do not fit in LDS)
+  const float* a_in;
+  float* a_out;
+  const float* gys;            // running-cost cotangent of this step or null
+  Ctl* ctl;
+  float* scale_hist;
+  int detect, dynamic, raw_norm, skip_recompute;
+};
+
+// theta (fp32) -> fragment-major low-precision copies of one dense layer (see FusedLayer).
+template <class T>
+__global__ void cast_dense_fragments(const float* __restrict__ W, int out, int in, int in_full, u16x8* Wf,
+                                     u16x8* WTf, int Npad, int Kpad) {
+  const int lane = threadIdx.x & 63;
+  const int frag = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int nfw = (Kpad / 32) * (Npad / 16);
+  const int nft = (Npad / 32) * (Kpad / 16);
+  if (frag < nfw) {
+    const int kb = frag / (Npad / 16), nt = frag % (Npad / 16);
+    const int n = nt * 16 + (lane & 15), k0 = kb * 32 + (lane >> 4) * 8;
+    u16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int k = k0 + e;
+      v[e] = (n < out && k < in) ? Low<T>::from_f32(W[(size_t)n * in_full + k]) : (uint16_t)0;
+    }
+    Wf[(size_t)frag * 64 + lane] = v;
+  } else if (frag < nfw + nft) {
+    const int f = frag - nfw;
+    const int nb = f / (Kpad / 16), kt = f % (Kpad / 16);
+    const int k = kt * 16 + (lane & 15), n0 = nb * 32 + (lane >> 4) * 8;
+    u16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int n = n0 + e;
+      v[e] = (n < out && k < in) ? Low<T>::from_f32(W[(size_t)n * in_full + k]) : (uint16_t)0;
+    }
+    WTf[(size_t)f * 64 + lane] = v;
+  }
+}
+
+// tanh of an fp32 pre-activation, a few ulp: odd polynomial for |x| < 1/8, 1 - 2/(exp(2x) + 1)
+// elsewhere (exact limits +-1 for large |x|).  The result is rounded to 16 bits by the caller.
+__device__ inline float tanh_fast(float x) {
+#ifdef RAMPDE_PROBE_NOTANH
+  return x * 0.5f;
+#endif
+  const float e = __builtin_amdgcn_exp2f(2.885390081777927f * x);
+  const float big = fmaf(-2.f, __builtin_amdgcn_rcpf(e + 1.f), 1.f);
+  const float x2 = x * x;
+  const float small = x * fmaf(x2, fmaf(x2, fmaf(x2, -17.f / 315.f, 2.f / 15.f), -1.f / 3.f), 1.f);
+  return x2 < 0.015625f ? small : big;
+}
+
+template <class T>
+__device__ inline uint2 pack4(const float (&v)[4]) {
+  uint2 p;
+  p.x = Low<T>::pack2(v[0], v[1]);
+  p.y = Low<T>::pack2(v[2], v[3]);
+  return p;
+}
+template <class T>
+__device__ inline void unpack4(uint2 p, float (&v)[4]) {
+  v[0] = Low<T>::to_f32((uint16_t)p.x);
+  v[1] = Low<T>::to_f32((uint16_t)(p.x >> 16));
+  v[2] = Low<T>::to_f32((uint16_t)p.y);
+  v[3] = Low<T>::to_f32((uint16_t)(p.y >> 16));
+}
+template <class T>
+__device__ inline bool any_nonfinite4(uint2 p) {
+  return Low<T>::nonfinite((uint16_t)p.x) || Low<T>::nonfinite((uint16_t)(p.x >> 16)) ||
+         Low<T>::nonfinite((uint16_t)p.y) || Low<T>::nonfinite((uint16_t)(p.y >> 16));
+}
+
+// 4 consecutive fp32 / 16-bit state elements of row `row`, columns c..c+3 of a [R][d] array;
+// columns >= d and rows >= R read as zero and are not written.  d % 4 == 0 takes the vector path.
+__device__ inline void load4f(const float* p, int64_t row, int64_t R, int c, int d, float (&v)[4]) {
+  v[0] = v[1] = v[2] = v[3] = 0.f;
+  if (row >= R) return;
+  if ((d & 3) == 0) {
+    if (c < d) {
+      const float4 t = *reinterpret_cast<const float4*>(&p[(size_t)row * d + c]);
+      v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (c + r < d) v[r] = p[(size_t)row * d + c + r];
+  }
+}
+__device__ inline void store4f(float* p, int64_t row, int64_t R, int c, int d, const float (&v)[4]) {
+  if (row >= R) return;
+  if ((d & 3) == 0) {
+    if (c < d) *reinterpret_cast<float4*>(&p[(size_t)row * d + c]) = make_float4(v[0], v[1], v[2], v[3]);
+  } else {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (c + r < d) p[(size_t)row * d + c + r] = v[r];
+  }
+}
+__device__ inline uint2 load4h(const uint16_t* p, int64_t row, int64_t R, int c, int d) {
+  uint2 q = make_uint2(0u, 0u);
+  if (row >= R) return q;
+  if ((d & 3) == 0) {
+    if (c < d) q = *reinterpret_cast<const uint2*>(&p[(size_t)row * d + c]);
+  } else {
+    uint32_t e[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (c + r < d) e[r] = p[(size_t)row * d + c + r];
+    q.x = e[0] | (e[1] << 16);
+    q.y = e[2] | (e[3] << 16);
+  }
+  return q;
+}
+__device__ inline void store4h(uint16_t* p, int64_t row, int64_t R, int c, int d, uint2 q) {
+  if (row >= R) return;
+  if ((d & 3) == 0) {
+    if (c < d) *reinterpret_cast<uint2*>(&p[(size_t)row * d + c]) = q;
+  } else {
+    const uint16_t e[4] = {(uint16_t)q.x, (uint16_t)(q.x >> 16), (uint16_t)q.y, (uint16_t)(q.y >> 16)};
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (c + r < d) p[(size_t)row * d + c + r] = e[r];
+  }
+}
+
+// 4 consecutive features of one row into a feature-major array: XT[n + r][k], r = 0..3
+__device__ inline void store4t(uint16_t* XT, int64_t ldk, int64_t k, int n, uint2 q) {
+  XT[(size_t)n * ldk + k] = (uint16_t)q.x;
+  XT[(size_t)(n + 1) * ldk + k] = (uint16_t)(q.x >> 16);
+  XT[(size_t)(n + 2) * ldk + k] = (uint16_t)q.y;
+  XT[(size_t)(n + 3) * ldk + k] = (uint16_t)(q.y >> 16);
+}
+
+// One contraction pass of a row tile: out[TM][Ncols] = in[TM][32*KB] * Wfrag^T for the
+// calling wavefront's slice of output-column tiles.
+struct PassDesc {
+  const glb_u16x8* Wf;
+  int KB;    // k-blocks of 32
+  int NT16;  // column tiles of 16 in total; a wavefront owns NT16/4 consecutive ones
+};
+
+// The weight stream of a pass is software-pipelined PD k-blocks deep.  Both functions are
+// branch-free (out-of-range k-blocks are clamped to the last one and masked out of the MFMA
+// by a zero activation operand) so that the number of loads in flight is known statically
+// and every wait is for exactly the fragment that is consumed next.
+template <int NTG>
+__device__ inline void ring_preload(u16x8 (&ring)[PD][4], const PassDesc& p, int nt0, int lane) {
+  const glb_u16x8* base = p.Wf + (size_t)nt0 * 64 + lane;
+  const size_t kstride = (size_t)p.NT16 * 64;
+#pragma unroll
+  for (int u = 0; u < PD; ++u) {
+    const int kb = min(u, p.KB - 1);
+#pragma unroll
+    for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = base[kb * kstride + nt * 64];
+  }
+}
+
+template <class T, int MT, int NTG>
+__device__ inline void tile_mma(f32x4 (&acc)[4][MT], u16x8 (&ring)[PD][4], const PassDesc& p, int nt0,
+                                const lds_u16* in, int ldp, int lane) {
+  static_assert(PD % 2 == 0, "activation fragments are double-buffered by k-block parity");
+  const int lm = lane & 15, lq = lane >> 4;
+#pragma unroll
+  for (int nt = 0; nt < NTG; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const glb_u16x8* wbase = p.Wf + (size_t)nt0 * 64 + lane;
+  const int kstride = p.NT16 * 64;
+  const lds_u16* abase = in + lm * ldp + lq * 8;
+  const int KB = p.KB;
+  const int kb_tail = ((KB + PD - 1) / PD - 1) * PD;  // first k-block of the last group of PD
+
+  u16x8 a[2][MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) a[0][mt] = *(const lds_u16x8*)(abase + mt * 16 * ldp);
+
+  // steady state: fetch the next activation fragment, consume ring[u], refill it PD k-blocks ahead
+  for (int kb0 = 0; kb0 < kb_tail; kb0 += PD) {
+    const glb_u16x8* wnext = wbase + (size_t)(kb0 + PD) * kstride;
+#pragma unroll
+    for (int u = 0; u < PD; ++u) {
+      const int kb = kb0 + u;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        a[(u + 1) & 1][mt] = *(const lds_u16x8*)(abase + mt * 16 * ldp + (kb + 1) * 32);
+#pragma unroll
+      for (int nt = 0; nt < NTG; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = Low<T>::mfma16(ring[u][nt], a[u & 1][mt], acc[nt][mt]);
+#ifndef RAMPDE_PROBE_NOLOAD
+      const int ku = min(u, KB - 1 - kb0 - PD);  // clamp to the last k-block (only in the last main group)
+#pragma unroll
+      for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = wnext[ku * kstride + nt * 64];
+#endif
+    }
+  }
+  // drain: the last group of PD k-blocks, no refills; k-blocks past the end contribute zero
+#pragma unroll
+  for (int u = 0; u < PD; ++u) {
+    const int kb = kb_tail + u;
+    const int ka = min(kb + 1, KB - 1);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      a[(u + 1) & 1][mt] = *(const lds_u16x8*)(abase + mt * 16 * ldp + ka * 32);
+    const bool valid = kb < KB;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const u16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+      const u16x8 a_use = valid ? a[u & 1][mt] : zero;
+#pragma unroll
+      for (int nt = 0; nt < NTG; ++nt) acc[nt][mt] = Low<T>::mfma16(ring[u][nt], a_use, acc[nt][mt]);
+    }
+  }
+}
+
+// Software pipeline of weight fragments + the pass drivers.  A pass calls, per owned 16x16 tile,
+//   pre(n, m)                 -> uint2   before the contraction (early global loads the epilogue needs)
+//   epi(acc, pf, nt, mt, n, m)           after it (nt is the tile's index within the group)
+// with n = first of the lane's 4 columns and m = the lane's row within the tile of TM rows, and
+//   nxt()                                between contraction and epilogue: it must preload the
+//                                        first PD k-blocks of whatever pass runs next.
+// The sequence of passes is static in the kernels, so there is no run-time bookkeeping of what
+// the ring holds: every pass finds its first fragments already requested by its predecessor.
+// Hidden widths are padded to multiples of 256 by the host, so a wavefront owns a multiple of 4
+// column tiles in every hidden pass; state-shaped passes own NTL = dpad / 64 tiles (1, 2 or 4).
+template <class T, int MT>
+struct TileEngine {
+  u16x8 ring[PD][4];
+  int lane, wave;
+
+  // request the first PD k-blocks of group g of pass p (NTG tiles per wavefront and group)
+  template <int NTG>
+  __device__ inline void preload(const PassDesc& p, int g) {
+    const int ntw = p.NT16 >> 2;
+    ring_preload<NTG>(ring, p, wave * ntw + g * NTG, lane);
+  }
+
+  template <int NTG, class Pre, class Epi, class Nxt>
+  __device__ inline void group(const PassDesc& p, int nt0, const lds_u16* in, int ld_in, bool sync_before_epi,
+                               Pre& pre, Epi& epi, Nxt& nxt) {
+    const int lm = lane & 15, lq = lane >> 4;
+    uint2 pf[NTG][MT];
+#pragma unroll
+    for (int nt = 0; nt < NTG; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) pf[nt][mt] = pre((nt0 + nt) * 16 + lq * 4, mt * 16 + lm);
+    f32x4 acc[4][MT];
+    tile_mma<T, MT, NTG>(acc, ring, p, nt0, in, ld_in, lane);
+    nxt();
+    if (sync_before_epi) __syncthreads();
+#pragma unroll
+    for (int nt = 0; nt < NTG; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) epi(acc[nt][mt], pf[nt][mt], nt, mt, (nt0 + nt) * 16 + lq * 4, mt * 16 + lm);
+  }
+
+  // hidden pass: groups of 4 column tiles per wavefront.  Ends with a barrier.
+  template <class Pre, class Epi, class Nxt>
+  __device__ inline void run_hidden(const PassDesc& p, const lds_u16* in, int ld_in, Pre pre, Epi epi, Nxt nxt) {
+    const int ntw = p.NT16 >> 2;
+    const int groups = ntw >> 2;
+    for (int g = 0; g < groups; ++g) {
+      auto nx = [&]() {
+        if (g + 1 < groups) preload<4>(p, g + 1);
+        else nxt();
+      };
+      group<4>(p, wave * ntw + g * 4, in, ld_in, false, pre, epi, nx);
+    }
+    __syncthreads();
+  }
+
+  // state-shaped pass (the contraction that ends a stage): one group of NTG tiles, compile-time
+  // tile indices so that per-tile state registers can be addressed.  Ends with a barrier.
+  template <int NTG, class Pre, class Epi, class Nxt>
+  __device__ inline void run_fixed(const PassDesc& p, const lds_u16* in, int ld_in, bool sync_before_epi, Pre pre,
+                                   Epi epi, Nxt nxt) {
+    group<NTG>(p, wave * NTG, in, ld_in, sync_before_epi, pre, epi, nxt);
+    __syncthreads();
+  }
+};
+
+__device__ inline PassDesc fwd_pass(const FusedArgs& g, int l) {
+  return PassDesc{(const glb_u16x8*)g.layer[l].Wf, g.layer[l].Kpad / 32, g.layer[l].Npad / 16};
+}
+__device__ inline PassDesc bwd_pass(const FusedArgs& g, int l) {
+  return PassDesc{(const glb_u16x8*)g.layer[l].WTf, g.layer[l].Npad / 32, g.layer[l].Kpad / 16};
+}
+
+// LDS carve-up shared by both kernels.
+template <int MT>
+struct TileLds {
+  static constexpr int TM = 16 * MT;
+  lds_f32* param;   // [nparam] biases of all layers, then time-column weights
+  lds_u16* zbuf;    // [TM][ldz]  stage input / stage cotangent tile
+  lds_u16* buf0;    // [TM][ldp]
+  lds_u16* buf1;    // [TM][ldp]
+  lds_u16* kl;      // [s][TM][dpad] slopes or stage cotangents (when k_in_lds)
+  int ldz, ldp;
+  __device__ inline TileLds(lds_u16* smem, const FusedArgs& g) {
+    param = (lds_f32*)smem;
+    ldz = g.dpad + 8;
+    ldp = g.ldp;
+    zbuf = smem + 2 * g.nparam;
+    buf0 = zbuf + TM * ldz;
+    buf1 = buf0 + TM * ldp;
+    kl = buf1 + TM * ldp;
+  }
+  // tile that layer / transposed pass number q (0 = first of its chain) reads and writes
+  __device__ inline const lds_u16* in(int q) const { return q == 0 ? zbuf : (((q - 1) & 1) ? buf1 : buf0); }
+  __device__ inline int ld_in(int q) const { return q == 0 ? ldz : ldp; }
+  __device__ inline lds_u16* out(int q) const { return (q & 1) ? buf1 : buf0; }
+};
+
+__device__ inline void load_params(lds_f32* param, const FusedArgs& g) {
+  for (int l = 0; l < g.L; ++l)
+    for (int i = threadIdx.x; i < g.layer[l].Npad; i += 256) param[g.layer[l].bias_off + i] = g.layer[l].bias[i];
+  for (int i = threadIdx.x; i < g.layer[0].Npad; i += 256) param[g.wt_off + i] = g.layer[0].wt ? g.layer[0].wt[i] : 0.f;
+}
+
+// Low-precision per-stage vectors of a tile (slopes, stage cotangents): LDS or global.
+template <int MT>
+struct StageStore {
+  lds_u16* lds;    // used when in_lds
+  bool in_lds;
+  uint16_t* glob;
+  int dpad;
+  int64_t stage_stride, row0, R;
+  __device__ inline void put(int j, int m, int n, uint2 q) const {
+    if (in_lds) lds_store_u2(&lds[(j * 16 * MT + m) * dpad + n], q);
+    else if (row0 + m < R) *reinterpret_cast<uint2*>(&glob[(size_t)j * stage_stride + (size_t)(row0 + m) * dpad + n]) = q;
+  }
+  __device__ inline uint2 get(int j, int m, int n) const {
+    if (in_lds) return lds_load_u2(&lds[(j * 16 * MT + m) * dpad + n]);
+    if (row0 + m < R) return *reinterpret_cast<const uint2*>(&glob[(size_t)j * stage_stride + (size_t)(row0 + m) * dpad + n]);
+    return make_uint2(0u, 0u);
+  }
+};
+
+// Hidden layers of one velocity evaluation (all but the last layer) for stage j.  The ring must
+// hold the first fragments of layer 0 (if L > 1); on return it holds those of the last layer.
+template <class T, int MT, int NTL, bool KEEP>
+__device__ inline void hidden_layers(TileEngine<T, MT>& eng, const TileLds<MT>& lds, const FusedArgs& g, int j,
+                                     float tau, int64_t row0) {
+  for (int l = 0; l + 1 < g.L; ++l) {
+    const PassDesc p = fwd_pass(g, l);
+    const PassDesc nx = fwd_pass(g, l + 1);
+    const bool next_is_last = (l + 2 == g.L);
+    const lds_f32* bias = lds.param + g.layer[l].bias_off;
+    const lds_f32* wt = lds.param + g.wt_off;
+    const bool has_wt = (l == 0);
+    lds_u16* out = lds.out(l);
+    const int ldp = lds.ldp;
+    uint16_t* gout = KEEP ? g.ACT[l] + (size_t)j * g.R * g.layer[l].Npad : nullptr;
+    uint16_t* goutT = KEEP ? g.ACTT[l] : nullptr;
+    const int64_t kj = (int64_t)j * g.Rp + row0;
+    const int ldg = g.layer[l].Npad;
+    eng.run_hidden(
+        p, lds.in(l), lds.ld_in(l), [](int, int) { return make_uint2(0u, 0u); },
+        [&](const f32x4& acc, uint2, int, int, int n, int m) {
+          const float4 bv = lds_load_f4(&bias[n]);
+          float v[4] = {acc[0] + bv.x, acc[1] + bv.y, acc[2] + bv.z, acc[3] + bv.w};
+          if (has_wt) {
+            const float4 tv = lds_load_f4(&wt[n]);
+            v[0] = fmaf(tv.x, tau, v[0]); v[1] = fmaf(tv.y, tau, v[1]);
+            v[2] = fmaf(tv.z, tau, v[2]); v[3] = fmaf(tv.w, tau, v[3]);
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = tanh_fast(v[r]);
+          const uint2 q = pack4<T>(v);
+          lds_store_u2(&out[m * ldp + n], q);
+          if (KEEP && row0 + m < g.R) {
+            *reinterpret_cast<uint2*>(&gout[(size_t)(row0 + m) * ldg + n]) = q;
+            store4t(goutT, g.ldk, kj + m, n, q);
+          }
+        },
+        [&]() {
+          if (next_is_last) eng.template preload<NTL>(nx, 0);
+          else eng.template preload<4>(nx, 0);
+        });
+  }
+}
+
+// fp32 pre-activation of the last layer for the lane's 4 columns
+__device__ inline void last_layer_values(const f32x4& acc, const lds_f32* param, const FusedArgs& g, float tau, int n,
+                                         float (&v)[4]) {
+  const float4 bv = lds_load_f4(&param[g.layer[g.L - 1].bias_off + n]);
+  v[0] = acc[0] + bv.x; v[1] = acc[1] + bv.y; v[2] = acc[2] + bv.z; v[3] = acc[3] + bv.w;
+  if (g.L == 1) {  // the only layer also carries the time column
+    const float4 tv = lds_load_f4(&param[g.wt_off + n]);
+    v[0] = fmaf(tv.x, tau, v[0]); v[1] = fmaf(tv.y, tau, v[1]);
+    v[2] = fmaf(tv.z, tau, v[2]); v[3] = fmaf(tv.w, tau, v[3]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Forward pass, all steps in one launch (paper Algorithm 1).  NTL = dpad / 64: column tiles of
+// the state that one wavefront owns.
+template <class T, int MT, int NTL>
+__global__ __launch_bounds__(256) void mlp_forward_fused(FusedArgs g) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  constexpr int TM = 16 * MT;
+  const TileLds<MT> lds((lds_u16*)smem, g);
+  const int tid = threadIdx.x;
+  TileEngine<T, MT> eng;
+  eng.lane = tid & 63;
+  eng.wave = tid >> 6;
+  const int lm = eng.lane & 15, lq = eng.lane >> 4;
+  const int64_t row0 = (int64_t)blockIdx.x * TM;
+  const int64_t n_state = g.R * g.d;
+  const int L = g.L, s = g.s;
+  StageStore<MT> ks{lds.kl, g.k_in_lds != 0, g.K, g.dpad, g.stage_stride, row0, g.R};
+
+  load_params(lds.param, g);
+  // y <- y0 (registers), first stored state, first stage input
+  float yv[NTL][MT][4];
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int n = (eng.wave * NTL + nt) * 16 + lq * 4, m = mt * 16 + lm;
+      load4f(g.y0, row0 + m, g.R, n, g.d, yv[nt][mt]);
+      const uint2 q = pack4<T>(yv[nt][mt]);
+      store4h(g.ckpt, row0 + m, g.R, n, g.d, q);
+      lds_store_u2(&lds.zbuf[m * lds.ldz + n], q);
+    }
+  __syncthreads();
+
+  const PassDesc first = fwd_pass(g, 0);
+  const PassDesc last = fwd_pass(g, L - 1);
+  auto preload_first = [&]() {  // first pass of a velocity evaluation
+    if (L > 1) eng.template preload<4>(first, 0);
+    else eng.template preload<NTL>(first, 0);
+  };
+  preload_first();
+  for (int i = 0; i < g.N; ++i) {
+    const float* st = g.steptab + (size_t)i * (1 + s);
+    const float h = st[0];
+    uint16_t* ck_next = g.ckpt + (size_t)(i + 1) * n_state;
+    for (int j = 0; j < s; ++j) {
+      const float tau = st[1 + j];
+      hidden_layers<T, MT, NTL, false>(eng, lds, g, j, tau, row0);
+      const bool more = (j + 1 < s) || (i + 1 < g.N);
+      eng.template run_fixed<NTL>(
+          last, lds.in(L - 1), lds.ld_in(L - 1), L == 1, [](int, int) { return make_uint2(0u, 0u); },
+          [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
+            float v[4];
+            last_layer_values(acc, lds.param, g, tau, n, v);
+            const uint2 kq = pack4<T>(v);
+            float kf[4];
+            unpack4<T>(kq, kf);
+            float (&y)[4] = yv[nt][mt];
+            float incr[4] = {0.f, 0.f, 0.f, 0.f};
+            uint2 zq;
+            if (j + 1 < s) {
+              // next stage input  z = Q(yhat + h * sum_l a_{j+1,l} k_l)
+              ks.put(j, m, n, kq);
+              for (int l = 0; l < j; ++l) {
+                const float a = g.A[(j + 1) * s + l];
+                if (a != 0.f) {
+                  float kl[4];
+                  unpack4<T>(ks.get(l, m, n), kl);
+#pragma unroll
+                  for (int r = 0; r < 4; ++r) incr[r] = fmaf(a, kl[r], incr[r]);
+                }
+              }
+              const float aj = g.A[(j + 1) * s + j];
+              float z[4];
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                incr[r] = fmaf(aj, kf[r], incr[r]);
+                z[r] = fmaf(h, incr[r], Low<T>::to_f32(Low<T>::from_f32(y[r])));
+              }
+              zq = pack4<T>(z);
+            } else {
+              // y <- y + h * sum_l b_l k_l (fp32); next stored state; first stage input of the next step
+              for (int l = 0; l < j; ++l) {
+                float kl[4];
+                unpack4<T>(ks.get(l, m, n), kl);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) incr[r] = fmaf(g.b[l], kl[r], incr[r]);
+              }
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                incr[r] = fmaf(g.b[j], kf[r], incr[r]);
+                if (g.round_incr) incr[r] = Low<T>::to_f32(Low<T>::from_f32(incr[r]));
+                y[r] = fmaf(h, incr[r], y[r]);
+              }
+              zq = pack4<T>(y);
+              store4h(ck_next, row0 + m, g.R, n, g.d, zq);
+            }
+            lds_store_u2(&lds.zbuf[m * lds.ldz + n], zq);
+          },
+          [&]() {
+            if (more) preload_first();
+          });
+    }
+  }
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      store4f(g.y, row0 + mt * 16 + lm, g.R, (eng.wave * NTL + nt) * 16 + lq * 4, g.d, yv[nt][mt]);
+}
+
+// ---------------------------------------------------------------------------------------
+// One step of the adjoint for a row tile (paper Algorithm 2, the body of the loop over steps).
+template <class T, int MT, int NTL>
+__global__ __launch_bounds__(256) void mlp_adjoint_step(FusedArgs g) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  if (g.ctl->poison) return;
+  constexpr int TM = 16 * MT;
+  const TileLds<MT> lds((lds_u16*)smem, g);
+  const int tid = threadIdx.x;
+  TileEngine<T, MT> eng;
+  eng.lane = tid & 63;
+  eng.wave = tid >> 6;
+  const int lm = eng.lane & 15, lq = eng.lane >> 4;
+  const int64_t row0 = (int64_t)blockIdx.x * TM;
+  const int64_t n_state = g.R * g.d;
+  const int L = g.L, s = g.s, D = g.dpad;
+  const float S = g.ctl->S;
+  const float* st = g.steptab + (size_t)g.step * (1 + s);
+  const float h = st[0];
+  StageStore<MT> ks{lds.kl, g.k_in_lds != 0, g.K, D, g.stage_stride, row0, g.R};
+  StageStore<MT> zs{lds.kl, g.k_in_lds != 0, g.ZBAR, D, g.stage_stride, row0, g.R};
+
+  load_params(lds.param, g);
+  // lane-resident state: the adjoint a (fp32) and lambda = Q(S a); yhat = stored state
+  float av[NTL][MT][4];
+  uint2 lamq[NTL][MT], yhat[NTL][MT];
+  bool bad = false;
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int n = (eng.wave * NTL + nt) * 16 + lq * 4, m = mt * 16 + lm;
+      load4f(g.a_in, row0 + m, g.R, n, g.d, av[nt][mt]);
+      float sa[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) sa[r] = S * av[nt][mt][r];
+      lamq[nt][mt] = pack4<T>(sa);
+      bad = bad || any_nonfinite4<T>(lamq[nt][mt]);
+      yhat[nt][mt] = load4h(g.ckpt + (size_t)g.step * n_state, row0 + m, g.R, n, g.d);
+    }
+
+  // cotangent of the slope of stage j:  kbar_j = Q( b_j lambda + h sum_{l>j} a_lj zbar_l ),
+  // with zbar_{j+1} still in registers (zn) and the later ones read back from the stage store
+  auto make_kbar = [&](int j, int nt, int mt, int m, int n, const float* zn) -> uint2 {
+    float lam[4], acc[4] = {0.f, 0.f, 0.f, 0.f}, v[4];
+    unpack4<T>(lamq[nt][mt], lam);
+    for (int l = s - 1; l > j + 1; --l) {
+      const float a = g.A[l * s + j];
+      if (a != 0.f) {
+        float zl[4];
+        unpack4<T>(zs.get(l, m, n), zl);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[r] = fmaf(a, zl[r], acc[r]);
+      }
+    }
+    if (zn) {
+      const float a = g.A[(j + 1) * s + j];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[r] = fmaf(a, zn[r], acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) v[r] = fmaf(h, acc[r], g.b[j] * lam[r]);
+    const uint2 q = pack4<T>(v);
+    bad = bad || any_nonfinite4<T>(q);
+    lds_store_u2(&lds.zbuf[m * lds.ldz + n], q);
+    if (row0 + m < g.R) store4t(g.KBART, g.ldk, (int64_t)j * g.Rp + row0 + m, n, q);
+    return q;
+  };
+
+  const PassDesc firstf = fwd_pass(g, 0);
+  const PassDesc lastf = fwd_pass(g, L - 1);
+  const PassDesc firstb = bwd_pass(g, L - 1);
+  const PassDesc lastb = bwd_pass(g, 0);
+
+  auto preload_first_f = [&]() {
+    if (L > 1) eng.template preload<4>(firstf, 0);
+    else eng.template preload<NTL>(firstf, 0);
+  };
+  auto preload_first_b = [&]() {
+    if (L > 1) eng.template preload<4>(firstb, 0);
+    else eng.template preload<NTL>(firstb, 0);
+  };
+
+  if (!g.skip_recompute) {
+    // ---- stage recomputation from the stored state, keeping inputs and activations
+    preload_first_f();
+#pragma unroll
+    for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int n = (eng.wave * NTL + nt) * 16 + lq * 4, m = mt * 16 + lm;
+        lds_store_u2(&lds.zbuf[m * lds.ldz + n], yhat[nt][mt]);
+        if (row0 + m < g.R) store4t(g.ZT, g.ldk, row0 + m, n, yhat[nt][mt]);
+      }
+    __syncthreads();
+    for (int j = 0; j < s; ++j) {
+      const float tau = st[1 + j];
+      hidden_layers<T, MT, NTL, true>(eng, lds, g, j, tau, row0);
+      const bool more = j + 1 < s;
+      eng.template run_fixed<NTL>(
+          lastf, lds.in(L - 1), lds.ld_in(L - 1), L == 1, [](int, int) { return make_uint2(0u, 0u); },
+          [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
+            float v[4];
+            last_layer_values(acc, lds.param, g, tau, n, v);
+            const uint2 kq = pack4<T>(v);
+            if (j + 1 < s) {
+              float kf[4], incr[4] = {0.f, 0.f, 0.f, 0.f}, yh[4], z[4];
+              unpack4<T>(kq, kf);
+              unpack4<T>(yhat[nt][mt], yh);
+              ks.put(j, m, n, kq);
+              for (int l = 0; l < j; ++l) {
+                const float a = g.A[(j + 1) * s + l];
+                if (a != 0.f) {
+                  float kl[4];
+                  unpack4<T>(ks.get(l, m, n), kl);
+#pragma unroll
+                  for (int r = 0; r < 4; ++r) incr[r] = fmaf(a, kl[r], incr[r]);
+                }
+              }
+              const float aj = g.A[(j + 1) * s + j];
+#pragma unroll
+              for (int r = 0; r < 4; ++r) z[r] = fmaf(h, fmaf(aj, kf[r], incr[r]), yh[r]);
+              const uint2 zq = pack4<T>(z);
+              lds_store_u2(&lds.zbuf[m * lds.ldz + n], zq);
+              if (row0 + m < g.R) store4t(g.ZT, g.ldk, (int64_t)(j + 1) * g.Rp + row0 + m, n, zq);
+            } else {
+              make_kbar(s - 1, nt, mt, m, n, nullptr);  // the slope of the last stage is not needed again
+            }
+          },
+          [&]() {
+            if (more) preload_first_f();
+            else preload_first_b();
+          });
+    }
+  } else {
+    preload_first_b();
+#pragma unroll
+    for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        make_kbar(s - 1, nt, mt, mt * 16 + lm, (eng.wave * NTL + nt) * 16 + lq * 4, nullptr);
+    __syncthreads();
+  }
+
+  // ---- cotangent chain, stages in reverse (eq. (vjp) pushed through the stage recursion)
+  float da[NTL][MT][4];
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) da[nt][mt][r] = 0.f;
+
+  for (int j = s - 1; j >= 0; --j) {
+    for (int l = L - 1; l >= 1; --l) {
+      const int q = L - 1 - l;
+      const PassDesc p = bwd_pass(g, l);
+      const PassDesc nx = bwd_pass(g, l - 1);
+      const bool next_is_last = (l == 1);
+      const uint16_t* act = g.ACT[l - 1] + (size_t)j * g.R * g.layer[l].Kpad;
+      uint16_t* goutT = g.DELTAT[l - 1];
+      const int64_t kj = (int64_t)j * g.Rp + row0;
+      const int ldg = g.layer[l].Kpad;
+      lds_u16* out = lds.out(q);
+      const int ldp = lds.ldp;
+      eng.run_hidden(p, lds.in(q), lds.ld_in(q),
+              [&](int n, int m) {
+                return (row0 + m < g.R) ? *reinterpret_cast<const uint2*>(&act[(size_t)(row0 + m) * ldg + n])
+                                        : make_uint2(0u, 0u);
+              },
+              [&](const f32x4& acc, uint2 pf, int, int, int n, int m) {
+                float a[4], v[4];
+                unpack4<T>(pf, a);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = acc[r] * (1.f - a[r] * a[r]);
+                const uint2 dq = pack4<T>(v);
+                lds_store_u2(&out[m * ldp + n], dq);
+                if (row0 + m < g.R) {
+                  store4t(goutT, g.ldk, kj + m, n, dq);
+                  bad = bad || any_nonfinite4<T>(dq);
+                }
+              },
+              [&]() {
+                if (next_is_last) eng.template preload<NTL>(nx, 0);
+                else eng.template preload<4>(nx, 0);
+              });
+    }
+    const int q = L - 1;
+    eng.template run_fixed<NTL>(
+        lastb, lds.in(q), lds.ld_in(q), L == 1, [](int, int) { return make_uint2(0u, 0u); },
+        [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
+          const float v[4] = {acc[0], acc[1], acc[2], acc[3]};
+          const uint2 zq = pack4<T>(v);
+          if (row0 + m < g.R) bad = bad || any_nonfinite4<T>(zq);
+          float zf[4];
+          unpack4<T>(zq, zf);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) da[nt][mt][r] += zf[r];
+          if (j > 0) {
+            zs.put(j, m, n, zq);
+            make_kbar(j - 1, nt, mt, m, n, zf);
+          }
+        },
+        [&]() {
+          if (j > 0) preload_first_b();
+        });
+  }
+  if (g.detect) raise_if_any(bad, g.ctl);
+
+  // ---- a <- a + (h / S) sum_j zbar_j (+ running-cost cotangent), fp32; max |a|
+  unsigned bits = 0;
+  const float hs = h / S;
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int n = (eng.wave * NTL + nt) * 16 + lq * 4, m = mt * 16 + lm;
+      float v[4], gy[4] = {0.f, 0.f, 0.f, 0.f};
+      if (g.gys) load4f(g.gys, row0 + m, g.R, n, g.d, gy);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        v[r] = fmaf(hs, da[nt][mt][r], av[nt][mt][r]) + gy[r];
+        const unsigned bb = __builtin_bit_cast(unsigned, fabsf(v[r]));
+        if (row0 + m < g.R && n + r < g.d) bits = bb > bits ? bb : bits;
+      }
+      store4f(g.a_out, row0 + m, g.R, n, g.d, v);
+    }
+  block_amax(bits, &g.ctl->amax_bits);
+
+  // ---- the last workgroup to get here takes the decision of this step (accept / grow, or poison)
+  __shared__ int is_last;
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) is_last = (atomicAdd(&g.ctl->done, 1) == (int)gridDim.x - 1);
+  __syncthreads();
+  if (is_last && tid == 0) {
+    __threadfence();
+    Ctl* c = g.ctl;
+    const unsigned nonfinite = atomicOr(&c->nonfinite, 0u);
+    const unsigned amax_bits = atomicMax(&c->amax_bits, 0u);
+    if (g.detect && nonfinite) {
+      c->poison = 1;
+      c->failed_step = g.step;
+    } else {
+      g.scale_hist[g.step] = S;
+      c->S_step = S;
+      c->s_min = fminf(c->s_min, S);
+      c->s_max = fmaxf(c->s_max, S);
+      if (g.dynamic && c->attempt == 1) {
+        const float amax = __builtin_bit_cast(float, amax_bits);
+        const float test = g.raw_norm ? amax : S * amax;
+        if (test <= ldexpf(1.f, Low<T>::p_bits - 1) && S < ldexpf(1.f, 126)) c->S = 2.f * S;
+      }
+      c->attempt = 1;
+      c->amax_bits = 0;
+      c->nonfinite = 0;
+    }
+    c->done = 0;
+  }
+}
+
+}  // namespace rampde

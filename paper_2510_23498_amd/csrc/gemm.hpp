@@ -202,7 +202,7 @@ struct GemmTN {
   float* G; int ldg;            // fp32 gradient block, row pitch ldg
   int Na, Nb;                   // valid extents (unpadded)
   int NaPad, NbPad;             // padded extents (multiples of 64): columns that exist in A / B
-  float h;                      // step size; scale = h / ctl->S
+  float h;                      // step size; scale = h / ctl->S_step
   const Ctl* ctl;
   // conv: B rows are gathered with a tap shift, G index = na*ldg + nb*9 + tap
   int H, Wd, taps;              // taps = 1 (dense) or 9 (conv)
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(256) void gemm_tn(GemmTN g) {
     }
   }
 
-  const float scale = g.h / g.ctl->S;
+  const float scale = g.h / g.ctl->S_step;
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
     const int nb = b0 + wn * 64 + b * 32 + (lane & 31);
@@ -315,6 +315,173 @@ __global__ __launch_bounds__(256) void gemm_tn(GemmTN g) {
           size_t idx = CONV ? ((size_t)na * g.ldg + (size_t)nb * 9 + tap) : ((size_t)na * g.ldg + nb);
           unsafeAtomicAdd(&g.G[idx], scale * acc[a][b][q]);
         }
+      }
+    }
+  }
+}
+
+
+// ------------------------------------------------------------------------------------
+// Parameter gradients of one adjoint step for dense networks whose cotangents and layer
+// inputs were stored FEATURE-MAJOR ([feature][k], k = stage * Rp + row, Rp = rows padded to
+// 64, padding zero) by the row-tile-persistent adjoint kernel.  With k contiguous both operands
+// of  dW_l = delta_l^T act_{l-1}  are "K-contiguous", i.e. the same staging as gemm_nt applies
+// and nothing has to be transposed.  One launch covers every layer:
+//   blocks [0, gemm_blocks)  : 128 x 128 output tiles x K-chunks, fp32 atomics into dW_l
+//   blocks [gemm_blocks, ..) : row sums of delta_l^T for db_l and the time-column gradient
+// All contributions are scaled by h / S_step (paper Sec. 3, update of g).
+struct WgradLayer {
+  const uint16_t* DT;   // [NaPad][ldk] cotangent of the layer's output
+  const uint16_t* AT;   // [NbPad][ldk] the layer's input
+  float* G;             // dW_l block of the gradient vector, row pitch ldg
+  float* gb;            // db_l
+  float* gwt;           // time-column gradient (element stride ldg) or null
+  int ldg;
+  int Na, Nb;           // valid extents
+  int NaPad, NbPad;     // rows that exist in DT / AT
+  int tiles_a, tiles_b; // 128-tiles
+  int blk0;             // first gemm block of this layer
+  int rs0;              // first row-sum block of this layer (relative to gemm_blocks)
+};
+
+struct WgradArgs {
+  WgradLayer layer[8];
+  int L;
+  int gemm_blocks;
+  int ksplits;          // K-chunks per output tile
+  int kchunk;           // k extent of a chunk (multiple of 64)
+  int64_t ldk;          // s * Rp
+  int64_t Rp;
+  int s;
+  float taus[kMaxStages];
+  float h;
+  const Ctl* ctl;
+};
+
+template <class T>
+__global__ __launch_bounds__(256) void wgrad_feature_major(WgradArgs g) {
+  if (g.ctl->poison) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float scale = g.h / g.ctl->S_step;
+  int bid = blockIdx.x;
+
+  if (bid >= g.gemm_blocks) {
+    // ---- row sums: one wavefront per feature row of delta^T
+    bid -= g.gemm_blocks;
+    WgradLayer y = g.layer[0];
+#pragma unroll
+    for (int q = 1; q < 8; ++q)
+      if (q < g.L && bid >= g.layer[q].rs0) y = g.layer[q];
+    const int f = (bid - y.rs0) * 4 + wave;
+    if (f >= y.Na) return;
+    const uint16_t* row = y.DT + (size_t)f * g.ldk;
+    float sb = 0.f, st = 0.f;
+    for (int64_t k = (int64_t)lane * 8; k < g.ldk; k += 64 * 8) {
+      const u16x8 v = *reinterpret_cast<const u16x8*>(row + k);
+      float part = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part += Low<T>::to_f32(v[e]);
+      const int j = (int)(k / g.Rp);
+      float tau = 0.f;
+#pragma unroll
+      for (int q = 0; q < kMaxStages; ++q) tau = (q == j) ? g.taus[q] : tau;
+      sb += part;
+      st = fmaf(tau, part, st);
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      sb += __shfl_xor(sb, o);
+      st += __shfl_xor(st, o);
+    }
+    if (lane == 0) {
+      unsafeAtomicAdd(&y.gb[f], scale * sb);
+      if (y.gwt) unsafeAtomicAdd(&y.gwt[(size_t)f * y.ldg], scale * st);
+    }
+    return;
+  }
+
+  // ---- 128 x 128 tile of dW_l over one K-chunk
+  WgradLayer y = g.layer[0];
+#pragma unroll
+  for (int q = 1; q < 8; ++q)
+    if (q < g.L && bid >= g.layer[q].blk0) y = g.layer[q];
+  int r = bid - y.blk0;
+  const int split = r % g.ksplits;
+  r /= g.ksplits;
+  const int ta = r % y.tiles_a, tb = r / y.tiles_a;
+  const int a0 = ta * 128, b0 = tb * 128;
+  const int64_t k_begin = (int64_t)split * g.kchunk;
+  int64_t k_end = k_begin + g.kchunk;
+  if (k_end > g.ldk) k_end = g.ldk;
+  if (k_begin >= k_end) return;
+
+  __shared__ __attribute__((aligned(16))) uint16_t sA[128 * LDS_PITCH];
+  __shared__ __attribute__((aligned(16))) uint16_t sB[128 * LDS_PITCH];
+  const int wm = wave >> 1, wn = wave & 1;
+  u16x8 ra[4], rb[4];
+  auto load_tiles = [&](int64_t k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int id = tid + i * 256;
+      const int row = id >> 3, kc = (id & 7) * 8;
+      u16x8 va = {0, 0, 0, 0, 0, 0, 0, 0}, vb = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (a0 + row < y.NaPad) va = *reinterpret_cast<const u16x8*>(y.DT + (size_t)(a0 + row) * g.ldk + k0 + kc);
+      if (b0 + row < y.NbPad) vb = *reinterpret_cast<const u16x8*>(y.AT + (size_t)(b0 + row) * g.ldk + k0 + kc);
+      ra[i] = va;
+      rb[i] = vb;
+    }
+  };
+  auto store_tiles = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int id = tid + i * 256;
+      *reinterpret_cast<u16x8*>(&sA[(id >> 3) * LDS_PITCH + (id & 7) * 8]) = ra[i];
+      *reinterpret_cast<u16x8*>(&sB[(id >> 3) * LDS_PITCH + (id & 7) * 8]) = rb[i];
+    }
+  };
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.f;
+
+  const int frow = lane & 31, fk = (lane >> 5) * 8;
+  load_tiles(k_begin);
+  store_tiles();
+  __syncthreads();
+  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+    const bool more = k0 + BK < k_end;
+    if (more) load_tiles(k0 + BK);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      u16x8 fa[2], fb[2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+        fa[a] = *reinterpret_cast<const u16x8*>(&sA[(wm * 64 + a * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+        fb[b] = *reinterpret_cast<const u16x8*>(&sB[(wn * 64 + b * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = Low<T>::mfma32(fa[a], fb[b], acc[a][b]);
+    }
+    __syncthreads();
+    if (more) {
+      store_tiles();
+      __syncthreads();
+    }
+  }
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    const int nb = b0 + wn * 64 + b * 32 + (lane & 31);
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int na = a0 + wm * 64 + a * 32 + 8 * (q >> 2) + 4 * (lane >> 5) + (q & 3);
+        if (na < y.Na && nb < y.Nb) unsafeAtomicAdd(&y.G[(size_t)na * y.ldg + nb], scale * acc[a][b][q]);
       }
     }
   }

@@ -8,13 +8,16 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
 #include "common.hpp"
 #include "elementwise.hpp"
+#include "fused.hpp"
 #include "gemm.hpp"
 
 namespace rampde {
@@ -43,6 +46,7 @@ struct Layer {
   size_t theta_w, theta_b;  // offsets (elements) into theta
   // workspace offsets (bytes)
   size_t Wp, WTp, bias_f, wt_f;
+  size_t Wf, WTf;  // fragment-major copies (row-tile-persistent kernels)
   int ldw;  // K extent of the forward GEMM (dense: Kpad; conv: 9 * Cpad)
 };
 
@@ -64,9 +68,20 @@ struct Plan {
   std::vector<size_t> ACT, DELTA;  // per hidden layer l = 0..L-2: output of layer l / its cotangent
   size_t total = 0;
   int64_t stage_stride = 0;  // elements between stages in Z/K/KBAR/ZBAR: R * dpad
+  // row-tile-persistent path (dense networks whose widest layer fits the LDS tiles)
+  bool fused = false;
+  int MT = 1;          // row tile = 16 * MT
+  int ldp = 0;         // LDS row pitch (elements)
+  size_t lds_bytes = 0;
+  size_t steptab = 0, a_alt = 0;
+  int nparam = 0, wt_off = 0;
+  bool k_in_lds = false;
+  int64_t Rp = 0, ldk = 0;          // feature-major buffers: k = stage * Rp + row
+  size_t ZT = 0, KBART = 0;
+  std::vector<size_t> ACTT, DELTAT;
 };
 
-static bool build_layers(const rampde_velocity* vel, Plan& p) {
+static bool build_layers(const rampde_velocity* vel, Plan& p, int hidden_pad = kPad) {
   if (!vel) return false;
   size_t off = 0;
   if (vel->kind == RAMPDE_VEL_MLP) {
@@ -83,8 +98,9 @@ static bool build_layers(const rampde_velocity* vel, Plan& p) {
       y.in = vel->widths[l];
       y.has_time = (l == 0 && vel->time_input) ? 1 : 0;
       y.in_full = y.in + y.has_time;
-      y.Npad = pad64(y.out);
-      y.Kpad = pad64(y.in);
+      // hidden widths may be padded further (the row-tile-persistent kernels want multiples of 256)
+      y.Npad = (l + 1 < p.L) ? (y.out + hidden_pad - 1) / hidden_pad * hidden_pad : pad64(y.out);
+      y.Kpad = (l > 0) ? (y.in + hidden_pad - 1) / hidden_pad * hidden_pad : pad64(y.in);
       y.ldw = y.Kpad;
       y.theta_w = off;
       off += (size_t)y.out * y.in_full;
@@ -122,9 +138,18 @@ static bool build_layers(const rampde_velocity* vel, Plan& p) {
   return true;
 }
 
-static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde_tableau* tab, int is_backward) {
+static bool fused_candidate(const rampde_velocity* vel, const rampde_policy* pol) {
+  if (!vel || vel->kind != RAMPDE_VEL_MLP || (pol && (pol->flags & RAMPDE_PER_LAYER_KERNELS))) return false;
+  if (vel->n_layers < 1 || vel->n_layers > kMaxLayers || !vel->widths) return false;
+  const int dp = pad64(vel->widths[0]);
+  return dp == 64 || dp == 128 || dp == 256;
+}
+
+static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde_tableau* tab,
+                      const rampde_policy* pol, int is_backward) {
   Plan p;
-  if (!build_layers(vel, p)) return p;
+  const bool allow_fused = fused_candidate(vel, pol);
+  if (!build_layers(vel, p, allow_fused ? 256 : kPad)) return p;
   if (B < 1 || N < 1 || !tab || tab->s < 1 || tab->s > kMaxStages) return p;
   p.s = tab->s;
   p.R = p.conv ? B * (int64_t)p.H * p.Wd : B;
@@ -146,6 +171,42 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
     y.bias_f = take(sizeof(float) * y.Npad);
     y.wt_f = take(sizeof(float) * y.Npad * (p.conv ? 9 : 1));
   }
+  if (allow_fused) {
+    int maxw = 0, nparam = 0;
+    for (auto& y : p.layers) {
+      maxw = std::max(maxw, std::max(y.Npad, y.Kpad));
+      nparam += y.Npad;
+    }
+    p.wt_off = nparam;
+    p.nparam = nparam + p.layers[0].Npad;
+    p.ldp = maxw + 8;
+    const size_t lds_limit = 159 * 1024;  // 160 KB per compute unit minus the kernels' small static arrays
+    auto lds_need = [&](int mt, bool with_k) {
+      const size_t tm = 16 * (size_t)mt;
+      return (size_t)p.nparam * 4 + tm * (p.dpad + 8) * 2 + 2 * tm * p.ldp * 2 +
+             (with_k ? (size_t)p.s * tm * p.dpad * 2 : 0);
+    };
+    int mt = 4;
+    // largest row tile that still gives every compute unit a workgroup and fits the LDS tiles
+    while (mt > 1 && ((p.R + 16 * mt - 1) / (16 * mt) < 256 || lds_need(mt, false) > lds_limit)) mt >>= 1;
+    if (lds_need(mt, false) <= lds_limit) {
+      p.fused = true;
+      p.MT = mt;
+      p.k_in_lds = lds_need(mt, true) <= lds_limit;
+      p.lds_bytes = lds_need(mt, p.k_in_lds);
+      for (auto& y : p.layers) {
+        y.Wf = take((size_t)y.Npad * y.Kpad * 2);
+        y.WTf = take((size_t)y.Npad * y.Kpad * 2);
+      }
+      p.steptab = take(sizeof(float) * (size_t)N * (1 + p.s));
+      if (is_backward) p.a_alt = take(sizeof(float) * (size_t)p.n);
+    } else {
+      // the tiles do not fit in LDS: fall back to the per-layer kernels with their own padding
+      rampde_policy pl = pol ? *pol : rampde_policy{};
+      pl.flags |= RAMPDE_PER_LAYER_KERNELS;
+      return make_plan(vel, B, N, tab, &pl, is_backward);
+    }
+  }
   const int sbuf = is_backward ? p.s : 1;  // forward keeps one stage of inputs/activations
   if (p.conv) {
     p.y_rows = take(sizeof(float) * (size_t)p.n);
@@ -154,13 +215,32 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
       p.gys_rows = take(sizeof(float) * (size_t)p.n);
     }
   }
-  p.Z = take((size_t)sbuf * p.R * p.dpad * 2);
-  p.K = take((size_t)p.s * p.R * p.dpad * 2);
-  for (int l = 0; l + 1 < p.L; ++l) p.ACT.push_back(take((size_t)sbuf * p.R * p.layers[l].Npad * 2));
-  if (is_backward) {
-    p.KBAR = take((size_t)p.s * p.R * p.dpad * 2);
-    p.ZBAR = take((size_t)p.s * p.R * p.dpad * 2);
-    for (int l = 0; l + 1 < p.L; ++l) p.DELTA.push_back(take((size_t)p.s * p.R * p.layers[l].Npad * 2));
+  if (p.fused) {
+    // row-tile-persistent kernels: slopes / stage cotangents only when they do not fit in LDS;
+    // the adjoint keeps row-major hidden activations (for tanh') and feature-major copies of
+    // everything the parameter-gradient contraction reads
+    p.K = take((size_t)p.s * p.R * p.dpad * 2);
+    if (is_backward) {
+      p.ZBAR = take((size_t)p.s * p.R * p.dpad * 2);
+      p.Rp = (p.R + 63) / 64 * 64;
+      p.ldk = (int64_t)p.s * p.Rp;
+      p.ZT = take((size_t)p.dpad * p.ldk * 2);
+      p.KBART = take((size_t)p.dpad * p.ldk * 2);
+      for (int l = 0; l + 1 < p.L; ++l) {
+        p.ACT.push_back(take((size_t)p.s * p.R * p.layers[l].Npad * 2));
+        p.ACTT.push_back(take((size_t)p.layers[l].Npad * p.ldk * 2));
+        p.DELTAT.push_back(take((size_t)p.layers[l].Npad * p.ldk * 2));
+      }
+    }
+  } else {
+    p.Z = take((size_t)sbuf * p.R * p.dpad * 2);
+    p.K = take((size_t)p.s * p.R * p.dpad * 2);
+    for (int l = 0; l + 1 < p.L; ++l) p.ACT.push_back(take((size_t)sbuf * p.R * p.layers[l].Npad * 2));
+    if (is_backward) {
+      p.KBAR = take((size_t)p.s * p.R * p.dpad * 2);
+      p.ZBAR = take((size_t)p.s * p.R * p.dpad * 2);
+      for (int l = 0; l + 1 < p.L; ++l) p.DELTA.push_back(take((size_t)p.s * p.R * p.layers[l].Npad * 2));
+    }
   }
   p.total = off;
   p.ok = true;
@@ -197,6 +277,20 @@ static int hip_fail(hipError_t e, const char* where) {
 
 static inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
+// workgroups aimed at per parameter-gradient launch (tunable for experiments)
+static int wgrad_target_blocks() {
+  static int v = [] {
+    const char* e = getenv("RAMPDE_WGRAD_BLOCKS");
+    const int x = e ? atoi(e) : 0;
+    return x > 0 ? x : 512;
+  }();
+  return v;
+}
+
+__global__ void fill_zero_u32(uint32_t* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
 // ---------------------------------------------------------------- optional per-kernel timing
 // When enabled, launches of the kernel classes below are bracketed by HIP events on the
 // caller's stream; rampde_timing_read sums the elapsed times.  Process-global, not thread safe:
@@ -229,6 +323,16 @@ struct TimeScope {
     g_timed.push_back(t);
   }
 };
+
+// Host floats -> device memory by way of kernel arguments (copied at launch: no host buffer has
+// to outlive the call, and the write is an ordinary kernel node for a caller capturing a graph).
+struct FloatChunk {
+  float v[96];
+};
+__global__ void write_floats(FloatChunk c, float* dst, int count) {
+  const int i = threadIdx.x;
+  if (i < count) dst[i] = c.v[i];
+}
 
 // ---------------------------------------------------------------- typed launch sequences
 template <class T>
@@ -322,8 +426,135 @@ struct Runner {
     }
   }
 
+  // ------------------------------------------------ row-tile-persistent path (dense networks)
+  bool use_fused = false;
+
+  void cast_fragments(const float* theta) {
+    for (const Layer& y : p.layers) {
+      const int nfr = (y.Kpad / 32) * (y.Npad / 16) + (y.Npad / 32) * (y.Kpad / 16);
+      cast_dense_fragments<T><<<blocks_for(nfr, 4), 256, 0, st>>>(theta + y.theta_w, y.out, y.in, y.in_full,
+                                                                 (u16x8*)(ws + y.Wf), (u16x8*)(ws + y.WTf), y.Npad,
+                                                                 y.Kpad);
+    }
+  }
+
+  // per step: h_i, then the stage times rounded to low precision
+  void write_steptab(const double* tgrid, int N, const rampde_tableau* tab, rampde_dtype low) {
+    std::vector<float> tabv((size_t)N * (1 + p.s));
+    for (int i = 0; i < N; ++i) {
+      const float h = (float)(tgrid[i + 1] - tgrid[i]);
+      tabv[(size_t)i * (1 + p.s)] = h;
+      for (int j = 0; j < p.s; ++j)
+        tabv[(size_t)i * (1 + p.s) + 1 + j] = round_low_host((float)(tgrid[i] + tab->c[j] * (double)h), low);
+    }
+    for (size_t off = 0; off < tabv.size(); off += 96) {
+      FloatChunk c;
+      const int cnt = (int)std::min<size_t>(96, tabv.size() - off);
+      memcpy(c.v, tabv.data() + off, sizeof(float) * cnt);
+      write_floats<<<1, 128, 0, st>>>(c, f32(p.steptab) + off, cnt);
+    }
+  }
+
+  FusedArgs fused_args(const rampde_tableau* tab, int N) const {
+    FusedArgs a{};
+    int boff = 0;
+    for (int l = 0; l < p.L; ++l) {
+      const Layer& y = p.layers[l];
+      a.layer[l].Wf = (const u16x8*)(ws + y.Wf);
+      a.layer[l].WTf = (const u16x8*)(ws + y.WTf);
+      a.layer[l].bias = f32(y.bias_f);
+      a.layer[l].wt = y.has_time ? f32(y.wt_f) : nullptr;
+      a.layer[l].Kpad = y.Kpad;
+      a.layer[l].Npad = y.Npad;
+      a.layer[l].bias_off = boff;
+      boff += y.Npad;
+    }
+    a.wt_off = p.wt_off;
+    a.nparam = p.nparam;
+    a.k_in_lds = p.k_in_lds ? 1 : 0;
+    a.L = p.L;
+    a.s = p.s;
+    a.N = N;
+    a.d = p.d;
+    a.dpad = p.dpad;
+    a.ldp = p.ldp;
+    a.R = p.R;
+    a.stage_stride = p.stage_stride;
+    for (int i = 0; i < p.s; ++i) {
+      a.b[i] = (float)tab->b[i];
+      for (int j = 0; j < p.s; ++j) a.A[i * p.s + j] = (float)tab->A[i * p.s + j];
+    }
+    a.steptab = f32(p.steptab);
+    a.K = u16(p.K);
+    return a;
+  }
+
+  template <class Kern>
+  int launch_fused(Kern kern, const FusedArgs& a) {
+    if (p.lds_bytes > 48 * 1024)
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)p.lds_bytes));
+    const unsigned grid = blocks_for(p.R, 16 * p.MT);
+    kern<<<grid, 256, p.lds_bytes, st>>>(a);
+    return RAMPDE_OK;
+  }
+
+  template <bool FWD, int MT, int NTL>
+  int launch_one(const FusedArgs& a) {
+    if (FWD) return launch_fused(mlp_forward_fused<T, MT, NTL>, a);
+    return launch_fused(mlp_adjoint_step<T, MT, NTL>, a);
+  }
+  template <bool FWD, int MT>
+  int dispatch_ntl(const FusedArgs& a) {
+    switch (p.dpad / 64) {
+      case 1: return launch_one<FWD, MT, 1>(a);
+      case 2: return launch_one<FWD, MT, 2>(a);
+      default: return launch_one<FWD, MT, 4>(a);
+    }
+  }
+  template <bool FWD>
+  int dispatch_fused(const FusedArgs& a) {
+    switch (p.MT) {
+      case 1: return dispatch_ntl<FWD, 1>(a);
+      case 2: return dispatch_ntl<FWD, 2>(a);
+      default: return dispatch_ntl<FWD, 4>(a);
+    }
+  }
+
+  double step_flops() const {  // one velocity evaluation of the whole batch, padded shapes
+    double f = 0.0;
+    for (const Layer& y : p.layers) f += 2.0 * (double)p.R * y.Npad * y.Kpad;
+    return f;
+  }
+
+  int forward_fused(const float* theta, const float* y0, const double* tgrid, int N, const rampde_tableau* tab,
+                    const rampde_policy* pol, uint16_t* ckpt, float* yN) {
+    cast_weights(theta);
+    cast_fragments(theta);
+    write_steptab(tgrid, N, tab, pol->low);
+    FusedArgs a = fused_args(tab, N);
+    a.y0 = y0;
+    a.y = yN;
+    a.ckpt = ckpt;
+    a.round_incr = (pol->flags & RAMPDE_ROUND_INCREMENT) ? 1 : 0;
+    int rc;
+    {
+      TimeScope ts(RAMPDE_K_FUSED_FORWARD, step_flops() * p.s * N, st);
+      rc = dispatch_fused<true>(a);
+    }
+    if (rc) return rc;
+    HIP_TRY(hipGetLastError());
+    return RAMPDE_OK;
+  }
+
+  int adjoint_step_fused(const FusedArgs& a) {
+    TimeScope ts(RAMPDE_K_FUSED_ADJOINT_STEP, step_flops() * p.s * (a.skip_recompute ? 1.0 : 2.0), st);
+    return dispatch_fused<false>(a);
+  }
+
   int forward(const float* theta, const float* y0, const double* tgrid, int N, const rampde_tableau* tab,
               const rampde_policy* pol, uint16_t* ckpt, float* yN) {
+    if (use_fused) return forward_fused(theta, y0, tgrid, N, tab, pol, ckpt, yN);
     cast_weights(theta);
     float* y = yN;
     if (p.conv) {
@@ -402,8 +633,22 @@ struct Runner {
         delta = out;
       }
     }
-    if (detect) chain_decide<<<1, 1, 0, st>>>(ctl, i);
-    // parameter gradient: contraction over all stages and rows at once
+    chain_decide<<<1, 1, 0, st>>>(ctl, i, detect);
+    param_grads(h, taus, grad_theta);
+    {
+      // bytes per state element: read a (4) + s stage cotangents (2 each) + write a (4)
+      TimeScope ts(RAMPDE_K_ADJOINT_UPDATE, (double)p.n * (8.0 + 2.0 * s), st);
+      adjoint_update<T><<<blocks_for(p.n, 256), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, s, h, gys_i, p.dpad,
+                                                             p.R, ctl);
+    }
+    scale_grow<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), i, Low<T>::p_bits, dynamic,
+                                (pol->flags & RAMPDE_GROW_RAW_NORM) ? 1 : 0);
+  }
+
+  // parameter gradient of one accepted step: contraction over all stages and rows at once,
+  // scaled by h / S_step and accumulated in fp32 (paper Sec. 3, update of g)
+  void param_grads(float h, const Coefs& taus, float* grad_theta) {
+    const int s = p.s;
     const int64_t rows = (int64_t)s * p.R;
     for (int l = 0; l < p.L; ++l) {
       const Layer& y = p.layers[l];
@@ -453,14 +698,53 @@ struct Runner {
         column_sums<T, false><<<cgrid, 256, 0, st>>>(g.A, y.Npad, p.R, s, y.out, taus, h, gb, gwt, y.in_full, p.H,
                                                      p.Wd, rpb, ctl);
     }
-    {
-      // bytes per state element: read a (4) + s stage cotangents (2 each) + write a (4)
-      TimeScope ts(RAMPDE_K_ADJOINT_UPDATE, (double)p.n * (8.0 + 2.0 * s), st);
-      adjoint_update<T><<<blocks_for(p.n, 256), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, s, h, gys_i, p.dpad,
-                                                             p.R, ctl);
+  }
+
+  // parameter gradients from the feature-major buffers of the row-tile-persistent adjoint kernel
+  void param_grads_fused(float h, const Coefs& taus, float* grad_theta) {
+    WgradArgs w{};
+    w.L = p.L;
+    int tiles = 0;
+    for (int l = 0; l < p.L; ++l) tiles += ((p.layers[l].Npad + 127) / 128) * ((p.layers[l].Kpad + 127) / 128);
+    // K-chunks: enough workgroups to fill the chip, but at least 256 k per chunk
+    int64_t ksplits = (wgrad_target_blocks() + tiles - 1) / tiles;
+    ksplits = std::max<int64_t>(1, std::min<int64_t>(ksplits, p.ldk / 256 > 0 ? p.ldk / 256 : 1));
+    int64_t kchunk = ((p.ldk + ksplits - 1) / ksplits + 63) / 64 * 64;
+    ksplits = (p.ldk + kchunk - 1) / kchunk;
+    w.ksplits = (int)ksplits;
+    w.kchunk = (int)kchunk;
+    w.ldk = p.ldk;
+    w.Rp = p.Rp;
+    w.s = p.s;
+    for (int j = 0; j < kMaxStages; ++j) w.taus[j] = j < p.s ? taus.v[j] : 0.f;
+    w.h = h;
+    w.ctl = ctl;
+    int blk = 0, rs = 0;
+    double flops = 0.0;
+    for (int l = 0; l < p.L; ++l) {
+      const Layer& y = p.layers[l];
+      WgradLayer& d = w.layer[l];
+      d.DT = (l == p.L - 1) ? u16(p.KBART) : u16(p.DELTAT[l]);
+      d.AT = (l == 0) ? u16(p.ZT) : u16(p.ACTT[l - 1]);
+      d.G = grad_theta + y.theta_w;
+      d.gb = grad_theta + y.theta_b;
+      d.gwt = y.has_time ? grad_theta + y.theta_w + y.in : nullptr;
+      d.ldg = y.in_full;
+      d.Na = y.out;
+      d.Nb = y.in;
+      d.NaPad = y.Npad;
+      d.NbPad = y.Kpad;
+      d.tiles_a = (y.Npad + 127) / 128;
+      d.tiles_b = (y.Kpad + 127) / 128;
+      d.blk0 = blk;
+      d.rs0 = rs;
+      blk += d.tiles_a * d.tiles_b * w.ksplits;
+      rs += (y.out + 3) / 4;
+      flops += 2.0 * (double)p.ldk * y.Npad * y.Kpad;
     }
-    scale_grow<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), i, Low<T>::p_bits, dynamic,
-                                (pol->flags & RAMPDE_GROW_RAW_NORM) ? 1 : 0);
+    w.gemm_blocks = blk;
+    TimeScope ts(RAMPDE_K_WGRAD_GEMM, flops, st);
+    wgrad_feature_major<T><<<blk + rs, 256, 0, st>>>(w);
   }
 
   int backward(const float* theta, const double* tgrid, int N, const rampde_tableau* tab, const rampde_policy* pol,
@@ -472,7 +756,38 @@ struct Runner {
     const int HW = p.H * p.Wd;
     ctl_reset<<<1, 1, 0, st>>>(ctl);
     cast_weights(theta);
-    float* a = grad_y0;
+    // fused path: the adjoint alternates between two buffers so that a step whose chain
+    // overflowed leaves its input adjoint intact; step 0 writes grad_y0
+    auto a_buf = [&](int i) -> float* { return (i % 2 == 0) ? grad_y0 : f32(p.a_alt); };
+    FusedArgs fa{};
+    if (use_fused) {
+      cast_fragments(theta);
+      write_steptab(tgrid, N, tab, pol->low);
+      fa = fused_args(tab, N);
+      fa.ckpt = const_cast<uint16_t*>(ckpt);
+      for (int l = 0; l + 1 < p.L; ++l) {
+        fa.ACT[l] = u16(p.ACT[l]);
+        fa.ACTT[l] = u16(p.ACTT[l]);
+        fa.DELTAT[l] = u16(p.DELTAT[l]);
+      }
+      fa.ZT = u16(p.ZT);
+      fa.KBART = u16(p.KBART);
+      fa.ldk = p.ldk;
+      fa.Rp = p.Rp;
+      fa.ZBAR = u16(p.ZBAR);
+      if (p.Rp != p.R) {
+        // rows R..Rp of every stage are padding of the contraction: they must read as zero
+        const size_t first = p.ZT, last = p.DELTAT.empty() ? p.KBART + align256((size_t)p.dpad * p.ldk * 2)
+                                                           : p.DELTAT.back() + align256((size_t)p.layers[p.L - 2].Npad * p.ldk * 2);
+        fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + first), (last - first) / 4);
+      }
+      fa.ctl = ctl;
+      fa.scale_hist = f32(p.scale_hist);
+      fa.detect = detect;
+      fa.dynamic = dynamic;
+      fa.raw_norm = (pol->flags & RAMPDE_GROW_RAW_NORM) ? 1 : 0;
+    }
+    float* a = use_fused ? a_buf(N) : grad_y0;
     float* gys_rows = nullptr;
     auto gys_at = [&](int i) -> const float* {
       if (!grad_ys) return nullptr;
@@ -499,9 +814,24 @@ struct Runner {
     const bool must_sync = detect || stats || scale_hist;
     for (;;) {
       for (int i = from; i >= 0; --i) {
-        backward_step(i, tgrid, tab, pol, ckpt, a, gys_at(i), grad_theta, dynamic, detect,
-                      i == from ? recompute_first : true);
+        if (use_fused) {
+          fa.step = i;
+          fa.a_in = a_buf(i + 1);
+          fa.a_out = a_buf(i);
+          fa.gys = gys_at(i);
+          fa.skip_recompute = (i == from && !recompute_first) ? 1 : 0;
+          int rc = adjoint_step_fused(fa);
+          if (rc) return rc;
+          const float h = (float)(tgrid[i + 1] - tgrid[i]);
+          Coefs taus{};
+          for (int j = 0; j < p.s; ++j) taus.v[j] = round_low_host((float)(tgrid[i] + tab->c[j] * (double)h), pol->low);
+          param_grads_fused(h, taus, grad_theta);
+        } else {
+          backward_step(i, tgrid, tab, pol, ckpt, a, gys_at(i), grad_theta, dynamic, detect,
+                        i == from ? recompute_first : true);
+        }
       }
+      if (use_fused) a = grad_y0;
       HIP_TRY(hipGetLastError());
       if (!must_sync) break;
       HIP_TRY(hipMemcpyAsync(&hctl, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
@@ -569,8 +899,7 @@ int64_t rampde_num_params(const rampde_velocity* vel) {
 
 size_t rampde_workspace_bytes(const rampde_velocity* vel, int64_t B, int N, const rampde_tableau* tab,
                               const rampde_policy* pol, int is_backward) {
-  (void)pol;
-  Plan p = make_plan(vel, B, N, tab, is_backward);
+  Plan p = make_plan(vel, B, N, tab, pol, is_backward);
   return p.ok ? p.total : 0;
 }
 
@@ -580,15 +909,18 @@ int rampde_odeint_fwd(const rampde_velocity* vel, const float* theta, const floa
   int rc = check_common(vel, tgrid, N, tab, pol);
   if (rc) return rc;
   if (!theta || !y0 || !ckpt || !yN || !workspace || B < 1) return RAMPDE_EINVAL;
-  Plan p = make_plan(vel, B, N, tab, 0);
+  Plan p = make_plan(vel, B, N, tab, pol, 0);
   if (!p.ok) return RAMPDE_EINVAL;
   if (workspace_bytes < p.total || ((uintptr_t)workspace & 255)) return RAMPDE_EWORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
+  const bool fused = p.fused;
   if (pol->low == RAMPDE_F16) {
     Runner<F16> r(p, workspace, st);
+    r.use_fused = fused;
     return r.forward(theta, y0, tgrid, N, tab, pol, (uint16_t*)ckpt, yN);
   }
   Runner<BF16> r(p, workspace, st);
+  r.use_fused = fused;
   return r.forward(theta, y0, tgrid, N, tab, pol, (uint16_t*)ckpt, yN);
 }
 
@@ -599,17 +931,20 @@ int rampde_odeint_bwd(const rampde_velocity* vel, const float* theta, int64_t B,
   int rc = check_common(vel, tgrid, N, tab, pol);
   if (rc) return rc;
   if (!theta || !ckpt || !grad_yN || !grad_y0 || !grad_theta || !workspace || B < 1) return RAMPDE_EINVAL;
-  Plan p = make_plan(vel, B, N, tab, 1);
+  Plan p = make_plan(vel, B, N, tab, pol, 1);
   if (!p.ok) return RAMPDE_EINVAL;
   if (workspace_bytes < p.total || ((uintptr_t)workspace & 255)) return RAMPDE_EWORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
   const rampde_scaling sc = resolve_scaling(pol);
+  const bool fused = p.fused;
   if (pol->low == RAMPDE_F16) {
     Runner<F16> r(p, workspace, st);
+    r.use_fused = fused;
     return r.backward(theta, tgrid, N, tab, pol, sc, (const uint16_t*)ckpt, grad_yN, grad_ys, grad_y0, grad_theta,
                       scale_hist, stats);
   }
   Runner<BF16> r(p, workspace, st);
+  r.use_fused = fused;
   return r.backward(theta, tgrid, N, tab, pol, sc, (const uint16_t*)ckpt, grad_yN, grad_ys, grad_y0, grad_theta,
                     scale_hist, stats);
 }

@@ -16,10 +16,15 @@ import parity as par
 pytestmark = pytest.mark.gpu
 
 
-def _both(cfg, bias_std=0.0, scaling=None, tol_emul=par.TOL_EMUL):
+PER_LAYER = 4  # policy flag: one kernel per layer instead of the row-tile-persistent kernels
+PATHS = pytest.mark.parametrize("flags", [0, PER_LAYER], ids=["tile", "layer"])
+
+
+def _both(cfg, bias_std=0.0, scaling=None, tol_emul=par.TOL_EMUL, flags=0):
     theta, y0, target = par.make_inputs(cfg, bias_std=bias_std)
-    print(f"[case] {cfg.name} kind={cfg.kind} B={cfg.B} N={cfg.N} low={cfg.low} tab={cfg.tableau}", flush=True)
-    gpu = par.run_gpu(cfg, theta, y0, target, scaling=scaling)
+    print(f"[case] {cfg.name} kind={cfg.kind} B={cfg.B} N={cfg.N} low={cfg.low} tab={cfg.tableau} flags={flags}",
+          flush=True)
+    gpu = par.run_gpu(cfg, theta, y0, target, scaling=scaling, flags=flags)
     emu = par.run_oracle(cfg, theta, y0, target, "emul", scaling=scaling)
     f64 = par.run_oracle(cfg, theta, y0, target, "f64")
     e1 = par.compare(cfg, gpu, emu, tol_emul, "emulation oracle")
@@ -32,32 +37,44 @@ def _both(cfg, bias_std=0.0, scaling=None, tol_emul=par.TOL_EMUL):
     return gpu, emu, f64
 
 
-def test_cfg1_tiny_mlp_full_size():
-    _both(wl.CONFIGS["cfg1"])
+@PATHS
+def test_cfg1_tiny_mlp_full_size(flags):
+    _both(wl.CONFIGS["cfg1"], flags=flags)
 
 
-def test_cfg1_nonzero_bias_and_ragged_batch():
-    _both(wl.CONFIGS["cfg1"].with_(name="cfg1r", B=77, N=5), bias_std=0.3)
+@PATHS
+def test_cfg1_nonzero_bias_and_ragged_batch(flags):
+    _both(wl.CONFIGS["cfg1"].with_(name="cfg1r", B=77, N=5), bias_std=0.3, flags=flags)
 
 
+@PATHS
 @pytest.mark.parametrize("tab", ["euler", "heun", "rk4", "kutta3"])
-def test_small_mlp_all_tableaux(tab):
+def test_small_mlp_all_tableaux(tab, flags):
     cfg = wl.CONFIGS["cfg1"].with_(name="tabs", B=130, N=6, widths=(5, 40, 24, 5), tableau=tab)
-    _both(cfg, bias_std=0.2)
+    _both(cfg, bias_std=0.2, flags=flags)
 
 
-def test_cfg2_shape_reduced_batch():
-    # widths of the bf16 workload; batch spans two 128-row tiles and a ragged tail
-    _both(wl.CONFIGS["cfg2"].with_(name="cfg2s", B=300, N=6), bias_std=0.1)
+@PATHS
+def test_mlp_odd_widths_many_layers(flags):
+    # widths that pad to 64/128/192/320 columns: every column-group size of the tile kernels
+    cfg = wl.CONFIGS["cfg1"].with_(name="odd", B=50, N=3, widths=(70, 130, 300, 190, 70), tableau="heun")
+    _both(cfg, bias_std=0.1, flags=flags)
 
 
-def test_cfg3_shape_reduced_needs_dynamic_scaling():
+@PATHS
+def test_cfg2_shape_reduced_batch(flags):
+    # widths of the bf16 workload; batch spans several row tiles and a ragged tail
+    _both(wl.CONFIGS["cfg2"].with_(name="cfg2s", B=300, N=6), bias_std=0.1, flags=flags)
+
+
+@PATHS
+def test_cfg3_shape_reduced_needs_dynamic_scaling(flags):
     cfg = wl.CONFIGS["cfg3"].with_(name="cfg3s", B=200, N=6)
-    gpu, emu, f64 = _both(cfg)
+    gpu, emu, f64 = _both(cfg, flags=flags)
     assert gpu["scale_hist"][cfg.N] > 2.0 ** 20  # the 1e-6 loss gradient needs a large scale
     # negative control: without scaling the fp16 cotangents underflow and the gradient is lost
     theta, y0, target = par.make_inputs(cfg)
-    raw = par.run_gpu(cfg, theta, y0, target, scaling="none")
+    raw = par.run_gpu(cfg, theta, y0, target, scaling="none", flags=flags)
     e_raw = par.rel_err(raw["grad_theta"], f64["grad_theta"])
     e_dyn = par.rel_err(gpu["grad_theta"], f64["grad_theta"])
     assert e_raw > par.TOL_F64["f16"] and e_raw > 10 * e_dyn, (e_raw, e_dyn)
@@ -72,15 +89,17 @@ def test_conv_small_odd_geometry():
     _both(cfg, bias_std=0.1)
 
 
+@PATHS
 @pytest.mark.parametrize("tab", ["rk4", "heun", "euler"])
-def test_cfg5_shape_reduced(tab):
-    _both(wl.CONFIGS["cfg5"].with_(name="cfg5s", B=96, N=5, tableau=tab))
+def test_cfg5_shape_reduced(tab, flags):
+    _both(wl.CONFIGS["cfg5"].with_(name="cfg5s", B=96, N=5, tableau=tab), flags=flags)
 
 
-def test_running_cost_cotangents():
+@PATHS
+def test_running_cost_cotangents(flags):
     cfg = wl.CONFIGS["cfg1"].with_(name="run", B=64, N=4, widths=(6, 32, 6))
     theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
     gys = wl.normals(3, "run.gys", (cfg.N + 1, cfg.B, 6), 0.1)
-    gpu = par.run_gpu(cfg, theta, y0, target, grad_ys=gys)
+    gpu = par.run_gpu(cfg, theta, y0, target, grad_ys=gys, flags=flags)
     emu = par.run_oracle(cfg, theta, y0, target, "emul", grad_ys=gys.astype(np.float64))
     par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
