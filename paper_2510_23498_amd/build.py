@@ -1,4 +1,4 @@
-"""Build step of the HIP library: one hipcc call, gfx950 only, output in-tree.
+"""Build step of the HIP library: hipcc, gfx950 only, output in-tree.
 
     python -m paper_2510_23498_amd.build
 
@@ -16,11 +16,6 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "librampde.so")
 
-HIPCC_FLAGS = [
-    "-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC",
-    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-]
-
 
 def hipcc_path() -> str:
     cand = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
@@ -29,15 +24,44 @@ def hipcc_path() -> str:
     return cand
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile csrc/rampde.hip into librampde.so next to this file; returns its path."""
-    cmd = [hipcc_path()] + HIPCC_FLAGS + [os.path.join(CSRC, "rampde.hip"), "-o", LIB_PATH + ".tmp"]
+FUSED_HIDDEN_WIDTHS = (0, 256, 512, 1024)  # one translation unit of fused_inst.hip per width
+
+COMPILE_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wno-pass-failed",
+                 "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def _compile(args):
+    src, obj, defs = args
+    cmd = [hipcc_path()] + COMPILE_FLAGS + defs + ["-c", src, "-o", obj]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    return res.returncode, res.stdout + res.stderr, obj
+
+
+def build_library(verbose: bool = False, jobs: int = 0) -> str:
+    """Compile the translation units under csrc/ in parallel and link librampde.so next to this
+    file; returns its path."""
+    from concurrent.futures import ThreadPoolExecutor
+    objdir = os.path.join(PKG_DIR, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    units = [(os.path.join(CSRC, "rampde.hip"), os.path.join(objdir, "rampde.o"), [])]
+    for hp in FUSED_HIDDEN_WIDTHS:
+        units.append((os.path.join(CSRC, "fused_inst.hip"), os.path.join(objdir, f"fused_hp{hp}.o"),
+                      [f"-DRAMPDE_INST_HP={hp}"]))
+    jobs = jobs or min(len(units), os.cpu_count() or 1, 16)
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        results = list(pool.map(_compile, units))
+    for rc, out, obj in results:
+        if rc != 0:
+            sys.stderr.write(out)
+            raise RuntimeError(f"hipcc failed building {obj}")
+        if verbose:
+            sys.stderr.write(out)
+    cmd = [hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC"] + [r[2] for r in results] + \
+          ["-o", LIB_PATH + ".tmp"]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         sys.stderr.write(res.stdout + res.stderr)
-        raise RuntimeError("hipcc failed building librampde.so")
-    if verbose:
-        sys.stderr.write(res.stderr)
+        raise RuntimeError("hipcc failed linking librampde.so")
     os.replace(LIB_PATH + ".tmp", LIB_PATH)
     return LIB_PATH
 

@@ -239,20 +239,33 @@ struct PassDesc {
 // branch-free (out-of-range k-blocks are clamped to the last one and masked out of the MFMA
 // by a zero activation operand) so that the number of loads in flight is known statically
 // and every wait is for exactly the fragment that is consumed next.
-template <int NTG>
-__device__ inline void ring_preload(u16x8 (&ring)[PD][4], const PassDesc& p, int nt0, int lane) {
+// KBC / NTC > 0: the pass's k-blocks and column tiles are compile-time constants (kernels
+// specialised for a network shape): the whole pipeline unrolls into straight-line code with
+// immediate offsets.  KBC = 0: both are taken from the descriptor at run time.
+template <int NTG, int RW, int KBC, int NTC>
+__device__ inline void ring_preload(u16x8 (&ring)[PD][RW], const PassDesc& p, int nt0, int lane) {
   const glb_u16x8* base = p.Wf + (size_t)nt0 * 64 + lane;
-  const size_t kstride = (size_t)p.NT16 * 64;
+  if constexpr (KBC > 0) {
 #pragma unroll
-  for (int u = 0; u < PD; ++u) {
-    const int kb = min(u, p.KB - 1);
+    for (int u = 0; u < PD; ++u) {
+      if (u < KBC) {
 #pragma unroll
-    for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = base[kb * kstride + nt * 64];
+        for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = base[(size_t)u * NTC * 64 + nt * 64];
+      }
+    }
+  } else {
+    const size_t kstride = (size_t)p.NT16 * 64;
+#pragma unroll
+    for (int u = 0; u < PD; ++u) {
+      const int kb = min(u, p.KB - 1);
+#pragma unroll
+      for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = base[kb * kstride + nt * 64];
+    }
   }
 }
 
-template <class T, int MT, int NTG>
-__device__ inline void tile_mma(f32x4 (&acc)[4][MT], u16x8 (&ring)[PD][4], const PassDesc& p, int nt0,
+template <class T, int MT, int NTG, int RW, int KBC, int NTC>
+__device__ inline void tile_mma(f32x4 (&acc)[RW][MT], u16x8 (&ring)[PD][RW], const PassDesc& p, int nt0,
                                 const lds_u16* in, int ldp, int lane) {
   static_assert(PD % 2 == 0, "activation fragments are double-buffered by k-block parity");
   const int lm = lane & 15, lq = lane >> 4;
@@ -261,50 +274,73 @@ __device__ inline void tile_mma(f32x4 (&acc)[4][MT], u16x8 (&ring)[PD][4], const
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
   const glb_u16x8* wbase = p.Wf + (size_t)nt0 * 64 + lane;
-  const int kstride = p.NT16 * 64;
   const lds_u16* abase = in + lm * ldp + lq * 8;
-  const int KB = p.KB;
-  const int kb_tail = ((KB + PD - 1) / PD - 1) * PD;  // first k-block of the last group of PD
-
   u16x8 a[2][MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) a[0][mt] = *(const lds_u16x8*)(abase + mt * 16 * ldp);
 
-  // steady state: fetch the next activation fragment, consume ring[u], refill it PD k-blocks ahead
-  for (int kb0 = 0; kb0 < kb_tail; kb0 += PD) {
-    const glb_u16x8* wnext = wbase + (size_t)(kb0 + PD) * kstride;
+  if constexpr (KBC > 0) {
 #pragma unroll
-    for (int u = 0; u < PD; ++u) {
-      const int kb = kb0 + u;
+    for (int kb = 0; kb < KBC; ++kb) {
+      constexpr int dummy = 0;
+      (void)dummy;
+      const int u = kb % PD;
+      if (kb + 1 < KBC) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        a[(u + 1) & 1][mt] = *(const lds_u16x8*)(abase + mt * 16 * ldp + (kb + 1) * 32);
+        for (int mt = 0; mt < MT; ++mt)
+          a[(kb + 1) & 1][mt] = *(const lds_u16x8*)(abase + mt * 16 * ldp + (kb + 1) * 32);
+      }
 #pragma unroll
       for (int nt = 0; nt < NTG; ++nt)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = Low<T>::mfma16(ring[u][nt], a[u & 1][mt], acc[nt][mt]);
+        for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = Low<T>::mfma16(ring[u][nt], a[kb & 1][mt], acc[nt][mt]);
 #ifndef RAMPDE_PROBE_NOLOAD
-      const int ku = min(u, KB - 1 - kb0 - PD);  // clamp to the last k-block (only in the last main group)
+      if (kb + PD < KBC) {
 #pragma unroll
-      for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = wnext[ku * kstride + nt * 64];
+        for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = wbase[(size_t)(kb + PD) * NTC * 64 + nt * 64];
+      }
 #endif
     }
-  }
-  // drain: the last group of PD k-blocks, no refills; k-blocks past the end contribute zero
+  } else {
+    const int kstride = p.NT16 * 64;
+    const int KB = p.KB;
+    const int kb_tail = ((KB + PD - 1) / PD - 1) * PD;  // first k-block of the last group of PD
+    // steady state: fetch the next activation fragment, consume ring[u], refill it PD k-blocks ahead
+    for (int kb0 = 0; kb0 < kb_tail; kb0 += PD) {
+      const glb_u16x8* wnext = wbase + (size_t)(kb0 + PD) * kstride;
 #pragma unroll
-  for (int u = 0; u < PD; ++u) {
-    const int kb = kb_tail + u;
-    const int ka = min(kb + 1, KB - 1);
+      for (int u = 0; u < PD; ++u) {
+        const int kb = kb0 + u;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-      a[(u + 1) & 1][mt] = *(const lds_u16x8*)(abase + mt * 16 * ldp + ka * 32);
-    const bool valid = kb < KB;
+        for (int mt = 0; mt < MT; ++mt)
+          a[(u + 1) & 1][mt] = *(const lds_u16x8*)(abase + mt * 16 * ldp + (kb + 1) * 32);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const u16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-      const u16x8 a_use = valid ? a[u & 1][mt] : zero;
+        for (int nt = 0; nt < NTG; ++nt)
 #pragma unroll
-      for (int nt = 0; nt < NTG; ++nt) acc[nt][mt] = Low<T>::mfma16(ring[u][nt], a_use, acc[nt][mt]);
+          for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = Low<T>::mfma16(ring[u][nt], a[u & 1][mt], acc[nt][mt]);
+#ifndef RAMPDE_PROBE_NOLOAD
+        const int ku = min(u, KB - 1 - kb0 - PD);  // clamp to the last k-block (only in the last main group)
+#pragma unroll
+        for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = wnext[ku * kstride + nt * 64];
+#endif
+      }
+    }
+    // drain: the last group of PD k-blocks, no refills; k-blocks past the end contribute zero
+#pragma unroll
+    for (int u = 0; u < PD; ++u) {
+      const int kb = kb_tail + u;
+      const int ka = min(kb + 1, KB - 1);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        a[(u + 1) & 1][mt] = *(const lds_u16x8*)(abase + mt * 16 * ldp + ka * 32);
+      const bool valid = kb < KB;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const u16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+        const u16x8 a_use = valid ? a[u & 1][mt] : zero;
+#pragma unroll
+        for (int nt = 0; nt < NTG; ++nt) acc[nt][mt] = Low<T>::mfma16(ring[u][nt], a_use, acc[nt][mt]);
+      }
     }
   }
 }
@@ -317,21 +353,51 @@ __device__ inline void tile_mma(f32x4 (&acc)[4][MT], u16x8 (&ring)[PD][4], const
 //                                        first PD k-blocks of whatever pass runs next.
 // The sequence of passes is static in the kernels, so there is no run-time bookkeeping of what
 // the ring holds: every pass finds its first fragments already requested by its predecessor.
-// Hidden widths are padded to multiples of 256 by the host, so a wavefront owns a multiple of 4
-// column tiles in every hidden pass; state-shaped passes own NTL = dpad / 64 tiles (1, 2 or 4).
-template <class T, int MT>
+//
+// A workgroup has NW wavefronts (4 or 8; 8 = two per SIMD, which hides the LDS / MFMA / barrier
+// latencies of a single row tile).  Hidden widths are padded to multiples of 256 by the host, so
+// in a hidden pass every wavefront owns a multiple of NTH = 16 / NW column tiles.  A state-shaped
+// pass has 4 * NTL column tiles (NTL = dpad / 64): the first ACTIVE wavefronts own NTS each.
+// HP > 0: all hidden layers have (padded) width HP, known at compile time; HP = 0: run-time widths.
+template <int NTL, int NW, int HP>
+struct Shape {
+  static constexpr int NTH = 16 / NW;
+  static constexpr int NTS = (4 * NTL >= NW) ? (4 * NTL) / NW : 1;
+  static constexpr int ACTIVE = (4 * NTL >= NW) ? NW : 4 * NTL;
+  static constexpr int RW = NTH > NTS ? NTH : NTS;
+  // k-blocks of a contraction over the state width / over a hidden width; column tiles of a
+  // hidden-shaped / state-shaped output (0 = not known at compile time)
+  static constexpr int KB_S = HP > 0 ? 2 * NTL : 0;
+  static constexpr int KB_H = HP / 32;
+  static constexpr int NT_H = HP / 16;
+  static constexpr int NT_S = HP > 0 ? 4 * NTL : 0;
+};
+
+template <class T, int MT, int NTL, int NW, int HP>
 struct TileEngine {
-  u16x8 ring[PD][4];
+  using Sh = Shape<NTL, NW, HP>;
+  static constexpr int NTH = Sh::NTH, NTS = Sh::NTS, ACTIVE = Sh::ACTIVE, RW = Sh::RW;
+  u16x8 ring[PD][RW];
   int lane, wave;
 
-  // request the first PD k-blocks of group g of pass p (NTG tiles per wavefront and group)
-  template <int NTG>
-  __device__ inline void preload(const PassDesc& p, int g) {
-    const int ntw = p.NT16 >> 2;
-    ring_preload<NTG>(ring, p, wave * ntw + g * NTG, lane);
+  __device__ inline bool state_wave() const { return ACTIVE == NW || wave < ACTIVE; }
+  __device__ inline int state_col(int nt, int lq) const { return (wave * NTS + nt) * 16 + lq * 4; }
+
+  // request the first PD k-blocks of group g of a hidden pass / of a state-shaped pass.
+  // FROM_STATE: the pass contracts over the state width (first layer, or first transposed layer).
+  template <bool FROM_STATE>
+  __device__ inline void preload_hidden(const PassDesc& p, int g) {
+    constexpr int KBC = FROM_STATE ? Sh::KB_S : Sh::KB_H;
+    const int ntw = HP > 0 ? Sh::NT_H / NW : p.NT16 / NW;
+    ring_preload<NTH, RW, KBC, Sh::NT_H>(ring, p, wave * ntw + g * NTH, lane);
+  }
+  template <bool FROM_STATE>
+  __device__ inline void preload_state(const PassDesc& p) {
+    constexpr int KBC = FROM_STATE ? Sh::KB_S : Sh::KB_H;
+    if (state_wave()) ring_preload<NTS, RW, KBC, Sh::NT_S>(ring, p, wave * NTS, lane);
   }
 
-  template <int NTG, class Pre, class Epi, class Nxt>
+  template <int NTG, int KBC, int NTC, class Pre, class Epi, class Nxt>
   __device__ inline void group(const PassDesc& p, int nt0, const lds_u16* in, int ld_in, bool sync_before_epi,
                                Pre& pre, Epi& epi, Nxt& nxt) {
     const int lm = lane & 15, lq = lane >> 4;
@@ -340,8 +406,8 @@ struct TileEngine {
     for (int nt = 0; nt < NTG; ++nt)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) pf[nt][mt] = pre((nt0 + nt) * 16 + lq * 4, mt * 16 + lm);
-    f32x4 acc[4][MT];
-    tile_mma<T, MT, NTG>(acc, ring, p, nt0, in, ld_in, lane);
+    f32x4 acc[RW][MT];
+    tile_mma<T, MT, NTG, RW, KBC, NTC>(acc, ring, p, nt0, in, ld_in, lane);
     nxt();
     if (sync_before_epi) __syncthreads();
 #pragma unroll
@@ -350,27 +416,36 @@ struct TileEngine {
       for (int mt = 0; mt < MT; ++mt) epi(acc[nt][mt], pf[nt][mt], nt, mt, (nt0 + nt) * 16 + lq * 4, mt * 16 + lm);
   }
 
-  // hidden pass: groups of 4 column tiles per wavefront.  Ends with a barrier.
-  template <class Pre, class Epi, class Nxt>
+  // hidden pass: groups of NTH column tiles per wavefront.  Ends with a barrier.
+  template <bool FROM_STATE, class Pre, class Epi, class Nxt>
   __device__ inline void run_hidden(const PassDesc& p, const lds_u16* in, int ld_in, Pre pre, Epi epi, Nxt nxt) {
-    const int ntw = p.NT16 >> 2;
-    const int groups = ntw >> 2;
+    constexpr int KBC = FROM_STATE ? Sh::KB_S : Sh::KB_H;
+    const int ntw = HP > 0 ? Sh::NT_H / NW : p.NT16 / NW;
+    const int groups = ntw / NTH;
+#pragma unroll
     for (int g = 0; g < groups; ++g) {
       auto nx = [&]() {
-        if (g + 1 < groups) preload<4>(p, g + 1);
+        if (g + 1 < groups) preload_hidden<FROM_STATE>(p, g + 1);
         else nxt();
       };
-      group<4>(p, wave * ntw + g * 4, in, ld_in, false, pre, epi, nx);
+      group<NTH, KBC, Sh::NT_H>(p, wave * ntw + g * NTH, in, ld_in, false, pre, epi, nx);
     }
     __syncthreads();
   }
 
-  // state-shaped pass (the contraction that ends a stage): one group of NTG tiles, compile-time
-  // tile indices so that per-tile state registers can be addressed.  Ends with a barrier.
-  template <int NTG, class Pre, class Epi, class Nxt>
-  __device__ inline void run_fixed(const PassDesc& p, const lds_u16* in, int ld_in, bool sync_before_epi, Pre pre,
+  // state-shaped pass (the contraction that ends a stage): one group of NTS tiles on the ACTIVE
+  // wavefronts, compile-time tile indices so that per-tile state registers can be addressed; the
+  // other wavefronts only request their next fragments.  Ends with a barrier.
+  template <bool FROM_STATE, class Pre, class Epi, class Nxt>
+  __device__ inline void run_state(const PassDesc& p, const lds_u16* in, int ld_in, bool sync_before_epi, Pre pre,
                                    Epi epi, Nxt nxt) {
-    group<NTG>(p, wave * NTG, in, ld_in, sync_before_epi, pre, epi, nxt);
+    constexpr int KBC = FROM_STATE ? Sh::KB_S : Sh::KB_H;
+    if (state_wave()) {
+      group<NTS, KBC, Sh::NT_S>(p, wave * NTS, in, ld_in, sync_before_epi, pre, epi, nxt);
+    } else {
+      nxt();
+      if (sync_before_epi) __syncthreads();
+    }
     __syncthreads();
   }
 };
@@ -409,8 +484,8 @@ struct TileLds {
 
 __device__ inline void load_params(lds_f32* param, const FusedArgs& g) {
   for (int l = 0; l < g.L; ++l)
-    for (int i = threadIdx.x; i < g.layer[l].Npad; i += 256) param[g.layer[l].bias_off + i] = g.layer[l].bias[i];
-  for (int i = threadIdx.x; i < g.layer[0].Npad; i += 256) param[g.wt_off + i] = g.layer[0].wt ? g.layer[0].wt[i] : 0.f;
+    for (int i = threadIdx.x; i < g.layer[l].Npad; i += blockDim.x) param[g.layer[l].bias_off + i] = g.layer[l].bias[i];
+  for (int i = threadIdx.x; i < g.layer[0].Npad; i += blockDim.x) param[g.wt_off + i] = g.layer[0].wt ? g.layer[0].wt[i] : 0.f;
 }
 
 // Low-precision per-stage vectors of a tile (slopes, stage cotangents): LDS or global.
@@ -434,9 +509,9 @@ struct StageStore {
 
 // Hidden layers of one velocity evaluation (all but the last layer) for stage j.  The ring must
 // hold the first fragments of layer 0 (if L > 1); on return it holds those of the last layer.
-template <class T, int MT, int NTL, bool KEEP>
-__device__ inline void hidden_layers(TileEngine<T, MT>& eng, const TileLds<MT>& lds, const FusedArgs& g, int j,
-                                     float tau, int64_t row0) {
+template <class T, int MT, int NTL, int NW, int HP, bool KEEP>
+__device__ inline void hidden_layers(TileEngine<T, MT, NTL, NW, HP>& eng, const TileLds<MT>& lds, const FusedArgs& g,
+                                     int j, float tau, int64_t row0) {
   for (int l = 0; l + 1 < g.L; ++l) {
     const PassDesc p = fwd_pass(g, l);
     const PassDesc nx = fwd_pass(g, l + 1);
@@ -450,29 +525,30 @@ __device__ inline void hidden_layers(TileEngine<T, MT>& eng, const TileLds<MT>& 
     uint16_t* goutT = KEEP ? g.ACTT[l] : nullptr;
     const int64_t kj = (int64_t)j * g.Rp + row0;
     const int ldg = g.layer[l].Npad;
-    eng.run_hidden(
-        p, lds.in(l), lds.ld_in(l), [](int, int) { return make_uint2(0u, 0u); },
-        [&](const f32x4& acc, uint2, int, int, int n, int m) {
-          const float4 bv = lds_load_f4(&bias[n]);
-          float v[4] = {acc[0] + bv.x, acc[1] + bv.y, acc[2] + bv.z, acc[3] + bv.w};
-          if (has_wt) {
-            const float4 tv = lds_load_f4(&wt[n]);
-            v[0] = fmaf(tv.x, tau, v[0]); v[1] = fmaf(tv.y, tau, v[1]);
-            v[2] = fmaf(tv.z, tau, v[2]); v[3] = fmaf(tv.w, tau, v[3]);
-          }
+    auto pre = [](int, int) { return make_uint2(0u, 0u); };
+    auto epi = [&](const f32x4& acc, uint2, int, int, int n, int m) {
+      const float4 bv = lds_load_f4(&bias[n]);
+      float v[4] = {acc[0] + bv.x, acc[1] + bv.y, acc[2] + bv.z, acc[3] + bv.w};
+      if (has_wt) {
+        const float4 tv = lds_load_f4(&wt[n]);
+        v[0] = fmaf(tv.x, tau, v[0]); v[1] = fmaf(tv.y, tau, v[1]);
+        v[2] = fmaf(tv.z, tau, v[2]); v[3] = fmaf(tv.w, tau, v[3]);
+      }
 #pragma unroll
-          for (int r = 0; r < 4; ++r) v[r] = tanh_fast(v[r]);
-          const uint2 q = pack4<T>(v);
-          lds_store_u2(&out[m * ldp + n], q);
-          if (KEEP && row0 + m < g.R) {
-            *reinterpret_cast<uint2*>(&gout[(size_t)(row0 + m) * ldg + n]) = q;
-            store4t(goutT, g.ldk, kj + m, n, q);
-          }
-        },
-        [&]() {
-          if (next_is_last) eng.template preload<NTL>(nx, 0);
-          else eng.template preload<4>(nx, 0);
-        });
+      for (int r = 0; r < 4; ++r) v[r] = tanh_fast(v[r]);
+      const uint2 q = pack4<T>(v);
+      lds_store_u2(&out[m * ldp + n], q);
+      if (KEEP && row0 + m < g.R) {
+        *reinterpret_cast<uint2*>(&gout[(size_t)(row0 + m) * ldg + n]) = q;
+        store4t(goutT, g.ldk, kj + m, n, q);
+      }
+    };
+    auto nxt = [&]() {
+      if (next_is_last) eng.template preload_state<false>(nx);
+      else eng.template preload_hidden<false>(nx, 0);
+    };
+    if (l == 0) eng.template run_hidden<true>(p, lds.in(l), lds.ld_in(l), pre, epi, nxt);
+    else eng.template run_hidden<false>(p, lds.in(l), lds.ld_in(l), pre, epi, nxt);
   }
 }
 
@@ -491,13 +567,14 @@ __device__ inline void last_layer_values(const f32x4& acc, const lds_f32* param,
 // ---------------------------------------------------------------------------------------
 // Forward pass, all steps in one launch (paper Algorithm 1).  NTL = dpad / 64: column tiles of
 // the state that one wavefront owns.
-template <class T, int MT, int NTL>
-__global__ __launch_bounds__(256) void mlp_forward_fused(FusedArgs g) {
+template <class T, int MT, int NTL, int NW, int HP>
+__global__ __launch_bounds__(64 * NW) void mlp_forward_fused(FusedArgs g) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   constexpr int TM = 16 * MT;
   const TileLds<MT> lds((lds_u16*)smem, g);
   const int tid = threadIdx.x;
-  TileEngine<T, MT> eng;
+  TileEngine<T, MT, NTL, NW, HP> eng;
+  constexpr int NTS = Shape<NTL, NW, HP>::NTS;
   eng.lane = tid & 63;
   eng.wave = tid >> 6;
   const int lm = eng.lane & 15, lq = eng.lane >> 4;
@@ -508,24 +585,26 @@ __global__ __launch_bounds__(256) void mlp_forward_fused(FusedArgs g) {
 
   load_params(lds.param, g);
   // y <- y0 (registers), first stored state, first stage input
-  float yv[NTL][MT][4];
+  float yv[NTS][MT][4];
+  if (eng.state_wave()) {
 #pragma unroll
-  for (int nt = 0; nt < NTL; ++nt)
+    for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int n = (eng.wave * NTL + nt) * 16 + lq * 4, m = mt * 16 + lm;
-      load4f(g.y0, row0 + m, g.R, n, g.d, yv[nt][mt]);
-      const uint2 q = pack4<T>(yv[nt][mt]);
-      store4h(g.ckpt, row0 + m, g.R, n, g.d, q);
-      lds_store_u2(&lds.zbuf[m * lds.ldz + n], q);
-    }
+      for (int mt = 0; mt < MT; ++mt) {
+        const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
+        load4f(g.y0, row0 + m, g.R, n, g.d, yv[nt][mt]);
+        const uint2 q = pack4<T>(yv[nt][mt]);
+        store4h(g.ckpt, row0 + m, g.R, n, g.d, q);
+        lds_store_u2(&lds.zbuf[m * lds.ldz + n], q);
+      }
+  }
   __syncthreads();
 
   const PassDesc first = fwd_pass(g, 0);
   const PassDesc last = fwd_pass(g, L - 1);
   auto preload_first = [&]() {  // first pass of a velocity evaluation
-    if (L > 1) eng.template preload<4>(first, 0);
-    else eng.template preload<NTL>(first, 0);
+    if (L > 1) eng.template preload_hidden<true>(first, 0);
+    else eng.template preload_state<true>(first);
   };
   preload_first();
   for (int i = 0; i < g.N; ++i) {
@@ -534,11 +613,10 @@ __global__ __launch_bounds__(256) void mlp_forward_fused(FusedArgs g) {
     uint16_t* ck_next = g.ckpt + (size_t)(i + 1) * n_state;
     for (int j = 0; j < s; ++j) {
       const float tau = st[1 + j];
-      hidden_layers<T, MT, NTL, false>(eng, lds, g, j, tau, row0);
+      hidden_layers<T, MT, NTL, NW, HP, false>(eng, lds, g, j, tau, row0);
       const bool more = (j + 1 < s) || (i + 1 < g.N);
-      eng.template run_fixed<NTL>(
-          last, lds.in(L - 1), lds.ld_in(L - 1), L == 1, [](int, int) { return make_uint2(0u, 0u); },
-          [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
+      auto pre0 = [](int, int) { return make_uint2(0u, 0u); };
+      auto epi_last = [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
             float v[4];
             last_layer_values(acc, lds.param, g, tau, n, v);
             const uint2 kq = pack4<T>(v);
@@ -585,29 +663,34 @@ __global__ __launch_bounds__(256) void mlp_forward_fused(FusedArgs g) {
               store4h(ck_next, row0 + m, g.R, n, g.d, zq);
             }
             lds_store_u2(&lds.zbuf[m * lds.ldz + n], zq);
-          },
-          [&]() {
-            if (more) preload_first();
-          });
+          };
+      auto nxt_last = [&]() {
+        if (more) preload_first();
+      };
+      if (L == 1) eng.template run_state<true>(last, lds.in(0), lds.ld_in(0), true, pre0, epi_last, nxt_last);
+      else eng.template run_state<false>(last, lds.in(L - 1), lds.ld_in(L - 1), false, pre0, epi_last, nxt_last);
     }
   }
+  if (eng.state_wave()) {
 #pragma unroll
-  for (int nt = 0; nt < NTL; ++nt)
+    for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-      store4f(g.y, row0 + mt * 16 + lm, g.R, (eng.wave * NTL + nt) * 16 + lq * 4, g.d, yv[nt][mt]);
+      for (int mt = 0; mt < MT; ++mt)
+        store4f(g.y, row0 + mt * 16 + lm, g.R, eng.state_col(nt, lq), g.d, yv[nt][mt]);
+  }
 }
 
 // ---------------------------------------------------------------------------------------
 // One step of the adjoint for a row tile (paper Algorithm 2, the body of the loop over steps).
-template <class T, int MT, int NTL>
-__global__ __launch_bounds__(256) void mlp_adjoint_step(FusedArgs g) {
+template <class T, int MT, int NTL, int NW, int HP>
+__global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   if (g.ctl->poison) return;
   constexpr int TM = 16 * MT;
   const TileLds<MT> lds((lds_u16*)smem, g);
   const int tid = threadIdx.x;
-  TileEngine<T, MT> eng;
+  TileEngine<T, MT, NTL, NW, HP> eng;
+  constexpr int NTS = Shape<NTL, NW, HP>::NTS;
   eng.lane = tid & 63;
   eng.wave = tid >> 6;
   const int lm = eng.lane & 15, lq = eng.lane >> 4;
@@ -622,14 +705,14 @@ __global__ __launch_bounds__(256) void mlp_adjoint_step(FusedArgs g) {
 
   load_params(lds.param, g);
   // lane-resident state: the adjoint a (fp32) and lambda = Q(S a); yhat = stored state
-  float av[NTL][MT][4];
-  uint2 lamq[NTL][MT], yhat[NTL][MT];
+  float av[NTS][MT][4];
+  uint2 lamq[NTS][MT], yhat[NTS][MT];
   bool bad = false;
 #pragma unroll
-  for (int nt = 0; nt < NTL; ++nt)
+  for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      const int n = (eng.wave * NTL + nt) * 16 + lq * 4, m = mt * 16 + lm;
+      const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
       load4f(g.a_in, row0 + m, g.R, n, g.d, av[nt][mt]);
       float sa[4];
 #pragma unroll
@@ -673,33 +756,34 @@ __global__ __launch_bounds__(256) void mlp_adjoint_step(FusedArgs g) {
   const PassDesc lastb = bwd_pass(g, 0);
 
   auto preload_first_f = [&]() {
-    if (L > 1) eng.template preload<4>(firstf, 0);
-    else eng.template preload<NTL>(firstf, 0);
+    if (L > 1) eng.template preload_hidden<true>(firstf, 0);
+    else eng.template preload_state<true>(firstf);
   };
   auto preload_first_b = [&]() {
-    if (L > 1) eng.template preload<4>(firstb, 0);
-    else eng.template preload<NTL>(firstb, 0);
+    if (L > 1) eng.template preload_hidden<true>(firstb, 0);
+    else eng.template preload_state<true>(firstb);
   };
 
   if (!g.skip_recompute) {
     // ---- stage recomputation from the stored state, keeping inputs and activations
     preload_first_f();
+    if (eng.state_wave()) {
 #pragma unroll
-    for (int nt = 0; nt < NTL; ++nt)
+      for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int n = (eng.wave * NTL + nt) * 16 + lq * 4, m = mt * 16 + lm;
-        lds_store_u2(&lds.zbuf[m * lds.ldz + n], yhat[nt][mt]);
-        if (row0 + m < g.R) store4t(g.ZT, g.ldk, row0 + m, n, yhat[nt][mt]);
-      }
+        for (int mt = 0; mt < MT; ++mt) {
+          const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
+          lds_store_u2(&lds.zbuf[m * lds.ldz + n], yhat[nt][mt]);
+          if (row0 + m < g.R) store4t(g.ZT, g.ldk, row0 + m, n, yhat[nt][mt]);
+        }
+    }
     __syncthreads();
     for (int j = 0; j < s; ++j) {
       const float tau = st[1 + j];
-      hidden_layers<T, MT, NTL, true>(eng, lds, g, j, tau, row0);
+      hidden_layers<T, MT, NTL, NW, HP, true>(eng, lds, g, j, tau, row0);
       const bool more = j + 1 < s;
-      eng.template run_fixed<NTL>(
-          lastf, lds.in(L - 1), lds.ld_in(L - 1), L == 1, [](int, int) { return make_uint2(0u, 0u); },
-          [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
+      auto pre0 = [](int, int) { return make_uint2(0u, 0u); };
+      auto epi_last = [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
             float v[4];
             last_layer_values(acc, lds.param, g, tau, n, v);
             const uint2 kq = pack4<T>(v);
@@ -726,26 +810,30 @@ __global__ __launch_bounds__(256) void mlp_adjoint_step(FusedArgs g) {
             } else {
               make_kbar(s - 1, nt, mt, m, n, nullptr);  // the slope of the last stage is not needed again
             }
-          },
-          [&]() {
-            if (more) preload_first_f();
-            else preload_first_b();
-          });
+          };
+      auto nxt_last = [&]() {
+        if (more) preload_first_f();
+        else preload_first_b();
+      };
+      if (L == 1) eng.template run_state<true>(lastf, lds.in(0), lds.ld_in(0), true, pre0, epi_last, nxt_last);
+      else eng.template run_state<false>(lastf, lds.in(L - 1), lds.ld_in(L - 1), false, pre0, epi_last, nxt_last);
     }
   } else {
     preload_first_b();
+    if (eng.state_wave()) {
 #pragma unroll
-    for (int nt = 0; nt < NTL; ++nt)
+      for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        make_kbar(s - 1, nt, mt, mt * 16 + lm, (eng.wave * NTL + nt) * 16 + lq * 4, nullptr);
+        for (int mt = 0; mt < MT; ++mt)
+          make_kbar(s - 1, nt, mt, mt * 16 + lm, eng.state_col(nt, lq), nullptr);
+    }
     __syncthreads();
   }
 
   // ---- cotangent chain, stages in reverse (eq. (vjp) pushed through the stage recursion)
-  float da[NTL][MT][4];
+  float da[NTS][MT][4];
 #pragma unroll
-  for (int nt = 0; nt < NTL; ++nt)
+  for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -763,12 +851,11 @@ __global__ __launch_bounds__(256) void mlp_adjoint_step(FusedArgs g) {
       const int ldg = g.layer[l].Kpad;
       lds_u16* out = lds.out(q);
       const int ldp = lds.ldp;
-      eng.run_hidden(p, lds.in(q), lds.ld_in(q),
-              [&](int n, int m) {
+      auto pre_act = [&](int n, int m) {
                 return (row0 + m < g.R) ? *reinterpret_cast<const uint2*>(&act[(size_t)(row0 + m) * ldg + n])
                                         : make_uint2(0u, 0u);
-              },
-              [&](const f32x4& acc, uint2 pf, int, int, int n, int m) {
+              };
+      auto epi_delta = [&](const f32x4& acc, uint2 pf, int, int, int n, int m) {
                 float a[4], v[4];
                 unpack4<T>(pf, a);
 #pragma unroll
@@ -779,16 +866,17 @@ __global__ __launch_bounds__(256) void mlp_adjoint_step(FusedArgs g) {
                   store4t(goutT, g.ldk, kj + m, n, dq);
                   bad = bad || any_nonfinite4<T>(dq);
                 }
-              },
-              [&]() {
-                if (next_is_last) eng.template preload<NTL>(nx, 0);
-                else eng.template preload<4>(nx, 0);
-              });
+              };
+      auto nxt_b = [&]() {
+        if (next_is_last) eng.template preload_state<false>(nx);
+        else eng.template preload_hidden<false>(nx, 0);
+      };
+      if (q == 0) eng.template run_hidden<true>(p, lds.in(q), lds.ld_in(q), pre_act, epi_delta, nxt_b);
+      else eng.template run_hidden<false>(p, lds.in(q), lds.ld_in(q), pre_act, epi_delta, nxt_b);
     }
     const int q = L - 1;
-    eng.template run_fixed<NTL>(
-        lastb, lds.in(q), lds.ld_in(q), L == 1, [](int, int) { return make_uint2(0u, 0u); },
-        [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
+    auto pre0 = [](int, int) { return make_uint2(0u, 0u); };
+    auto epi_zbar = [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
           const float v[4] = {acc[0], acc[1], acc[2], acc[3]};
           const uint2 zq = pack4<T>(v);
           if (row0 + m < g.R) bad = bad || any_nonfinite4<T>(zq);
@@ -800,10 +888,12 @@ __global__ __launch_bounds__(256) void mlp_adjoint_step(FusedArgs g) {
             zs.put(j, m, n, zq);
             make_kbar(j - 1, nt, mt, m, n, zf);
           }
-        },
-        [&]() {
-          if (j > 0) preload_first_b();
-        });
+        };
+    auto nxt_z = [&]() {
+      if (j > 0) preload_first_b();
+    };
+    if (L == 1) eng.template run_state<true>(lastb, lds.in(0), lds.ld_in(0), true, pre0, epi_zbar, nxt_z);
+    else eng.template run_state<false>(lastb, lds.in(q), lds.ld_in(q), false, pre0, epi_zbar, nxt_z);
   }
   if (g.detect) raise_if_any(bad, g.ctl);
 
@@ -811,10 +901,10 @@ __global__ __launch_bounds__(256) void mlp_adjoint_step(FusedArgs g) {
   unsigned bits = 0;
   const float hs = h / S;
 #pragma unroll
-  for (int nt = 0; nt < NTL; ++nt)
+  for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      const int n = (eng.wave * NTL + nt) * 16 + lq * 4, m = mt * 16 + lm;
+      const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
       float v[4], gy[4] = {0.f, 0.f, 0.f, 0.f};
       if (g.gys) load4f(g.gys, row0 + m, g.R, n, g.d, gy);
 #pragma unroll

@@ -1,0 +1,57 @@
+// One translation unit per hidden width: compile with -DRAMPDE_INST_HP={0,256,512,1024}.
+#include "fused_launch.hpp"
+
+#ifndef RAMPDE_INST_HP
+#error "define RAMPDE_INST_HP"
+#endif
+#define RAMPDE_CAT2(a, b) a##b
+#define RAMPDE_CAT(a, b) RAMPDE_CAT2(a, b)
+
+namespace rampde {
+
+namespace {
+
+template <class Kern>
+hipError_t launch_kernel(Kern kern, const FusedLaunch& l, const FusedArgs& a) {
+  if (l.lds_bytes > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)l.lds_bytes);
+    if (e != hipSuccess) return e;
+  }
+  kern<<<l.grid, 64 * kFusedWaves, l.lds_bytes, l.stream>>>(a);
+  return hipGetLastError();
+}
+
+template <class T, int MT, int NTL>
+hipError_t pick_kernel(const FusedLaunch& l, const FusedArgs& a) {
+  if (l.adjoint) return launch_kernel(mlp_adjoint_step<T, MT, NTL, kFusedWaves, RAMPDE_INST_HP>, l, a);
+  return launch_kernel(mlp_forward_fused<T, MT, NTL, kFusedWaves, RAMPDE_INST_HP>, l, a);
+}
+
+template <class T, int MT>
+hipError_t pick_ntl(const FusedLaunch& l, const FusedArgs& a) {
+  switch (l.NTL) {
+    case 1: return pick_kernel<T, MT, 1>(l, a);
+    case 2: return pick_kernel<T, MT, 2>(l, a);
+    case 4: return pick_kernel<T, MT, 4>(l, a);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+template <class T>
+hipError_t pick_mt(const FusedLaunch& l, const FusedArgs& a) {
+  switch (l.MT) {
+    case 1: return pick_ntl<T, 1>(l, a);
+    case 2: return pick_ntl<T, 2>(l, a);
+    case 4: return pick_ntl<T, 4>(l, a);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+hipError_t RAMPDE_CAT(fused_launch_hp, RAMPDE_INST_HP)(const FusedLaunch& l, const FusedArgs& a) {
+  return l.bf16 ? pick_mt<BF16>(l, a) : pick_mt<F16>(l, a);
+}
+
+}  // namespace rampde

@@ -1,0 +1,29 @@
+// Launchers of the row-tile-persistent kernels.  The kernels are instantiated per hidden width
+// (0 = run-time widths, 256 / 512 / 1024 = all hidden layers padded to that width, known at
+// compile time), one translation unit each so that they compile in parallel.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "fused.hpp"
+
+namespace rampde {
+
+constexpr int kFusedWaves = 8;  // wavefronts per workgroup: two per SIMD
+
+struct FusedLaunch {
+  int adjoint;   // 0: mlp_forward_fused, 1: mlp_adjoint_step
+  int bf16;      // 0: fp16, 1: bfloat16
+  int MT;        // row tile = 16 * MT rows, MT in {1, 2, 4}
+  int NTL;       // dpad / 64, in {1, 2, 4}
+  unsigned grid;
+  size_t lds_bytes;
+  hipStream_t stream;
+};
+
+// Each returns hipSuccess or the error of the attribute call / launch.
+hipError_t fused_launch_hp0(const FusedLaunch& l, const FusedArgs& a);
+hipError_t fused_launch_hp256(const FusedLaunch& l, const FusedArgs& a);
+hipError_t fused_launch_hp512(const FusedLaunch& l, const FusedArgs& a);
+hipError_t fused_launch_hp1024(const FusedLaunch& l, const FusedArgs& a);
+
+}  // namespace rampde

@@ -13,11 +13,12 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <type_traits>
 #include <vector>
 
 #include "common.hpp"
 #include "elementwise.hpp"
-#include "fused.hpp"
+#include "fused_launch.hpp"
 #include "gemm.hpp"
 
 namespace rampde {
@@ -489,36 +490,34 @@ struct Runner {
     return a;
   }
 
-  template <class Kern>
-  int launch_fused(Kern kern, const FusedArgs& a) {
-    if (p.lds_bytes > 48 * 1024)
-      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)p.lds_bytes));
-    const unsigned grid = blocks_for(p.R, 16 * p.MT);
-    kern<<<grid, 256, p.lds_bytes, st>>>(a);
-    return RAMPDE_OK;
+  // hidden width for which a shape-specialised instantiation exists (all hidden layers padded
+  // to the same width), or 0
+  int static_hidden_width() const {
+    if (p.L < 2) return 0;
+    const int hp = p.layers[0].Npad;
+    for (int l = 0; l + 1 < p.L; ++l)
+      if (p.layers[l].Npad != hp) return 0;
+    return (hp == 256 || hp == 512 || hp == 1024) ? hp : 0;
   }
 
-  template <bool FWD, int MT, int NTL>
-  int launch_one(const FusedArgs& a) {
-    if (FWD) return launch_fused(mlp_forward_fused<T, MT, NTL>, a);
-    return launch_fused(mlp_adjoint_step<T, MT, NTL>, a);
-  }
-  template <bool FWD, int MT>
-  int dispatch_ntl(const FusedArgs& a) {
-    switch (p.dpad / 64) {
-      case 1: return launch_one<FWD, MT, 1>(a);
-      case 2: return launch_one<FWD, MT, 2>(a);
-      default: return launch_one<FWD, MT, 4>(a);
+  int launch_fused(bool adjoint, const FusedArgs& a) {
+    FusedLaunch l{};
+    l.adjoint = adjoint ? 1 : 0;
+    l.bf16 = std::is_same<T, BF16>::value ? 1 : 0;
+    l.MT = p.MT;
+    l.NTL = p.dpad / 64;
+    l.grid = blocks_for(p.R, 16 * p.MT);
+    l.lds_bytes = p.lds_bytes;
+    l.stream = st;
+    hipError_t e;
+    switch (static_hidden_width()) {
+      case 256: e = fused_launch_hp256(l, a); break;
+      case 512: e = fused_launch_hp512(l, a); break;
+      case 1024: e = fused_launch_hp1024(l, a); break;
+      default: e = fused_launch_hp0(l, a); break;
     }
-  }
-  template <bool FWD>
-  int dispatch_fused(const FusedArgs& a) {
-    switch (p.MT) {
-      case 1: return dispatch_ntl<FWD, 1>(a);
-      case 2: return dispatch_ntl<FWD, 2>(a);
-      default: return dispatch_ntl<FWD, 4>(a);
-    }
+    if (e != hipSuccess) return hip_fail(e, "row-tile-persistent kernel launch");
+    return RAMPDE_OK;
   }
 
   double step_flops() const {  // one velocity evaluation of the whole batch, padded shapes
@@ -540,7 +539,7 @@ struct Runner {
     int rc;
     {
       TimeScope ts(RAMPDE_K_FUSED_FORWARD, step_flops() * p.s * N, st);
-      rc = dispatch_fused<true>(a);
+      rc = launch_fused(false, a);
     }
     if (rc) return rc;
     HIP_TRY(hipGetLastError());
@@ -549,7 +548,7 @@ struct Runner {
 
   int adjoint_step_fused(const FusedArgs& a) {
     TimeScope ts(RAMPDE_K_FUSED_ADJOINT_STEP, step_flops() * p.s * (a.skip_recompute ? 1.0 : 2.0), st);
-    return dispatch_fused<false>(a);
+    return launch_fused(true, a);
   }
 
   int forward(const float* theta, const float* y0, const double* tgrid, int N, const rampde_tableau* tab,
