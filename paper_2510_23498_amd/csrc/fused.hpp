@@ -85,12 +85,15 @@ struct FusedArgs {
   uint16_t* K;  // [s][R][dpad] slopes (used when they do not fit in LDS)
   // one adjoint step
   int step;
-  uint16_t* ACT[kMaxLayers];   // [s][R][Npad_l], l = 0..L-2: hidden activations (read back for tanh')
-  // feature-major copies for the parameter-gradient contraction: [feature][k], k = stage * Rp + row
-  uint16_t* ZT;                // [dpad][ldk] stage inputs
-  uint16_t* ACTT[kMaxLayers];  // [Npad_l][ldk] hidden activations
-  uint16_t* DELTAT[kMaxLayers];// [Npad_l][ldk] their cotangents
-  uint16_t* KBART;             // [dpad][ldk] cotangents of the slopes
+  // Everything the parameter-gradient contraction reads is stored "feature-group-major":
+  // element (feature f, k) at ((f / 4) * ldk + k) * 4 + f % 4, k = stage * Rp + row.  A lane's 4
+  // consecutive features of one row are one 8-byte word (stores stay as cheap as row-major ones,
+  // and the same word is what the tanh' factor of the transposed passes needs), while for a fixed
+  // feature group k runs contiguously, which is what the contraction over k wants.
+  uint16_t* ZT;                // [dpad / 4][ldk][4] stage inputs
+  uint16_t* ACTT[kMaxLayers];  // [Npad_l / 4][ldk][4] hidden activations, l = 0..L-2
+  uint16_t* DELTAT[kMaxLayers];// [Npad_l / 4][ldk][4] their cotangents
+  uint16_t* KBART;             // [dpad / 4][ldk][4] cotangents of the slopes
   int64_t ldk, Rp;
   uint16_t* ZBAR;              // [s][R][dpad] (used when they do not fit in LDS)
   const float* a_in;
@@ -219,13 +222,15 @@ __device__ inline void store4h(uint16_t* p, int64_t row, int64_t R, int c, int d
   }
 }
 
-// 4 consecutive features of one row into a feature-major array: XT[n + r][k], r = 0..3
-__device__ inline void store4t(uint16_t* XT, int64_t ldk, int64_t k, int n, uint2 q) {
-  XT[(size_t)n * ldk + k] = (uint16_t)q.x;
-  XT[(size_t)(n + 1) * ldk + k] = (uint16_t)(q.x >> 16);
-  XT[(size_t)(n + 2) * ldk + k] = (uint16_t)q.y;
-  XT[(size_t)(n + 3) * ldk + k] = (uint16_t)(q.y >> 16);
+// 4 consecutive features n..n+3 (n % 4 == 0) of contraction index k in a feature-group-major array
+__device__ inline uint2* group4(uint16_t* XT, int64_t ldk, int64_t k, int n) {
+  return reinterpret_cast<uint2*>(XT + ((size_t)(n >> 2) * ldk + k) * 4);
 }
+#ifdef RAMPDE_PROBE_NOSTORE
+#define RAMPDE_STORE_G4(ptr, val) do { if (g.N < 0) *(ptr) = (val); } while (0)
+#else
+#define RAMPDE_STORE_G4(ptr, val) (*(ptr) = (val))
+#endif
 
 // One contraction pass of a row tile: out[TM][Ncols] = in[TM][32*KB] * Wfrag^T for the
 // calling wavefront's slice of output-column tiles.
@@ -521,10 +526,8 @@ __device__ inline void hidden_layers(TileEngine<T, MT, NTL, NW, HP>& eng, const 
     const bool has_wt = (l == 0);
     lds_u16* out = lds.out(l);
     const int ldp = lds.ldp;
-    uint16_t* gout = KEEP ? g.ACT[l] + (size_t)j * g.R * g.layer[l].Npad : nullptr;
     uint16_t* goutT = KEEP ? g.ACTT[l] : nullptr;
     const int64_t kj = (int64_t)j * g.Rp + row0;
-    const int ldg = g.layer[l].Npad;
     auto pre = [](int, int) { return make_uint2(0u, 0u); };
     auto epi = [&](const f32x4& acc, uint2, int, int, int n, int m) {
       const float4 bv = lds_load_f4(&bias[n]);
@@ -538,10 +541,7 @@ __device__ inline void hidden_layers(TileEngine<T, MT, NTL, NW, HP>& eng, const 
       for (int r = 0; r < 4; ++r) v[r] = tanh_fast(v[r]);
       const uint2 q = pack4<T>(v);
       lds_store_u2(&out[m * ldp + n], q);
-      if (KEEP && row0 + m < g.R) {
-        *reinterpret_cast<uint2*>(&gout[(size_t)(row0 + m) * ldg + n]) = q;
-        store4t(goutT, g.ldk, kj + m, n, q);
-      }
+      if (KEEP && row0 + m < g.R) RAMPDE_STORE_G4(group4(goutT, g.ldk, kj + m, n), q);
     };
     auto nxt = [&]() {
       if (next_is_last) eng.template preload_state<false>(nx);
@@ -746,7 +746,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
     const uint2 q = pack4<T>(v);
     bad = bad || any_nonfinite4<T>(q);
     lds_store_u2(&lds.zbuf[m * lds.ldz + n], q);
-    if (row0 + m < g.R) store4t(g.KBART, g.ldk, (int64_t)j * g.Rp + row0 + m, n, q);
+    if (row0 + m < g.R) RAMPDE_STORE_G4(group4(g.KBART, g.ldk, (int64_t)j * g.Rp + row0 + m, n), q);
     return q;
   };
 
@@ -774,7 +774,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
         for (int mt = 0; mt < MT; ++mt) {
           const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
           lds_store_u2(&lds.zbuf[m * lds.ldz + n], yhat[nt][mt]);
-          if (row0 + m < g.R) store4t(g.ZT, g.ldk, row0 + m, n, yhat[nt][mt]);
+          if (row0 + m < g.R) RAMPDE_STORE_G4(group4(g.ZT, g.ldk, row0 + m, n), yhat[nt][mt]);
         }
     }
     __syncthreads();
@@ -806,7 +806,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
               for (int r = 0; r < 4; ++r) z[r] = fmaf(h, fmaf(aj, kf[r], incr[r]), yh[r]);
               const uint2 zq = pack4<T>(z);
               lds_store_u2(&lds.zbuf[m * lds.ldz + n], zq);
-              if (row0 + m < g.R) store4t(g.ZT, g.ldk, (int64_t)(j + 1) * g.Rp + row0 + m, n, zq);
+              if (row0 + m < g.R) RAMPDE_STORE_G4(group4(g.ZT, g.ldk, (int64_t)(j + 1) * g.Rp + row0 + m, n), zq);
             } else {
               make_kbar(s - 1, nt, mt, m, n, nullptr);  // the slope of the last stage is not needed again
             }
@@ -845,15 +845,13 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
       const PassDesc p = bwd_pass(g, l);
       const PassDesc nx = bwd_pass(g, l - 1);
       const bool next_is_last = (l == 1);
-      const uint16_t* act = g.ACT[l - 1] + (size_t)j * g.R * g.layer[l].Kpad;
+      uint16_t* actT = g.ACTT[l - 1];
       uint16_t* goutT = g.DELTAT[l - 1];
       const int64_t kj = (int64_t)j * g.Rp + row0;
-      const int ldg = g.layer[l].Kpad;
       lds_u16* out = lds.out(q);
       const int ldp = lds.ldp;
       auto pre_act = [&](int n, int m) {
-                return (row0 + m < g.R) ? *reinterpret_cast<const uint2*>(&act[(size_t)(row0 + m) * ldg + n])
-                                        : make_uint2(0u, 0u);
+                return (row0 + m < g.R) ? *group4(actT, g.ldk, kj + m, n) : make_uint2(0u, 0u);
               };
       auto epi_delta = [&](const f32x4& acc, uint2 pf, int, int, int n, int m) {
                 float a[4], v[4];
@@ -863,7 +861,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
                 const uint2 dq = pack4<T>(v);
                 lds_store_u2(&out[m * ldp + n], dq);
                 if (row0 + m < g.R) {
-                  store4t(goutT, g.ldk, kj + m, n, dq);
+                  RAMPDE_STORE_G4(group4(goutT, g.ldk, kj + m, n), dq);
                   bad = bad || any_nonfinite4<T>(dq);
                 }
               };
@@ -918,10 +916,16 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
   block_amax(bits, &g.ctl->amax_bits);
 
   // ---- the last workgroup to get here takes the decision of this step (accept / grow, or poison)
+  // (the flags and the max-norm travel by device-scope atomics; one fence per workgroup orders
+  // them before the arrival counter)
   __shared__ int is_last;
-  __threadfence();
   __syncthreads();
-  if (tid == 0) is_last = (atomicAdd(&g.ctl->done, 1) == (int)gridDim.x - 1);
+  if (tid == 0) {
+#ifndef RAMPDE_PROBE_NOFENCE
+    __threadfence();
+#endif
+    is_last = (atomicAdd(&g.ctl->done, 1) == (int)gridDim.x - 1);
+  }
   __syncthreads();
   if (is_last && tid == 0) {
     __threadfence();

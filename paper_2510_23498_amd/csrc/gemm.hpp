@@ -323,31 +323,35 @@ __global__ __launch_bounds__(256) void gemm_tn(GemmTN g) {
 
 // ------------------------------------------------------------------------------------
 // Parameter gradients of one adjoint step for dense networks whose cotangents and layer
-// inputs were stored FEATURE-MAJOR ([feature][k], k = stage * Rp + row, Rp = rows padded to
-// 64, padding zero) by the row-tile-persistent adjoint kernel.  With k contiguous both operands
-// of  dW_l = delta_l^T act_{l-1}  are "K-contiguous", i.e. the same staging as gemm_nt applies
-// and nothing has to be transposed.  One launch covers every layer:
-//   blocks [0, gemm_blocks)  : 128 x 128 output tiles x K-chunks, fp32 atomics into dW_l
-//   blocks [gemm_blocks, ..) : row sums of delta_l^T for db_l and the time-column gradient
+// inputs were stored FEATURE-GROUP-MAJOR by the row-tile-persistent adjoint kernel: element
+// (feature f, k) at ((f / 4) * ldk + k) * 4 + f % 4, k = stage * Rp + row, Rp = rows padded to
+// 64, padding zero.  For a feature group k runs contiguously, so the tiles of both operands of
+// dW_l = delta_l^T act_{l-1}  are read with coalesced 16-byte loads (2 k x 4 features) and
+// regrouped into k-contiguous LDS rows on the way in.  One launch covers every layer:
+//   blocks [0, gemm_blocks)  : 128 x 128 output tiles x K-chunks; chunk c accumulates into its own
+//                              copy c of the gradient vector (no atomics, fixed summation order);
+//                              the copies are summed once at the end of the backward pass
+//   the blocks of the first tile column also sum their cotangent tile over k (from LDS) for db_l
+//   and the time-column gradient;
 // All contributions are scaled by h / S_step (paper Sec. 3, update of g).
 struct WgradLayer {
-  const uint16_t* DT;   // [NaPad][ldk] cotangent of the layer's output
-  const uint16_t* AT;   // [NbPad][ldk] the layer's input
-  float* G;             // dW_l block of the gradient vector, row pitch ldg
+  const uint16_t* DT;   // [NaPad / 4][ldk][4] cotangent of the layer's output
+  const uint16_t* AT;   // [NbPad / 4][ldk][4] the layer's input
+  float* G;             // dW_l block of partial-gradient copy 0, row pitch ldg
   float* gb;            // db_l
   float* gwt;           // time-column gradient (element stride ldg) or null
   int ldg;
   int Na, Nb;           // valid extents
   int NaPad, NbPad;     // rows that exist in DT / AT
   int tiles_a, tiles_b; // 128-tiles
-  int blk0;             // first gemm block of this layer
-  int rs0;              // first row-sum block of this layer (relative to gemm_blocks)
+  int blk0;             // first block of this layer
 };
 
 struct WgradArgs {
   WgradLayer layer[8];
   int L;
   int gemm_blocks;
+  int64_t P;            // parameters: distance between the per-K-chunk copies of the gradient
   int ksplits;          // K-chunks per output tile
   int kchunk;           // k extent of a chunk (multiple of 64)
   int64_t ldk;          // s * Rp
@@ -364,40 +368,6 @@ __global__ __launch_bounds__(256) void wgrad_feature_major(WgradArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float scale = g.h / g.ctl->S_step;
   int bid = blockIdx.x;
-
-  if (bid >= g.gemm_blocks) {
-    // ---- row sums: one wavefront per feature row of delta^T
-    bid -= g.gemm_blocks;
-    WgradLayer y = g.layer[0];
-#pragma unroll
-    for (int q = 1; q < 8; ++q)
-      if (q < g.L && bid >= g.layer[q].rs0) y = g.layer[q];
-    const int f = (bid - y.rs0) * 4 + wave;
-    if (f >= y.Na) return;
-    const uint16_t* row = y.DT + (size_t)f * g.ldk;
-    float sb = 0.f, st = 0.f;
-    for (int64_t k = (int64_t)lane * 8; k < g.ldk; k += 64 * 8) {
-      const u16x8 v = *reinterpret_cast<const u16x8*>(row + k);
-      float part = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) part += Low<T>::to_f32(v[e]);
-      const int j = (int)(k / g.Rp);
-      float tau = 0.f;
-#pragma unroll
-      for (int q = 0; q < kMaxStages; ++q) tau = (q == j) ? g.taus[q] : tau;
-      sb += part;
-      st = fmaf(tau, part, st);
-    }
-    for (int o = 32; o > 0; o >>= 1) {
-      sb += __shfl_xor(sb, o);
-      st += __shfl_xor(st, o);
-    }
-    if (lane == 0) {
-      unsafeAtomicAdd(&y.gb[f], scale * sb);
-      if (y.gwt) unsafeAtomicAdd(&y.gwt[(size_t)f * y.ldg], scale * st);
-    }
-    return;
-  }
 
   // ---- 128 x 128 tile of dW_l over one K-chunk
   WgradLayer y = g.layer[0];
@@ -417,26 +387,45 @@ __global__ __launch_bounds__(256) void wgrad_feature_major(WgradArgs g) {
   __shared__ __attribute__((aligned(16))) uint16_t sA[128 * LDS_PITCH];
   __shared__ __attribute__((aligned(16))) uint16_t sB[128 * LDS_PITCH];
   const int wm = wave >> 1, wn = wave & 1;
-  u16x8 ra[4], rb[4];
-  auto load_tiles = [&](int64_t k0) {
+  // tile of an operand: 32 feature groups x 64 k.  A thread owns one feature group and 8
+  // consecutive k: 64 contiguous bytes in memory (8 k x 4 features), which it regroups in
+  // registers into 4 rows of 8 k (one per feature) for k-contiguous LDS rows.
+  // The loads run WG_STAGES k-steps ahead of the MFMAs (a workgroup streams its operands once,
+  // from the other XCDs' writes via memory: the latency is long and there is no reuse to hide it).
+  constexpr int WG_STAGES = 3;
+  const int fg = tid >> 3, oct = tid & 7;
+  u16x8 ra[WG_STAGES][4], rb[WG_STAGES][4];
+  // feature groups beyond the padded extent read group 0 instead and are masked in the epilogue
+  const uint16_t* pa0 = y.DT + ((size_t)((a0 + fg * 4 < y.NaPad) ? a0 / 4 + fg : 0) * g.ldk + oct * 8) * 4;
+  const uint16_t* pb0 = y.AT + ((size_t)((b0 + fg * 4 < y.NbPad) ? b0 / 4 + fg : 0) * g.ldk + oct * 8) * 4;
+#ifdef RAMPDE_PROBE_NOGEMMLOOP
+  const int nsteps = 1;
+#else
+  const int nsteps = (int)((k_end - k_begin) / BK);
+#endif
+  auto load_tiles = [&](u16x8 (&qa)[4], u16x8 (&qb)[4], int step) {
+    const int64_t k0 = k_begin + (int64_t)(step < nsteps ? step : nsteps - 1) * BK;  // clamped: branch-free
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int id = tid + i * 256;
-      const int row = id >> 3, kc = (id & 7) * 8;
-      u16x8 va = {0, 0, 0, 0, 0, 0, 0, 0}, vb = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (a0 + row < y.NaPad) va = *reinterpret_cast<const u16x8*>(y.DT + (size_t)(a0 + row) * g.ldk + k0 + kc);
-      if (b0 + row < y.NbPad) vb = *reinterpret_cast<const u16x8*>(y.AT + (size_t)(b0 + row) * g.ldk + k0 + kc);
-      ra[i] = va;
-      rb[i] = vb;
+      qa[i] = *reinterpret_cast<const u16x8*>(pa0 + k0 * 4 + i * 8);  // k = 2i, 2i+1
+      qb[i] = *reinterpret_cast<const u16x8*>(pb0 + k0 * 4 + i * 8);
     }
   };
-  auto store_tiles = [&]() {
+  auto regroup_store = [&](uint16_t* sX, const u16x8 (&r)[4]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + i * 256;
-      *reinterpret_cast<u16x8*>(&sA[(id >> 3) * LDS_PITCH + (id & 7) * 8]) = ra[i];
-      *reinterpret_cast<u16x8*>(&sB[(id >> 3) * LDS_PITCH + (id & 7) * 8]) = rb[i];
+    for (int f = 0; f < 4; ++f) {
+      u16x8 o;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        o[2 * i] = r[i][f];
+        o[2 * i + 1] = r[i][4 + f];
+      }
+      *reinterpret_cast<u16x8*>(&sX[(fg * 4 + f) * LDS_PITCH + oct * 8]) = o;
     }
+  };
+  auto store_tiles = [&](const u16x8 (&qa)[4], const u16x8 (&qb)[4]) {
+    regroup_store(sA, qa);
+    regroup_store(sB, qb);
   };
   f32x16 acc[2][2];
 #pragma unroll
@@ -447,30 +436,64 @@ __global__ __launch_bounds__(256) void wgrad_feature_major(WgradArgs g) {
       for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.f;
 
   const int frow = lane & 31, fk = (lane >> 5) * 8;
-  load_tiles(k_begin);
-  store_tiles();
-  __syncthreads();
-  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
-    const bool more = k0 + BK < k_end;
-    if (more) load_tiles(k0 + BK);
+  float sum_b = 0.f, sum_t = 0.f;
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      u16x8 fa[2], fb[2];
+  for (int u = 0; u < WG_STAGES; ++u) load_tiles(ra[u], rb[u], u);
+  for (int step0 = 0; step0 < nsteps; step0 += WG_STAGES) {
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
-        fa[a] = *reinterpret_cast<const u16x8*>(&sA[(wm * 64 + a * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-        fb[b] = *reinterpret_cast<const u16x8*>(&sB[(wn * 64 + b * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = Low<T>::mfma32(fa[a], fb[b], acc[a][b]);
-    }
-    __syncthreads();
-    if (more) {
-      store_tiles();
+    for (int u = 0; u < WG_STAGES; ++u) {
+      const int step = step0 + u;  // steps past the end recompute nothing: their tiles are zeroed
+      store_tiles(ra[u], rb[u]);
       __syncthreads();
+      load_tiles(ra[u], rb[u], step + WG_STAGES);
+      if (step < nsteps) {
+        if (tb == 0) {
+          // sums of the cotangent tile over k for db_l and the time-column gradient: thread ->
+          // (feature tid / 2, half tid % 2 of the 64 k); a k-step lies within one stage
+          const int64_t k0 = k_begin + (int64_t)step * BK;
+          const int j = (int)(k0 / g.Rp);
+          float tau = 0.f;
+#pragma unroll
+          for (int q = 0; q < kMaxStages; ++q) tau = (q == j) ? g.taus[q] : tau;
+          float part = 0.f;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const u16x8 v = *reinterpret_cast<const u16x8*>(&sA[(tid >> 1) * LDS_PITCH + (tid & 1) * 32 + c * 8]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) part += Low<T>::to_f32(v[e]);
+          }
+          sum_b += part;
+          sum_t = fmaf(tau, part, sum_t);
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+          u16x8 fa[2], fb[2];
+#pragma unroll
+          for (int a = 0; a < 2; ++a)
+            fa[a] = *reinterpret_cast<const u16x8*>(&sA[(wm * 64 + a * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+            fb[b] = *reinterpret_cast<const u16x8*>(&sB[(wn * 64 + b * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
+#pragma unroll
+          for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) acc[a][b] = Low<T>::mfma32(fa[a], fb[b], acc[a][b]);
+        }
+      }
+      __syncthreads();
+    }
+  }
+  if (tb == 0) {
+    sum_b += __shfl_xor(sum_b, 1);
+    sum_t += __shfl_xor(sum_t, 1);
+    const int na = a0 + (tid >> 1);
+    if ((tid & 1) == 0 && na < y.Na) {
+      float* db = y.gb + (size_t)split * g.P + na;
+      *db = fmaf(scale, sum_b, *db);
+      if (y.gwt) {
+        float* dt = y.gwt + (size_t)split * g.P + (size_t)na * y.ldg;
+        *dt = fmaf(scale, sum_t, *dt);
+      }
     }
   }
 #pragma unroll
@@ -481,10 +504,26 @@ __global__ __launch_bounds__(256) void wgrad_feature_major(WgradArgs g) {
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
         const int na = a0 + wm * 64 + a * 32 + 8 * (q >> 2) + 4 * (lane >> 5) + (q & 3);
-        if (na < y.Na && nb < y.Nb) unsafeAtomicAdd(&y.G[(size_t)na * y.ldg + nb], scale * acc[a][b][q]);
+        // every (K-chunk, tile) owns its slot of the partial-gradient copies: plain read-modify-write
+        if (na < y.Na && nb < y.Nb) {
+          float* dst = y.G + (size_t)split * g.P + (size_t)na * y.ldg + nb;
+          *dst = fmaf(scale, acc[a][b][q], *dst);
+        }
       }
     }
   }
+}
+
+
+// g[i] += sum_c part[c][i]   (end of the backward pass: fold the per-K-chunk copies)
+__global__ void reduce_partial_gradients(float* __restrict__ g, const float* __restrict__ part, int64_t P, int copies,
+                                         const Ctl* ctl) {
+  if (ctl->poison) return;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= P) return;
+  float acc = 0.f;
+  for (int c = 0; c < copies; ++c) acc += part[(size_t)c * P + i];
+  g[i] += acc;
 }
 
 }  // namespace rampde

@@ -78,6 +78,8 @@ struct Plan {
   int nparam = 0, wt_off = 0;
   bool k_in_lds = false;
   int64_t Rp = 0, ldk = 0;          // feature-major buffers: k = stage * Rp + row
+  int ksplits = 1, kchunk = 64;     // K-chunks of the parameter-gradient contraction
+  size_t gpart = 0;                 // ksplits copies of the gradient vector
   size_t ZT = 0, KBART = 0;
   std::vector<size_t> ACTT, DELTAT;
 };
@@ -138,6 +140,8 @@ static bool build_layers(const rampde_velocity* vel, Plan& p, int hidden_pad = k
   p.dpad = pad64(p.d);
   return true;
 }
+
+static int wgrad_target_blocks();
 
 static bool fused_candidate(const rampde_velocity* vel, const rampde_policy* pol) {
   if (!vel || vel->kind != RAMPDE_VEL_MLP || (pol && (pol->flags & RAMPDE_PER_LAYER_KERNELS))) return false;
@@ -218,17 +222,27 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
   }
   if (p.fused) {
     // row-tile-persistent kernels: slopes / stage cotangents only when they do not fit in LDS;
-    // the adjoint keeps row-major hidden activations (for tanh') and feature-major copies of
-    // everything the parameter-gradient contraction reads
+    // the adjoint stores everything the parameter-gradient contraction (and tanh') reads
+    // feature-group-major
     p.K = take((size_t)p.s * p.R * p.dpad * 2);
     if (is_backward) {
       p.ZBAR = take((size_t)p.s * p.R * p.dpad * 2);
       p.Rp = (p.R + 63) / 64 * 64;
       p.ldk = (int64_t)p.s * p.Rp;
+      {
+        int tiles = 0;
+        for (auto& y : p.layers) tiles += ((y.Npad + 127) / 128) * ((y.Kpad + 127) / 128);
+        // K-chunks: enough workgroups to fill the chip, but at least 256 k per chunk
+        int64_t ks = (wgrad_target_blocks() + tiles - 1) / tiles;
+        ks = std::max<int64_t>(1, std::min<int64_t>(ks, p.ldk / 256 > 0 ? p.ldk / 256 : 1));
+        const int64_t kc = ((p.ldk + ks - 1) / ks + 63) / 64 * 64;
+        p.kchunk = (int)kc;
+        p.ksplits = (int)((p.ldk + kc - 1) / kc);
+        p.gpart = take(sizeof(float) * (size_t)p.ksplits * p.P);
+      }
       p.ZT = take((size_t)p.dpad * p.ldk * 2);
       p.KBART = take((size_t)p.dpad * p.ldk * 2);
       for (int l = 0; l + 1 < p.L; ++l) {
-        p.ACT.push_back(take((size_t)p.s * p.R * p.layers[l].Npad * 2));
         p.ACTT.push_back(take((size_t)p.layers[l].Npad * p.ldk * 2));
         p.DELTAT.push_back(take((size_t)p.layers[l].Npad * p.ldk * 2));
       }
@@ -283,7 +297,7 @@ static int wgrad_target_blocks() {
   static int v = [] {
     const char* e = getenv("RAMPDE_WGRAD_BLOCKS");
     const int x = e ? atoi(e) : 0;
-    return x > 0 ? x : 512;
+    return x > 0 ? x : 256;
   }();
   return v;
 }
@@ -700,25 +714,20 @@ struct Runner {
   }
 
   // parameter gradients from the feature-major buffers of the row-tile-persistent adjoint kernel
-  void param_grads_fused(float h, const Coefs& taus, float* grad_theta) {
+  void param_grads_fused(float h, const Coefs& taus) {
+    float* grad_theta = f32(p.gpart);  // copy 0; chunk c adds into copy c
     WgradArgs w{};
     w.L = p.L;
-    int tiles = 0;
-    for (int l = 0; l < p.L; ++l) tiles += ((p.layers[l].Npad + 127) / 128) * ((p.layers[l].Kpad + 127) / 128);
-    // K-chunks: enough workgroups to fill the chip, but at least 256 k per chunk
-    int64_t ksplits = (wgrad_target_blocks() + tiles - 1) / tiles;
-    ksplits = std::max<int64_t>(1, std::min<int64_t>(ksplits, p.ldk / 256 > 0 ? p.ldk / 256 : 1));
-    int64_t kchunk = ((p.ldk + ksplits - 1) / ksplits + 63) / 64 * 64;
-    ksplits = (p.ldk + kchunk - 1) / kchunk;
-    w.ksplits = (int)ksplits;
-    w.kchunk = (int)kchunk;
+    w.ksplits = p.ksplits;
+    w.kchunk = p.kchunk;
+    w.P = p.P;
     w.ldk = p.ldk;
     w.Rp = p.Rp;
     w.s = p.s;
     for (int j = 0; j < kMaxStages; ++j) w.taus[j] = j < p.s ? taus.v[j] : 0.f;
     w.h = h;
     w.ctl = ctl;
-    int blk = 0, rs = 0;
+    int blk = 0;
     double flops = 0.0;
     for (int l = 0; l < p.L; ++l) {
       const Layer& y = p.layers[l];
@@ -736,14 +745,12 @@ struct Runner {
       d.tiles_a = (y.Npad + 127) / 128;
       d.tiles_b = (y.Kpad + 127) / 128;
       d.blk0 = blk;
-      d.rs0 = rs;
       blk += d.tiles_a * d.tiles_b * w.ksplits;
-      rs += (y.out + 3) / 4;
       flops += 2.0 * (double)p.ldk * y.Npad * y.Kpad;
     }
     w.gemm_blocks = blk;
     TimeScope ts(RAMPDE_K_WGRAD_GEMM, flops, st);
-    wgrad_feature_major<T><<<blk + rs, 256, 0, st>>>(w);
+    wgrad_feature_major<T><<<blk, 256, 0, st>>>(w);
   }
 
   int backward(const float* theta, const double* tgrid, int N, const rampde_tableau* tab, const rampde_policy* pol,
@@ -765,7 +772,6 @@ struct Runner {
       fa = fused_args(tab, N);
       fa.ckpt = const_cast<uint16_t*>(ckpt);
       for (int l = 0; l + 1 < p.L; ++l) {
-        fa.ACT[l] = u16(p.ACT[l]);
         fa.ACTT[l] = u16(p.ACTT[l]);
         fa.DELTAT[l] = u16(p.DELTAT[l]);
       }
@@ -774,6 +780,7 @@ struct Runner {
       fa.ldk = p.ldk;
       fa.Rp = p.Rp;
       fa.ZBAR = u16(p.ZBAR);
+      fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + p.gpart), (size_t)p.ksplits * p.P);
       if (p.Rp != p.R) {
         // rows R..Rp of every stage are padding of the contraction: they must read as zero
         const size_t first = p.ZT, last = p.DELTAT.empty() ? p.KBART + align256((size_t)p.dpad * p.ldk * 2)
@@ -824,13 +831,16 @@ struct Runner {
           const float h = (float)(tgrid[i + 1] - tgrid[i]);
           Coefs taus{};
           for (int j = 0; j < p.s; ++j) taus.v[j] = round_low_host((float)(tgrid[i] + tab->c[j] * (double)h), pol->low);
-          param_grads_fused(h, taus, grad_theta);
+          param_grads_fused(h, taus);
         } else {
           backward_step(i, tgrid, tab, pol, ckpt, a, gys_at(i), grad_theta, dynamic, detect,
                         i == from ? recompute_first : true);
         }
       }
-      if (use_fused) a = grad_y0;
+      if (use_fused) {
+        a = grad_y0;
+        reduce_partial_gradients<<<blocks_for(p.P, 256), 256, 0, st>>>(grad_theta, f32(p.gpart), p.P, p.ksplits, ctl);
+      }
       HIP_TRY(hipGetLastError());
       if (!must_sync) break;
       HIP_TRY(hipMemcpyAsync(&hctl, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
