@@ -132,7 +132,7 @@ class Config:
     @property
     def n_params(self) -> int:
         if self.kind == "mlp":
-            return sum((self.widths[l] + 1) * self.widths[l + 1] + self.widths[l + 1]
+            return sum((self.widths[l] + (1 if l == 0 else 0)) * self.widths[l + 1] + self.widths[l + 1]
                        for l in range(len(self.widths) - 1))
         return 2 * (self.C * (self.C + 1) * 9 + self.C)
 
