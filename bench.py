@@ -32,7 +32,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--cpu-steps", type=int, default=2, help="RK steps of the oracle sample")
+    ap.add_argument("--cpu-steps", type=int, default=0,
+                    help="RK steps of the oracle sample (0: the whole grid for the benchmark workload, "
+                         "1-2 steps for the larger ones: about 10-30 s of CPU work)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -137,7 +139,8 @@ def main():
     }
 
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(cfg, theta_np, y0_np, target_np, args.cpu_steps)
+        default_steps = {"cfg1": cfg.N, "cfg2": cfg.N, "cfg3": 1, "cfg4": 1, "cfg5": 16}.get(cfg.name, 1)
+        out["cpu_baseline"] = cpu_baseline(cfg, theta_np, y0_np, target_np, args.cpu_steps or default_steps)
     print(json.dumps(out))
 
 

@@ -61,6 +61,30 @@ def run_oracle(cfg: wl.Config, theta, y0, target, mode: str, scaling: str = None
                 failed_step=res.failed_step)
 
 
+def run_oracle_rows(cfg: wl.Config, theta, y0, target, rows, mode: str):
+    """Oracle forward + adjoint on a sample of batch rows of a full-size workload.  Samples are
+    independent in the forward recursion and in the adjoint (paper Sec. 3 assumes batch size one),
+    so y_N, the stored states and dL/dy_0 of these rows are those of the full batch -- in fp64 mode
+    exactly, in emulation mode as long as the batch-wide adjoint scale causes no range event.
+    The mean-type losses are normalised by the FULL batch size."""
+    from oracle import rampde_oracle as orc
+    rows = np.asarray(rows)
+    sub = cfg.with_(B=len(rows))
+    vel = oracle_velocity(sub)
+    tab = wl.TABLEAUX[cfg.tableau]
+    low = cfg.low if mode == "emul" else "f64"
+    pol = orc.Policy(low=low, scaling=wl.resolve_scaling(cfg))
+    tgrid = cfg.tgrid()
+    yN, ckpt = orc.odeint_fwd(vel, theta, y0[rows].reshape(len(rows), -1), tgrid, tab, pol)
+    yN32 = yN.astype(np.float32).reshape(sub.state_shape)
+    _, gyN = wl.loss_and_grad(sub, yN32, None if target is None else target[rows])
+    if cfg.loss in ("mse", "mean_sq"):
+        gyN = (gyN.astype(np.float64) * (len(rows) / cfg.B)).astype(np.float32)
+    res = orc.odeint_bwd(vel, theta, tgrid, tab, pol, ckpt, gyN.reshape(len(rows), -1))
+    return dict(yN=yN.reshape(sub.state_shape), ckpt=ckpt, grad_y0=res.grad_y0.reshape(sub.state_shape),
+                status=res.status)
+
+
 # ------------------------------------------------------------------ HIP side
 def gpu_descriptors(cfg: wl.Config, scaling: str = None, k_max: int = 16, flags: int = 0):
     from paper_2510_23498_amd import binding as rb
