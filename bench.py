@@ -35,6 +35,10 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=0,
                     help="RK steps of the oracle sample (0: the whole grid for the benchmark workload, "
                          "1-2 steps for the larger ones: about 10-30 s of CPU work)")
+    ap.add_argument("--calibrate-mib", type=int, default=0,
+                    help="before the timed region run ONE plain elementwise copy (read + write) of this many MiB: "
+                         "under `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE` its counter value calibrates the HBM byte "
+                         "counters of the other kernels")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -85,6 +89,14 @@ def main():
         grad_theta.zero_()
         rb.rampde_odeint_bwd(vel, theta, tgrid, tab, pol, ckpt, grad_yN, grad_y0=grad_y0, grad_theta=grad_theta,
                              workspace=ws_b, want_info=dynamic)
+
+    if args.calibrate_mib > 0:
+        src = torch.ones(args.calibrate_mib * (1 << 18), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)  # one elementwise kernel: reads and writes calibrate_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         one_pass()
