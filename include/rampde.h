@@ -17,10 +17,13 @@
  *     from the caller's workspace (size from rampde_workspace_bytes).
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*, may be NULL
  *     for the default stream).  rampde_odeint_fwd never synchronises.  rampde_odeint_bwd
- *     synchronises the stream once before returning (it must read the outcome of the
- *     overflow detector) -- and once more per detected overflow, to retry from that step.
+ *     synchronises the stream once before returning when it has to read something back: under
+ *     DYNAMIC / NONE_SAFE scaling (the outcome of the overflow detector), or when scale_hist /
+ *     stats are requested -- and once more per detected overflow, to retry from that step.
+ *     Under SCALE_NONE with scale_hist = stats = NULL it does not synchronise at all.
  *   - Return value: 0 on success, otherwise a rampde_status code; rampde_strerror gives
- *     a message.  No exceptions, no global state besides an immutable device-property cache.
+ *     a message.  No exceptions; no global state except the optional timing facility below.
+ *   - Calls that share a workspace must not overlap; distinct workspaces on distinct streams may.
  *   - theta layout (flat fp32, also the layout of grad_theta):
  *       MLP  : for each layer l: W_l[out_l][in_l] row-major, then b_l[out_l];
  *              layer 1 has in_1 = d + 1 when time_input is set (time column LAST).
