@@ -131,7 +131,10 @@ __global__ void combine_store(float* __restrict__ y, const uint16_t* __restrict_
 }
 
 // ------------------------------------------------------------------------- backward
-__global__ void ctl_reset(Ctl* ctl) {
+// also marks every step "not accepted yet" (scale 0): a step's parameter-gradient kernel runs
+// only once the step's scale has been recorded
+__global__ void ctl_reset(Ctl* ctl, float* scale_hist, int N) {
+  for (int i = 0; i < N; ++i) scale_hist[i] = 0.f;
   ctl->S = 1.f; ctl->attempt = 1; ctl->poison = 0; ctl->failed_step = -1; ctl->nonfinite = 0;
   ctl->amax_bits = 0; ctl->retries = 0; ctl->s_min = 1.f; ctl->s_max = 1.f; ctl->done = 0; ctl->S_step = 1.f;
 }

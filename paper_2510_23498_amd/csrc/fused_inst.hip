@@ -12,20 +12,21 @@ namespace rampde {
 namespace {
 
 template <class Kern>
-hipError_t launch_kernel(Kern kern, const FusedLaunch& l, const FusedArgs& a) {
+hipError_t launch_kernel(Kern kern, int waves, const FusedLaunch& l, const FusedArgs& a) {
   if (l.lds_bytes > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)l.lds_bytes);
     if (e != hipSuccess) return e;
   }
-  kern<<<l.grid, 64 * kFusedWaves, l.lds_bytes, l.stream>>>(a);
+  kern<<<l.grid, 64 * waves, l.lds_bytes, l.stream>>>(a);
   return hipGetLastError();
 }
 
 template <class T, int MT, int NTL>
 hipError_t pick_kernel(const FusedLaunch& l, const FusedArgs& a) {
-  if (l.adjoint) return launch_kernel(mlp_adjoint_step<T, MT, NTL, kFusedWaves, RAMPDE_INST_HP>, l, a);
-  return launch_kernel(mlp_forward_fused<T, MT, NTL, kFusedWaves, RAMPDE_INST_HP>, l, a);
+  if (l.adjoint && l.waves == 4) return launch_kernel(mlp_adjoint_step<T, MT, NTL, 4, RAMPDE_INST_HP>, 4, l, a);
+  if (l.adjoint) return launch_kernel(mlp_adjoint_step<T, MT, NTL, 8, RAMPDE_INST_HP>, 8, l, a);
+  return launch_kernel(mlp_forward_fused<T, MT, NTL, kForwardWaves, RAMPDE_INST_HP>, kForwardWaves, l, a);
 }
 
 template <class T, int MT>

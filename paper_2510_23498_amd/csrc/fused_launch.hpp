@@ -8,10 +8,14 @@
 
 namespace rampde {
 
-constexpr int kFusedWaves = 8;  // wavefronts per workgroup: two per SIMD
+// Wavefronts per workgroup.  Forward: 8, two per SIMD (hides the latencies of a single row tile).
+// Adjoint step: 8, or 4 (one per SIMD) for narrow networks, which leaves registers and LDS for the
+// parameter-gradient kernel of the previous step to run on the same compute units at the same time.
+constexpr int kForwardWaves = 8;
 
 struct FusedLaunch {
   int adjoint;   // 0: mlp_forward_fused, 1: mlp_adjoint_step
+  int waves;     // adjoint only: 4 or 8 wavefronts per workgroup
   int bf16;      // 0: fp16, 1: bfloat16
   int MT;        // row tile = 16 * MT rows, MT in {1, 2, 4}
   int NTL;       // dpad / 64, in {1, 2, 4}

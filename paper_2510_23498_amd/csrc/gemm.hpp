@@ -359,14 +359,16 @@ struct WgradArgs {
   int s;
   float taus[kMaxStages];
   float h;
-  const Ctl* ctl;
+  const float* scale_hist;  // [N + 1]: scale_hist[step] = accepted scale of the step, 0 = not accepted
+  int step;
 };
 
 template <class T>
-__global__ __launch_bounds__(256) void wgrad_feature_major(WgradArgs g) {
-  if (g.ctl->poison) return;
+__global__ __launch_bounds__(256, 2) void wgrad_feature_major(WgradArgs g) {
+  const float S = g.scale_hist[g.step];
+  if (S == 0.f) return;  // the step's cotangent chain was rejected (or never ran)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const float scale = g.h / g.ctl->S_step;
+  const float scale = g.h / S;
   int bid = blockIdx.x;
 
   // ---- 128 x 128 tile of dW_l over one K-chunk
@@ -392,7 +394,7 @@ __global__ __launch_bounds__(256) void wgrad_feature_major(WgradArgs g) {
   // registers into 4 rows of 8 k (one per feature) for k-contiguous LDS rows.
   // The loads run WG_STAGES k-steps ahead of the MFMAs (a workgroup streams its operands once,
   // from the other XCDs' writes via memory: the latency is long and there is no reuse to hide it).
-  constexpr int WG_STAGES = 3;
+  constexpr int WG_STAGES = 2;
   const int fg = tid >> 3, oct = tid & 7;
   u16x8 ra[WG_STAGES][4], rb[WG_STAGES][4];
   // feature groups beyond the padded extent read group 0 instead and are masked in the epilogue

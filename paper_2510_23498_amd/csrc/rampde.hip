@@ -77,10 +77,12 @@ struct Plan {
   size_t steptab = 0, a_alt = 0;
   int nparam = 0, wt_off = 0;
   bool k_in_lds = false;
+  bool overlap_wgrad = false;       // narrow nets: 4-wave adjoint kernel + parameter gradients on a helper stream
   int64_t Rp = 0, ldk = 0;          // feature-major buffers: k = stage * Rp + row
   int ksplits = 1, kchunk = 64;     // K-chunks of the parameter-gradient contraction
   size_t gpart = 0;                 // ksplits copies of the gradient vector
   size_t ZT = 0, KBART = 0;
+  size_t fm_stride = 0;             // distance between the two sets of feature-group-major buffers
   std::vector<size_t> ACTT, DELTAT;
 };
 
@@ -198,6 +200,7 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
       p.fused = true;
       p.MT = mt;
       p.k_in_lds = lds_need(mt, true) <= lds_limit;
+      p.overlap_wgrad = (mt == 1 && maxw <= 256);
       p.lds_bytes = lds_need(mt, p.k_in_lds);
       for (auto& y : p.layers) {
         y.Wf = take((size_t)y.Npad * y.Kpad * 2);
@@ -240,12 +243,17 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
         p.ksplits = (int)((p.ldk + kc - 1) / kc);
         p.gpart = take(sizeof(float) * (size_t)p.ksplits * p.P);
       }
+      // two sets of the per-step buffers: the parameter-gradient kernel of step i reads set i % 2
+      // on a helper stream while the adjoint kernel of step i - 1 already fills the other set
+      const size_t fm_begin = off;
       p.ZT = take((size_t)p.dpad * p.ldk * 2);
       p.KBART = take((size_t)p.dpad * p.ldk * 2);
       for (int l = 0; l + 1 < p.L; ++l) {
         p.ACTT.push_back(take((size_t)p.layers[l].Npad * p.ldk * 2));
         p.DELTAT.push_back(take((size_t)p.layers[l].Npad * p.ldk * 2));
       }
+      p.fm_stride = off - fm_begin;
+      take(p.fm_stride);  // second set
     }
   } else {
     p.Z = take((size_t)sbuf * p.R * p.dpad * 2);
@@ -348,6 +356,31 @@ __global__ void write_floats(FloatChunk c, float* dst, int count) {
   const int i = threadIdx.x;
   if (i < count) dst[i] = c.v[i];
 }
+
+// Helper stream on which the parameter-gradient kernel of step i runs while the adjoint kernel
+// of step i - 1 runs on the caller's stream (fork / join by events: from the caller's point of
+// view all work is still ordered on its stream).  One per process, default priority, created
+// on first use; events are pooled.  Calls of the backward pass from several host threads at
+// once would share it: they are serialised by the pool's owner (not supported concurrently).
+struct SideStream {
+  hipStream_t stream = nullptr;
+  std::vector<hipEvent_t> ev;  // 2 per step: adjoint done, parameter gradient done
+  static SideStream& get() {
+    static SideStream s;
+    return s;
+  }
+  int prepare(int N) {
+    if (!stream) HIP_TRY(hipStreamCreateWithFlags(&stream, hipStreamNonBlocking));
+    while ((int)ev.size() < 2 * N) {
+      hipEvent_t e;
+      HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+      ev.push_back(e);
+    }
+    return RAMPDE_OK;
+  }
+  hipEvent_t adjoint_done(int i) { return ev[2 * i]; }
+  hipEvent_t wgrad_done(int i) { return ev[2 * i + 1]; }
+};
 
 // ---------------------------------------------------------------- typed launch sequences
 template <class T>
@@ -517,6 +550,7 @@ struct Runner {
   int launch_fused(bool adjoint, const FusedArgs& a) {
     FusedLaunch l{};
     l.adjoint = adjoint ? 1 : 0;
+    l.waves = p.overlap_wgrad ? 4 : 8;
     l.bf16 = std::is_same<T, BF16>::value ? 1 : 0;
     l.MT = p.MT;
     l.NTL = p.dpad / 64;
@@ -714,8 +748,9 @@ struct Runner {
   }
 
   // parameter gradients from the feature-major buffers of the row-tile-persistent adjoint kernel
-  void param_grads_fused(float h, const Coefs& taus) {
+  void param_grads_fused(int step, float h, const Coefs& taus, hipStream_t stream) {
     float* grad_theta = f32(p.gpart);  // copy 0; chunk c adds into copy c
+    const size_t set = (size_t)(step & 1) * p.fm_stride;
     WgradArgs w{};
     w.L = p.L;
     w.ksplits = p.ksplits;
@@ -726,14 +761,15 @@ struct Runner {
     w.s = p.s;
     for (int j = 0; j < kMaxStages; ++j) w.taus[j] = j < p.s ? taus.v[j] : 0.f;
     w.h = h;
-    w.ctl = ctl;
+    w.scale_hist = f32(p.scale_hist);
+    w.step = step;
     int blk = 0;
     double flops = 0.0;
     for (int l = 0; l < p.L; ++l) {
       const Layer& y = p.layers[l];
       WgradLayer& d = w.layer[l];
-      d.DT = (l == p.L - 1) ? u16(p.KBART) : u16(p.DELTAT[l]);
-      d.AT = (l == 0) ? u16(p.ZT) : u16(p.ACTT[l - 1]);
+      d.DT = (l == p.L - 1) ? u16(p.KBART + set) : u16(p.DELTAT[l] + set);
+      d.AT = (l == 0) ? u16(p.ZT + set) : u16(p.ACTT[l - 1] + set);
       d.G = grad_theta + y.theta_w;
       d.gb = grad_theta + y.theta_b;
       d.gwt = y.has_time ? grad_theta + y.theta_w + y.in : nullptr;
@@ -749,8 +785,8 @@ struct Runner {
       flops += 2.0 * (double)p.ldk * y.Npad * y.Kpad;
     }
     w.gemm_blocks = blk;
-    TimeScope ts(RAMPDE_K_WGRAD_GEMM, flops, st);
-    wgrad_feature_major<T><<<blk, 256, 0, st>>>(w);
+    TimeScope ts(RAMPDE_K_WGRAD_GEMM, flops, stream);
+    wgrad_feature_major<T><<<blk, 256, 0, stream>>>(w);
   }
 
   int backward(const float* theta, const double* tgrid, int N, const rampde_tableau* tab, const rampde_policy* pol,
@@ -760,8 +796,13 @@ struct Runner {
     const int detect = dynamic || scaling == RAMPDE_SCALE_NONE_SAFE;
     const int k_max = pol->k_max > 0 ? pol->k_max : 16;
     const int HW = p.H * p.Wd;
-    ctl_reset<<<1, 1, 0, st>>>(ctl);
+    ctl_reset<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), N);
     cast_weights(theta);
+    SideStream& side = SideStream::get();
+    if (use_fused && p.overlap_wgrad) {
+      int rc = side.prepare(N);
+      if (rc) return rc;
+    }
     // fused path: the adjoint alternates between two buffers so that a step whose chain
     // overflowed leaves its input adjoint intact; step 0 writes grad_y0
     auto a_buf = [&](int i) -> float* { return (i % 2 == 0) ? grad_y0 : f32(p.a_alt); };
@@ -771,21 +812,13 @@ struct Runner {
       write_steptab(tgrid, N, tab, pol->low);
       fa = fused_args(tab, N);
       fa.ckpt = const_cast<uint16_t*>(ckpt);
-      for (int l = 0; l + 1 < p.L; ++l) {
-        fa.ACTT[l] = u16(p.ACTT[l]);
-        fa.DELTAT[l] = u16(p.DELTAT[l]);
-      }
-      fa.ZT = u16(p.ZT);
-      fa.KBART = u16(p.KBART);
       fa.ldk = p.ldk;
       fa.Rp = p.Rp;
       fa.ZBAR = u16(p.ZBAR);
       fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + p.gpart), (size_t)p.ksplits * p.P);
       if (p.Rp != p.R) {
         // rows R..Rp of every stage are padding of the contraction: they must read as zero
-        const size_t first = p.ZT, last = p.DELTAT.empty() ? p.KBART + align256((size_t)p.dpad * p.ldk * 2)
-                                                           : p.DELTAT.back() + align256((size_t)p.layers[p.L - 2].Npad * p.ldk * 2);
-        fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + first), (last - first) / 4);
+        fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + p.ZT), 2 * p.fm_stride / 4);
       }
       fa.ctl = ctl;
       fa.scale_hist = f32(p.scale_hist);
@@ -821,6 +854,15 @@ struct Runner {
     for (;;) {
       for (int i = from; i >= 0; --i) {
         if (use_fused) {
+          const size_t set = (size_t)(i & 1) * p.fm_stride;
+          for (int l = 0; l + 1 < p.L; ++l) {
+            fa.ACTT[l] = u16(p.ACTT[l] + set);
+            fa.DELTAT[l] = u16(p.DELTAT[l] + set);
+          }
+          fa.ZT = u16(p.ZT + set);
+          fa.KBART = u16(p.KBART + set);
+          // this set was last read by the parameter-gradient kernel of step i + 2
+          if (p.overlap_wgrad && i + 2 <= N - 1) HIP_TRY(hipStreamWaitEvent(st, side.wgrad_done(i + 2), 0));
           fa.step = i;
           fa.a_in = a_buf(i + 1);
           fa.a_out = a_buf(i);
@@ -831,7 +873,14 @@ struct Runner {
           const float h = (float)(tgrid[i + 1] - tgrid[i]);
           Coefs taus{};
           for (int j = 0; j < p.s; ++j) taus.v[j] = round_low_host((float)(tgrid[i] + tab->c[j] * (double)h), pol->low);
-          param_grads_fused(h, taus);
+          if (p.overlap_wgrad) {
+            HIP_TRY(hipEventRecord(side.adjoint_done(i), st));
+            HIP_TRY(hipStreamWaitEvent(side.stream, side.adjoint_done(i), 0));
+            param_grads_fused(i, h, taus, side.stream);
+            HIP_TRY(hipEventRecord(side.wgrad_done(i), side.stream));
+          } else {
+            param_grads_fused(i, h, taus, st);
+          }
         } else {
           backward_step(i, tgrid, tab, pol, ckpt, a, gys_at(i), grad_theta, dynamic, detect,
                         i == from ? recompute_first : true);
@@ -839,6 +888,7 @@ struct Runner {
       }
       if (use_fused) {
         a = grad_y0;
+        if (p.overlap_wgrad) HIP_TRY(hipStreamWaitEvent(st, side.wgrad_done(0), 0));  // helper stream is in order: joins all
         reduce_partial_gradients<<<blocks_for(p.P, 256), 256, 0, st>>>(grad_theta, f32(p.gpart), p.P, p.ksplits, ctl);
       }
       HIP_TRY(hipGetLastError());
