@@ -323,4 +323,168 @@ __global__ void fill_inf_if_poisoned(float* p, int64_t n, const Ctl* ctl) {
   if (i < n) p[i] = __builtin_inff();
 }
 
+
+// ----------------------------------------------------------------------------------------
+// 8-wide versions of the streaming kernels above, for state widths that are multiples of 8:
+// 16-byte accesses to the 16-bit arrays, 2 x 16-byte to the fp32 ones, one index division per
+// 8 elements, grid-stride loops.  Same arithmetic, element for element.
+template <class T>
+__device__ inline void unpack8(const u16x8& v, float (&f)[8]) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) f[e] = Low<T>::to_f32(v[e]);
+}
+template <class T>
+__device__ inline u16x8 pack8(const float (&f)[8]) {
+  u16x8 v;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = Low<T>::from_f32(f[e]);
+  return v;
+}
+__device__ inline void load8f(const float* p, float (&f)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+}
+__device__ inline void store8f(float* p, const float (&f)[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(f[0], f[1], f[2], f[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(f[4], f[5], f[6], f[7]);
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void stage_input_v8(const uint16_t* __restrict__ ck, int d,
+                                                      const uint16_t* __restrict__ K, int64_t stage_stride, int j,
+                                                      Coefs arow, float h, uint16_t* __restrict__ z, int ld, int64_t R,
+                                                      const Ctl* ctl) {
+  if (poisoned(ctl)) return;
+  const int gpr = ld >> 3;  // groups of 8 per padded row
+  const int64_t G = R * gpr;
+  for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < G; g += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = g / gpr;
+    const int c = (int)(g - r * gpr) << 3;
+    u16x8 q = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (c < d) {
+      q = *reinterpret_cast<const u16x8*>(ck + r * d + c);
+      if (j > 0) {
+        float incr[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, base[8], kl[8];
+        for (int l = 0; l < j; ++l) {
+          if (arow.v[l] != 0.f) {
+            unpack8<T>(*reinterpret_cast<const u16x8*>(K + l * stage_stride + r * ld + c), kl);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) incr[e] = fmaf(arow.v[l], kl[e], incr[e]);
+          }
+        }
+        unpack8<T>(q, base);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) base[e] = fmaf(h, incr[e], base[e]);
+        q = pack8<T>(base);
+      }
+    }
+    *reinterpret_cast<u16x8*>(z + r * ld + c) = q;
+  }
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void combine_store_v8(float* __restrict__ y, const uint16_t* __restrict__ K,
+                                                        int64_t stage_stride, int s, Coefs b, float h, int round_incr,
+                                                        uint16_t* __restrict__ ck_next, int d, int ld, int64_t R) {
+  const int gpr = d >> 3;
+  const int64_t G = R * gpr;
+  for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < G; g += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = g / gpr;
+    const int c = (int)(g - r * gpr) << 3;
+    float incr[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, kj[8], yv[8];
+    for (int j = 0; j < s; ++j) {
+      unpack8<T>(*reinterpret_cast<const u16x8*>(K + j * stage_stride + r * ld + c), kj);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) incr[e] = fmaf(b.v[j], kj[e], incr[e]);
+    }
+    load8f(y + r * d + c, yv);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (round_incr) incr[e] = Low<T>::to_f32(Low<T>::from_f32(incr[e]));
+      yv[e] = fmaf(h, incr[e], yv[e]);
+    }
+    store8f(y + r * d + c, yv);
+    *reinterpret_cast<u16x8*>(ck_next + r * d + c) = pack8<T>(yv);
+  }
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void stage_cotangent_v8(const float* __restrict__ a, int d,
+                                                          const uint16_t* __restrict__ zbar, int64_t stage_stride,
+                                                          int j, int s, float bj, Coefs acol, float h,
+                                                          uint16_t* __restrict__ kbar, int ld, int64_t R, Ctl* ctl,
+                                                          int detect) {
+  if (ctl->poison) return;
+  const int gpr = ld >> 3;
+  const int64_t G = R * gpr;
+  const float S = ctl->S;
+  bool bad = false;
+  for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < G; g += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = g / gpr;
+    const int c = (int)(g - r * gpr) << 3;
+    u16x8 q = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (c < d) {
+      float av[8], acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, zl[8], v[8];
+      load8f(a + r * d + c, av);
+      for (int l = j + 1; l < s; ++l) {
+        if (acol.v[l] != 0.f) {
+          unpack8<T>(*reinterpret_cast<const u16x8*>(zbar + l * stage_stride + r * ld + c), zl);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[e] = fmaf(acol.v[l], zl[e], acc[e]);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint16_t lam = Low<T>::from_f32(S * av[e]);
+        v[e] = fmaf(h, acc[e], bj * Low<T>::to_f32(lam));
+        bad = bad || Low<T>::nonfinite(lam);
+      }
+      q = pack8<T>(v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) bad = bad || Low<T>::nonfinite(q[e]);
+    }
+    *reinterpret_cast<u16x8*>(kbar + r * ld + c) = q;
+  }
+  if (detect) raise_if_any(bad, ctl);
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void adjoint_update_v8(float* __restrict__ a, int d,
+                                                         const uint16_t* __restrict__ zbar, int64_t stage_stride, int s,
+                                                         float h, const float* __restrict__ gys_i, int ld, int64_t R,
+                                                         Ctl* ctl) {
+  if (ctl->poison) return;
+  const int gpr = d >> 3;
+  const int64_t G = R * gpr;
+  const float hs = h / ctl->S;
+  unsigned bits = 0;
+  for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < G; g += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = g / gpr;
+    const int c = (int)(g - r * gpr) << 3;
+    float da[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, zj[8], av[8];
+    for (int j = 0; j < s; ++j) {
+      unpack8<T>(*reinterpret_cast<const u16x8*>(zbar + j * stage_stride + r * ld + c), zj);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) da[e] += zj[e];
+    }
+    load8f(a + r * d + c, av);
+    if (gys_i) {
+      float gy[8];
+      load8f(gys_i + r * d + c, gy);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) av[e] = fmaf(hs, da[e], av[e]) + gy[e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) av[e] = fmaf(hs, da[e], av[e]);
+    }
+    store8f(a + r * d + c, av);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const unsigned bb = __builtin_bit_cast(unsigned, fabsf(av[e]));
+      bits = bb > bits ? bb : bits;
+    }
+  }
+  block_amax(bits, &ctl->amax_bits);
+}
+
 }  // namespace rampde

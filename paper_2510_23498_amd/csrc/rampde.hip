@@ -437,8 +437,12 @@ struct Runner {
       uint16_t* z = u16(p.Z) + (size_t)jb * p.stage_stride;
       Coefs arow{};
       for (int l = 0; l < j; ++l) arow.v[l] = (float)tab->A[j * s + l];
-      stage_input<T><<<blocks_for(p.R * p.dpad, 256), 256, 0, st>>>(ck, p.d, u16(p.K), p.stage_stride, j, arow, h, z,
-                                                                   p.dpad, p.R, c);
+      if (vec8())
+        stage_input_v8<T><<<stream_blocks(p.R * (p.dpad / 8)), 256, 0, st>>>(ck, p.d, u16(p.K), p.stage_stride, j, arow,
+                                                                            h, z, p.dpad, p.R, c);
+      else
+        stage_input<T><<<blocks_for(p.R * p.dpad, 256), 256, 0, st>>>(ck, p.d, u16(p.K), p.stage_stride, j, arow, h, z,
+                                                                     p.dpad, p.R, c);
       const float tau = round_low_host((float)(t_i + tab->c[j] * (double)h), low);
       if (taus_out) taus_out[j] = tau;
       const uint16_t* in = z;
@@ -472,6 +476,13 @@ struct Runner {
         in = out;
       }
     }
+  }
+
+  // streaming kernels: 8-wide variants when the state width allows 16-byte accesses
+  bool vec8() const { return (p.d & 7) == 0; }
+  static unsigned stream_blocks(int64_t groups, int64_t cap = 4096) {  // grid-stride loops
+    const int64_t b = (groups + 255) / 256;
+    return (unsigned)std::max<int64_t>(1, std::min<int64_t>(b, cap));
   }
 
   // ------------------------------------------------ row-tile-persistent path (dense networks)
@@ -619,9 +630,14 @@ struct Runner {
       stages(ck, tgrid[i], h, tab, pol->low, 0, nullptr, nullptr);
       // bytes per state element: read y (4) + s slopes (2 each) + write y (4) + write checkpoint (2)
       TimeScope ts(RAMPDE_K_COMBINE_STORE, (double)p.n * (10.0 + 2.0 * p.s), st);
-      combine_store<T><<<blocks_for(p.n, 256), 256, 0, st>>>(y, u16(p.K), p.stage_stride, p.s, bw, h,
-                                                            (pol->flags & RAMPDE_ROUND_INCREMENT) ? 1 : 0,
-                                                            ckpt + (size_t)(i + 1) * p.n, p.d, p.dpad, p.R);
+      if (vec8())
+        combine_store_v8<T><<<stream_blocks(p.n / 8), 256, 0, st>>>(y, u16(p.K), p.stage_stride, p.s, bw, h,
+                                                                   (pol->flags & RAMPDE_ROUND_INCREMENT) ? 1 : 0,
+                                                                   ckpt + (size_t)(i + 1) * p.n, p.d, p.dpad, p.R);
+      else
+        combine_store<T><<<blocks_for(p.n, 256), 256, 0, st>>>(y, u16(p.K), p.stage_stride, p.s, bw, h,
+                                                              (pol->flags & RAMPDE_ROUND_INCREMENT) ? 1 : 0,
+                                                              ckpt + (size_t)(i + 1) * p.n, p.d, p.dpad, p.R);
     }
     if (p.conv) rows_to_nchw<<<blocks_for(p.n, 256), 256, 0, st>>>(y, yN, p.R, p.d, p.H * p.Wd, nullptr, 0);
     HIP_TRY(hipGetLastError());
@@ -645,9 +661,13 @@ struct Runner {
       Coefs acol{};
       for (int l = j + 1; l < s; ++l) acol.v[l] = (float)tab->A[l * s + j];
       uint16_t* kbar = u16(p.KBAR) + (size_t)j * p.stage_stride;
-      stage_cotangent<T><<<blocks_for(p.R * p.dpad, 256), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, j, s,
-                                                                       (float)tab->b[j], acol, h, kbar, p.dpad, p.R,
-                                                                       ctl, detect);
+      if (vec8())
+        stage_cotangent_v8<T><<<stream_blocks(p.R * (p.dpad / 8)), 256, 0, st>>>(
+            a, p.d, u16(p.ZBAR), p.stage_stride, j, s, (float)tab->b[j], acol, h, kbar, p.dpad, p.R, ctl, detect);
+      else
+        stage_cotangent<T><<<blocks_for(p.R * p.dpad, 256), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, j, s,
+                                                                         (float)tab->b[j], acol, h, kbar, p.dpad, p.R,
+                                                                         ctl, detect);
       const uint16_t* delta = kbar;
       for (int l = p.L - 1; l >= 0; --l) {
         const Layer& y = p.layers[l];
@@ -685,8 +705,12 @@ struct Runner {
     {
       // bytes per state element: read a (4) + s stage cotangents (2 each) + write a (4)
       TimeScope ts(RAMPDE_K_ADJOINT_UPDATE, (double)p.n * (8.0 + 2.0 * s), st);
-      adjoint_update<T><<<blocks_for(p.n, 256), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, s, h, gys_i, p.dpad,
-                                                             p.R, ctl);
+      if (vec8())
+        adjoint_update_v8<T><<<stream_blocks(p.n / 8, 1024), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, s, h, gys_i,
+                                                                    p.dpad, p.R, ctl);
+      else
+        adjoint_update<T><<<blocks_for(p.n, 256), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, s, h, gys_i,
+                                                               p.dpad, p.R, ctl);
     }
     scale_grow<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), i, Low<T>::p_bits, dynamic,
                                 (pol->flags & RAMPDE_GROW_RAW_NORM) ? 1 : 0);
