@@ -283,11 +283,10 @@ __device__ inline void tile_mma(f32x4 (&acc)[RW][MT], u16x8 (&ring)[PD][RW], con
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) a[0][mt] = *(const lds_u16x8*)(abase + mt * 16 * ldp);
 
-  if constexpr (KBC > 0) {
+  if constexpr (KBC > 0 && KBC <= 2 * PD) {
+    // short contraction: fully unrolled
 #pragma unroll
     for (int kb = 0; kb < KBC; ++kb) {
-      constexpr int dummy = 0;
-      (void)dummy;
       const int u = kb % PD;
       if (kb + 1 < KBC) {
 #pragma unroll
@@ -304,6 +303,40 @@ __device__ inline void tile_mma(f32x4 (&acc)[RW][MT], u16x8 (&ring)[PD][RW], con
         for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = wbase[(size_t)(kb + PD) * NTC * 64 + nt * 64];
       }
 #endif
+    }
+  } else if constexpr (KBC > 0) {
+    // long contraction (KBC a multiple of PD): a rolled steady-state loop that always refills,
+    // then the last PD k-blocks without refills; no clamps, no masks
+    static_assert(KBC % PD == 0 || KBC <= 2 * PD, "compile-time contraction lengths are multiples of the pipeline depth");
+#pragma unroll 1
+    for (int kb0 = 0; kb0 < KBC - PD; kb0 += PD) {
+      const glb_u16x8* wnext = wbase + (size_t)(kb0 + PD) * NTC * 64;
+      const lds_u16* an = abase + (kb0 + 1) * 32;
+#pragma unroll
+      for (int u = 0; u < PD; ++u) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) a[(u + 1) & 1][mt] = *(const lds_u16x8*)(an + mt * 16 * ldp + u * 32);
+#pragma unroll
+        for (int nt = 0; nt < NTG; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = Low<T>::mfma16(ring[u][nt], a[u & 1][mt], acc[nt][mt]);
+#ifndef RAMPDE_PROBE_NOLOAD
+#pragma unroll
+        for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = wnext[(size_t)u * NTC * 64 + nt * 64];
+#endif
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < PD; ++u) {
+      if (u + 1 < PD) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          a[(u + 1) & 1][mt] = *(const lds_u16x8*)(abase + mt * 16 * ldp + (KBC - PD + u + 1) * 32);
+      }
+#pragma unroll
+      for (int nt = 0; nt < NTG; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = Low<T>::mfma16(ring[u][nt], a[u & 1][mt], acc[nt][mt]);
     }
   } else {
     const int kstride = p.NT16 * 64;
@@ -501,11 +534,11 @@ struct StageStore {
   int dpad;
   int64_t stage_stride, row0, R;
   __device__ inline void put(int j, int m, int n, uint2 q) const {
-    if (in_lds) lds_store_u2(&lds[(j * 16 * MT + m) * dpad + n], q);
+    if (in_lds) lds_store_u2(&lds[(j * 16 * MT + m) * (dpad + 8) + n], q);  // row pitch padded: no bank conflicts
     else if (row0 + m < R) *reinterpret_cast<uint2*>(&glob[(size_t)j * stage_stride + (size_t)(row0 + m) * dpad + n]) = q;
   }
   __device__ inline uint2 get(int j, int m, int n) const {
-    if (in_lds) return lds_load_u2(&lds[(j * 16 * MT + m) * dpad + n]);
+    if (in_lds) return lds_load_u2(&lds[(j * 16 * MT + m) * (dpad + 8) + n]);
     if (row0 + m < R) return *reinterpret_cast<const uint2*>(&glob[(size_t)j * stage_stride + (size_t)(row0 + m) * dpad + n]);
     return make_uint2(0u, 0u);
   }

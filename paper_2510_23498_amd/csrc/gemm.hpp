@@ -413,16 +413,21 @@ __global__ __launch_bounds__(256, 2) void wgrad_feature_major(WgradArgs g) {
       qb[i] = *reinterpret_cast<const u16x8*>(pb0 + k0 * 4 + i * 8);
     }
   };
+  // r[i] = (k = 2i: f0 f1 f2 f3, k = 2i + 1: f0 f1 f2 f3); row of feature f = 8 consecutive k.
+  // One byte permute per output word: halves of word d (k even) and word d + 2 (k odd).
   auto regroup_store = [&](uint16_t* sX, const u16x8 (&r)[4]) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = __builtin_bit_cast(u32x4, r[i]);
 #pragma unroll
     for (int f = 0; f < 4; ++f) {
-      u16x8 o;
+      const int d = f >> 1;
+      const uint32_t sel = (f & 1) ? 0x07060302u : 0x05040100u;
+      u32x4 o;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        o[2 * i] = r[i][f];
-        o[2 * i + 1] = r[i][4 + f];
-      }
-      *reinterpret_cast<u16x8*>(&sX[(fg * 4 + f) * LDS_PITCH + oct * 8]) = o;
+      for (int i = 0; i < 4; ++i) o[i] = __builtin_amdgcn_perm(w[i][d + 2], w[i][d], sel);
+      *reinterpret_cast<u32x4*>(&sX[(fg * 4 + f) * LDS_PITCH + oct * 8]) = o;
     }
   };
   auto store_tiles = [&](const u16x8 (&qa)[4], const u16x8 (&qb)[4]) {

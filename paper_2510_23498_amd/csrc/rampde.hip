@@ -191,9 +191,10 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
     auto lds_need = [&](int mt, bool with_k) {
       const size_t tm = 16 * (size_t)mt;
       return (size_t)p.nparam * 4 + tm * (p.dpad + 8) * 2 + 2 * tm * p.ldp * 2 +
-             (with_k ? (size_t)p.s * tm * p.dpad * 2 : 0);
+             (with_k ? (size_t)p.s * tm * (p.dpad + 8) * 2 : 0);
     };
-    int mt = 4;
+    // (the adjoint kernel carries more per-tile state in registers: it spills beyond 32-row tiles)
+    int mt = is_backward ? 2 : 4;
     // largest row tile that still gives every compute unit a workgroup and fits the LDS tiles
     while (mt > 1 && ((p.R + 16 * mt - 1) / (16 * mt) < 256 || lds_need(mt, false) > lds_limit)) mt >>= 1;
     if (lds_need(mt, false) <= lds_limit) {
