@@ -141,9 +141,6 @@ __global__ void cast_dense_fragments(const float* __restrict__ W, int out, int i
 // |x| > 0.1 and a relative error that grows like 1.5e-7 / |x| towards zero: still 50 times below the
 // half-spacing of fp16 (2^-12 relative) at |x| = 1e-3.  The result is rounded to 16 bits by the caller.
 __device__ inline float tanh_fast(float x) {
-#ifdef RAMPDE_PROBE_NOTANH
-  return x * 0.5f;
-#endif
   const float e = __builtin_amdgcn_exp2f(2.885390081777927f * x);
   return fmaf(-2.f, __builtin_amdgcn_rcpf(e + 1.f), 1.f);
 }
@@ -225,11 +222,7 @@ __device__ inline void store4h(uint16_t* p, int64_t row, int64_t R, int c, int d
 __device__ inline uint2* group4(uint16_t* XT, int64_t ldk, int64_t k, int n) {
   return reinterpret_cast<uint2*>(XT + ((size_t)(n >> 2) * ldk + k) * 4);
 }
-#ifdef RAMPDE_PROBE_NOSTORE
-#define RAMPDE_STORE_G4(ptr, val) do { if (g.N < 0) *(ptr) = (val); } while (0)
-#else
 #define RAMPDE_STORE_G4(ptr, val) (*(ptr) = (val))
-#endif
 
 // One contraction pass of a row tile: out[TM][Ncols] = in[TM][32*KB] * Wfrag^T for the
 // calling wavefront's slice of output-column tiles.
@@ -297,12 +290,10 @@ __device__ inline void tile_mma(f32x4 (&acc)[RW][MT], u16x8 (&ring)[PD][RW], con
       for (int nt = 0; nt < NTG; ++nt)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = Low<T>::mfma16(ring[u][nt], a[kb & 1][mt], acc[nt][mt]);
-#ifndef RAMPDE_PROBE_NOLOAD
       if (kb + PD < KBC) {
 #pragma unroll
         for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = wbase[(size_t)(kb + PD) * NTC * 64 + nt * 64];
       }
-#endif
     }
   } else if constexpr (KBC > 0) {
     // long contraction (KBC a multiple of PD): a rolled steady-state loop that always refills,
@@ -320,10 +311,8 @@ __device__ inline void tile_mma(f32x4 (&acc)[RW][MT], u16x8 (&ring)[PD][RW], con
         for (int nt = 0; nt < NTG; ++nt)
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = Low<T>::mfma16(ring[u][nt], a[u & 1][mt], acc[nt][mt]);
-#ifndef RAMPDE_PROBE_NOLOAD
 #pragma unroll
         for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = wnext[(size_t)u * NTC * 64 + nt * 64];
-#endif
       }
     }
 #pragma unroll
@@ -355,11 +344,9 @@ __device__ inline void tile_mma(f32x4 (&acc)[RW][MT], u16x8 (&ring)[PD][RW], con
         for (int nt = 0; nt < NTG; ++nt)
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = Low<T>::mfma16(ring[u][nt], a[u & 1][mt], acc[nt][mt]);
-#ifndef RAMPDE_PROBE_NOLOAD
         const int ku = min(u, KB - 1 - kb0 - PD);  // clamp to the last k-block (only in the last main group)
 #pragma unroll
         for (int nt = 0; nt < NTG; ++nt) ring[u][nt] = wnext[ku * kstride + nt * 64];
-#endif
       }
     }
     // drain: the last group of PD k-blocks, no refills; k-blocks past the end contribute zero
@@ -953,9 +940,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
   __shared__ int is_last;
   __syncthreads();
   if (tid == 0) {
-#ifndef RAMPDE_PROBE_NOFENCE
     __threadfence();
-#endif
     is_last = (atomicAdd(&g.ctl->done, 1) == (int)gridDim.x - 1);
   }
   __syncthreads();

@@ -12,6 +12,8 @@
 // Tiles are built from v_mfma_f32_32x32x16_{f16,bf16}; a workgroup is 4 wavefronts (2x2).
 // Low-precision values travel as raw 16-bit patterns (uint16_t).
 #pragma once
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace rampde {
@@ -328,11 +330,11 @@ __global__ __launch_bounds__(256) void gemm_tn(GemmTN g) {
 // 64, padding zero.  For a feature group k runs contiguously, so the tiles of both operands of
 // dW_l = delta_l^T act_{l-1}  are read with coalesced 16-byte loads (2 k x 4 features) and
 // regrouped into k-contiguous LDS rows on the way in.  One launch covers every layer:
-//   blocks [0, gemm_blocks)  : 128 x 128 output tiles x K-chunks; chunk c accumulates into its own
-//                              copy c of the gradient vector (no atomics, fixed summation order);
-//                              the copies are summed once at the end of the backward pass
-//   the blocks of the first tile column also sum their cotangent tile over k (from LDS) for db_l
-//   and the time-column gradient;
+//   one workgroup per (K-chunk, 128 x 128 output tile); chunk c accumulates into its own copy c of
+//   the gradient vector (no atomics, fixed summation order); the copies are summed once at the end
+//   of the backward pass;
+//   the workgroups of the first tile column also sum their cotangent tile over k (from LDS) for
+//   db_l and the time-column gradient.
 // All contributions are scaled by h / S_step (paper Sec. 3, update of g).
 struct WgradLayer {
   const uint16_t* DT;   // [NaPad / 4][ldk][4] cotangent of the layer's output
@@ -344,13 +346,13 @@ struct WgradLayer {
   int Na, Nb;           // valid extents
   int NaPad, NbPad;     // rows that exist in DT / AT
   int tiles_a, tiles_b; // 128-tiles
-  int blk0;             // first block of this layer
+  int tile0;            // index of this layer's first tile among all layers' tiles
 };
 
 struct WgradArgs {
   WgradLayer layer[8];
   int L;
-  int gemm_blocks;
+  int ntiles;           // output tiles of all layers
   int64_t P;            // parameters: distance between the per-K-chunk copies of the gradient
   int ksplits;          // K-chunks per output tile
   int kchunk;           // k extent of a chunk (multiple of 64)
@@ -363,22 +365,29 @@ struct WgradArgs {
   int step;
 };
 
+// (register cap: for narrow networks this kernel shares the SIMDs with the 4-wave adjoint kernel,
+// which leaves it a little over 200 of the 512 registers of a lane)
 template <class T>
-__global__ __launch_bounds__(256, 2) void wgrad_feature_major(WgradArgs g) {
+__global__ __launch_bounds__(256, 2) __attribute__((amdgpu_num_vgpr(104))) void wgrad_feature_major(WgradArgs g) {
   const float S = g.scale_hist[g.step];
   if (S == 0.f) return;  // the step's cotangent chain was rejected (or never ran)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float scale = g.h / S;
-  int bid = blockIdx.x;
+  // Workgroups go to the 8 XCDs round-robin by block index.  Re-linearise so that an XCD owns a
+  // contiguous range of (K-chunk, tile) pairs, K-chunk-major: the tiles that run together on an
+  // XCD then read the same k range of the operands and share it through that XCD's L2.
+  const int per_xcd = (int)gridDim.x >> 3;
+  const int gp = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  if (gp >= g.ntiles * g.ksplits) return;
+  const int split = gp / g.ntiles;
+  const int t = gp - split * g.ntiles;
 
   // ---- 128 x 128 tile of dW_l over one K-chunk
   WgradLayer y = g.layer[0];
 #pragma unroll
   for (int q = 1; q < 8; ++q)
-    if (q < g.L && bid >= g.layer[q].blk0) y = g.layer[q];
-  int r = bid - y.blk0;
-  const int split = r % g.ksplits;
-  r /= g.ksplits;
+    if (q < g.L && t >= g.layer[q].tile0) y = g.layer[q];
+  const int r = t - y.tile0;
   const int ta = r % y.tiles_a, tb = r / y.tiles_a;
   const int a0 = ta * 128, b0 = tb * 128;
   const int64_t k_begin = (int64_t)split * g.kchunk;
@@ -400,11 +409,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_feature_major(WgradArgs g) {
   // feature groups beyond the padded extent read group 0 instead and are masked in the epilogue
   const uint16_t* pa0 = y.DT + ((size_t)((a0 + fg * 4 < y.NaPad) ? a0 / 4 + fg : 0) * g.ldk + oct * 8) * 4;
   const uint16_t* pb0 = y.AT + ((size_t)((b0 + fg * 4 < y.NbPad) ? b0 / 4 + fg : 0) * g.ldk + oct * 8) * 4;
-#ifdef RAMPDE_PROBE_NOGEMMLOOP
-  const int nsteps = 1;
-#else
   const int nsteps = (int)((k_end - k_begin) / BK);
-#endif
   auto load_tiles = [&](u16x8 (&qa)[4], u16x8 (&qb)[4], int step) {
     const int64_t k0 = k_begin + (int64_t)(step < nsteps ? step : nsteps - 1) * BK;  // clamped: branch-free
 #pragma unroll
@@ -446,50 +451,63 @@ __global__ __launch_bounds__(256, 2) void wgrad_feature_major(WgradArgs g) {
   float sum_b = 0.f, sum_t = 0.f;
 #pragma unroll
   for (int u = 0; u < WG_STAGES; ++u) load_tiles(ra[u], rb[u], u);
-  for (int step0 = 0; step0 < nsteps; step0 += WG_STAGES) {
+  // One k-step, free of branches (a branch inside the software pipeline makes every wait for a
+  // load a wait for all of them).  SUMS: also accumulate the sums of the cotangent tile over k for
+  // db_l and the time-column gradient: thread -> (feature tid / 2, half tid % 2 of the 64 k);
+  // a k-step lies within one stage.
+  auto k_step = [&](auto sums, u16x8 (&qa)[4], u16x8 (&qb)[4], int step) {
+    // (scheduling fences: the loads of step + WG_STAGES must issue here, a full WG_STAGES k-steps
+    // ahead of their use, and the next step's regrouping must not drift up into this one)
+    __builtin_amdgcn_sched_barrier(0);
+    store_tiles(qa, qb);
+    __syncthreads();
+    load_tiles(qa, qb, step + WG_STAGES);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (decltype(sums)::value) {
+      const int64_t k0 = k_begin + (int64_t)step * BK;
+      const int j = (int)(k0 / g.Rp);
+      float tau = 0.f;
 #pragma unroll
-    for (int u = 0; u < WG_STAGES; ++u) {
-      const int step = step0 + u;  // steps past the end recompute nothing: their tiles are zeroed
-      store_tiles(ra[u], rb[u]);
-      __syncthreads();
-      load_tiles(ra[u], rb[u], step + WG_STAGES);
-      if (step < nsteps) {
-        if (tb == 0) {
-          // sums of the cotangent tile over k for db_l and the time-column gradient: thread ->
-          // (feature tid / 2, half tid % 2 of the 64 k); a k-step lies within one stage
-          const int64_t k0 = k_begin + (int64_t)step * BK;
-          const int j = (int)(k0 / g.Rp);
-          float tau = 0.f;
+      for (int q = 0; q < kMaxStages; ++q) tau = (q == j) ? g.taus[q] : tau;
+      float part = 0.f;
 #pragma unroll
-          for (int q = 0; q < kMaxStages; ++q) tau = (q == j) ? g.taus[q] : tau;
-          float part = 0.f;
+      for (int c = 0; c < 4; ++c) {
+        const u16x8 v = *reinterpret_cast<const u16x8*>(&sA[(tid >> 1) * LDS_PITCH + (tid & 1) * 32 + c * 8]);
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const u16x8 v = *reinterpret_cast<const u16x8*>(&sA[(tid >> 1) * LDS_PITCH + (tid & 1) * 32 + c * 8]);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) part += Low<T>::to_f32(v[e]);
-          }
-          sum_b += part;
-          sum_t = fmaf(tau, part, sum_t);
-        }
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-          u16x8 fa[2], fb[2];
-#pragma unroll
-          for (int a = 0; a < 2; ++a)
-            fa[a] = *reinterpret_cast<const u16x8*>(&sA[(wm * 64 + a * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
-#pragma unroll
-          for (int b = 0; b < 2; ++b)
-            fb[b] = *reinterpret_cast<const u16x8*>(&sB[(wn * 64 + b * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
-#pragma unroll
-          for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int b = 0; b < 2; ++b) acc[a][b] = Low<T>::mfma32(fa[a], fb[b], acc[a][b]);
-        }
+        for (int e = 0; e < 8; ++e) part += Low<T>::to_f32(v[e]);
       }
-      __syncthreads();
+      sum_b += part;
+      sum_t = fmaf(tau, part, sum_t);
     }
-  }
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      u16x8 fa[2], fb[2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+        fa[a] = *reinterpret_cast<const u16x8*>(&sA[(wm * 64 + a * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+        fb[b] = *reinterpret_cast<const u16x8*>(&sB[(wn * 64 + b * 32 + frow) * LDS_PITCH + kk * 16 + fk]);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = Low<T>::mfma32(fa[a], fb[b], acc[a][b]);
+    }
+    __syncthreads();
+  };
+  auto k_loop = [&](auto sums) {
+    static_assert(WG_STAGES == 2, "the loop below rotates two register stages");
+    int step = 0;
+    for (; step + 2 <= nsteps; step += 2) {
+      k_step(sums, ra[0], rb[0], step);
+      k_step(sums, ra[1], rb[1], step + 1);
+    }
+    if (step < nsteps) k_step(sums, ra[0], rb[0], step);
+  };
+  if (tb == 0)
+    k_loop(std::true_type{});
+  else
+    k_loop(std::false_type{});
   if (tb == 0) {
     sum_b += __shfl_xor(sum_b, 1);
     sum_t += __shfl_xor(sum_t, 1);

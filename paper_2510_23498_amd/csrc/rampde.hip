@@ -236,8 +236,11 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
       {
         int tiles = 0;
         for (auto& y : p.layers) tiles += ((y.Npad + 127) / 128) * ((y.Kpad + 127) / 128);
-        // K-chunks: enough workgroups to fill the chip, but at least 256 k per chunk
-        int64_t ks = (wgrad_target_blocks() + tiles - 1) / tiles;
+        // K-chunks: as many workgroups as are resident at once (two per CU; one when the kernel
+        // shares the CUs with the adjoint kernel) and no more -- a second, partial round of
+        // workgroups costs more than it spreads --, but at least 256 k per chunk
+        const int resident = wgrad_target_blocks() * (p.overlap_wgrad ? 1 : 2);
+        int64_t ks = std::max(1, resident / tiles);
         ks = std::max<int64_t>(1, std::min<int64_t>(ks, p.ldk / 256 > 0 ? p.ldk / 256 : 1));
         const int64_t kc = ((p.ldk + ks - 1) / ks + 63) / 64 * 64;
         p.kchunk = (int)kc;
@@ -301,7 +304,8 @@ static int hip_fail(hipError_t e, const char* where) {
 
 static inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
-// workgroups aimed at per parameter-gradient launch (tunable for experiments)
+// workgroups of the parameter-gradient kernel per resident slot of the chip: one per CU
+// (tunable for experiments)
 static int wgrad_target_blocks() {
   static int v = [] {
     const char* e = getenv("RAMPDE_WGRAD_BLOCKS");
@@ -805,13 +809,14 @@ struct Runner {
       d.NbPad = y.Kpad;
       d.tiles_a = (y.Npad + 127) / 128;
       d.tiles_b = (y.Kpad + 127) / 128;
-      d.blk0 = blk;
-      blk += d.tiles_a * d.tiles_b * w.ksplits;
+      d.tile0 = blk;
+      blk += d.tiles_a * d.tiles_b;
       flops += 2.0 * (double)p.ldk * y.Npad * y.Kpad;
     }
-    w.gemm_blocks = blk;
+    w.ntiles = blk;
+    const int grid = (blk * w.ksplits + 7) / 8 * 8;  // a multiple of the XCD count: see the kernel's block mapping
     TimeScope ts(RAMPDE_K_WGRAD_GEMM, flops, stream);
-    wgrad_feature_major<T><<<blk, 256, 0, stream>>>(w);
+    wgrad_feature_major<T><<<grid, 256, 0, stream>>>(w);
   }
 
   int backward(const float* theta, const double* tgrid, int N, const rampde_tableau* tab, const rampde_policy* pol,
