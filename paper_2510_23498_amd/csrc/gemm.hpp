@@ -324,6 +324,181 @@ __global__ __launch_bounds__(256) void gemm_tn(GemmTN g) {
 
 
 // ------------------------------------------------------------------------------------
+// Weight gradient of a 3x3 zero-padded convolution on channels-last rows (paper Sec. 3, update
+// of g, for the convolutional velocity):
+//   dW[co][ci][tap] += scale * sum_k delta[k][co] * x[k + dy W + dx][ci] * [pixel (y+dy, x+dx) inside]
+// over the rows k (pixels of all samples and stages) of one K-chunk, all 9 taps in one workgroup.
+// A workgroup owns a 64 (co) x 64 (ci) block.  Per k-step of 64 rows it transposes into LDS
+//   - the cotangent tile, in 3 copies: as is, and with the rows of the first / last image line
+//     zeroed (taps with dy = -1 / +1: the line above / below does not exist),
+//   - the input tile with a halo of one image line on both sides (64 + 2 W rows), in 3 copies
+//     shifted by dx = -1, 0, +1 rows with the pixels that fall off the line zeroed,
+// so that the operand fragment of tap (dy, dx) is an aligned read at row offset (1 + dy) W of copy
+// dx, and every tap is one MFMA per 16 k.  Needs W % 8 == 0, W <= 64 and rows % 64 == 0 (the
+// 8-row blocks a thread transposes then lie within one image line).
+struct ConvWgrad {
+  const uint16_t* A; int lda;   // [rows, >= 64 gridDim.x] cotangents of the layer's output
+  const uint16_t* B; int ldb;   // [rows, >= 64 gridDim.y] the layer's input
+  int64_t rows;                 // stages * batch * H * W
+  int rows_per_split;           // multiple of 64
+  float* part;                  // [gridDim.z][gridDim.x][gridDim.y][9 taps][64 co][64 ci] fp32: the private
+                                // accumulators of every (K-chunk, channel block), summed at the end of the pass
+  float h;                      // scale = h / ctl->S_step
+  const Ctl* ctl;
+  int H, Wd;
+};
+
+constexpr int CW_PA = BK + 8;   // LDS pitch of the cotangent copies (elements)
+inline size_t conv_wgrad_lds_bytes(int Wd) { return (size_t)(3 * 64 * CW_PA + 3 * 64 * (64 + 2 * Wd + 8)) * 2; }
+
+template <class T>
+__global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
+  if (g.ctl->poison) return;
+  extern __shared__ __attribute__((aligned(16))) uint16_t cw_smem[];
+  const int W = g.Wd, XR = 64 + 2 * W, PX = XR + 8;
+  uint16_t* sA = cw_smem;                 // [3 (dy)][64 co][CW_PA]
+  uint16_t* sX = cw_smem + 3 * 64 * CW_PA;  // [3 (dx)][64 ci][PX]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int a0 = blockIdx.x * 64, b0 = blockIdx.y * 64;
+  const int64_t k_begin = (int64_t)blockIdx.z * g.rows_per_split;
+  int64_t k_end = k_begin + g.rows_per_split;
+  if (k_end > g.rows) k_end = g.rows;
+  if (k_begin >= k_end) return;
+
+  // work items of the transposing loaders: 8 rows x 8 channels each.  Items [0, 3 nXb): input
+  // copies (copy, 8-row block, channel group); then 64 items of the cotangent tile.
+  constexpr int MAXI = 3;
+  const int nXb = XR;  // (XR / 8) row blocks x 8 channel groups
+  const int nI = 3 * nXb + 64;
+  bool it_on[MAXI], it_isA[MAXI];
+  int it_rel[MAXI], it_dx[MAXI], it_fg[MAXI], it_dst[MAXI];
+#pragma unroll
+  for (int j = 0; j < MAXI; ++j) {
+    const int id = tid + 256 * j;
+    it_on[j] = id < nI;
+    it_isA[j] = id >= 3 * nXb;
+    if (!it_isA[j]) {
+      const int v = id / nXb, r = id - v * nXb;
+      it_fg[j] = r & 7;
+      it_rel[j] = -W + (r >> 3) * 8;
+      it_dx[j] = v - 1;
+      it_dst[j] = (v * 64 + it_fg[j] * 8) * PX + (r >> 3) * 8;
+    } else {
+      const int r = id - 3 * nXb;
+      it_fg[j] = r & 7;
+      it_rel[j] = (r >> 3) * 8;
+      it_dx[j] = 0;
+      it_dst[j] = it_fg[j] * 8 * CW_PA + (r >> 3) * 8;
+    }
+  }
+  u16x8 reg[MAXI][8];
+  auto load_items = [&](int64_t k0) {
+#pragma unroll
+    for (int j = 0; j < MAXI; ++j) {
+      if (!it_on[j]) continue;
+      const int64_t qb = k0 + it_rel[j];
+      if (it_isA[j]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          reg[j][i] = *reinterpret_cast<const u16x8*>(g.A + (size_t)(qb + i) * g.lda + a0 + it_fg[j] * 8);
+      } else {
+        const bool inside = qb >= 0 && qb < g.rows;
+        const int xq0 = inside ? (int)(qb % W) : 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int xi = xq0 + i + it_dx[j];
+          u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+          if (inside && xi >= 0 && xi < W)
+            v = *reinterpret_cast<const u16x8*>(g.B + (size_t)(qb + i + it_dx[j]) * g.ldb + b0 + it_fg[j] * 8);
+          reg[j][i] = v;
+        }
+      }
+    }
+  };
+  auto store_items = [&](int64_t k0) {
+#pragma unroll
+    for (int j = 0; j < MAXI; ++j) {
+      if (!it_on[j]) continue;
+      int y = 0;
+      if (it_isA[j]) y = (int)(((k0 + it_rel[j]) / W) % g.H);
+#pragma unroll
+      for (int f = 0; f < 8; ++f) {
+        u16x8 o;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = reg[j][i][f];
+        if (it_isA[j]) {
+          const u16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+          uint16_t* d = sA + it_dst[j] + f * CW_PA;
+          *reinterpret_cast<u16x8*>(d) = (y == 0) ? z : o;                        // dy = -1
+          *reinterpret_cast<u16x8*>(d + 64 * CW_PA) = o;                          // dy = 0
+          *reinterpret_cast<u16x8*>(d + 2 * 64 * CW_PA) = (y == g.H - 1) ? z : o;  // dy = +1
+        } else {
+          *reinterpret_cast<u16x8*>(sX + it_dst[j] + f * PX) = o;
+        }
+      }
+    }
+  };
+
+  f32x16 acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[t][q] = 0.f;
+
+  const int frow = lane & 31, fk = (lane >> 5) * 8;
+  load_items(k_begin);
+  for (int64_t k0 = k_begin; k0 < k_end; k0 += 64) {
+    store_items(k0);
+    __syncthreads();
+    if (k0 + 64 < k_end) load_items(k0 + 64);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      u16x8 fa[3];
+#pragma unroll
+      for (int dyv = 0; dyv < 3; ++dyv)
+        fa[dyv] = *reinterpret_cast<const u16x8*>(&sA[(dyv * 64 + wm * 32 + frow) * CW_PA + kk * 16 + fk]);
+#pragma unroll
+      for (int dyv = 0; dyv < 3; ++dyv)
+#pragma unroll
+        for (int dxv = 0; dxv < 3; ++dxv) {
+          const u16x8 fb =
+              *reinterpret_cast<const u16x8*>(&sX[(dxv * 64 + wn * 32 + frow) * PX + dyv * W + kk * 16 + fk]);
+          acc[dyv * 3 + dxv] = Low<T>::mfma32(fa[dyv], fb, acc[dyv * 3 + dxv]);
+        }
+    }
+    __syncthreads();
+  }
+
+  // plain read-modify-write: the slot belongs to this workgroup for the whole backward pass
+  const float scale = g.h / g.ctl->S_step;
+  float* slot = g.part + ((size_t)(blockIdx.z * gridDim.x + blockIdx.x) * gridDim.y + blockIdx.y) * (9 * 4096);
+  const int nb = wn * 32 + (lane & 31);
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int na = wm * 32 + 8 * (q >> 2) + 4 * (lane >> 5) + (q & 3);
+      float* dst = slot + (t * 64 + na) * 64 + nb;
+      *dst = fmaf(scale, acc[t][q], *dst);
+    }
+}
+
+// dW[co][ci][tap] += sum over K-chunks of the private accumulators (end of the backward pass)
+__global__ void conv_wgrad_reduce(float* __restrict__ G, int ldg, const float* __restrict__ part, int splits,
+                                  int tiles_a, int tiles_b, int Na, int Nb, const Ctl* ctl) {
+  if (ctl->poison) return;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)Na * Nb * 9) return;
+  const int nb = (int)(i % Nb), t = (int)((i / Nb) % 9), na = (int)(i / ((int64_t)Nb * 9));
+  const size_t in_tile = ((size_t)t * 64 + (na & 63)) * 64 + (nb & 63);
+  const size_t tile = (size_t)(na >> 6) * tiles_b + (nb >> 6);
+  float acc = 0.f;
+  for (int c = 0; c < splits; ++c) acc += part[((size_t)c * tiles_a * tiles_b + tile) * (9 * 4096) + in_tile];
+  G[(size_t)na * ldg + (size_t)nb * 9 + t] += acc;
+}
+
+// ------------------------------------------------------------------------------------
 // Parameter gradients of one adjoint step for dense networks whose cotangents and layer
 // inputs were stored FEATURE-GROUP-MAJOR by the row-tile-persistent adjoint kernel: element
 // (feature f, k) at ((f / 4) * ldk + k) * 4 + f % 4, k = stage * Rp + row, Rp = rows padded to

@@ -49,6 +49,9 @@ struct Layer {
   size_t Wp, WTp, bias_f, wt_f;
   size_t Wf, WTf;  // fragment-major copies (row-tile-persistent kernels)
   int ldw;  // K extent of the forward GEMM (dense: Kpad; conv: 9 * Cpad)
+  // all-taps convolution weight gradient: K-chunk length, chunk count, the chunks' private copies
+  int cw_per = 0, cw_splits = 0;
+  size_t cw_part = 0;
 };
 
 struct Plan {
@@ -144,6 +147,10 @@ static bool build_layers(const rampde_velocity* vel, Plan& p, int hidden_pad = k
 }
 
 static int wgrad_target_blocks();
+struct Plan;
+// the all-taps convolution weight-gradient kernel: image lines of a multiple of 8 pixels, at most
+// 64, and whole 64-row k-steps
+static bool conv_wgrad_applies(const Plan& p);
 
 static bool fused_candidate(const rampde_velocity* vel, const rampde_policy* pol) {
   if (!vel || vel->kind != RAMPDE_VEL_MLP || (pol && (pol->flags & RAMPDE_PER_LAYER_KERNELS))) return false;
@@ -267,12 +274,28 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
       p.KBAR = take((size_t)p.s * p.R * p.dpad * 2);
       p.ZBAR = take((size_t)p.s * p.R * p.dpad * 2);
       for (int l = 0; l + 1 < p.L; ++l) p.DELTA.push_back(take((size_t)p.s * p.R * p.layers[l].Npad * 2));
+      if (conv_wgrad_applies(p)) {
+        // every (K-chunk, 64 x 64 channel block) accumulates its 9 tap blocks over all steps in a
+        // copy of its own; about 512 workgroups per launch, at least 4 k-steps each
+        const int64_t rows = (int64_t)p.s * p.R;
+        for (auto& y : p.layers) {
+          const int tiles = (y.Npad / 64) * (y.Kpad / 64);
+          const int64_t want = std::max(1, 512 / tiles);
+          int64_t per = ((rows + want - 1) / want + 63) / 64 * 64;
+          if (per < 4 * 64) per = 4 * 64;
+          y.cw_per = (int)per;
+          y.cw_splits = (int)((rows + per - 1) / per);
+          y.cw_part = take(sizeof(float) * (size_t)y.cw_splits * tiles * 9 * 4096);
+        }
+      }
     }
   }
   p.total = off;
   p.ok = true;
   return p;
 }
+
+static bool conv_wgrad_applies(const Plan& p) { return p.conv && !p.fused && p.Wd % 8 == 0 && p.Wd <= 64 && p.R % 64 == 0; }
 
 static int check_common(const rampde_velocity* vel, const double* tgrid, int N, const rampde_tableau* tab,
                         const rampde_policy* pol) {
@@ -734,32 +757,45 @@ struct Runner {
       g.B = (l == 0) ? u16(p.Z) : u16(p.ACT[l - 1]);
       g.ldb = y.Kpad;
       g.rows = rows;
-      // split the contraction so that about 1024 workgroups are in flight
-      const int tiles = ((y.Npad + 127) / 128) * ((y.Kpad + 127) / 128) * (p.conv ? 9 : 1);
-      int64_t want = (1024 + tiles - 1) / tiles;
-      int64_t per = (rows + want - 1) / want;
-      per = (per + BK - 1) / BK * BK;
-      if (per < 4 * BK) per = 4 * BK;
-      g.rows_per_split = (int)per;
-      const int splits = (int)((rows + per - 1) / per);
-      g.G = grad_theta + y.theta_w;
-      g.ldg = p.conv ? y.in_full * 9 : y.in_full;
-      g.Na = y.out;
-      g.Nb = y.in;
-      g.NaPad = y.Npad;
-      g.NbPad = y.Kpad;
-      g.h = h;
-      g.ctl = ctl;
-      g.H = p.H;
-      g.Wd = p.Wd;
-      g.taps = p.conv ? 9 : 1;
-      dim3 grid((y.Npad + 127) / 128, (y.Kpad + 127) / 128, splits * g.taps);
-      {
-        TimeScope ts(RAMPDE_K_WGRAD_GEMM, 2.0 * rows * (double)y.Npad * y.Kpad * g.taps, st);
-        if (p.conv)
-          gemm_tn<T, true><<<grid, 256, 0, st>>>(g);
-        else
-          gemm_tn<T, false><<<grid, 256, 0, st>>>(g);
+      if (conv_wgrad_applies(p)) {
+        // all 9 taps of a 64 x 64 channel block per workgroup
+        ConvWgrad c{};
+        c.A = g.A; c.lda = g.lda; c.B = g.B; c.ldb = g.ldb;
+        c.rows = rows;
+        c.rows_per_split = y.cw_per;
+        c.part = f32(y.cw_part);
+        c.h = h; c.ctl = ctl; c.H = p.H; c.Wd = p.Wd;
+        dim3 cgrid(y.Npad / 64, y.Kpad / 64, y.cw_splits);
+        TimeScope ts(RAMPDE_K_WGRAD_GEMM, 2.0 * rows * (double)y.Npad * y.Kpad * 9, st);
+        conv_wgrad<T><<<cgrid, 256, conv_wgrad_lds_bytes(p.Wd), st>>>(c);
+      } else {
+        // split the contraction so that about 1024 workgroups are in flight
+        const int tiles = ((y.Npad + 127) / 128) * ((y.Kpad + 127) / 128) * (p.conv ? 9 : 1);
+        int64_t want = (1024 + tiles - 1) / tiles;
+        int64_t per = (rows + want - 1) / want;
+        per = (per + BK - 1) / BK * BK;
+        if (per < 4 * BK) per = 4 * BK;
+        g.rows_per_split = (int)per;
+        const int splits = (int)((rows + per - 1) / per);
+        g.G = grad_theta + y.theta_w;
+        g.ldg = p.conv ? y.in_full * 9 : y.in_full;
+        g.Na = y.out;
+        g.Nb = y.in;
+        g.NaPad = y.Npad;
+        g.NbPad = y.Kpad;
+        g.h = h;
+        g.ctl = ctl;
+        g.H = p.H;
+        g.Wd = p.Wd;
+        g.taps = p.conv ? 9 : 1;
+        dim3 grid((y.Npad + 127) / 128, (y.Kpad + 127) / 128, splits * g.taps);
+        {
+          TimeScope ts(RAMPDE_K_WGRAD_GEMM, 2.0 * rows * (double)y.Npad * y.Kpad * g.taps, st);
+          if (p.conv)
+            gemm_tn<T, true><<<grid, 256, 0, st>>>(g);
+          else
+            gemm_tn<T, false><<<grid, 256, 0, st>>>(g);
+        }
       }
       // bias and time-weight gradients
       int rpb = (int)((rows + 255) / 256);
@@ -826,7 +862,14 @@ struct Runner {
     const int detect = dynamic || scaling == RAMPDE_SCALE_NONE_SAFE;
     const int k_max = pol->k_max > 0 ? pol->k_max : 16;
     const int HW = p.H * p.Wd;
+    if (conv_wgrad_applies(p))
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_wgrad_lds_bytes(p.Wd)));
     ctl_reset<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), N);
+    if (conv_wgrad_applies(p))
+      for (auto& y : p.layers)
+        fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + y.cw_part),
+                                            (size_t)y.cw_splits * (y.Npad / 64) * (y.Kpad / 64) * 9 * 4096);
     cast_weights(theta);
     SideStream& side = SideStream::get();
     if (use_fused && p.overlap_wgrad) {
@@ -921,6 +964,12 @@ struct Runner {
         if (p.overlap_wgrad) HIP_TRY(hipStreamWaitEvent(st, side.wgrad_done(0), 0));  // helper stream is in order: joins all
         reduce_partial_gradients<<<blocks_for(p.P, 256), 256, 0, st>>>(grad_theta, f32(p.gpart), p.P, p.ksplits, ctl);
       }
+      if (conv_wgrad_applies(p))
+        for (auto& y : p.layers) {
+          const int64_t n = (int64_t)y.out * y.in * 9;
+          conv_wgrad_reduce<<<blocks_for(n, 256), 256, 0, st>>>(grad_theta + y.theta_w, y.in_full * 9, f32(y.cw_part),
+                                                                y.cw_splits, y.Npad / 64, y.Kpad / 64, y.out, y.in, ctl);
+        }
       HIP_TRY(hipGetLastError());
       if (!must_sync) break;
       HIP_TRY(hipMemcpyAsync(&hctl, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));

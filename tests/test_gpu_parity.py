@@ -84,6 +84,14 @@ def test_cfg4_conv_shape_reduced():
     _both(wl.CONFIGS["cfg4"].with_(name="cfg4s", B=3, N=3), bias_std=0.1)
 
 
+@pytest.mark.parametrize("C,H,W,B", [(96, 4, 8, 4), (8, 8, 16, 2), (70, 2, 64, 1)])
+def test_conv_weight_gradient_all_taps_kernel(C, H, W, B):
+    # image lines of 8 k pixels: the convolution weight gradient runs in the kernel that handles all
+    # nine taps per workgroup (several channel blocks, a halo wider than the k-step, one-line images)
+    cfg = wl.CONFIGS["cfg4"].with_(name=f"convw{C}x{H}x{W}", B=B, N=2, C=C, H=H, W=W, tableau="kutta3")
+    _both(cfg, bias_std=0.1)
+
+
 def test_conv_small_odd_geometry():
     cfg = wl.CONFIGS["cfg4"].with_(name="convodd", B=2, N=2, C=5, H=7, W=6, tableau="kutta3")
     _both(cfg, bias_std=0.1)
