@@ -346,6 +346,13 @@ struct ConvWgrad {
   float h;                      // scale = h / ctl->S_step
   const Ctl* ctl;
   int H, Wd;
+  // bias and time-channel gradients (folded into the workgroups of the first input-channel block):
+  //   db[co] += scale * sum_k delta[k][co];   dwt[co][tap] += scale * sum_k tau(k) delta[k][co] * [tap inside]
+  float* gb;                    // db, or null
+  float* gwt; int wt_stride;    // dwt: element (co, tap) at co * wt_stride + tap, or null
+  int Na;                       // valid output channels
+  int64_t R;                    // rows per stage (a multiple of 64)
+  float taus[kMaxStages];       // stage times
 };
 
 constexpr int CW_PA = BK + 8;   // LDS pitch of the cotangent copies (elements)
@@ -447,11 +454,42 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
     for (int q = 0; q < 16; ++q) acc[t][q] = 0.f;
 
   const int frow = lane & 31, fk = (lane >> 5) * 8;
+  const bool sums = blockIdx.y == 0 && g.gb != nullptr;
+  float sum_b = 0.f, sum_t[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) sum_t[t] = 0.f;
   load_items(k_begin);
   for (int64_t k0 = k_begin; k0 < k_end; k0 += 64) {
     store_items(k0);
     __syncthreads();
     if (k0 + 64 < k_end) load_items(k0 + 64);
+    if (sums) {
+      // thread -> (channel tid / 4, quarter tid % 4 of the 64 rows = two 8-row blocks); a block lies in
+      // one image line: only its first row can have x = 0, only its last x = W - 1
+      const int co = tid >> 2, qt = tid & 3;
+      const int j = (int)(k0 / g.R);
+      float tau = 0.f;
+#pragma unroll
+      for (int q = 0; q < kMaxStages; ++q) tau = (q == j) ? g.taus[q] : tau;
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const int kq = qt * 16 + b * 8;
+        const int xq0 = (int)((k0 + kq) % W);
+#pragma unroll
+        for (int dyv = 0; dyv < 3; ++dyv) {
+          const u16x8 v = *reinterpret_cast<const u16x8*>(&sA[(dyv * 64 + co) * CW_PA + kq]);
+          float inner = 0.f;
+#pragma unroll
+          for (int e = 1; e < 7; ++e) inner += Low<T>::to_f32(v[e]);
+          const float f0 = Low<T>::to_f32(v[0]), f7 = Low<T>::to_f32(v[7]);
+          const float full = inner + f0 + f7;
+          sum_t[dyv * 3 + 0] = fmaf(tau, inner + f7 + (xq0 == 0 ? 0.f : f0), sum_t[dyv * 3 + 0]);      // dx = -1
+          sum_t[dyv * 3 + 1] = fmaf(tau, full, sum_t[dyv * 3 + 1]);
+          sum_t[dyv * 3 + 2] = fmaf(tau, inner + f0 + (xq0 == W - 8 ? 0.f : f7), sum_t[dyv * 3 + 2]);  // dx = +1
+          if (dyv == 1) sum_b += full;
+        }
+      }
+    }
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       u16x8 fa[3];
@@ -470,8 +508,25 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
     __syncthreads();
   }
 
-  // plain read-modify-write: the slot belongs to this workgroup for the whole backward pass
   const float scale = g.h / g.ctl->S_step;
+  if (sums) {
+    sum_b += __shfl_xor(sum_b, 1);
+    sum_b += __shfl_xor(sum_b, 2);
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+      sum_t[t] += __shfl_xor(sum_t[t], 1);
+      sum_t[t] += __shfl_xor(sum_t[t], 2);
+    }
+    const int na = a0 + (tid >> 2);
+    if ((tid & 3) == 0 && na < g.Na) {
+      unsafeAtomicAdd(&g.gb[na], scale * sum_b);
+      if (g.gwt) {
+#pragma unroll
+        for (int t = 0; t < 9; ++t) unsafeAtomicAdd(&g.gwt[(size_t)na * g.wt_stride + t], scale * sum_t[t]);
+      }
+    }
+  }
+  // plain read-modify-write: the slot belongs to this workgroup for the whole backward pass
   float* slot = g.part + ((size_t)(blockIdx.z * gridDim.x + blockIdx.x) * gridDim.y + blockIdx.y) * (9 * 4096);
   const int nb = wn * 32 + (lane & 31);
 #pragma unroll

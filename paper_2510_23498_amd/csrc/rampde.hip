@@ -765,9 +765,16 @@ struct Runner {
         c.rows_per_split = y.cw_per;
         c.part = f32(y.cw_part);
         c.h = h; c.ctl = ctl; c.H = p.H; c.Wd = p.Wd;
+        c.gb = grad_theta + y.theta_b;
+        c.gwt = y.has_time ? grad_theta + y.theta_w + (size_t)y.in * 9 : nullptr;
+        c.wt_stride = y.in_full * 9;
+        c.Na = y.out;
+        c.R = p.R;
+        for (int j = 0; j < kMaxStages; ++j) c.taus[j] = j < s ? taus.v[j] : 0.f;
         dim3 cgrid(y.Npad / 64, y.Kpad / 64, y.cw_splits);
         TimeScope ts(RAMPDE_K_WGRAD_GEMM, 2.0 * rows * (double)y.Npad * y.Kpad * 9, st);
         conv_wgrad<T><<<cgrid, 256, conv_wgrad_lds_bytes(p.Wd), st>>>(c);
+        continue;  // (bias and time-channel gradients included)
       } else {
         // split the contraction so that about 1024 workgroups are in flight
         const int tiles = ((y.Npad + 127) / 128) * ((y.Kpad + 127) / 128) * (p.conv ? 9 : 1);
