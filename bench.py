@@ -126,7 +126,8 @@ def main():
     td = timing[dom]
     ach_tflops = td["work"] / (td["ms"] * 1e-3) / 1e12 if td["ms"] > 0 else 0.0
     roofline = {"bound": "mfma", "kernel": dom, "achieved": ach_tflops, "peak": PEAK_TFLOPS[cfg.low],
-                "unit": "TFLOP/s", "frac": ach_tflops / PEAK_TFLOPS[cfg.low], "traffic": None,
+                "unit": "TFLOP/s", "frac": ach_tflops / PEAK_TFLOPS[cfg.low],
+                "traffic": profiled_traffic(cfg.name, dom),
                 "launches_per_step": td["launches"] / args.steps,
                 "avg_launch_us": 1e3 * td["ms"] / max(1, td["launches"]),
                 "flops_per_launch": td["work"] / max(1, td["launches"])}
@@ -154,6 +155,21 @@ def main():
         default_steps = {"cfg1": cfg.N, "cfg2": cfg.N, "cfg3": 1, "cfg4": 1, "cfg5": 16}.get(cfg.name, 1)
         out["cpu_baseline"] = cpu_baseline(cfg, theta_np, y0_np, target_np, args.cpu_steps or default_steps)
     print(json.dumps(out))
+
+
+def profiled_traffic(workload, kernel_class):
+    """HBM bytes per launch of a kernel class as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (calibrated against a plain copy) and recorded in the committed profile summary; None when the
+    summary has no figure for this workload and kernel."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "bench_cfg2_kernels_and_hbm_traffic.md")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and f[0] == "traffic_bytes_per_launch" and f[1] == workload and f[2] == kernel_class:
+                return int(f[3])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(cfg, theta, y0, target, n_steps):
