@@ -22,8 +22,14 @@
  *     stats are requested -- and once more per detected overflow, to retry from that step.
  *     Under SCALE_NONE with scale_hist = stats = NULL it does not synchronise at all.
  *   - Return value: 0 on success, otherwise a rampde_status code; rampde_strerror gives
- *     a message.  No exceptions; no global state except the optional timing facility below.
+ *     a message.  No exceptions.  Process-global state: the optional timing facility below, and
+ *     one helper stream with a pool of events (default priority, created on first use, kept until
+ *     the process ends) on which rampde_odeint_bwd runs the parameter-gradient kernels of narrow
+ *     networks beside the adjoint kernels; it is joined into `hip_stream` before the call returns
+ *     its last work, so callers see ordinary stream order.
  *   - Calls that share a workspace must not overlap; distinct workspaces on distinct streams may.
+ *     The host side is not thread safe: calls from several host threads must be serialised by
+ *     the caller.
  *   - theta layout (flat fp32, also the layout of grad_theta):
  *       MLP  : for each layer l: W_l[out_l][in_l] row-major, then b_l[out_l];
  *              layer 1 has in_1 = d + 1 when time_input is set (time column LAST).
