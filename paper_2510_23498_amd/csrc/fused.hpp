@@ -96,9 +96,15 @@ struct FusedArgs {
   uint16_t* KBART;             // [dpad / 4][ldk][4] cotangents of the slopes
   int64_t ldk, Rp;
   uint16_t* ZBAR;              // [s][R][dpad] (used when they do not fit in LDS)
+  // The kernel runs steps step, step - 1, ..., step - nsteps + 1 (nsteps > 1 only when nothing is
+  // decided between steps: no overflow detection, fixed scale).  The feature-group-major buffers of
+  // step i are set i % nsets; the pointers above are those of set 0, sets are set_stride elements apart.
+  int nsteps, nsets;
+  int64_t set_stride;
   const float* a_in;
   float* a_out;
-  const float* gys;            // running-cost cotangent of this step or null
+  const float* gys;            // running-cost cotangent of step `step` or null; step i - 1 lies gys_stride before step i
+  int64_t gys_stride;
   Ctl* ctl;
   float* scale_hist;
   int detect, dynamic, raw_norm, skip_recompute;
@@ -535,7 +541,7 @@ struct StageStore {
 // hold the first fragments of layer 0 (if L > 1); on return it holds those of the last layer.
 template <class T, int MT, int NTL, int NW, int HP, bool KEEP>
 __device__ inline void hidden_layers(TileEngine<T, MT, NTL, NW, HP>& eng, const TileLds<MT>& lds, const FusedArgs& g,
-                                     int j, float tau, int64_t row0) {
+                                     int j, float tau, int64_t row0, int64_t set_off = 0) {
   for (int l = 0; l + 1 < g.L; ++l) {
     const PassDesc p = fwd_pass(g, l);
     const PassDesc nx = fwd_pass(g, l + 1);
@@ -545,7 +551,7 @@ __device__ inline void hidden_layers(TileEngine<T, MT, NTL, NW, HP>& eng, const 
     const bool has_wt = (l == 0);
     lds_u16* out = lds.out(l);
     const int ldp = lds.ldp;
-    uint16_t* goutT = KEEP ? g.ACTT[l] : nullptr;
+    uint16_t* goutT = KEEP ? g.ACTT[l] + set_off : nullptr;
     const int64_t kj = (int64_t)j * g.Rp + row0;
     auto pre = [](int, int) { return make_uint2(0u, 0u); };
     auto epi = [&](const f32x4& acc, uint2, int, int, int n, int m) {
@@ -717,28 +723,41 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
   const int64_t n_state = g.R * g.d;
   const int L = g.L, s = g.s, D = g.dpad;
   const float S = g.ctl->S;
-  const float* st = g.steptab + (size_t)g.step * (1 + s);
-  const float h = st[0];
   StageStore<MT> ks{lds.kl, g.k_in_lds != 0, g.K, D, g.stage_stride, row0, g.R};
   StageStore<MT> zs{lds.kl, g.k_in_lds != 0, g.ZBAR, D, g.stage_stride, row0, g.R};
 
   load_params(lds.param, g);
-  // lane-resident state: the adjoint a (fp32) and lambda = Q(S a); yhat = stored state
+  // lane-resident state: the adjoint a (fp32), carried in registers from step to step
   float av[NTS][MT][4];
-  uint2 lamq[NTS][MT], yhat[NTS][MT];
   bool bad = false;
+  unsigned bits = 0;
+#pragma unroll
+  for (int nt = 0; nt < NTS; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      load4f(g.a_in, row0 + mt * 16 + lm, g.R, eng.state_col(nt, lq), g.d, av[nt][mt]);
+
+#pragma unroll 1
+  for (int it = 0; it < g.nsteps; ++it) {
+  const int step = g.step - it;
+  const float* st = g.steptab + (size_t)step * (1 + s);
+  const float h = st[0];
+  const int64_t set_off = (int64_t)(step % g.nsets) * g.set_stride;
+  uint16_t* const ZT = g.ZT + set_off;
+  uint16_t* const KBART = g.KBART + set_off;
+  // lambda = Q(S a); yhat = stored state
+  uint2 lamq[NTS][MT], yhat[NTS][MT];
 #pragma unroll
   for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
-      load4f(g.a_in, row0 + m, g.R, n, g.d, av[nt][mt]);
       float sa[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) sa[r] = S * av[nt][mt][r];
       lamq[nt][mt] = pack4<T>(sa);
       bad = bad || any_nonfinite4<T>(lamq[nt][mt]);
-      yhat[nt][mt] = load4h(g.ckpt + (size_t)g.step * n_state, row0 + m, g.R, n, g.d);
+      yhat[nt][mt] = load4h(g.ckpt + (size_t)step * n_state, row0 + m, g.R, n, g.d);
     }
 
   // cotangent of the slope of stage j:  kbar_j = Q( b_j lambda + h sum_{l>j} a_lj zbar_l ),
@@ -765,7 +784,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
     const uint2 q = pack4<T>(v);
     bad = bad || any_nonfinite4<T>(q);
     lds_store_u2(&lds.zbuf[m * lds.ldz + n], q);
-    if (row0 + m < g.R) RAMPDE_STORE_G4(group4(g.KBART, g.ldk, (int64_t)j * g.Rp + row0 + m, n), q);
+    if (row0 + m < g.R) RAMPDE_STORE_G4(group4(KBART, g.ldk, (int64_t)j * g.Rp + row0 + m, n), q);
     return q;
   };
 
@@ -793,13 +812,13 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
         for (int mt = 0; mt < MT; ++mt) {
           const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
           lds_store_u2(&lds.zbuf[m * lds.ldz + n], yhat[nt][mt]);
-          if (row0 + m < g.R) RAMPDE_STORE_G4(group4(g.ZT, g.ldk, row0 + m, n), yhat[nt][mt]);
+          if (row0 + m < g.R) RAMPDE_STORE_G4(group4(ZT, g.ldk, row0 + m, n), yhat[nt][mt]);
         }
     }
     __syncthreads();
     for (int j = 0; j < s; ++j) {
       const float tau = st[1 + j];
-      hidden_layers<T, MT, NTL, NW, HP, true>(eng, lds, g, j, tau, row0);
+      hidden_layers<T, MT, NTL, NW, HP, true>(eng, lds, g, j, tau, row0, set_off);
       const bool more = j + 1 < s;
       auto pre0 = [](int, int) { return make_uint2(0u, 0u); };
       auto epi_last = [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
@@ -825,7 +844,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
               for (int r = 0; r < 4; ++r) z[r] = fmaf(h, fmaf(aj, kf[r], incr[r]), yh[r]);
               const uint2 zq = pack4<T>(z);
               lds_store_u2(&lds.zbuf[m * lds.ldz + n], zq);
-              if (row0 + m < g.R) RAMPDE_STORE_G4(group4(g.ZT, g.ldk, (int64_t)(j + 1) * g.Rp + row0 + m, n), zq);
+              if (row0 + m < g.R) RAMPDE_STORE_G4(group4(ZT, g.ldk, (int64_t)(j + 1) * g.Rp + row0 + m, n), zq);
             } else {
               make_kbar(s - 1, nt, mt, m, n, nullptr);  // the slope of the last stage is not needed again
             }
@@ -864,8 +883,8 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
       const PassDesc p = bwd_pass(g, l);
       const PassDesc nx = bwd_pass(g, l - 1);
       const bool next_is_last = (l == 1);
-      uint16_t* actT = g.ACTT[l - 1];
-      uint16_t* goutT = g.DELTAT[l - 1];
+      uint16_t* actT = g.ACTT[l - 1] + set_off;
+      uint16_t* goutT = g.DELTAT[l - 1] + set_off;
       const int64_t kj = (int64_t)j * g.Rp + row0;
       lds_u16* out = lds.out(q);
       const int ldp = lds.ldp;
@@ -912,26 +931,31 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
     if (L == 1) eng.template run_state<true>(lastb, lds.in(0), lds.ld_in(0), true, pre0, epi_zbar, nxt_z);
     else eng.template run_state<false>(lastb, lds.in(q), lds.ld_in(q), false, pre0, epi_zbar, nxt_z);
   }
-  if (g.detect) raise_if_any(bad, g.ctl);
-
-  // ---- a <- a + (h / S) sum_j zbar_j (+ running-cost cotangent), fp32; max |a|
-  unsigned bits = 0;
+  // ---- a <- a + (h / S) sum_j zbar_j (+ running-cost cotangent), fp32; max |a| after the last step
+  bits = 0;
   const float hs = h / S;
 #pragma unroll
   for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
-      float v[4], gy[4] = {0.f, 0.f, 0.f, 0.f};
-      if (g.gys) load4f(g.gys, row0 + m, g.R, n, g.d, gy);
+      float gy[4] = {0.f, 0.f, 0.f, 0.f};
+      if (g.gys) load4f(g.gys - (int64_t)it * g.gys_stride, row0 + m, g.R, n, g.d, gy);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        v[r] = fmaf(hs, da[nt][mt][r], av[nt][mt][r]) + gy[r];
-        const unsigned bb = __builtin_bit_cast(unsigned, fabsf(v[r]));
+        av[nt][mt][r] = fmaf(hs, da[nt][mt][r], av[nt][mt][r]) + gy[r];
+        const unsigned bb = __builtin_bit_cast(unsigned, fabsf(av[nt][mt][r]));
         if (row0 + m < g.R && n + r < g.d) bits = bb > bits ? bb : bits;
       }
-      store4f(g.a_out, row0 + m, g.R, n, g.d, v);
     }
+  }  // steps of this launch
+
+  if (g.detect) raise_if_any(bad, g.ctl);
+#pragma unroll
+  for (int nt = 0; nt < NTS; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      store4f(g.a_out, row0 + mt * 16 + lm, g.R, eng.state_col(nt, lq), g.d, av[nt][mt]);
   block_amax(bits, &g.ctl->amax_bits);
 
   // ---- the last workgroup to get here takes the decision of this step (accept / grow, or poison)
@@ -953,7 +977,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
       c->poison = 1;
       c->failed_step = g.step;
     } else {
-      g.scale_hist[g.step] = S;
+      for (int it = 0; it < g.nsteps; ++it) g.scale_hist[g.step - it] = S;
       c->S_step = S;
       c->s_min = fminf(c->s_min, S);
       c->s_max = fmaxf(c->s_max, S);

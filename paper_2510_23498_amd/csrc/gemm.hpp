@@ -593,7 +593,13 @@ struct WgradArgs {
   float h;
   const float* scale_hist;  // [N + 1]: scale_hist[step] = accepted scale of the step, 0 = not accepted
   int step;
+  // several steps per launch (wgrad_feature_major_steps): steps step, step - 1, ..., step - nsteps + 1;
+  // the buffers of step i are set i % nsets, set_stride elements apart; row i of steptab = (h_i, tau_i1..tau_is)
+  int nsteps, nsets;
+  int64_t set_stride;
+  const float* steptab;
 };
+constexpr int kMaxWgradSteps = 64;  // steps per launch of wgrad_feature_major_steps
 
 // (register cap: for narrow networks this kernel shares the SIMDs with the 4-wave adjoint kernel,
 // which leaves it a little over 200 of the 512 registers of a lane)
@@ -769,6 +775,190 @@ __global__ __launch_bounds__(256, 2) __attribute__((amdgpu_num_vgpr(104))) void 
   }
 }
 
+
+// The same contraction over SEVERAL steps in one launch (no scale decisions between the steps:
+// every step of the range is accepted before the launch).  A workgroup keeps its (K-chunk, tile)
+// and walks through the steps' buffer sets as one continuous sequence of k-steps, so the load
+// pipeline never drains at a step boundary; the per-step factor h_i / S_i is applied when a
+// step's partial sum is folded into the running total.  One launch then costs one epilogue and
+// one pipeline fill per workgroup instead of one per step.
+template <class T>
+__global__ __launch_bounds__(256, 2) void wgrad_feature_major_steps(WgradArgs g) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per_xcd = (int)gridDim.x >> 3;
+  const int gp = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  if (gp >= g.ntiles * g.ksplits) return;
+  const int split = gp / g.ntiles;
+  const int t = gp - split * g.ntiles;
+  WgradLayer y = g.layer[0];
+#pragma unroll
+  for (int q = 1; q < 8; ++q)
+    if (q < g.L && t >= g.layer[q].tile0) y = g.layer[q];
+  const int r = t - y.tile0;
+  const int ta = r % y.tiles_a, tb = r / y.tiles_a;
+  const int a0 = ta * 128, b0 = tb * 128;
+  const int64_t k_begin = (int64_t)split * g.kchunk;
+  int64_t k_end = k_begin + g.kchunk;
+  if (k_end > g.ldk) k_end = g.ldk;
+  if (k_begin >= k_end) return;
+
+  __shared__ __attribute__((aligned(16))) uint16_t sA[128 * LDS_PITCH];
+  __shared__ __attribute__((aligned(16))) uint16_t sB[128 * LDS_PITCH];
+  __shared__ float s_scale[kMaxWgradSteps];
+  __shared__ float s_tau[kMaxWgradSteps][kMaxStages];
+  // s_scale[i] = c_i / c_{i+1} with c_i = h / S of the launch's i-th step (the last: c_i itself):
+  // multiplying the running sums by it when step i is complete leaves, at the end,
+  // sum_i c_i * (partial sum of step i) without a second set of accumulators
+  for (int i = tid; i < g.nsteps; i += 256) {
+    const int step = g.step - i;
+    const float* row = g.steptab + (size_t)step * (1 + g.s);
+    const float c = row[0] / g.scale_hist[step];
+    float cn = 1.f;
+    if (i + 1 < g.nsteps) cn = g.steptab[(size_t)(step - 1) * (1 + g.s)] / g.scale_hist[step - 1];
+    s_scale[i] = c / cn;
+    for (int j = 0; j < kMaxStages; ++j) s_tau[i][j] = j < g.s ? row[1 + j] : 0.f;
+  }
+  __syncthreads();
+
+  const int wm = wave >> 1, wn = wave & 1;
+  constexpr int WG_STAGES = 2;
+  const int fg = tid >> 3, oct = tid & 7;
+  u16x8 ra[WG_STAGES][4], rb[WG_STAGES][4];
+  const uint16_t* pa0 = y.DT + ((size_t)((a0 + fg * 4 < y.NaPad) ? a0 / 4 + fg : 0) * g.ldk + oct * 8) * 4;
+  const uint16_t* pb0 = y.AT + ((size_t)((b0 + fg * 4 < y.NbPad) ? b0 / 4 + fg : 0) * g.ldk + oct * 8) * 4;
+  const int nk = (int)((k_end - k_begin) / BK);  // k-steps per step
+  const int total = nk * g.nsteps;
+  // position of the next tile to load: (step number it within the launch, k-step kk, buffer set)
+  int ld_it = 0, ld_kk = 0, ld_set = g.step % g.nsets;
+  auto load_tiles = [&](u16x8 (&qa)[4], u16x8 (&qb)[4]) __attribute__((always_inline)) {
+    const int64_t off = (int64_t)ld_set * g.set_stride + (k_begin + (int64_t)ld_kk * BK) * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      qa[i] = *reinterpret_cast<const u16x8*>(pa0 + off + i * 8);
+      qb[i] = *reinterpret_cast<const u16x8*>(pb0 + off + i * 8);
+    }
+    // advance, staying on the last tile once it is reached (the extra loads of the pipeline tail)
+    const bool last = (ld_it == g.nsteps - 1) && (ld_kk == nk - 1);
+    const bool wrap = (ld_kk == nk - 1);
+    ld_kk = last ? ld_kk : (wrap ? 0 : ld_kk + 1);
+    ld_it = (last || !wrap) ? ld_it : ld_it + 1;
+    ld_set = (last || !wrap) ? ld_set : (ld_set == 0 ? g.nsets - 1 : ld_set - 1);
+  };
+  auto regroup_store = [&](uint16_t* sX, const u16x8 (&rr)[4]) __attribute__((always_inline)) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = __builtin_bit_cast(u32x4, rr[i]);
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+      const int d = f >> 1;
+      const uint32_t sel = (f & 1) ? 0x07060302u : 0x05040100u;
+      u32x4 o;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[i] = __builtin_amdgcn_perm(w[i][d + 2], w[i][d], sel);
+      *reinterpret_cast<u32x4*>(&sX[(fg * 4 + f) * LDS_PITCH + oct * 8]) = o;
+    }
+  };
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.f;
+
+  const int frow = lane & 31, fk = (lane >> 5) * 8;
+  float sum_b = 0.f, sum_t = 0.f;
+#pragma unroll
+  for (int u = 0; u < WG_STAGES; ++u) load_tiles(ra[u], rb[u]);
+  int it = 0, kk = 0;  // position of the tile being consumed
+  auto k_step = [&](auto sums, u16x8 (&qa)[4], u16x8 (&qb)[4]) __attribute__((always_inline)) {
+    __builtin_amdgcn_sched_barrier(0);
+    regroup_store(sA, qa);
+    regroup_store(sB, qb);
+    __syncthreads();
+    load_tiles(qa, qb);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (decltype(sums)::value) {
+      const int j = (int)((k_begin + (int64_t)kk * BK) / g.Rp);
+      const float tau = s_tau[it][j];
+      float part = 0.f;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const u16x8 v = *reinterpret_cast<const u16x8*>(&sA[(tid >> 1) * LDS_PITCH + (tid & 1) * 32 + c * 8]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part += Low<T>::to_f32(v[e]);
+      }
+      sum_b += part;
+      sum_t = fmaf(tau, part, sum_t);
+    }
+#pragma unroll
+    for (int q4 = 0; q4 < BK / 16; ++q4) {
+      u16x8 fa[2], fb[2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+        fa[a] = *reinterpret_cast<const u16x8*>(&sA[(wm * 64 + a * 32 + frow) * LDS_PITCH + q4 * 16 + fk]);
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+        fb[b] = *reinterpret_cast<const u16x8*>(&sB[(wn * 64 + b * 32 + frow) * LDS_PITCH + q4 * 16 + fk]);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = Low<T>::mfma32(fa[a], fb[b], acc[a][b]);
+    }
+    if (kk == nk - 1) {
+      // the step's partial sums are complete: rescale the running sums for the next step
+      const float sc = s_scale[it];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int q = 0; q < 16; ++q) acc[a][b][q] *= sc;
+      sum_b *= sc;
+      sum_t *= sc;
+      kk = 0;
+      ++it;
+    } else {
+      ++kk;
+    }
+    __syncthreads();
+  };
+  auto k_loop = [&](auto sums) __attribute__((always_inline)) {
+    int n = 0;
+    for (; n + 2 <= total; n += 2) {
+      k_step(sums, ra[0], rb[0]);
+      k_step(sums, ra[1], rb[1]);
+    }
+    if (n < total) k_step(sums, ra[0], rb[0]);
+  };
+  if (tb == 0)
+    k_loop(std::true_type{});
+  else
+    k_loop(std::false_type{});
+
+  if (tb == 0) {
+    sum_b += __shfl_xor(sum_b, 1);
+    sum_t += __shfl_xor(sum_t, 1);
+    const int na = a0 + (tid >> 1);
+    if ((tid & 1) == 0 && na < y.Na) {
+      y.gb[(size_t)split * g.P + na] += sum_b;
+      if (y.gwt) y.gwt[(size_t)split * g.P + (size_t)na * y.ldg] += sum_t;
+    }
+  }
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    const int nb = b0 + wn * 64 + b * 32 + (lane & 31);
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int na = a0 + wm * 64 + a * 32 + 8 * (q >> 2) + 4 * (lane >> 5) + (q & 3);
+        if (na < y.Na && nb < y.Nb) y.G[(size_t)split * g.P + (size_t)na * y.ldg + nb] += acc[a][b][q];
+      }
+    }
+  }
+}
 
 // g[i] += sum_c part[c][i]   (end of the backward pass: fold the per-K-chunk copies)
 __global__ void reduce_partial_gradients(float* __restrict__ g, const float* __restrict__ part, int64_t P, int copies,

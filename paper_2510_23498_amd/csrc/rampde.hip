@@ -85,7 +85,9 @@ struct Plan {
   int ksplits = 1, kchunk = 64;     // K-chunks of the parameter-gradient contraction
   size_t gpart = 0;                 // ksplits copies of the gradient vector
   size_t ZT = 0, KBART = 0;
-  size_t fm_stride = 0;             // distance between the two sets of feature-group-major buffers
+  size_t fm_stride = 0;             // distance between the sets of feature-group-major buffers
+  int nsets = 2;                    // sets: step i uses set i % nsets
+  int step_group = 1;               // adjoint steps per kernel launch (> 1: fixed scale, no detection)
   std::vector<size_t> ACTT, DELTAT;
 };
 
@@ -147,6 +149,8 @@ static bool build_layers(const rampde_velocity* vel, Plan& p, int hidden_pad = k
 }
 
 static int wgrad_target_blocks();
+static int step_group_cap();
+static rampde_scaling resolve_scaling(const rampde_policy* pol);
 struct Plan;
 // the all-taps convolution weight-gradient kernel: image lines of a multiple of 8 pixels, at most
 // 64, and whole 64-row k-steps
@@ -241,6 +245,21 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
       p.Rp = (p.R + 63) / 64 * 64;
       p.ldk = (int64_t)p.s * p.Rp;
       {
+        // Without overflow detection nothing is decided between steps: a launch of the adjoint
+        // kernel then runs a group of steps (the adjoint stays in registers) and the parameter
+        // gradients of the whole group are one contraction.  Every step of a group needs its own
+        // set of buffers; groups are as long as about 4 GiB of sets allow.
+        size_t per_set = 2 * (size_t)p.dpad * p.ldk * 2;
+        for (int l = 0; l + 1 < p.L; ++l) per_set += 2 * (size_t)p.layers[l].Npad * p.ldk * 2;
+        const int64_t fit = (int64_t)((size_t(4) << 30) / per_set);
+        const int64_t cap = std::min<int64_t>(step_group_cap(), std::min<int64_t>(fit, kMaxWgradSteps));
+        if (pol && resolve_scaling(pol) == RAMPDE_SCALE_NONE && cap >= 2) {
+          p.step_group = (int)std::min<int64_t>(N, cap);
+          p.nsets = p.step_group;
+          p.overlap_wgrad = false;
+        }
+      }
+      {
         int tiles = 0;
         for (auto& y : p.layers) tiles += ((y.Npad + 127) / 128) * ((y.Kpad + 127) / 128);
         // K-chunks: as many workgroups as are resident at once (two per CU; one when the kernel
@@ -248,7 +267,9 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
         // workgroups costs more than it spreads --, but at least 256 k per chunk
         const int resident = wgrad_target_blocks() * (p.overlap_wgrad ? 1 : 2);
         int64_t ks = std::max(1, resident / tiles);
-        ks = std::max<int64_t>(1, std::min<int64_t>(ks, p.ldk / 256 > 0 ? p.ldk / 256 : 1));
+        // (a group of steps multiplies a workgroup's k-steps: chunks can be shorter)
+        const int64_t min_chunk = p.step_group > 1 ? 128 : 256;
+        ks = std::max<int64_t>(1, std::min<int64_t>(ks, p.ldk / min_chunk > 0 ? p.ldk / min_chunk : 1));
         const int64_t kc = ((p.ldk + ks - 1) / ks + 63) / 64 * 64;
         p.kchunk = (int)kc;
         p.ksplits = (int)((p.ldk + kc - 1) / kc);
@@ -264,7 +285,7 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
         p.DELTAT.push_back(take((size_t)p.layers[l].Npad * p.ldk * 2));
       }
       p.fm_stride = off - fm_begin;
-      take(p.fm_stride);  // second set
+      for (int q = 1; q < p.nsets; ++q) take(p.fm_stride);  // the other sets
     }
   } else {
     p.Z = take((size_t)sbuf * p.R * p.dpad * 2);
@@ -293,6 +314,13 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
   p.total = off;
   p.ok = true;
   return p;
+}
+
+// upper limit of the adjoint steps per launch (environment RAMPDE_STEP_GROUP, for experiments and tests)
+static int step_group_cap() {
+  const char* e = getenv("RAMPDE_STEP_GROUP");
+  const int x = e ? atoi(e) : 0;
+  return x > 0 ? x : kMaxWgradSteps;
 }
 
 static bool conv_wgrad_applies(const Plan& p) { return p.conv && !p.fused && p.Wd % 8 == 0 && p.Wd <= 64 && p.R % 64 == 0; }
@@ -634,7 +662,7 @@ struct Runner {
   }
 
   int adjoint_step_fused(const FusedArgs& a) {
-    TimeScope ts(RAMPDE_K_FUSED_ADJOINT_STEP, step_flops() * p.s * (a.skip_recompute ? 1.0 : 2.0), st);
+    TimeScope ts(RAMPDE_K_FUSED_ADJOINT_STEP, step_flops() * p.s * (a.skip_recompute ? 1.0 : 2.0) * a.nsteps, st);
     return launch_fused(true, a);
   }
 
@@ -820,9 +848,10 @@ struct Runner {
   }
 
   // parameter gradients from the feature-major buffers of the row-tile-persistent adjoint kernel
-  void param_grads_fused(int step, float h, const Coefs& taus, hipStream_t stream) {
+  // steps step, step - 1, ..., step - nsteps + 1 in one launch (nsteps > 1: h and taus come from the step table)
+  void param_grads_fused(int step, float h, const Coefs& taus, hipStream_t stream, int nsteps = 1) {
     float* grad_theta = f32(p.gpart);  // copy 0; chunk c adds into copy c
-    const size_t set = (size_t)(step & 1) * p.fm_stride;
+    const size_t set = nsteps > 1 ? 0 : (size_t)(step % p.nsets) * p.fm_stride;
     WgradArgs w{};
     w.L = p.L;
     w.ksplits = p.ksplits;
@@ -835,6 +864,10 @@ struct Runner {
     w.h = h;
     w.scale_hist = f32(p.scale_hist);
     w.step = step;
+    w.nsteps = nsteps;
+    w.nsets = p.nsets;
+    w.set_stride = (int64_t)(p.fm_stride / 2);
+    w.steptab = f32(p.steptab);
     int blk = 0;
     double flops = 0.0;
     for (int l = 0; l < p.L; ++l) {
@@ -854,12 +887,15 @@ struct Runner {
       d.tiles_b = (y.Kpad + 127) / 128;
       d.tile0 = blk;
       blk += d.tiles_a * d.tiles_b;
-      flops += 2.0 * (double)p.ldk * y.Npad * y.Kpad;
+      flops += 2.0 * (double)p.ldk * y.Npad * y.Kpad * nsteps;
     }
     w.ntiles = blk;
     const int grid = (blk * w.ksplits + 7) / 8 * 8;  // a multiple of the XCD count: see the kernel's block mapping
     TimeScope ts(RAMPDE_K_WGRAD_GEMM, flops, stream);
-    wgrad_feature_major<T><<<grid, 256, 0, stream>>>(w);
+    if (nsteps > 1)
+      wgrad_feature_major_steps<T><<<grid, 256, 0, stream>>>(w);
+    else
+      wgrad_feature_major<T><<<grid, 256, 0, stream>>>(w);
   }
 
   int backward(const float* theta, const double* tgrid, int N, const rampde_tableau* tab, const rampde_policy* pol,
@@ -895,10 +931,19 @@ struct Runner {
       fa.ldk = p.ldk;
       fa.Rp = p.Rp;
       fa.ZBAR = u16(p.ZBAR);
+      for (int l = 0; l + 1 < p.L; ++l) {
+        fa.ACTT[l] = u16(p.ACTT[l]);
+        fa.DELTAT[l] = u16(p.DELTAT[l]);
+      }
+      fa.ZT = u16(p.ZT);
+      fa.KBART = u16(p.KBART);
+      fa.nsets = p.nsets;
+      fa.set_stride = (int64_t)(p.fm_stride / 2);
+      fa.nsteps = 1;
       fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + p.gpart), (size_t)p.ksplits * p.P);
       if (p.Rp != p.R) {
         // rows R..Rp of every stage are padding of the contraction: they must read as zero
-        fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + p.ZT), 2 * p.fm_stride / 4);
+        fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + p.ZT), (size_t)p.nsets * p.fm_stride / 4);
       }
       fa.ctl = ctl;
       fa.scale_hist = f32(p.scale_hist);
@@ -932,18 +977,35 @@ struct Runner {
     int status = RAMPDE_OK;
     const bool must_sync = detect || stats || scale_hist;
     for (;;) {
-      for (int i = from; i >= 0; --i) {
+      if (use_fused && p.step_group > 1) {
+        // groups of steps: one adjoint launch and one parameter-gradient launch per group, all on
+        // the caller's stream; the adjoint ping-pongs between two buffers per launch so that the
+        // last launch writes grad_y0
+        const int groups = (N + p.step_group - 1) / p.step_group;
+        int hi = N - 1;
+        const float* cur = a_buf(N);
+        for (int gi = 0; gi < groups; ++gi) {
+          const int n = std::min(p.step_group, hi + 1);
+          fa.step = hi;
+          fa.nsteps = n;
+          fa.a_in = cur;
+          fa.a_out = ((groups - 1 - gi) % 2 == 0) ? grad_y0 : f32(p.a_alt);
+          cur = fa.a_out;
+          fa.gys = gys_at(hi);
+          fa.gys_stride = p.n;
+          fa.skip_recompute = 0;
+          int rc = adjoint_step_fused(fa);
+          if (rc) return rc;
+          param_grads_fused(hi, 0.f, Coefs{}, st, n);
+          hi -= n;
+        }
+      }
+      for (int i = (use_fused && p.step_group > 1) ? -1 : from; i >= 0; --i) {
         if (use_fused) {
-          const size_t set = (size_t)(i & 1) * p.fm_stride;
-          for (int l = 0; l + 1 < p.L; ++l) {
-            fa.ACTT[l] = u16(p.ACTT[l] + set);
-            fa.DELTAT[l] = u16(p.DELTAT[l] + set);
-          }
-          fa.ZT = u16(p.ZT + set);
-          fa.KBART = u16(p.KBART + set);
           // this set was last read by the parameter-gradient kernel of step i + 2
           if (p.overlap_wgrad && i + 2 <= N - 1) HIP_TRY(hipStreamWaitEvent(st, side.wgrad_done(i + 2), 0));
           fa.step = i;
+          fa.nsteps = 1;
           fa.a_in = a_buf(i + 1);
           fa.a_out = a_buf(i);
           fa.gys = gys_at(i);

@@ -111,3 +111,23 @@ def test_running_cost_cotangents(flags):
     gpu = par.run_gpu(cfg, theta, y0, target, grad_ys=gys, flags=flags)
     emu = par.run_oracle(cfg, theta, y0, target, "emul", grad_ys=gys.astype(np.float64))
     par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
+
+
+@pytest.mark.parametrize("group", [2, 3, 64])
+@pytest.mark.parametrize("low", ["bf16", "f16"])
+def test_fixed_scale_runs_groups_of_steps_per_launch(group, low, monkeypatch):
+    # Without overflow detection (scaling "none") the adjoint kernel runs several steps per launch and
+    # their parameter gradients are one contraction; groups of 2 / 3 (ragged last group of an 8-step
+    # grid) / all steps, ragged batch (rows padded inside the contraction), running-cost cotangents.
+    monkeypatch.setenv("RAMPDE_STEP_GROUP", str(group))
+    cfg = wl.CONFIGS["cfg2"].with_(name=f"grp{group}{low}", B=200, N=8, widths=(24, 256, 256, 24), low=low,
+                                   tableau="kutta3" if group == 3 else "rk4")
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    gys = wl.normals(5, "grp.gys", (cfg.N + 1, cfg.B, 24), 1e-3)
+    print(f"[case] {cfg.name}", flush=True)
+    gpu = par.run_gpu(cfg, theta, y0, target, scaling="none", grad_ys=gys)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul", scaling="none", grad_ys=gys.astype(np.float64))
+    e = par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
+    print("  vs emul:", {k: f"{v:.2e}" for k, v in e.items()}, flush=True)
+    assert gpu["status"] == 0
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
