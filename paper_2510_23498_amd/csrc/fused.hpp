@@ -110,35 +110,59 @@ struct FusedArgs {
   int detect, dynamic, raw_norm, skip_recompute;
 };
 
-// theta (fp32) -> fragment-major low-precision copies of one dense layer (see FusedLayer).
+// theta (fp32) -> fragment-major low-precision copies of all dense layers (see FusedLayer) and the
+// rounded biases / time-column weights (kept as fp32 for the epilogues), in one launch.
+struct CastLayer {
+  const float* W;   // [out][in_full]
+  const float* b;   // [out]
+  u16x8* Wf;
+  u16x8* WTf;
+  float* bias_f;    // [Npad]
+  float* wt_f;      // [Npad]
+  int out, in, in_full, has_time, Npad, Kpad;
+  int frag0;        // index of the layer's first fragment among all layers' fragments
+};
+struct CastArgs {
+  CastLayer layer[kMaxLayers];
+  int L, nfrag;
+};
+
 template <class T>
-__global__ void cast_dense_fragments(const float* __restrict__ W, int out, int in, int in_full, u16x8* Wf,
-                                     u16x8* WTf, int Npad, int Kpad) {
+__global__ void cast_dense_fragments(CastArgs c) {
   const int lane = threadIdx.x & 63;
-  const int frag = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  const int nfw = (Kpad / 32) * (Npad / 16);
-  const int nft = (Npad / 32) * (Kpad / 16);
+  int frag = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (frag >= c.nfrag) return;
+  CastLayer y = c.layer[0];
+#pragma unroll
+  for (int q = 1; q < kMaxLayers; ++q)
+    if (q < c.L && frag >= c.layer[q].frag0) y = c.layer[q];
+  frag -= y.frag0;
+  const int nfw = (y.Kpad / 32) * (y.Npad / 16);
   if (frag < nfw) {
-    const int kb = frag / (Npad / 16), nt = frag % (Npad / 16);
+    const int kb = frag / (y.Npad / 16), nt = frag % (y.Npad / 16);
     const int n = nt * 16 + (lane & 15), k0 = kb * 32 + (lane >> 4) * 8;
     u16x8 v;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int k = k0 + e;
-      v[e] = (n < out && k < in) ? Low<T>::from_f32(W[(size_t)n * in_full + k]) : (uint16_t)0;
+      v[e] = (n < y.out && k < y.in) ? Low<T>::from_f32(y.W[(size_t)n * y.in_full + k]) : (uint16_t)0;
     }
-    Wf[(size_t)frag * 64 + lane] = v;
-  } else if (frag < nfw + nft) {
+    y.Wf[(size_t)frag * 64 + lane] = v;
+    if (kb == 0 && lane < 16) {
+      y.bias_f[n] = (n < y.out) ? Low<T>::to_f32(Low<T>::from_f32(y.b[n])) : 0.f;
+      y.wt_f[n] = (n < y.out && y.has_time) ? Low<T>::to_f32(Low<T>::from_f32(y.W[(size_t)n * y.in_full + y.in])) : 0.f;
+    }
+  } else {
     const int f = frag - nfw;
-    const int nb = f / (Kpad / 16), kt = f % (Kpad / 16);
+    const int nb = f / (y.Kpad / 16), kt = f % (y.Kpad / 16);
     const int k = kt * 16 + (lane & 15), n0 = nb * 32 + (lane >> 4) * 8;
     u16x8 v;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int n = n0 + e;
-      v[e] = (n < out && k < in) ? Low<T>::from_f32(W[(size_t)n * in_full + k]) : (uint16_t)0;
+      v[e] = (n < y.out && k < y.in) ? Low<T>::from_f32(y.W[(size_t)n * y.in_full + k]) : (uint16_t)0;
     }
-    WTf[(size_t)f * 64 + lane] = v;
+    y.WTf[(size_t)f * 64 + lane] = v;
   }
 }
 

@@ -406,11 +406,10 @@ struct TimeScope {
 // Host floats -> device memory by way of kernel arguments (copied at launch: no host buffer has
 // to outlive the call, and the write is an ordinary kernel node for a caller capturing a graph).
 struct FloatChunk {
-  float v[96];
+  float v[768];
 };
 __global__ void write_floats(FloatChunk c, float* dst, int count) {
-  const int i = threadIdx.x;
-  if (i < count) dst[i] = c.v[i];
+  for (int i = threadIdx.x; i < count; i += blockDim.x) dst[i] = c.v[i];
 }
 
 // Helper stream on which the parameter-gradient kernel of step i runs while the adjoint kernel
@@ -545,12 +544,25 @@ struct Runner {
   bool use_fused = false;
 
   void cast_fragments(const float* theta) {
-    for (const Layer& y : p.layers) {
-      const int nfr = (y.Kpad / 32) * (y.Npad / 16) + (y.Npad / 32) * (y.Kpad / 16);
-      cast_dense_fragments<T><<<blocks_for(nfr, 4), 256, 0, st>>>(theta + y.theta_w, y.out, y.in, y.in_full,
-                                                                 (u16x8*)(ws + y.Wf), (u16x8*)(ws + y.WTf), y.Npad,
-                                                                 y.Kpad);
+    CastArgs c{};
+    c.L = p.L;
+    int nfrag = 0;
+    for (int l = 0; l < p.L; ++l) {
+      const Layer& y = p.layers[l];
+      CastLayer& d = c.layer[l];
+      d.W = theta + y.theta_w;
+      d.b = theta + y.theta_b;
+      d.Wf = (u16x8*)(ws + y.Wf);
+      d.WTf = (u16x8*)(ws + y.WTf);
+      d.bias_f = f32(y.bias_f);
+      d.wt_f = f32(y.wt_f);
+      d.out = y.out; d.in = y.in; d.in_full = y.in_full; d.has_time = y.has_time;
+      d.Npad = y.Npad; d.Kpad = y.Kpad;
+      d.frag0 = nfrag;
+      nfrag += (y.Kpad / 32) * (y.Npad / 16) + (y.Npad / 32) * (y.Kpad / 16);
     }
+    c.nfrag = nfrag;
+    cast_dense_fragments<T><<<blocks_for(nfrag, 4), 256, 0, st>>>(c);
   }
 
   // per step: h_i, then the stage times rounded to low precision
@@ -562,11 +574,11 @@ struct Runner {
       for (int j = 0; j < p.s; ++j)
         tabv[(size_t)i * (1 + p.s) + 1 + j] = round_low_host((float)(tgrid[i] + tab->c[j] * (double)h), low);
     }
-    for (size_t off = 0; off < tabv.size(); off += 96) {
+    for (size_t off = 0; off < tabv.size(); off += 768) {
       FloatChunk c;
-      const int cnt = (int)std::min<size_t>(96, tabv.size() - off);
+      const int cnt = (int)std::min<size_t>(768, tabv.size() - off);
       memcpy(c.v, tabv.data() + off, sizeof(float) * cnt);
-      write_floats<<<1, 128, 0, st>>>(c, f32(p.steptab) + off, cnt);
+      write_floats<<<1, 256, 0, st>>>(c, f32(p.steptab) + off, cnt);
     }
   }
 
@@ -643,7 +655,6 @@ struct Runner {
 
   int forward_fused(const float* theta, const float* y0, const double* tgrid, int N, const rampde_tableau* tab,
                     const rampde_policy* pol, uint16_t* ckpt, float* yN) {
-    cast_weights(theta);
     cast_fragments(theta);
     write_steptab(tgrid, N, tab, pol->low);
     FusedArgs a = fused_args(tab, N);
@@ -913,7 +924,7 @@ struct Runner {
       for (auto& y : p.layers)
         fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + y.cw_part),
                                             (size_t)y.cw_splits * (y.Npad / 64) * (y.Kpad / 64) * 9 * 4096);
-    cast_weights(theta);
+    if (!use_fused) cast_weights(theta);
     SideStream& side = SideStream::get();
     if (use_fused && p.overlap_wgrad) {
       int rc = side.prepare(N);
