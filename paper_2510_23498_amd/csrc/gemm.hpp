@@ -114,6 +114,25 @@ __global__ __launch_bounds__(256) void gemm_nt(GemmNT g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
+  // conv: the constant time channel contributes tau * (sum of its tap weights whose neighbour pixel
+  // exists).  That sum depends only on which of the four borders the pixel touches: 16 cases per
+  // output channel, tabulated once (same summation order as tap-by-tap accumulation).
+  __shared__ float s_tt[CONV ? 16 * BN : 1];
+  if (CONV && g.wt) {
+    for (int i = tid; i < 16 * BN; i += 256) {
+      const int combo = i / BN, n = n0 + i % BN;
+      float sum = 0.f;
+#pragma unroll
+      for (int t = 0; t < 9; ++t) {
+        const int dy = t / 3 - 1, dx = t % 3 - 1;
+        const bool ok = (dy >= 0 || (combo & 8)) && (dy <= 0 || (combo & 4)) && (dx >= 0 || (combo & 2)) &&
+                        (dx <= 0 || (combo & 1));
+        if (ok) sum += g.wt[t * g.N + n] * g.tau;
+      }
+      s_tt[i] = sum;
+    }
+  }
+
   const int KT = g.K / BK;
   load_tiles(0);
   store_tiles();
@@ -147,35 +166,35 @@ __global__ __launch_bounds__(256) void gemm_nt(GemmNT g) {
   bool bad = false;
 #pragma unroll
   for (int b = 0; b < NI; ++b) {
-    const int n = n0 + wn * 32 * NI + b * 32 + (lane & 31);
+    const int nn = wn * 32 * NI + b * 32 + (lane & 31);
+    const int n = n0 + nn;
     const float bv = g.bias ? g.bias[n] : 0.f;
-    float tv = 0.f;
-    float tw[9];
-    if (g.wt) {
-      if (CONV) {
-#pragma unroll
-        for (int t = 0; t < 9; ++t) tw[t] = g.wt[t * g.N + n] * g.tau;
-      } else {
-        tv = g.wt[n] * g.tau;
-      }
-    }
+    const float tv = (!CONV && g.wt) ? g.wt[n] * g.tau : 0.f;
 #pragma unroll
     for (int a = 0; a < MI; ++a) {
+      // pixel coordinates of the lane's first row; the other 15 rows follow by stepping
+      const int mb = m0 + wm * 32 * MI + a * 32 + 4 * (lane >> 5);
+      int x = 0, y = 0;
+      if (CONV && g.wt) {
+        x = mb % g.Wd;
+        y = (mb / g.Wd) % g.H;
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 32 * MI + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int m = mb + 8 * (r >> 2) + (r & 3);
+        if (CONV && g.wt && r > 0) {
+          x += (r & 3) ? 1 : 5;
+          while (x >= g.Wd) {
+            x -= g.Wd;
+            y = (y + 1 == g.H) ? 0 : y + 1;
+          }
+        }
         if (m < g.M) {
           float v = acc[a][b][r] + bv;
           if (g.wt) {
             if (CONV) {
-              int x = m % g.Wd, y = (m / g.Wd) % g.H;
-              float s = 0.f;
-#pragma unroll
-              for (int t = 0; t < 9; ++t) {
-                int yy = y + t / 3 - 1, xx = x + t % 3 - 1;
-                if (yy >= 0 && yy < g.H && xx >= 0 && xx < g.Wd) s += tw[t];
-              }
-              v += s;
+              const int combo = ((y > 0) << 3) | ((y < g.H - 1) << 2) | ((x > 0) << 1) | (x < g.Wd - 1 ? 1 : 0);
+              v += s_tt[combo * BN + nn];
             } else {
               v += tv;
             }
