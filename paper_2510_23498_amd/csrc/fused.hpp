@@ -731,7 +731,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_forward_fused(FusedArgs g) {
 
 // ---------------------------------------------------------------------------------------
 // One step of the adjoint for a row tile (paper Algorithm 2, the body of the loop over steps).
-template <class T, int MT, int NTL, int NW, int HP>
+template <class T, int MT, int NTL, int NW, int HP, bool MULTI>
 __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   if (g.ctl->poison) return;
@@ -761,217 +761,219 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
     for (int mt = 0; mt < MT; ++mt)
       load4f(g.a_in, row0 + mt * 16 + lm, g.R, eng.state_col(nt, lq), g.d, av[nt][mt]);
 
+  // (MULTI = false: exactly one step, and the loop below folds away)
+  const int nsteps = MULTI ? g.nsteps : 1;
 #pragma unroll 1
-  for (int it = 0; it < g.nsteps; ++it) {
-  const int step = g.step - it;
-  const float* st = g.steptab + (size_t)step * (1 + s);
-  const float h = st[0];
-  const int64_t set_off = (int64_t)(step % g.nsets) * g.set_stride;
-  uint16_t* const ZT = g.ZT + set_off;
-  uint16_t* const KBART = g.KBART + set_off;
-  // lambda = Q(S a); yhat = stored state
-  uint2 lamq[NTS][MT], yhat[NTS][MT];
+  for (int it = 0; it < nsteps; ++it) {
+    const int step = g.step - it;
+    const float* st = g.steptab + (size_t)step * (1 + s);
+    const float h = st[0];
+    const int64_t set_off = (int64_t)(step % g.nsets) * g.set_stride;
+    uint16_t* const ZT = g.ZT + set_off;
+    uint16_t* const KBART = g.KBART + set_off;
+    // lambda = Q(S a); yhat = stored state
+    uint2 lamq[NTS][MT], yhat[NTS][MT];
 #pragma unroll
-  for (int nt = 0; nt < NTS; ++nt)
+    for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
-      float sa[4];
+      for (int mt = 0; mt < MT; ++mt) {
+        const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
+        float sa[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) sa[r] = S * av[nt][mt][r];
-      lamq[nt][mt] = pack4<T>(sa);
-      bad = bad || any_nonfinite4<T>(lamq[nt][mt]);
-      yhat[nt][mt] = load4h(g.ckpt + (size_t)step * n_state, row0 + m, g.R, n, g.d);
-    }
-
-  // cotangent of the slope of stage j:  kbar_j = Q( b_j lambda + h sum_{l>j} a_lj zbar_l ),
-  // with zbar_{j+1} still in registers (zn) and the later ones read back from the stage store
-  auto make_kbar = [&](int j, int nt, int mt, int m, int n, const float* zn) -> uint2 {
-    float lam[4], acc[4] = {0.f, 0.f, 0.f, 0.f}, v[4];
-    unpack4<T>(lamq[nt][mt], lam);
-    for (int l = s - 1; l > j + 1; --l) {
-      const float a = g.A[l * s + j];
-      if (a != 0.f) {
-        float zl[4];
-        unpack4<T>(zs.get(l, m, n), zl);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[r] = fmaf(a, zl[r], acc[r]);
+        for (int r = 0; r < 4; ++r) sa[r] = S * av[nt][mt][r];
+        lamq[nt][mt] = pack4<T>(sa);
+        bad = bad || any_nonfinite4<T>(lamq[nt][mt]);
+        yhat[nt][mt] = load4h(g.ckpt + (size_t)step * n_state, row0 + m, g.R, n, g.d);
       }
-    }
-    if (zn) {
-      const float a = g.A[(j + 1) * s + j];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) acc[r] = fmaf(a, zn[r], acc[r]);
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) v[r] = fmaf(h, acc[r], g.b[j] * lam[r]);
-    const uint2 q = pack4<T>(v);
-    bad = bad || any_nonfinite4<T>(q);
-    lds_store_u2(&lds.zbuf[m * lds.ldz + n], q);
-    if (row0 + m < g.R) RAMPDE_STORE_G4(group4(KBART, g.ldk, (int64_t)j * g.Rp + row0 + m, n), q);
-    return q;
-  };
 
-  const PassDesc firstf = fwd_pass(g, 0);
-  const PassDesc lastf = fwd_pass(g, L - 1);
-  const PassDesc firstb = bwd_pass(g, L - 1);
-  const PassDesc lastb = bwd_pass(g, 0);
-
-  auto preload_first_f = [&]() {
-    if (L > 1) eng.template preload_hidden<true>(firstf, 0);
-    else eng.template preload_state<true>(firstf);
-  };
-  auto preload_first_b = [&]() {
-    if (L > 1) eng.template preload_hidden<true>(firstb, 0);
-    else eng.template preload_state<true>(firstb);
-  };
-
-  if (!g.skip_recompute) {
-    // ---- stage recomputation from the stored state, keeping inputs and activations
-    preload_first_f();
-    if (eng.state_wave()) {
+    // cotangent of the slope of stage j:  kbar_j = Q( b_j lambda + h sum_{l>j} a_lj zbar_l ),
+    // with zbar_{j+1} still in registers (zn) and the later ones read back from the stage store
+    auto make_kbar = [&](int j, int nt, int mt, int m, int n, const float* zn) -> uint2 {
+      float lam[4], acc[4] = {0.f, 0.f, 0.f, 0.f}, v[4];
+      unpack4<T>(lamq[nt][mt], lam);
+      for (int l = s - 1; l > j + 1; --l) {
+        const float a = g.A[l * s + j];
+        if (a != 0.f) {
+          float zl[4];
+          unpack4<T>(zs.get(l, m, n), zl);
 #pragma unroll
-      for (int nt = 0; nt < NTS; ++nt)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
-          lds_store_u2(&lds.zbuf[m * lds.ldz + n], yhat[nt][mt]);
-          if (row0 + m < g.R) RAMPDE_STORE_G4(group4(ZT, g.ldk, row0 + m, n), yhat[nt][mt]);
+          for (int r = 0; r < 4; ++r) acc[r] = fmaf(a, zl[r], acc[r]);
         }
-    }
-    __syncthreads();
-    for (int j = 0; j < s; ++j) {
-      const float tau = st[1 + j];
-      hidden_layers<T, MT, NTL, NW, HP, true>(eng, lds, g, j, tau, row0, set_off);
-      const bool more = j + 1 < s;
-      auto pre0 = [](int, int) { return make_uint2(0u, 0u); };
-      auto epi_last = [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
-            float v[4];
-            last_layer_values(acc, lds.param, g, tau, n, v);
-            const uint2 kq = pack4<T>(v);
-            if (j + 1 < s) {
-              float kf[4], incr[4] = {0.f, 0.f, 0.f, 0.f}, yh[4], z[4];
-              unpack4<T>(kq, kf);
-              unpack4<T>(yhat[nt][mt], yh);
-              ks.put(j, m, n, kq);
-              for (int l = 0; l < j; ++l) {
-                const float a = g.A[(j + 1) * s + l];
-                if (a != 0.f) {
-                  float kl[4];
-                  unpack4<T>(ks.get(l, m, n), kl);
+      }
+      if (zn) {
+        const float a = g.A[(j + 1) * s + j];
 #pragma unroll
-                  for (int r = 0; r < 4; ++r) incr[r] = fmaf(a, kl[r], incr[r]);
+        for (int r = 0; r < 4; ++r) acc[r] = fmaf(a, zn[r], acc[r]);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) v[r] = fmaf(h, acc[r], g.b[j] * lam[r]);
+      const uint2 q = pack4<T>(v);
+      bad = bad || any_nonfinite4<T>(q);
+      lds_store_u2(&lds.zbuf[m * lds.ldz + n], q);
+      if (row0 + m < g.R) RAMPDE_STORE_G4(group4(KBART, g.ldk, (int64_t)j * g.Rp + row0 + m, n), q);
+      return q;
+    };
+
+    const PassDesc firstf = fwd_pass(g, 0);
+    const PassDesc lastf = fwd_pass(g, L - 1);
+    const PassDesc firstb = bwd_pass(g, L - 1);
+    const PassDesc lastb = bwd_pass(g, 0);
+
+    auto preload_first_f = [&]() {
+      if (L > 1) eng.template preload_hidden<true>(firstf, 0);
+      else eng.template preload_state<true>(firstf);
+    };
+    auto preload_first_b = [&]() {
+      if (L > 1) eng.template preload_hidden<true>(firstb, 0);
+      else eng.template preload_state<true>(firstb);
+    };
+
+    if (!g.skip_recompute) {
+      // ---- stage recomputation from the stored state, keeping inputs and activations
+      preload_first_f();
+      if (eng.state_wave()) {
+#pragma unroll
+        for (int nt = 0; nt < NTS; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
+            lds_store_u2(&lds.zbuf[m * lds.ldz + n], yhat[nt][mt]);
+            if (row0 + m < g.R) RAMPDE_STORE_G4(group4(ZT, g.ldk, row0 + m, n), yhat[nt][mt]);
+          }
+      }
+      __syncthreads();
+      for (int j = 0; j < s; ++j) {
+        const float tau = st[1 + j];
+        hidden_layers<T, MT, NTL, NW, HP, true>(eng, lds, g, j, tau, row0, set_off);
+        const bool more = j + 1 < s;
+        auto pre0 = [](int, int) { return make_uint2(0u, 0u); };
+        auto epi_last = [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
+              float v[4];
+              last_layer_values(acc, lds.param, g, tau, n, v);
+              const uint2 kq = pack4<T>(v);
+              if (j + 1 < s) {
+                float kf[4], incr[4] = {0.f, 0.f, 0.f, 0.f}, yh[4], z[4];
+                unpack4<T>(kq, kf);
+                unpack4<T>(yhat[nt][mt], yh);
+                ks.put(j, m, n, kq);
+                for (int l = 0; l < j; ++l) {
+                  const float a = g.A[(j + 1) * s + l];
+                  if (a != 0.f) {
+                    float kl[4];
+                    unpack4<T>(ks.get(l, m, n), kl);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) incr[r] = fmaf(a, kl[r], incr[r]);
+                  }
                 }
-              }
-              const float aj = g.A[(j + 1) * s + j];
+                const float aj = g.A[(j + 1) * s + j];
 #pragma unroll
-              for (int r = 0; r < 4; ++r) z[r] = fmaf(h, fmaf(aj, kf[r], incr[r]), yh[r]);
-              const uint2 zq = pack4<T>(z);
-              lds_store_u2(&lds.zbuf[m * lds.ldz + n], zq);
-              if (row0 + m < g.R) RAMPDE_STORE_G4(group4(ZT, g.ldk, (int64_t)(j + 1) * g.Rp + row0 + m, n), zq);
-            } else {
-              make_kbar(s - 1, nt, mt, m, n, nullptr);  // the slope of the last stage is not needed again
+                for (int r = 0; r < 4; ++r) z[r] = fmaf(h, fmaf(aj, kf[r], incr[r]), yh[r]);
+                const uint2 zq = pack4<T>(z);
+                lds_store_u2(&lds.zbuf[m * lds.ldz + n], zq);
+                if (row0 + m < g.R) RAMPDE_STORE_G4(group4(ZT, g.ldk, (int64_t)(j + 1) * g.Rp + row0 + m, n), zq);
+              } else {
+                make_kbar(s - 1, nt, mt, m, n, nullptr);  // the slope of the last stage is not needed again
+              }
+            };
+        auto nxt_last = [&]() {
+          if (more) preload_first_f();
+          else preload_first_b();
+        };
+        if (L == 1) eng.template run_state<true>(lastf, lds.in(0), lds.ld_in(0), true, pre0, epi_last, nxt_last);
+        else eng.template run_state<false>(lastf, lds.in(L - 1), lds.ld_in(L - 1), false, pre0, epi_last, nxt_last);
+      }
+    } else {
+      preload_first_b();
+      if (eng.state_wave()) {
+#pragma unroll
+        for (int nt = 0; nt < NTS; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            make_kbar(s - 1, nt, mt, mt * 16 + lm, eng.state_col(nt, lq), nullptr);
+      }
+      __syncthreads();
+    }
+
+    // ---- cotangent chain, stages in reverse (eq. (vjp) pushed through the stage recursion)
+    float da[NTS][MT][4];
+#pragma unroll
+    for (int nt = 0; nt < NTS; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) da[nt][mt][r] = 0.f;
+
+    for (int j = s - 1; j >= 0; --j) {
+      for (int l = L - 1; l >= 1; --l) {
+        const int q = L - 1 - l;
+        const PassDesc p = bwd_pass(g, l);
+        const PassDesc nx = bwd_pass(g, l - 1);
+        const bool next_is_last = (l == 1);
+        uint16_t* actT = g.ACTT[l - 1] + set_off;
+        uint16_t* goutT = g.DELTAT[l - 1] + set_off;
+        const int64_t kj = (int64_t)j * g.Rp + row0;
+        lds_u16* out = lds.out(q);
+        const int ldp = lds.ldp;
+        auto pre_act = [&](int n, int m) {
+                  return (row0 + m < g.R) ? *group4(actT, g.ldk, kj + m, n) : make_uint2(0u, 0u);
+                };
+        auto epi_delta = [&](const f32x4& acc, uint2 pf, int, int, int n, int m) {
+                  float a[4], v[4];
+                  unpack4<T>(pf, a);
+#pragma unroll
+                  for (int r = 0; r < 4; ++r) v[r] = acc[r] * (1.f - a[r] * a[r]);
+                  const uint2 dq = pack4<T>(v);
+                  lds_store_u2(&out[m * ldp + n], dq);
+                  if (row0 + m < g.R) {
+                    RAMPDE_STORE_G4(group4(goutT, g.ldk, kj + m, n), dq);
+                    bad = bad || any_nonfinite4<T>(dq);
+                  }
+                };
+        auto nxt_b = [&]() {
+          if (next_is_last) eng.template preload_state<false>(nx);
+          else eng.template preload_hidden<false>(nx, 0);
+        };
+        if (q == 0) eng.template run_hidden<true>(p, lds.in(q), lds.ld_in(q), pre_act, epi_delta, nxt_b);
+        else eng.template run_hidden<false>(p, lds.in(q), lds.ld_in(q), pre_act, epi_delta, nxt_b);
+      }
+      const int q = L - 1;
+      auto pre0 = [](int, int) { return make_uint2(0u, 0u); };
+      auto epi_zbar = [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
+            const float v[4] = {acc[0], acc[1], acc[2], acc[3]};
+            const uint2 zq = pack4<T>(v);
+            if (row0 + m < g.R) bad = bad || any_nonfinite4<T>(zq);
+            float zf[4];
+            unpack4<T>(zq, zf);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) da[nt][mt][r] += zf[r];
+            if (j > 0) {
+              zs.put(j, m, n, zq);
+              make_kbar(j - 1, nt, mt, m, n, zf);
             }
           };
-      auto nxt_last = [&]() {
-        if (more) preload_first_f();
-        else preload_first_b();
+      auto nxt_z = [&]() {
+        if (j > 0) preload_first_b();
       };
-      if (L == 1) eng.template run_state<true>(lastf, lds.in(0), lds.ld_in(0), true, pre0, epi_last, nxt_last);
-      else eng.template run_state<false>(lastf, lds.in(L - 1), lds.ld_in(L - 1), false, pre0, epi_last, nxt_last);
+      if (L == 1) eng.template run_state<true>(lastb, lds.in(0), lds.ld_in(0), true, pre0, epi_zbar, nxt_z);
+      else eng.template run_state<false>(lastb, lds.in(q), lds.ld_in(q), false, pre0, epi_zbar, nxt_z);
     }
-  } else {
-    preload_first_b();
-    if (eng.state_wave()) {
+    // ---- a <- a + (h / S) sum_j zbar_j (+ running-cost cotangent), fp32; max |a| after the last step
+    bits = 0;
+    const float hs = h / S;
 #pragma unroll
-      for (int nt = 0; nt < NTS; ++nt)
+    for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          make_kbar(s - 1, nt, mt, mt * 16 + lm, eng.state_col(nt, lq), nullptr);
-    }
-    __syncthreads();
-  }
-
-  // ---- cotangent chain, stages in reverse (eq. (vjp) pushed through the stage recursion)
-  float da[NTS][MT][4];
+      for (int mt = 0; mt < MT; ++mt) {
+        const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
+        float gy[4] = {0.f, 0.f, 0.f, 0.f};
+        if (g.gys) load4f(g.gys - (int64_t)it * g.gys_stride, row0 + m, g.R, n, g.d, gy);
 #pragma unroll
-  for (int nt = 0; nt < NTS; ++nt)
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) da[nt][mt][r] = 0.f;
-
-  for (int j = s - 1; j >= 0; --j) {
-    for (int l = L - 1; l >= 1; --l) {
-      const int q = L - 1 - l;
-      const PassDesc p = bwd_pass(g, l);
-      const PassDesc nx = bwd_pass(g, l - 1);
-      const bool next_is_last = (l == 1);
-      uint16_t* actT = g.ACTT[l - 1] + set_off;
-      uint16_t* goutT = g.DELTAT[l - 1] + set_off;
-      const int64_t kj = (int64_t)j * g.Rp + row0;
-      lds_u16* out = lds.out(q);
-      const int ldp = lds.ldp;
-      auto pre_act = [&](int n, int m) {
-                return (row0 + m < g.R) ? *group4(actT, g.ldk, kj + m, n) : make_uint2(0u, 0u);
-              };
-      auto epi_delta = [&](const f32x4& acc, uint2 pf, int, int, int n, int m) {
-                float a[4], v[4];
-                unpack4<T>(pf, a);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) v[r] = acc[r] * (1.f - a[r] * a[r]);
-                const uint2 dq = pack4<T>(v);
-                lds_store_u2(&out[m * ldp + n], dq);
-                if (row0 + m < g.R) {
-                  RAMPDE_STORE_G4(group4(goutT, g.ldk, kj + m, n), dq);
-                  bad = bad || any_nonfinite4<T>(dq);
-                }
-              };
-      auto nxt_b = [&]() {
-        if (next_is_last) eng.template preload_state<false>(nx);
-        else eng.template preload_hidden<false>(nx, 0);
-      };
-      if (q == 0) eng.template run_hidden<true>(p, lds.in(q), lds.ld_in(q), pre_act, epi_delta, nxt_b);
-      else eng.template run_hidden<false>(p, lds.in(q), lds.ld_in(q), pre_act, epi_delta, nxt_b);
-    }
-    const int q = L - 1;
-    auto pre0 = [](int, int) { return make_uint2(0u, 0u); };
-    auto epi_zbar = [&](const f32x4& acc, uint2, int nt, int mt, int n, int m) {
-          const float v[4] = {acc[0], acc[1], acc[2], acc[3]};
-          const uint2 zq = pack4<T>(v);
-          if (row0 + m < g.R) bad = bad || any_nonfinite4<T>(zq);
-          float zf[4];
-          unpack4<T>(zq, zf);
-#pragma unroll
-          for (int r = 0; r < 4; ++r) da[nt][mt][r] += zf[r];
-          if (j > 0) {
-            zs.put(j, m, n, zq);
-            make_kbar(j - 1, nt, mt, m, n, zf);
-          }
-        };
-    auto nxt_z = [&]() {
-      if (j > 0) preload_first_b();
-    };
-    if (L == 1) eng.template run_state<true>(lastb, lds.in(0), lds.ld_in(0), true, pre0, epi_zbar, nxt_z);
-    else eng.template run_state<false>(lastb, lds.in(q), lds.ld_in(q), false, pre0, epi_zbar, nxt_z);
-  }
-  // ---- a <- a + (h / S) sum_j zbar_j (+ running-cost cotangent), fp32; max |a| after the last step
-  bits = 0;
-  const float hs = h / S;
-#pragma unroll
-  for (int nt = 0; nt < NTS; ++nt)
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
-      float gy[4] = {0.f, 0.f, 0.f, 0.f};
-      if (g.gys) load4f(g.gys - (int64_t)it * g.gys_stride, row0 + m, g.R, n, g.d, gy);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        av[nt][mt][r] = fmaf(hs, da[nt][mt][r], av[nt][mt][r]) + gy[r];
-        const unsigned bb = __builtin_bit_cast(unsigned, fabsf(av[nt][mt][r]));
-        if (row0 + m < g.R && n + r < g.d) bits = bb > bits ? bb : bits;
+        for (int r = 0; r < 4; ++r) {
+          av[nt][mt][r] = fmaf(hs, da[nt][mt][r], av[nt][mt][r]) + gy[r];
+          const unsigned bb = __builtin_bit_cast(unsigned, fabsf(av[nt][mt][r]));
+          if (row0 + m < g.R && n + r < g.d) bits = bb > bits ? bb : bits;
+        }
       }
-    }
   }  // steps of this launch
 
   if (g.detect) raise_if_any(bad, g.ctl);
@@ -1001,7 +1003,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
       c->poison = 1;
       c->failed_step = g.step;
     } else {
-      for (int it = 0; it < g.nsteps; ++it) g.scale_hist[g.step - it] = S;
+      for (int it = 0; it < nsteps; ++it) g.scale_hist[g.step - it] = S;
       c->S_step = S;
       c->s_min = fminf(c->s_min, S);
       c->s_max = fmaxf(c->s_max, S);

@@ -24,8 +24,17 @@ hipError_t launch_kernel(Kern kern, int waves, const FusedLaunch& l, const Fused
 
 template <class T, int MT, int NTL>
 hipError_t pick_kernel(const FusedLaunch& l, const FusedArgs& a) {
-  if (l.adjoint && l.waves == 4) return launch_kernel(mlp_adjoint_step<T, MT, NTL, 4, RAMPDE_INST_HP>, 4, l, a);
-  if (l.adjoint) return launch_kernel(mlp_adjoint_step<T, MT, NTL, 8, RAMPDE_INST_HP>, 8, l, a);
+  if (l.adjoint) {
+    // (the host caps the adjoint's row tile at 32 rows: 64-row tiles spill; several steps per launch
+    // only with 8 wavefronts)
+    if constexpr (MT <= 2) {
+      if (a.nsteps > 1) return launch_kernel(mlp_adjoint_step<T, MT, NTL, 8, RAMPDE_INST_HP, true>, 8, l, a);
+      if (l.waves == 4) return launch_kernel(mlp_adjoint_step<T, MT, NTL, 4, RAMPDE_INST_HP, false>, 4, l, a);
+      return launch_kernel(mlp_adjoint_step<T, MT, NTL, 8, RAMPDE_INST_HP, false>, 8, l, a);
+    } else {
+      return hipErrorInvalidValue;
+    }
+  }
   return launch_kernel(mlp_forward_fused<T, MT, NTL, kForwardWaves, RAMPDE_INST_HP>, kForwardWaves, l, a);
 }
 

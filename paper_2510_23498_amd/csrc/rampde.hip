@@ -859,10 +859,11 @@ struct Runner {
   }
 
   // parameter gradients from the feature-major buffers of the row-tile-persistent adjoint kernel
-  // steps step, step - 1, ..., step - nsteps + 1 in one launch (nsteps > 1: h and taus come from the step table)
-  void param_grads_fused(int step, float h, const Coefs& taus, hipStream_t stream, int nsteps = 1) {
+  // nsteps = 0: the one step `step`, h and taus as given; nsteps >= 1 (groups of steps): steps step,
+  // step - 1, ..., step - nsteps + 1 in one launch, h and taus from the step table
+  void param_grads_fused(int step, float h, const Coefs& taus, hipStream_t stream, int nsteps = 0) {
     float* grad_theta = f32(p.gpart);  // copy 0; chunk c adds into copy c
-    const size_t set = nsteps > 1 ? 0 : (size_t)(step % p.nsets) * p.fm_stride;
+    const size_t set = nsteps > 0 ? 0 : (size_t)(step % p.nsets) * p.fm_stride;
     WgradArgs w{};
     w.L = p.L;
     w.ksplits = p.ksplits;
@@ -898,12 +899,12 @@ struct Runner {
       d.tiles_b = (y.Kpad + 127) / 128;
       d.tile0 = blk;
       blk += d.tiles_a * d.tiles_b;
-      flops += 2.0 * (double)p.ldk * y.Npad * y.Kpad * nsteps;
+      flops += 2.0 * (double)p.ldk * y.Npad * y.Kpad * std::max(1, nsteps);
     }
     w.ntiles = blk;
     const int grid = (blk * w.ksplits + 7) / 8 * 8;  // a multiple of the XCD count: see the kernel's block mapping
     TimeScope ts(RAMPDE_K_WGRAD_GEMM, flops, stream);
-    if (nsteps > 1)
+    if (nsteps > 0)
       wgrad_feature_major_steps<T><<<grid, 256, 0, stream>>>(w);
     else
       wgrad_feature_major<T><<<grid, 256, 0, stream>>>(w);

@@ -117,10 +117,11 @@ def test_running_cost_cotangents(flags):
 @pytest.mark.parametrize("low", ["bf16", "f16"])
 def test_fixed_scale_runs_groups_of_steps_per_launch(group, low, monkeypatch):
     # Without overflow detection (scaling "none") the adjoint kernel runs several steps per launch and
-    # their parameter gradients are one contraction; groups of 2 / 3 (ragged last group of an 8-step
-    # grid) / all steps, ragged batch (rows padded inside the contraction), running-cost cotangents.
+    # their parameter gradients are one contraction; groups of 2 / 3 (ragged last group) / all steps, ragged batch (rows padded inside the contraction), running-cost cotangents.
     monkeypatch.setenv("RAMPDE_STEP_GROUP", str(group))
-    cfg = wl.CONFIGS["cfg2"].with_(name=f"grp{group}{low}", B=200, N=8, widths=(24, 256, 256, 24), low=low,
+    # (group 3 on a 7-step grid: groups of 3, 3 and 1 steps)
+    cfg = wl.CONFIGS["cfg2"].with_(name=f"grp{group}{low}", B=200, N=7 if group == 3 else 8,
+                                   widths=(24, 256, 256, 24), low=low,
                                    tableau="kutta3" if group == 3 else "rk4")
     theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
     gys = wl.normals(5, "grp.gys", (cfg.N + 1, cfg.B, 24), 1e-3)
