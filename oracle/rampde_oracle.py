@@ -167,8 +167,10 @@ class MLPVelocity:
         """Cotangents through one evaluation (paper eq. (vjp), network part).
 
         Returns (zbar, dtheta (flat fp64, unrounded), finite flag of every
-        low-precision cotangent formed).  tanh' is taken from the stored rounded
-        activation: 1 - act^2.
+        low-precision cotangent formed, taubar).  tanh' is taken from the stored
+        rounded activation: 1 - act^2.  taubar = kbar^T df/dtau summed over the
+        batch (the time entry of J_Phi in eq. (vjp)): the layer-1 cotangent times
+        the time column, unrounded like dtheta.
         """
         acts, tau = cache
         layers = self.split(theta_q)
@@ -176,6 +178,7 @@ class MLPVelocity:
         delta = kbar
         finite = True
         zbar = None
+        taubar = 0.0
         for l in range(self.L - 1, -1, -1):
             W, wt, b = layers[l]
             o, i, woff, boff = self.shapes[l]
@@ -184,6 +187,7 @@ class MLPVelocity:
             colsum = delta.sum(axis=0)
             if wt is not None:
                 dWfull[:, -1] = colsum * tau
+                taubar = float(colsum @ wt)
             dtheta[woff:woff + o * i] = dWfull.ravel()
             dtheta[boff:boff + o] = colsum
             back = R32(delta @ W)
@@ -193,7 +197,7 @@ class MLPVelocity:
             else:
                 zbar = Q(back)
                 finite = finite and bool(np.all(np.isfinite(zbar)))
-        return zbar, dtheta, finite
+        return zbar, dtheta, finite, taubar
 
 
 class Conv2Velocity:
@@ -277,13 +281,17 @@ class Conv2Velocity:
         wsz = self.C * self.Cin * 9
         dtheta[w2o:w2o + wsz] = self._conv_dW(d2, xp2).ravel()
         dtheta[b2o:b2o + self.C] = d2.sum(axis=(0, 2, 3))
-        back2 = R32(self._conv_T(d2, W2)[:, :self.C])
+        full2 = self._conv_T(d2, W2)
+        back2 = R32(full2[:, :self.C])
         d1 = Q(R32(back2 * (1.0 - act1 * act1)))
         dtheta[w1o:w1o + wsz] = self._conv_dW(d1, xp1).ravel()
         dtheta[b1o:b1o + self.C] = d1.sum(axis=(0, 2, 3))
-        zbar = Q(R32(self._conv_T(d1, W1)[:, :self.C]))
+        full1 = self._conv_T(d1, W1)
+        zbar = Q(R32(full1[:, :self.C]))
         finite = bool(np.all(np.isfinite(d1))) and bool(np.all(np.isfinite(zbar)))
-        return zbar.reshape(kbar.shape), dtheta, finite
+        # time cotangent: the input cotangent of the constant time channel of both convolutions
+        taubar = float(full2[:, self.C].sum() + full1[:, self.C].sum()) if self.time_input else 0.0
+        return zbar.reshape(kbar.shape), dtheta, finite, taubar
 
 
 class PolyDecayVelocity:
@@ -315,7 +323,7 @@ class PolyDecayVelocity:
         dtheta = np.array([np.sum(Q(lbar * t2)), np.sum(Q(lbar * t)), np.sum(lbar)], dtype=np.float64)
         finite = bool(np.all(np.isfinite(zbar))) and bool(np.all(np.isfinite(lbar))) \
             and bool(np.all(np.isfinite(dtheta)))
-        return zbar, dtheta, finite
+        return zbar, dtheta, finite, None   # (time cotangent not formed for this test problem)
 
 
 # --------------------------------------------------------------------------
@@ -340,6 +348,7 @@ class BwdResult:
     retries: int
     status: str                      # "ok" | "overflow_inf" | "scale_failed"
     failed_step: int = -1
+    grad_t: np.ndarray = None        # [N+1] dL/dt (None when the velocity forms no time cotangent)
 
 
 class ScaleFailure(Exception):
@@ -418,11 +427,21 @@ def odeint_fwd(vel, theta, y0, tgrid, tableau, policy: Policy):
 
 
 def odeint_bwd(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad_yN,
-               grad_theta_init=None, grad_ys=None) -> BwdResult:
+               grad_theta_init=None, grad_ys=None, grad_t_init=None) -> BwdResult:
     """Mixed-precision discrete adjoint with dynamic adjoint scaling (paper Algorithm 2).
 
-    Time-grid gradients are not formed.  `grad_ys` (optional, [N+1, ...]) are
-    per-step cotangents dL/dy_i of a running cost, added in high precision.
+    `grad_ys` (optional, [N+1, ...]) are per-step cotangents dL/dy_i of a running
+    cost, added in high precision.
+
+    Time-grid gradient t' = dL/dt (paper Sec. 3, the two update lines for t'_i and
+    t'_{i+1}; Alg. 2): with the step y_{i+1} = y_i + h Phi(y_i, t_i, h), h = t_{i+1} - t_i,
+        dt = lambda^T dPhi/dt = sum_j taubar_j,
+        dh = lambda^T dPhi/dh = sum_j ( c_j taubar_j + zbar_j^T sum_l a_jl k_l ),
+        t'_i     += (h/S)(dt - dh) - Phi^T a_{i+1},      t'_{i+1} += (h/S) dh + Phi^T a_{i+1},
+    where taubar_j, zbar_j come from the same low-precision cotangent chain as da and
+    dg, the sums are formed in the accumulator precision (not rounded to `low`, like
+    dg), Phi = sum_j b_j k_j from the low-precision slopes, and a_{i+1} is the fp32
+    adjoint before this step's update.  `grad_t_init` is the explicit dL/dt it starts from.
     """
     Q, R32 = make_quantisers(policy.low, policy.flush_subnormals)
     A, b, c = tableau.A, tableau.b, tableau.c
@@ -444,6 +463,8 @@ def odeint_bwd(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad_yN,
     theta_q = Q(np.asarray(theta, dtype=np.float64))
     scale_hist = np.ones(N + 1)
     retries = 0
+    tp = np.zeros(N + 1) if grad_t_init is None else R32(np.asarray(grad_t_init, np.float64)).copy()
+    have_t = True
 
     if dynamic:
         amax = float(np.max(np.abs(a))) if a.size else 0.0
@@ -466,6 +487,7 @@ def odeint_bwd(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad_yN,
             lam = Q(R32(S * a))                                        # R8
             finite = bool(np.all(np.isfinite(lam)))
             zbars = [None] * s
+            taubars = [0.0] * s
             dth = np.zeros(vel.n_params)
             for j in range(s - 1, -1, -1):
                 kb = b[j] * lam
@@ -474,7 +496,7 @@ def odeint_bwd(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad_yN,
                         kb = kb + h * A[l][j] * zbars[l]
                 kb = Q(R32(kb))                                        # R9a
                 finite = finite and bool(np.all(np.isfinite(kb)))
-                zbars[j], dth_j, fin_j = vel.vjp(theta_q, caches[j], kb, Q, R32)   # R9b, R9c
+                zbars[j], dth_j, fin_j, taubars[j] = vel.vjp(theta_q, caches[j], kb, Q, R32)   # R9b, R9c
                 finite = finite and fin_j
                 dth = dth + dth_j
             if finite or not check:
@@ -498,6 +520,23 @@ def odeint_bwd(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad_yN,
         da = np.zeros_like(a)
         for j in range(s):
             da = da + zbars[j]
+        if have_t and taubars[0] is None:
+            have_t = False
+        if have_t:
+            dt = 0.0
+            dh = 0.0
+            phi = np.zeros_like(a)
+            for j in range(s):
+                dt += taubars[j]
+                stage_incr = np.zeros_like(a)
+                for l in range(j):
+                    if A[j][l] != 0.0:
+                        stage_incr = stage_incr + A[j][l] * ks[l]
+                dh += c[j] * taubars[j] + float(np.sum(zbars[j] * stage_incr))
+                phi = phi + b[j] * ks[j]
+            phi_a = float(R32(np.sum(phi * a)))
+            tp[i] = R32(tp[i] + hs * float(R32(dt - dh)) - phi_a)
+            tp[i + 1] = R32(tp[i + 1] + hs * float(R32(dh)) + phi_a)
         a_new = a + hs * da
         if grad_ys is not None:
             a_new = a_new + flat(grad_ys[i])
@@ -510,7 +549,7 @@ def odeint_bwd(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad_yN,
             test = amax if policy.grow_raw_norm else S * amax
             if test <= 1.0 / (2.0 * u_low) and S < 2.0 ** 126:
                 S = 2.0 * S
-    return BwdResult(a.reshape(np.shape(grad_yN)), g, scale_hist, retries, "ok")
+    return BwdResult(a.reshape(np.shape(grad_yN)), g, scale_hist, retries, "ok", -1, tp if have_t else None)
 
 
 def checkpoint_bytes(N: int, n_state: int, low: str) -> int:

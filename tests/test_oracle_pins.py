@@ -236,6 +236,103 @@ def test_conv_gradients_match_finite_differences():
     _fd_check(vel, theta, y0, tg, tab("rk4"), target)
 
 
+# ------------------------------------------------------------------ time-grid gradient dL/dt
+def _fd_check_time_grid(vel, theta, y0, tg, tableau, target, grad_ys=None, step=1e-6, tol=5e-6):
+    """dL/dt_m for every grid point (both end points included) against central differences of the
+    discrete map of Algorithm 1 in fp64 (paper Sec. 3: the update lines for t'_i and t'_{i+1})."""
+    pol = orc.Policy(low="f64")
+
+    def loss(grid):
+        yN, ck = orc.odeint_fwd(vel, theta, y0, grid, tableau, pol)
+        L = 0.5 * np.sum((yN - target) ** 2)
+        if grad_ys is not None:
+            L += np.sum(grad_ys * ck)
+        return L
+
+    yN, ck = orc.odeint_fwd(vel, theta, y0, tg, tableau, pol)
+    res = orc.odeint_bwd(vel, theta, tg, tableau, pol, ck, yN - target, grad_ys=grad_ys)
+    fd = np.zeros(len(tg))
+    for m in range(len(tg)):
+        e = np.zeros(len(tg)); e[m] = step
+        fd[m] = (loss(tg + e) - loss(tg - e)) / (2 * step)
+    assert res.grad_t is not None and res.grad_t.shape == fd.shape
+    assert np.all(np.abs(fd) > 0)
+    assert np.max(np.abs(res.grad_t - fd)) < tol * np.max(np.abs(fd)), (res.grad_t, fd)
+    return res.grad_t
+
+
+@pytest.mark.parametrize("name", ["euler", "heun", "rk4", "kutta3"])
+def test_mlp_time_grid_gradient_matches_finite_differences(name):
+    rng = np.random.default_rng(15)
+    vel = orc.MLPVelocity((2, 5, 4, 2))
+    theta = rng.normal(size=vel.n_params) * 0.6
+    y0 = rng.normal(size=(3, 2))
+    tg = np.array([0.0, 0.2, 0.45, 0.6, 1.0])
+    target = rng.normal(size=(3, 2))
+    _fd_check_time_grid(vel, theta, y0, tg, tab(name), target)
+
+
+def test_time_grid_gradient_with_running_cost_and_conv():
+    rng = np.random.default_rng(16)
+    vel = orc.MLPVelocity((2, 4, 2))
+    theta = rng.normal(size=vel.n_params) * 0.6
+    y0 = rng.normal(size=(2, 2))
+    tg = np.array([0.0, 0.3, 0.5, 1.0])
+    gys = rng.normal(size=(4, 2, 2))
+    _fd_check_time_grid(vel, theta, y0, tg, tab("rk4"), rng.normal(size=(2, 2)), grad_ys=gys)
+    cv = orc.Conv2Velocity(2, 3, 4)
+    th = rng.normal(size=cv.n_params) * 0.4
+    yc = rng.normal(size=(2, 24))
+    _fd_check_time_grid(cv, th, yc, np.array([0.0, 0.3, 0.7]), tab("rk4"), rng.normal(size=yc.shape))
+
+
+def test_time_grid_gradient_closed_form_for_autonomous_linear_euler():
+    # f = A y without time input, explicit Euler: y_N = prod_i (I + h_i A) y_0, so
+    # dL/dt_m = a_N^T [prod_{i != ...}] with d/dt_m acting on h_{m-1} (+) and h_m (-):
+    # dL/dt_m = a_m^T A y_{m-1} - a_{m+1}^T A y_m   (a_i = cotangent of y_i; missing terms at the ends).
+    rng = np.random.default_rng(17)
+    d = 4
+    vel, theta, A = _linear_velocity(d, rng)
+    y0 = rng.normal(size=(1, d))
+    tg = np.array([0.0, 0.1, 0.35, 0.5, 0.9])
+    N = len(tg) - 1
+    pol = orc.Policy(low="f64")
+    yN, ck = orc.odeint_fwd(vel, theta, y0, tg, tab("euler"), pol)
+    aN = rng.normal(size=(1, d))
+    res = orc.odeint_bwd(vel, theta, tg, tab("euler"), pol, ck, aN)
+    ys = [ck[i].reshape(d) for i in range(N + 1)]
+    a = [None] * (N + 1)
+    a[N] = aN.reshape(d)
+    for i in range(N - 1, -1, -1):
+        a[i] = a[i + 1] + (tg[i + 1] - tg[i]) * (A.T @ a[i + 1])
+    want = np.zeros(N + 1)
+    for m in range(N + 1):
+        if m >= 1:
+            want[m] += a[m] @ (A @ ys[m - 1])
+        if m <= N - 1:
+            want[m] -= a[m + 1] @ (A @ ys[m])
+    assert rel(res.grad_t, want) < 1e-12
+    # shifting the whole grid changes nothing for an autonomous problem
+    assert abs(np.sum(res.grad_t)) < 1e-12 * np.max(np.abs(res.grad_t))
+
+
+def test_time_grid_gradient_emulation_is_close_to_fp64_and_scale_neutral():
+    rng = np.random.default_rng(18)
+    vel = orc.MLPVelocity((3, 16, 3))
+    theta = rng.normal(size=vel.n_params) * 0.5
+    y0 = rng.normal(size=(8, 3))
+    tg = np.linspace(0.0, 1.0, 9)
+    target = rng.normal(size=(8, 3))
+    out = {}
+    for low, sc in [("f64", "none"), ("f16", "dynamic"), ("bf16", "none"), ("bf16", "dynamic")]:
+        pol = orc.Policy(low=low, scaling=sc)
+        yN, ck = orc.odeint_fwd(vel, theta, y0, tg, tab("rk4"), pol)
+        out[(low, sc)] = orc.odeint_bwd(vel, theta, tg, tab("rk4"), pol, ck, yN - target).grad_t
+    assert rel(out[("f16", "dynamic")], out[("f64", "none")]) < 2e-2
+    assert rel(out[("bf16", "none")], out[("f64", "none")]) < 8e-2
+    np.testing.assert_array_equal(out[("bf16", "none")], out[("bf16", "dynamic")])   # power-of-two scaling
+
+
 def test_conv_matches_direct_definition():
     # brute-force loops over the definition of a zero-padded 3x3 cross-correlation
     rng = np.random.default_rng(8)
@@ -289,13 +386,14 @@ def test_conv_centre_tap_reduces_to_per_pixel_mlp():
     assert rel(kc_px, km) < 1e-13
     kb = rng.normal(size=km.shape)
     kb_c = kb.reshape(B, H, W, C).transpose(0, 3, 1, 2).reshape(B, -1)
-    zb_c, dth_c, _ = cv.vjp(th_c, cache_c, kb_c, Q, R32)
-    zb_m, dth_m, _ = mv.vjp(th_m, cache_m, kb, Q, R32)
+    zb_c, dth_c, _, tb_c = cv.vjp(th_c, cache_c, kb_c, Q, R32)
+    zb_m, dth_m, _, tb_m = mv.vjp(th_m, cache_m, kb, Q, R32)
     assert rel(zb_c.reshape(B, C, H, W).transpose(0, 2, 3, 1).reshape(-1, C), zb_m) < 1e-13
     (dW1m, dwt1m, db1m), (dW2m, _, db2m) = mv.split(dth_m)
     (dcw1, dcb1), (dcw2, dcb2) = cv.split(dth_c)
     assert rel(dcw1[:, :C, 1, 1], dW1m) < 1e-13 and rel(dcw1[:, C, 1, 1], dwt1m) < 1e-13
     assert rel(dcw2[:, :C, 1, 1], dW2m) < 1e-13 and rel(dcb1, db1m) < 1e-13 and rel(dcb2, db2m) < 1e-13
+    assert abs(tb_c - tb_m) < 1e-12 * max(1.0, abs(tb_m))     # time cotangent (second conv's time weight is zero)
 
 
 # ------------------------------------------------------------------ P4/P5: Example 3.1 / Table 1
