@@ -32,6 +32,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--grad-t", action="store_true",
+                    help="also form the time-grid gradient dL/dt in the backward pass (not part of the headline metric)")
     ap.add_argument("--cpu-steps", type=int, default=0,
                     help="RK steps of the oracle sample (0: the whole grid for the benchmark workload, "
                          "1-2 steps for the larger ones: about 10-30 s of CPU work)")
@@ -70,6 +72,7 @@ def main():
     ws_f = rb.alloc_workspace(vel, B, N, tab, pol, False, dev)
     ws_b = rb.alloc_workspace(vel, B, N, tab, pol, True, dev)
     dynamic = wl.resolve_scaling(cfg) == "dynamic"
+    grad_t = torch.zeros(N + 1, dtype=torch.float32, device=dev) if args.grad_t else None
 
     def loss_grad():
         # caller-side terminal loss gradient (outside the library), same formulas as the workload module
@@ -87,8 +90,10 @@ def main():
         rb.rampde_odeint_fwd(vel, theta, y0, tgrid, tab, pol, ckpt=ckpt, yN=yN, workspace=ws_f)
         loss_grad()
         grad_theta.zero_()
+        if grad_t is not None:
+            grad_t.zero_()
         rb.rampde_odeint_bwd(vel, theta, tgrid, tab, pol, ckpt, grad_yN, grad_y0=grad_y0, grad_theta=grad_theta,
-                             workspace=ws_b, want_info=dynamic)
+                             workspace=ws_b, want_info=dynamic, grad_t=grad_t)
 
     if args.calibrate_mib > 0:
         src = torch.ones(args.calibrate_mib * (1 << 18), dtype=torch.float32, device=dev)
@@ -147,7 +152,7 @@ def main():
         "dtype": cfg.low, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.kind} B={B} widths={list(cfg.widths) or [cfg.C, cfg.H, cfg.W]} "
                                f"{cfg.tableau} N={N} t=[{cfg.t0},{cfg.t1}] low={cfg.low} "
-                               f"scaling={wl.resolve_scaling(cfg)}"},
+                               f"scaling={wl.resolve_scaling(cfg)}" + (" +dL/dt" if args.grad_t else "")},
         "roofline": roofline, "hbm_kernels": hbm, "kernel_ms_per_step": kernel_share,
     }
 

@@ -132,7 +132,7 @@ int rampde_odeint_fwd(const rampde_velocity *vel, const float *theta, const floa
                       const rampde_policy *pol, void *ckpt, float *yN, void *workspace,
                       size_t workspace_bytes, void *hip_stream);
 
-/* Backward pass, Algorithm 2 (time-grid gradients are not formed).
+/* Backward pass, Algorithm 2 (without the time-grid gradient: see rampde_odeint_bwd_tgrid).
  *   ckpt       dev, read: the trajectory written by rampde_odeint_fwd with the same arguments
  *   grad_yN    dev, B*d fp32: dL/dy_N (the terminal-cost gradient, formed by the caller)
  *   grad_ys    dev or NULL: (N+1)*B*d fp32 per-step cotangents dL/dy_i of a running cost,
@@ -151,6 +151,25 @@ int rampde_odeint_bwd(const rampde_velocity *vel, const float *theta, int64_t B,
                       const float *grad_ys, float *grad_y0, float *grad_theta,
                       float *scale_hist, rampde_stats *stats, void *workspace,
                       size_t workspace_bytes, void *hip_stream);
+
+/* Backward pass that also forms the time-grid gradient dL/dt (paper Sec. 3, the update lines of
+ * t'_i and t'_{i+1}; Alg. 2 returns dL/dt beside dL/dx and dL/dtheta).  Arguments as for
+ * rampde_odeint_bwd, plus
+ *   grad_t   dev or NULL, N+1 fp32, ACCUMULATED into (Alg. 2 starts t' at the caller's explicit
+ *            dL/dt): zero it for a plain gradient.  NULL: exactly rampde_odeint_bwd.
+ * With h = t[i+1] - t[i] and the step y_{i+1} = y_i + h Phi(y_i, t_i, h), per accepted step
+ *   dt = lambda^T dPhi/dt,  dh = lambda^T dPhi/dh   from the same low-precision cotangent chain
+ *   as the state and parameter cotangents, summed in fp32 and not rounded to 16 bits,
+ *   t'_i += (h/S)(dt - dh) - Phi^T a_{i+1},   t'_{i+1} += (h/S) dh + Phi^T a_{i+1},
+ * Phi = sum_j b_j k_j from the low-precision slopes, a_{i+1} the fp32 adjoint before the step's
+ * update.  Sums over the batch use fp32 atomics: the result is reproducible to rounding only.
+ * Returns RAMPDE_EUNSUPPORTED for velocities / shapes that run on the per-layer kernels. */
+int rampde_odeint_bwd_tgrid(const rampde_velocity *vel, const float *theta, int64_t B,
+                            const double *tgrid, int N, const rampde_tableau *tab,
+                            const rampde_policy *pol, const void *ckpt, const float *grad_yN,
+                            const float *grad_ys, float *grad_y0, float *grad_theta,
+                            float *grad_t, float *scale_hist, rampde_stats *stats,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
 const char *rampde_strerror(int code);
 

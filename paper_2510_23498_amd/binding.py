@@ -25,7 +25,7 @@ _SCALING = {"none": SCALE_NONE, "none_safe": SCALE_NONE_SAFE, "dynamic": SCALE_D
 _TORCH_LOW = {F16: torch.float16, BF16: torch.bfloat16}
 
 EXPORTS = ("rampde_num_params", "rampde_workspace_bytes", "rampde_odeint_fwd", "rampde_odeint_bwd",
-           "rampde_strerror", "rampde_version", "rampde_timing_enable", "rampde_timing_read")
+           "rampde_odeint_bwd_tgrid", "rampde_strerror", "rampde_version", "rampde_timing_enable", "rampde_timing_read")
 
 K_VELOCITY_GEMM, K_WGRAD_GEMM, K_COMBINE_STORE, K_ADJOINT_UPDATE, K_FUSED_FORWARD, K_FUSED_ADJOINT_STEP = range(6)
 ROUND_INCREMENT, GROW_RAW_NORM, PER_LAYER_KERNELS = 1, 2, 4
@@ -87,6 +87,11 @@ def load_library():
                                       C.POINTER(_Tableau), C.POINTER(_Policy), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.POINTER(C.c_float), C.POINTER(_Stats), C.c_void_p,
                                       C.c_size_t, C.c_void_p]
+    lib.rampde_odeint_bwd_tgrid.restype = C.c_int
+    lib.rampde_odeint_bwd_tgrid.argtypes = [C.POINTER(_Velocity), C.c_void_p, C.c_int64, C.POINTER(C.c_double), C.c_int,
+                                            C.POINTER(_Tableau), C.POINTER(_Policy), C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_float),
+                                            C.POINTER(_Stats), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.rampde_strerror.restype = C.c_char_p
     lib.rampde_strerror.argtypes = [C.c_int]
     lib.rampde_version.restype = C.c_int
@@ -261,10 +266,12 @@ def rampde_odeint_fwd(vel: Velocity, theta: torch.Tensor, y0: torch.Tensor, tgri
 def rampde_odeint_bwd(vel: Velocity, theta: torch.Tensor, tgrid, tab: Tableau, pol: Policy, ckpt: torch.Tensor,
                       grad_yN: torch.Tensor, grad_ys: Optional[torch.Tensor] = None,
                       grad_y0: Optional[torch.Tensor] = None, grad_theta: Optional[torch.Tensor] = None,
-                      workspace: Optional[torch.Tensor] = None, stream=None, want_info: bool = True):
+                      workspace: Optional[torch.Tensor] = None, stream=None, want_info: bool = True,
+                      grad_t: Optional[torch.Tensor] = None):
     """Discrete adjoint (paper Algorithm 2).  Returns (grad_y0, grad_theta, BwdInfo or None).
 
-    grad_theta is accumulated into; when omitted a zero vector is created.
+    grad_theta is accumulated into; when omitted a zero vector is created.  With `grad_t` (N+1 fp32
+    on the device, accumulated into) the call goes to rampde_odeint_bwd_tgrid and also forms dL/dt.
     """
     lib = load_library()
     B = int(grad_yN.shape[0])
@@ -287,12 +294,19 @@ def rampde_odeint_bwd(vel: Velocity, theta: torch.Tensor, tgrid, tab: Tableau, p
     pc = pol.c
     stats = _Stats()
     hist = np.zeros(N + 1, dtype=np.float32) if want_info else None
-    rc = lib.rampde_odeint_bwd(C.byref(vel.c), _ptr(theta), B, tg.ctypes.data_as(C.POINTER(C.c_double)), N,
-                               C.byref(tab.c), C.byref(pc), _ptr(ckpt), _ptr(grad_yN), _ptr(grad_ys), _ptr(grad_y0),
-                               _ptr(grad_theta),
-                               hist.ctypes.data_as(C.POINTER(C.c_float)) if want_info else None,
-                               C.byref(stats) if want_info else None, _ptr(workspace), workspace.numel(),
-                               _stream_ptr(stream))
+    hist_p = hist.ctypes.data_as(C.POINTER(C.c_float)) if want_info else None
+    stats_p = C.byref(stats) if want_info else None
+    if grad_t is not None:
+        _check_dev(grad_t, torch.float32, N + 1, "grad_t")
+        rc = lib.rampde_odeint_bwd_tgrid(C.byref(vel.c), _ptr(theta), B, tg.ctypes.data_as(C.POINTER(C.c_double)), N,
+                                         C.byref(tab.c), C.byref(pc), _ptr(ckpt), _ptr(grad_yN), _ptr(grad_ys),
+                                         _ptr(grad_y0), _ptr(grad_theta), _ptr(grad_t), hist_p, stats_p,
+                                         _ptr(workspace), workspace.numel(), _stream_ptr(stream))
+    else:
+        rc = lib.rampde_odeint_bwd(C.byref(vel.c), _ptr(theta), B, tg.ctypes.data_as(C.POINTER(C.c_double)), N,
+                                   C.byref(tab.c), C.byref(pc), _ptr(ckpt), _ptr(grad_yN), _ptr(grad_ys),
+                                   _ptr(grad_y0), _ptr(grad_theta), hist_p, stats_p, _ptr(workspace),
+                                   workspace.numel(), _stream_ptr(stream))
     info = None
     if want_info:
         info = BwdInfo(stats.status, stats.failed_step, stats.retries, stats.s_first, stats.s_last, stats.s_min,
@@ -300,3 +314,13 @@ def rampde_odeint_bwd(vel: Velocity, theta: torch.Tensor, tgrid, tab: Tableau, p
     if rc != OK:
         raise RampdeError(rc, rampde_strerror(rc), info)
     return grad_y0, grad_theta, info
+
+
+def rampde_odeint_bwd_tgrid(vel: Velocity, theta: torch.Tensor, tgrid, tab: Tableau, pol: Policy, ckpt: torch.Tensor,
+                            grad_yN: torch.Tensor, grad_t: Optional[torch.Tensor] = None, **kw):
+    """Discrete adjoint with the time-grid gradient (paper Sec. 3, update lines of t'; Algorithm 2).
+    Returns (grad_y0, grad_theta, grad_t, BwdInfo or None); grad_t is accumulated into (zeros when omitted)."""
+    if grad_t is None:
+        grad_t = torch.zeros(len(tgrid), dtype=torch.float32, device=grad_yN.device)
+    gy0, gth, info = rampde_odeint_bwd(vel, theta, tgrid, tab, pol, ckpt, grad_yN, grad_t=grad_t, **kw)
+    return gy0, gth, grad_t, info

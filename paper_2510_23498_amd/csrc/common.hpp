@@ -119,4 +119,31 @@ __device__ inline void block_amax(unsigned bits, unsigned* dst) {
   }
 }
 
+// Block-wide sums of two per-thread values, then one atomicAdd each per workgroup (dst[0], dst[1]).
+// (Must be reached by every thread of the workgroup.)
+__device__ inline void block_sum2(float a, float b, float* dst) {
+  for (int o = 32; o > 0; o >>= 1) {
+    a += __shfl_xor(a, o);
+    b += __shfl_xor(b, o);
+  }
+  __shared__ float wsum[16][2];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  __syncthreads();  // (a previous call's readers are done)
+  if (lane == 0) {
+    wsum[w][0] = a;
+    wsum[w][1] = b;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float s0 = 0.f, s1 = 0.f;
+    const int nw = (blockDim.x + 63) >> 6;
+    for (int i = 0; i < nw; ++i) {
+      s0 += wsum[i][0];
+      s1 += wsum[i][1];
+    }
+    unsafeAtomicAdd(dst, s0);
+    unsafeAtomicAdd(dst + 1, s1);
+  }
+}
+
 }  // namespace rampde

@@ -223,6 +223,18 @@ __global__ void chain_retry(Ctl* ctl) {
   ctl->failed_step = -1;
 }
 
+// dL/dt[m] += tpart[m][0] + tpart[m - 1][1]   (paper Sec. 3: the two update lines of t'; the per-step
+// sums were collected while the steps ran and are folded in once every step is accepted)
+__global__ void fold_time_sums(float* __restrict__ grad_t, const float* __restrict__ tpart, int N, const Ctl* ctl) {
+  if (ctl->poison) return;
+  const int m = blockIdx.x * blockDim.x + threadIdx.x;
+  if (m > N) return;
+  float v = 0.f;
+  if (m < N) v += tpart[2 * m];
+  if (m > 0) v += tpart[2 * (m - 1) + 1];
+  grad_t[m] += v;
+}
+
 // a <- a + (h/S) * sum_j zbar_j (+ running-cost cotangent), fp32; new max|a|
 template <class T>
 __global__ void adjoint_update(float* __restrict__ a, int d, const uint16_t* __restrict__ zbar,

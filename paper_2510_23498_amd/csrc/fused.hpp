@@ -76,6 +76,7 @@ struct FusedArgs {
   int64_t stage_stride;  // R * dpad
   float A[kMaxStages * kMaxStages];
   float b[kMaxStages];
+  float c[kMaxStages];
   const float* steptab;  // [N][1 + s]: h_i, tau_{i,1..s} (tau already rounded to low precision)
   // forward
   const float* y0;
@@ -108,6 +109,10 @@ struct FusedArgs {
   Ctl* ctl;
   float* scale_hist;
   int detect, dynamic, raw_norm, skip_recompute;
+  // time-grid gradient (paper Sec. 3, update lines of t'): null, or [N][2] fp32 per-step sums
+  //   tpart[i][0] = (h/S)(dt - dh) - Phi^T a_{i+1},   tpart[i][1] = (h/S) dh + Phi^T a_{i+1}
+  // added to by every workgroup; folded into dL/dt once the steps are accepted
+  float* tpart;
 };
 
 // theta (fp32) -> fragment-major low-precision copies of all dense layers (see FusedLayer) and the
@@ -504,10 +509,10 @@ struct TileEngine {
   }
 };
 
-__device__ inline PassDesc fwd_pass(const FusedArgs& g, int l) {
+__device__ __forceinline__ PassDesc fwd_pass(const FusedArgs& g, int l) {
   return PassDesc{(const glb_u16x8*)g.layer[l].Wf, g.layer[l].Kpad / 32, g.layer[l].Npad / 16};
 }
-__device__ inline PassDesc bwd_pass(const FusedArgs& g, int l) {
+__device__ __forceinline__ PassDesc bwd_pass(const FusedArgs& g, int l) {
   return PassDesc{(const glb_u16x8*)g.layer[l].WTf, g.layer[l].Npad / 32, g.layer[l].Kpad / 16};
 }
 
@@ -521,7 +526,7 @@ struct TileLds {
   lds_u16* buf1;    // [TM][ldp]
   lds_u16* kl;      // [s][TM][dpad] slopes or stage cotangents (when k_in_lds)
   int ldz, ldp;
-  __device__ inline TileLds(lds_u16* smem, const FusedArgs& g) {
+  __device__ __forceinline__ TileLds(lds_u16* smem, const FusedArgs& g) {
     param = (lds_f32*)smem;
     ldz = g.dpad + 8;
     ldp = g.ldp;
@@ -536,7 +541,9 @@ struct TileLds {
   __device__ inline lds_u16* out(int q) const { return (q & 1) ? buf1 : buf0; }
 };
 
-__device__ inline void load_params(lds_f32* param, const FusedArgs& g) {
+// (every function that takes the kernel argument block by reference is force-inlined: an
+// out-of-line call would make the compiler copy the whole block to scratch memory)
+__device__ __forceinline__ void load_params(lds_f32* param, const FusedArgs& g) {
   for (int l = 0; l < g.L; ++l)
     for (int i = threadIdx.x; i < g.layer[l].Npad; i += blockDim.x) param[g.layer[l].bias_off + i] = g.layer[l].bias[i];
   for (int i = threadIdx.x; i < g.layer[0].Npad; i += blockDim.x) param[g.wt_off + i] = g.layer[0].wt ? g.layer[0].wt[i] : 0.f;
@@ -564,7 +571,7 @@ struct StageStore {
 // Hidden layers of one velocity evaluation (all but the last layer) for stage j.  The ring must
 // hold the first fragments of layer 0 (if L > 1); on return it holds those of the last layer.
 template <class T, int MT, int NTL, int NW, int HP, bool KEEP>
-__device__ inline void hidden_layers(TileEngine<T, MT, NTL, NW, HP>& eng, const TileLds<MT>& lds, const FusedArgs& g,
+__device__ __forceinline__ void hidden_layers(TileEngine<T, MT, NTL, NW, HP>& eng, const TileLds<MT>& lds, const FusedArgs& g,
                                      int j, float tau, int64_t row0, int64_t set_off = 0) {
   for (int l = 0; l + 1 < g.L; ++l) {
     const PassDesc p = fwd_pass(g, l);
@@ -602,7 +609,7 @@ __device__ inline void hidden_layers(TileEngine<T, MT, NTL, NW, HP>& eng, const 
 }
 
 // fp32 pre-activation of the last layer for the lane's 4 columns
-__device__ inline void last_layer_values(const f32x4& acc, const lds_f32* param, const FusedArgs& g, float tau, int n,
+__device__ __forceinline__ void last_layer_values(const f32x4& acc, const lds_f32* param, const FusedArgs& g, float tau, int n,
                                          float (&v)[4]) {
   const float4 bv = lds_load_f4(&param[g.layer[g.L - 1].bias_off + n]);
   v[0] = acc[0] + bv.x; v[1] = acc[1] + bv.y; v[2] = acc[2] + bv.z; v[3] = acc[3] + bv.w;
@@ -731,7 +738,8 @@ __global__ __launch_bounds__(64 * NW) void mlp_forward_fused(FusedArgs g) {
 
 // ---------------------------------------------------------------------------------------
 // One step of the adjoint for a row tile (paper Algorithm 2, the body of the loop over steps).
-template <class T, int MT, int NTL, int NW, int HP, bool MULTI>
+// TG: also collect the per-step sums of the time-grid gradient (g.tpart).
+template <class T, int MT, int NTL, int NW, int HP, bool MULTI, bool TG>
 __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   if (g.ctl->poison) return;
@@ -771,6 +779,9 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
     const int64_t set_off = (int64_t)(step % g.nsets) * g.set_stride;
     uint16_t* const ZT = g.ZT + set_off;
     uint16_t* const KBART = g.KBART + set_off;
+    // per-lane parts of this step's time-grid sums: Phi^T a_{i+1}, dt and dh of eq. (vjp)
+    constexpr bool want_t = TG;
+    float t_phia = 0.f, t_dt = 0.f, t_dh = 0.f;
     // lambda = Q(S a); yhat = stored state
     uint2 lamq[NTS][MT], yhat[NTS][MT];
 #pragma unroll
@@ -809,6 +820,17 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
       for (int r = 0; r < 4; ++r) v[r] = fmaf(h, acc[r], g.b[j] * lam[r]);
       const uint2 q = pack4<T>(v);
       bad = bad || any_nonfinite4<T>(q);
+      if (want_t && g.L == 1) {
+        // single-layer network: the slope cotangent is the layer-1 cotangent
+        // (g.L, not the local copy L: capturing that local here made the compiler keep the whole
+        // argument block and the closures in scratch memory)
+        float kb[4];
+        unpack4<T>(q, kb);
+        const float4 tv = lds_load_f4(&(lds.param + g.wt_off)[n]);
+        const float tb = kb[0] * tv.x + kb[1] * tv.y + kb[2] * tv.z + kb[3] * tv.w;
+        t_dt += tb;
+        t_dh = fmaf(g.c[j], tb, t_dh);
+      }
       lds_store_u2(&lds.zbuf[m * lds.ldz + n], q);
       if (row0 + m < g.R) RAMPDE_STORE_G4(group4(KBART, g.ldk, (int64_t)j * g.Rp + row0 + m, n), q);
       return q;
@@ -851,9 +873,14 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
               float v[4];
               last_layer_values(acc, lds.param, g, tau, n, v);
               const uint2 kq = pack4<T>(v);
+              float kf[4];
+              unpack4<T>(kq, kf);
+              if (want_t) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) t_phia = fmaf(g.b[j] * kf[r], av[nt][mt][r], t_phia);
+              }
               if (j + 1 < s) {
-                float kf[4], incr[4] = {0.f, 0.f, 0.f, 0.f}, yh[4], z[4];
-                unpack4<T>(kq, kf);
+                float incr[4] = {0.f, 0.f, 0.f, 0.f}, yh[4], z[4];
                 unpack4<T>(yhat[nt][mt], yh);
                 ks.put(j, m, n, kq);
                 for (int l = 0; l < j; ++l) {
@@ -923,6 +950,15 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
 #pragma unroll
                   for (int r = 0; r < 4; ++r) v[r] = acc[r] * (1.f - a[r] * a[r]);
                   const uint2 dq = pack4<T>(v);
+                  if (want_t && l == 1) {
+                    // layer-1 cotangent times the time column: this stage's part of dt and dh
+                    float dv[4];
+                    unpack4<T>(dq, dv);
+                    const float4 tv = lds_load_f4(&(lds.param + g.wt_off)[n]);
+                    const float tb = dv[0] * tv.x + dv[1] * tv.y + dv[2] * tv.z + dv[3] * tv.w;
+                    t_dt += tb;
+                    t_dh = fmaf(g.c[j], tb, t_dh);
+                  }
                   lds_store_u2(&out[m * ldp + n], dq);
                   if (row0 + m < g.R) {
                     RAMPDE_STORE_G4(group4(goutT, g.ldk, kj + m, n), dq);
@@ -946,6 +982,17 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
             unpack4<T>(zq, zf);
 #pragma unroll
             for (int r = 0; r < 4; ++r) da[nt][mt][r] += zf[r];
+            if (want_t) {
+              for (int l = 0; l < j; ++l) {
+                const float a = g.A[j * s + l];
+                if (a != 0.f) {
+                  float kl[4];
+                  unpack4<T>(ks.get(l, m, n), kl);
+#pragma unroll
+                  for (int r = 0; r < 4; ++r) t_dh = fmaf(a * kl[r], zf[r], t_dh);
+                }
+              }
+            }
             if (j > 0) {
               zs.put(j, m, n, zq);
               make_kbar(j - 1, nt, mt, m, n, zf);
@@ -960,6 +1007,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
     // ---- a <- a + (h / S) sum_j zbar_j (+ running-cost cotangent), fp32; max |a| after the last step
     bits = 0;
     const float hs = h / S;
+    if (want_t) block_sum2(fmaf(hs, t_dt - t_dh, -t_phia), fmaf(hs, t_dh, t_phia), g.tpart + 2 * (size_t)step);
 #pragma unroll
     for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll

@@ -28,9 +28,14 @@ hipError_t pick_kernel(const FusedLaunch& l, const FusedArgs& a) {
     // (the host caps the adjoint's row tile at 32 rows: 64-row tiles spill; several steps per launch
     // only with 8 wavefronts)
     if constexpr (MT <= 2) {
-      if (a.nsteps > 1) return launch_kernel(mlp_adjoint_step<T, MT, NTL, 8, RAMPDE_INST_HP, true>, 8, l, a);
-      if (l.waves == 4) return launch_kernel(mlp_adjoint_step<T, MT, NTL, 4, RAMPDE_INST_HP, false>, 4, l, a);
-      return launch_kernel(mlp_adjoint_step<T, MT, NTL, 8, RAMPDE_INST_HP, false>, 8, l, a);
+      if (a.tpart) {  // with the sums of the time-grid gradient
+        if (a.nsteps > 1) return launch_kernel(mlp_adjoint_step<T, MT, NTL, 8, RAMPDE_INST_HP, true, true>, 8, l, a);
+        if (l.waves == 4) return launch_kernel(mlp_adjoint_step<T, MT, NTL, 4, RAMPDE_INST_HP, false, true>, 4, l, a);
+        return launch_kernel(mlp_adjoint_step<T, MT, NTL, 8, RAMPDE_INST_HP, false, true>, 8, l, a);
+      }
+      if (a.nsteps > 1) return launch_kernel(mlp_adjoint_step<T, MT, NTL, 8, RAMPDE_INST_HP, true, false>, 8, l, a);
+      if (l.waves == 4) return launch_kernel(mlp_adjoint_step<T, MT, NTL, 4, RAMPDE_INST_HP, false, false>, 4, l, a);
+      return launch_kernel(mlp_adjoint_step<T, MT, NTL, 8, RAMPDE_INST_HP, false, false>, 8, l, a);
     } else {
       return hipErrorInvalidValue;
     }

@@ -78,6 +78,7 @@ struct Plan {
   int ldp = 0;         // LDS row pitch (elements)
   size_t lds_bytes = 0;
   size_t steptab = 0, a_alt = 0;
+  size_t tpart = 0;                 // [N][2] fp32 per-step sums of the time-grid gradient
   int nparam = 0, wt_off = 0;
   bool k_in_lds = false;
   bool overlap_wgrad = false;       // narrow nets: 4-wave adjoint kernel + parameter gradients on a helper stream
@@ -311,6 +312,7 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
       }
     }
   }
+  if (is_backward) p.tpart = take(sizeof(float) * 2 * (size_t)N);
   p.total = off;
   p.ok = true;
   return p;
@@ -609,6 +611,7 @@ struct Runner {
     a.stage_stride = p.stage_stride;
     for (int i = 0; i < p.s; ++i) {
       a.b[i] = (float)tab->b[i];
+      a.c[i] = (float)tab->c[i];
       for (int j = 0; j < p.s; ++j) a.A[i * p.s + j] = (float)tab->A[i * p.s + j];
     }
     a.steptab = f32(p.steptab);
@@ -912,8 +915,10 @@ struct Runner {
 
   int backward(const float* theta, const double* tgrid, int N, const rampde_tableau* tab, const rampde_policy* pol,
                rampde_scaling scaling, const uint16_t* ckpt, const float* grad_yN, const float* grad_ys,
-               float* grad_y0, float* grad_theta, float* scale_hist, rampde_stats* stats) {
+               float* grad_y0, float* grad_theta, float* grad_t, float* scale_hist, rampde_stats* stats) {
     const int dynamic = scaling == RAMPDE_SCALE_DYNAMIC;
+    if (grad_t && !use_fused) return RAMPDE_EUNSUPPORTED;  // (time-grid gradient: row-tile-persistent kernels only)
+    if (grad_t) fill_zero_u32<<<1, 256, 0, st>>>((uint32_t*)(ws + p.tpart), 2 * (size_t)N);
     const int detect = dynamic || scaling == RAMPDE_SCALE_NONE_SAFE;
     const int k_max = pol->k_max > 0 ? pol->k_max : 16;
     const int HW = p.H * p.Wd;
@@ -952,6 +957,7 @@ struct Runner {
       fa.nsets = p.nsets;
       fa.set_stride = (int64_t)(p.fm_stride / 2);
       fa.nsteps = 1;
+      fa.tpart = grad_t ? f32(p.tpart) : nullptr;
       fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + p.gpart), (size_t)p.ksplits * p.P);
       if (p.Rp != p.R) {
         // rows R..Rp of every stage are padding of the contraction: they must read as zero
@@ -1021,7 +1027,8 @@ struct Runner {
           fa.a_in = a_buf(i + 1);
           fa.a_out = a_buf(i);
           fa.gys = gys_at(i);
-          fa.skip_recompute = (i == from && !recompute_first) ? 1 : 0;
+          // (with the time-grid gradient the step's slopes are needed again: they are recomputed)
+          fa.skip_recompute = (i == from && !recompute_first && !grad_t) ? 1 : 0;
           int rc = adjoint_step_fused(fa);
           if (rc) return rc;
           const float h = (float)(tgrid[i + 1] - tgrid[i]);
@@ -1045,6 +1052,7 @@ struct Runner {
         if (p.overlap_wgrad) HIP_TRY(hipStreamWaitEvent(st, side.wgrad_done(0), 0));  // helper stream is in order: joins all
         reduce_partial_gradients<<<blocks_for(p.P, 256), 256, 0, st>>>(grad_theta, f32(p.gpart), p.P, p.ksplits, ctl);
       }
+      if (grad_t) fold_time_sums<<<blocks_for(N + 1, 256), 256, 0, st>>>(grad_t, f32(p.tpart), N, ctl);
       if (conv_wgrad_applies(p))
         for (auto& y : p.layers) {
           const int64_t n = (int64_t)y.out * y.in * 9;
@@ -1063,6 +1071,7 @@ struct Runner {
       }
       chain_retry<<<1, 1, 0, st>>>(ctl);
       from = hctl.failed_step;
+      if (grad_t) fill_zero_u32<<<1, 64, 0, st>>>((uint32_t*)(ws + p.tpart) + 2 * (size_t)from, 2);
       recompute_first = false;  // the stage values of the failed step are still in the workspace
     }
     int st_code = 0;
@@ -1147,6 +1156,15 @@ int rampde_odeint_bwd(const rampde_velocity* vel, const float* theta, int64_t B,
                       const rampde_tableau* tab, const rampde_policy* pol, const void* ckpt, const float* grad_yN,
                       const float* grad_ys, float* grad_y0, float* grad_theta, float* scale_hist,
                       rampde_stats* stats, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return rampde_odeint_bwd_tgrid(vel, theta, B, tgrid, N, tab, pol, ckpt, grad_yN, grad_ys, grad_y0, grad_theta, nullptr,
+                                 scale_hist, stats, workspace, workspace_bytes, hip_stream);
+}
+
+int rampde_odeint_bwd_tgrid(const rampde_velocity* vel, const float* theta, int64_t B, const double* tgrid, int N,
+                            const rampde_tableau* tab, const rampde_policy* pol, const void* ckpt,
+                            const float* grad_yN, const float* grad_ys, float* grad_y0, float* grad_theta,
+                            float* grad_t, float* scale_hist, rampde_stats* stats, void* workspace,
+                            size_t workspace_bytes, void* hip_stream) {
   int rc = check_common(vel, tgrid, N, tab, pol);
   if (rc) return rc;
   if (!theta || !ckpt || !grad_yN || !grad_y0 || !grad_theta || !workspace || B < 1) return RAMPDE_EINVAL;
@@ -1160,12 +1178,12 @@ int rampde_odeint_bwd(const rampde_velocity* vel, const float* theta, int64_t B,
     Runner<F16> r(p, workspace, st);
     r.use_fused = fused;
     return r.backward(theta, tgrid, N, tab, pol, sc, (const uint16_t*)ckpt, grad_yN, grad_ys, grad_y0, grad_theta,
-                      scale_hist, stats);
+                      grad_t, scale_hist, stats);
   }
   Runner<BF16> r(p, workspace, st);
   r.use_fused = fused;
   return r.backward(theta, tgrid, N, tab, pol, sc, (const uint16_t*)ckpt, grad_yN, grad_ys, grad_y0, grad_theta,
-                    scale_hist, stats);
+                    grad_t, scale_hist, stats);
 }
 
 const char* rampde_strerror(int code) {

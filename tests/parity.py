@@ -58,7 +58,7 @@ def run_oracle(cfg: wl.Config, theta, y0, target, mode: str, scaling: str = None
                          grad_ys=None if grad_ys is None else grad_ys.reshape(cfg.N + 1, cfg.B, -1))
     return dict(yN=yN.reshape(cfg.state_shape), ckpt=ckpt, grad_yN=gyN, grad_y0=res.grad_y0.reshape(cfg.state_shape),
                 grad_theta=res.grad_theta, scale_hist=res.scale_hist, retries=res.retries, status=res.status,
-                failed_step=res.failed_step)
+                failed_step=res.failed_step, grad_t=res.grad_t)
 
 
 def run_oracle_rows(cfg: wl.Config, theta, y0, target, rows, mode: str):
@@ -106,7 +106,7 @@ def ckpt_to_boundary_layout(cfg: wl.Config, ckpt_np: np.ndarray) -> np.ndarray:
 
 
 def run_gpu(cfg: wl.Config, theta, y0, target, scaling: str = None, k_max: int = 16, flags: int = 0,
-            grad_ys=None, expect_error: bool = False):
+            grad_ys=None, expect_error: bool = False, want_grad_t: bool = False):
     import torch
     from paper_2510_23498_amd import binding as rb
     vel, tab, pol = gpu_descriptors(cfg, scaling, k_max, flags)
@@ -121,14 +121,17 @@ def run_gpu(cfg: wl.Config, theta, y0, target, scaling: str = None, k_max: int =
     gyN_d = torch.from_numpy(np.ascontiguousarray(gyN)).to(dev)
     gys_d = None if grad_ys is None else torch.from_numpy(np.ascontiguousarray(grad_ys, dtype=np.float32)).to(dev)
     out = dict(yN=yN_np, ckpt=ckpt_to_boundary_layout(cfg, ckpt.float().cpu().numpy()), grad_yN=gyN)
+    gt_d = torch.zeros(cfg.N + 1, dtype=torch.float32, device=dev) if want_grad_t else None
     try:
-        gy0, gth, info = rb.rampde_odeint_bwd(vel, th, tgrid, tab, pol, ckpt, gyN_d, grad_ys=gys_d)
+        gy0, gth, info = rb.rampde_odeint_bwd(vel, th, tgrid, tab, pol, ckpt, gyN_d, grad_ys=gys_d, grad_t=gt_d)
     except rb.RampdeError as e:
         if not expect_error:
             raise
         out.update(error=e.code, info=e.stats)
         return out
     torch.cuda.synchronize()
+    if want_grad_t:
+        out["grad_t"] = gt_d.cpu().numpy()
     out.update(grad_y0=gy0.cpu().numpy(), grad_theta=gth.cpu().numpy(), scale_hist=info.scale_hist,
                retries=info.retries, status=info.status, failed_step=info.failed_step, info=info)
     return out

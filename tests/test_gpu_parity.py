@@ -132,3 +132,47 @@ def test_fixed_scale_runs_groups_of_steps_per_launch(group, low, monkeypatch):
     print("  vs emul:", {k: f"{v:.2e}" for k, v in e.items()}, flush=True)
     assert gpu["status"] == 0
     np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
+
+
+# ------------------------------------------------------------------ time-grid gradient dL/dt
+def _time_grid_case(cfg, scaling=None, bias_std=0.1, grad_ys=None, flags=0):
+    theta, y0, target = par.make_inputs(cfg, bias_std=bias_std)
+    print(f"[case] dL/dt {cfg.name} B={cfg.B} N={cfg.N} low={cfg.low} tab={cfg.tableau} flags={flags}", flush=True)
+    gpu = par.run_gpu(cfg, theta, y0, target, scaling=scaling, grad_ys=grad_ys, want_grad_t=True, flags=flags)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul", scaling=scaling,
+                         grad_ys=None if grad_ys is None else grad_ys.astype(np.float64))
+    f64 = par.run_oracle(cfg, theta, y0, target, "f64", grad_ys=None if grad_ys is None else grad_ys.astype(np.float64))
+    e_emu = par.rel_err(gpu["grad_t"], emu["grad_t"])
+    e_f64 = par.rel_err(gpu["grad_t"], f64["grad_t"])
+    print(f"  dL/dt vs emul {e_emu:.2e}  vs f64 {e_f64:.2e}", flush=True)
+    assert e_emu <= par.TOL_EMUL, (e_emu, gpu["grad_t"], emu["grad_t"])
+    assert e_f64 <= par.TOL_F64[cfg.low], e_f64
+    # the other outputs are those of the plain backward pass
+    par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
+    return gpu, emu
+
+
+@pytest.mark.parametrize("tab", ["euler", "heun", "rk4", "kutta3"])
+def test_time_grid_gradient_small_mlp_all_tableaux(tab):
+    cfg = wl.CONFIGS["cfg1"].with_(name="dt" + tab, B=130, N=6, widths=(5, 40, 24, 5), tableau=tab)
+    _time_grid_case(cfg)
+
+
+def test_time_grid_gradient_cfg1_and_running_cost():
+    _time_grid_case(wl.CONFIGS["cfg1"])
+    cfg = wl.CONFIGS["cfg1"].with_(name="dtrun", B=64, N=4, widths=(6, 32, 6))
+    _time_grid_case(cfg, grad_ys=wl.normals(3, "dtrun.gys", (cfg.N + 1, cfg.B, 6), 0.1))
+
+
+@pytest.mark.parametrize("group", [3, 64])
+def test_time_grid_gradient_fixed_scale_step_groups(group, monkeypatch):
+    monkeypatch.setenv("RAMPDE_STEP_GROUP", str(group))
+    cfg = wl.CONFIGS["cfg2"].with_(name=f"dtgrp{group}", B=200, N=7, widths=(24, 256, 256, 24))
+    _time_grid_case(cfg, scaling="none")
+
+
+def test_time_grid_gradient_wide_and_single_layer_networks():
+    _time_grid_case(wl.CONFIGS["cfg5"].with_(name="dt5", B=96, N=4))
+    _time_grid_case(wl.CONFIGS["cfg3"].with_(name="dt3", B=300, N=3))
+    _time_grid_case(wl.CONFIGS["cfg1"].with_(name="dtlin", B=40, N=5, widths=(12, 12)))

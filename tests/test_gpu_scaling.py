@@ -27,7 +27,7 @@ def _linear_case(N):
     return d, theta, y0, tg, aN
 
 
-def _gpu_linear(d, theta, y0, tg, aN, scaling, k_max, flags, tabname="euler"):
+def _gpu_linear(d, theta, y0, tg, aN, scaling, k_max, flags, tabname="euler", grad_t=None):
     dev = torch.device("cuda:0")
     vel = rb.Velocity.mlp((d, d), time_input=False)
     t = wl.TABLEAUX[tabname]
@@ -35,7 +35,7 @@ def _gpu_linear(d, theta, y0, tg, aN, scaling, k_max, flags, tabname="euler"):
     pol = rb.Policy(low="f16", scaling=scaling, k_max=k_max, flags=flags)
     th = torch.from_numpy(theta).to(dev)
     yN, ck = rb.rampde_odeint_fwd(vel, th, torch.from_numpy(y0).to(dev), tg, tab, pol)
-    return rb.rampde_odeint_bwd(vel, th, tg, tab, pol, ck, torch.from_numpy(aN).to(dev)), ck
+    return rb.rampde_odeint_bwd(vel, th, tg, tab, pol, ck, torch.from_numpy(aN).to(dev), grad_t=grad_t), ck
 
 
 def _oracle_linear(d, theta, y0, tg, aN, scaling, k_max, tabname="euler"):
@@ -156,3 +156,25 @@ def test_gradient_is_accumulated_into_the_callers_vector():
     init = torch.full_like(g0, 0.5)
     _, g1, _ = rb.rampde_odeint_bwd(vel, th, cfg.tgrid(), tab, pol, ck, gyN, grad_theta=init.clone())
     assert par.rel_err((g1 - 0.5).cpu().numpy(), g0.cpu().numpy()) < 1e-5
+
+
+
+@pytest.mark.parametrize("N,tabname", [(5, "euler"), (4, "rk4")])
+def test_time_grid_gradient_counts_a_retried_step_once(N, tabname):
+    # the sums of a step whose cotangent chain overflowed are discarded before the step is redone
+    case = _linear_case(N)
+    print(f"[case] dL/dt with overflow retry N={N} {tabname}", flush=True)
+    gt = torch.full((N + 1,), 0.25, dtype=torch.float32, device="cuda:0")   # accumulated into
+    (gy0, gth, info), _ = _gpu_linear(*case, "dynamic", 16, 0, tabname, grad_t=gt)
+    ref = _oracle_linear(*case, "dynamic", 16, tabname)
+    assert ref.retries >= 1 and info.retries == ref.retries
+    assert par.rel_err(gt.cpu().numpy() - 0.25, ref.grad_t) <= par.TOL_EMUL, (gt.cpu().numpy() - 0.25, ref.grad_t)
+    assert par.rel_err(gy0.cpu().numpy(), ref.grad_y0) <= par.TOL_EMUL
+
+
+def test_time_grid_gradient_is_refused_on_the_per_layer_path():
+    case = _linear_case(2)
+    gt = torch.zeros(3, dtype=torch.float32, device="cuda:0")
+    with pytest.raises(rb.RampdeError) as e:
+        _gpu_linear(*case, "dynamic", 16, rb.PER_LAYER_KERNELS, "euler", grad_t=gt)
+    assert e.value.code == rb.EUNSUPPORTED
