@@ -162,8 +162,7 @@ int rampde_odeint_bwd(const rampde_velocity *vel, const float *theta, int64_t B,
  *   as the state and parameter cotangents, summed in fp32 and not rounded to 16 bits,
  *   t'_i += (h/S)(dt - dh) - Phi^T a_{i+1},   t'_{i+1} += (h/S) dh + Phi^T a_{i+1},
  * Phi = sum_j b_j k_j from the low-precision slopes, a_{i+1} the fp32 adjoint before the step's
- * update.  Sums over the batch use fp32 atomics: the result is reproducible to rounding only.
- * Returns RAMPDE_EUNSUPPORTED for velocities / shapes that run on the per-layer kernels. */
+ * update.  Sums over the batch use fp32 atomics: the result is reproducible to rounding only. */
 int rampde_odeint_bwd_tgrid(const rampde_velocity *vel, const float *theta, int64_t B,
                             const double *tgrid, int N, const rampde_tableau *tab,
                             const rampde_policy *pol, const void *ckpt, const float *grad_yN,

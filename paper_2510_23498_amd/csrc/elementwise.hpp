@@ -278,11 +278,16 @@ __global__ void scale_grow(Ctl* ctl, float* scale_hist, int step, int p_bits, in
 //   dwt[c] += (h/S) * sum_j tau_j sum_{rows of stage j} delta[row][c]          (dense layer 1)
 //   conv: dwt[c][tap] += (h/S) * sum_j tau_j sum_{pixels whose tap neighbour exists} delta
 // rows = stages * R; `taus` gives tau_j.  Grid: (column blocks of 64, row chunks).
+// With `tpart` (time-grid gradient, paper Sec. 3): the time cotangent of stage j is
+// taubar_j = sum_{rows of stage j, c (, taps)} delta * w_t (wt: the rounded time weights, dense
+// [ncols], conv [9][ld]); the step's sums get   tpart[0] += (h/S) sum_j (1 - c_j) taubar_j
+// (the time part of dt - dh) and tpart[1] += (h/S) sum_j c_j taubar_j (the time part of dh).
 template <class T, bool CONV>
 __global__ __launch_bounds__(256) void column_sums(const uint16_t* __restrict__ delta, int ld, int64_t R, int s,
                                                    int ncols, Coefs taus, float h, float* __restrict__ gb,
                                                    float* __restrict__ gwt, int wt_stride, int H, int Wd,
-                                                   int rows_per_block, const Ctl* ctl) {
+                                                   int rows_per_block, const Ctl* ctl, const float* __restrict__ wt,
+                                                   Coefs cs, float* __restrict__ tpart) {
   if (ctl->poison) return;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + tx;
@@ -291,41 +296,117 @@ __global__ __launch_bounds__(256) void column_sums(const uint16_t* __restrict__ 
   int64_t r1 = r0 + rows_per_block;
   if (r1 > rows) r1 = rows;
   constexpr int NT = CONV ? 9 : 1;
-  float sb = 0.f, st[NT];
+  float sb = 0.f, st[NT], sc[NT], s1[NT];  // st: tau-weighted, sc: c_j-weighted, s1: unweighted
 #pragma unroll
-  for (int t = 0; t < NT; ++t) st[t] = 0.f;
+  for (int t = 0; t < NT; ++t) st[t] = sc[t] = s1[t] = 0.f;
   for (int64_t r = r0 + ty; r < r1; r += 4) {
     float v = Low<T>::to_f32(delta[r * ld + c]);
-    float tau = taus.v[r / R];
+    const int j = (int)(r / R);
+    float tau = taus.v[j], cj = cs.v[j];
     sb += v;
     if (CONV) {
       int x = (int)(r % Wd), y = (int)((r / Wd) % H);
 #pragma unroll
       for (int t = 0; t < 9; ++t) {
         int yy = y + t / 3 - 1, xx = x + t % 3 - 1;
-        if (yy >= 0 && yy < H && xx >= 0 && xx < Wd) st[t] = fmaf(tau, v, st[t]);
+        if (yy >= 0 && yy < H && xx >= 0 && xx < Wd) {
+          st[t] = fmaf(tau, v, st[t]);
+          sc[t] = fmaf(cj, v, sc[t]);
+          s1[t] += v;
+        }
       }
     } else {
       st[0] = fmaf(tau, v, st[0]);
+      sc[0] = fmaf(cj, v, sc[0]);
+      s1[0] += v;
     }
   }
-  __shared__ float red[4][64][NT + 1];
+  __shared__ float red[4][64][3 * NT + 1];
   red[ty][tx][0] = sb;
 #pragma unroll
-  for (int t = 0; t < NT; ++t) red[ty][tx][1 + t] = st[t];
+  for (int t = 0; t < NT; ++t) {
+    red[ty][tx][1 + t] = st[t];
+    red[ty][tx][1 + NT + t] = sc[t];
+    red[ty][tx][1 + 2 * NT + t] = s1[t];
+  }
   __syncthreads();
-  if (ty == 0 && c < ncols) {
+  if (ty == 0) {
     const float scale = h / ctl->S_step;
-    float v = red[0][tx][0] + red[1][tx][0] + red[2][tx][0] + red[3][tx][0];
-    unsafeAtomicAdd(&gb[c], scale * v);
-    if (gwt) {
+    float p0 = 0.f, p1 = 0.f;
+    if (c < ncols) {
+      float v = red[0][tx][0] + red[1][tx][0] + red[2][tx][0] + red[3][tx][0];
+      unsafeAtomicAdd(&gb[c], scale * v);
+      if (gwt) {
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        float w = red[0][tx][1 + t] + red[1][tx][1 + t] + red[2][tx][1 + t] + red[3][tx][1 + t];
-        unsafeAtomicAdd(&gwt[(size_t)c * wt_stride + t], scale * w);
+        for (int t = 0; t < NT; ++t) {
+          float w = red[0][tx][1 + t] + red[1][tx][1 + t] + red[2][tx][1 + t] + red[3][tx][1 + t];
+          unsafeAtomicAdd(&gwt[(size_t)c * wt_stride + t], scale * w);
+        }
+      }
+      if (tpart && wt) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const float wc = red[0][tx][1 + NT + t] + red[1][tx][1 + NT + t] + red[2][tx][1 + NT + t] +
+                           red[3][tx][1 + NT + t];
+          const float w1 = red[0][tx][1 + 2 * NT + t] + red[1][tx][1 + 2 * NT + t] + red[2][tx][1 + 2 * NT + t] +
+                           red[3][tx][1 + 2 * NT + t];
+          const float wv = CONV ? wt[t * ld + c] : wt[c];
+          p0 = fmaf(wv, w1 - wc, p0);
+          p1 = fmaf(wv, wc, p1);
+        }
+      }
+    }
+    if (tpart && wt) {  // (wavefront 0: sum over its 64 columns)
+      for (int o = 32; o > 0; o >>= 1) {
+        p0 += __shfl_xor(p0, o);
+        p1 += __shfl_xor(p1, o);
+      }
+      if (tx == 0) {
+        unsafeAtomicAdd(&tpart[0], scale * p0);
+        unsafeAtomicAdd(&tpart[1], scale * p1);
       }
     }
   }
+}
+
+// State-shaped terms of the time-grid gradient of one accepted step (paper Sec. 3, update lines of t'):
+//   phia = sum_i (sum_j b_j k_j[i]) a[i]                      (Phi^T a_{i+1}, a before this step's update)
+//   dhz  = sum_i sum_j zbar_j[i] * (sum_{l<j} a_jl k_l[i])    (the stage-input part of dh)
+//   tpart[0] += -(h/S) dhz - phia,   tpart[1] += (h/S) dhz + phia.
+struct CoefMat {
+  float v[kMaxStages * kMaxStages];
+};
+template <class T>
+__global__ __launch_bounds__(256) void time_grid_terms(const float* __restrict__ a, int d,
+                                                       const uint16_t* __restrict__ K,
+                                                       const uint16_t* __restrict__ zbar, int64_t stage_stride, int s,
+                                                       Coefs bw, CoefMat A, float h, int ld, int64_t R, const Ctl* ctl,
+                                                       float* __restrict__ tpart) {
+  if (ctl->poison) return;
+  float pa = 0.f, dz = 0.f;
+  const int64_t n = R * d;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t off = (i / d) * ld + (i % d);
+    float k[kMaxStages];
+    float phi = 0.f;
+#pragma unroll
+    for (int j = 0; j < kMaxStages; ++j) {
+      k[j] = (j < s) ? Low<T>::to_f32(K[j * stage_stride + off]) : 0.f;
+      phi = fmaf(bw.v[j], k[j], phi);
+    }
+    pa = fmaf(phi, a[i], pa);
+#pragma unroll
+    for (int j = 1; j < kMaxStages; ++j) {
+      if (j < s) {
+        float incr = 0.f;
+#pragma unroll
+        for (int l = 0; l < j; ++l) incr = fmaf(A.v[j * kMaxStages + l], k[l], incr);
+        dz = fmaf(Low<T>::to_f32(zbar[j * stage_stride + off]), incr, dz);
+      }
+    }
+  }
+  const float hs = h / ctl->S_step;
+  block_sum2(-hs * dz - pa, fmaf(hs, dz, pa), tpart);
 }
 
 // NONE_SAFE outcome: overflow => gradients are +inf

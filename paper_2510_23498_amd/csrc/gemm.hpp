@@ -372,6 +372,12 @@ struct ConvWgrad {
   int Na;                       // valid output channels
   int64_t R;                    // rows per stage (a multiple of 64)
   float taus[kMaxStages];       // stage times
+  // time-grid gradient (paper Sec. 3, update lines of t'): the time cotangent of stage j is
+  // taubar_j = sum_{k, co, tap} delta[k][co] * wt[tap][co] * [tap inside]; the step's sums get
+  //   tpart[0] += scale * sum_j (1 - c_j) taubar_j,   tpart[1] += scale * sum_j c_j taubar_j
+  const float* wt; int ldwt;    // rounded time-channel weights [9][ldwt], or null
+  float* tpart;                 // or null
+  float cs[kMaxStages];         // c_j
 };
 
 constexpr int CW_PA = BK + 8;   // LDS pitch of the cotangent copies (elements)
@@ -474,9 +480,10 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
 
   const int frow = lane & 31, fk = (lane >> 5) * 8;
   const bool sums = blockIdx.y == 0 && g.gb != nullptr;
-  float sum_b = 0.f, sum_t[9];
+  const bool tsums = g.tpart != nullptr && g.wt != nullptr;
+  float sum_b = 0.f, sum_t[9], sum_1[9], sum_c[9];  // tau-, un- and c_j-weighted tap sums
 #pragma unroll
-  for (int t = 0; t < 9; ++t) sum_t[t] = 0.f;
+  for (int t = 0; t < 9; ++t) sum_t[t] = sum_1[t] = sum_c[t] = 0.f;
   load_items(k_begin);
   for (int64_t k0 = k_begin; k0 < k_end; k0 += 64) {
     store_items(k0);
@@ -487,9 +494,12 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
       // one image line: only its first row can have x = 0, only its last x = W - 1
       const int co = tid >> 2, qt = tid & 3;
       const int j = (int)(k0 / g.R);
-      float tau = 0.f;
+      float tau = 0.f, cj = 0.f;
 #pragma unroll
-      for (int q = 0; q < kMaxStages; ++q) tau = (q == j) ? g.taus[q] : tau;
+      for (int q = 0; q < kMaxStages; ++q) {
+        tau = (q == j) ? g.taus[q] : tau;
+        cj = (q == j) ? g.cs[q] : cj;
+      }
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
         const int kq = qt * 16 + b * 8;
@@ -502,9 +512,19 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
           for (int e = 1; e < 7; ++e) inner += Low<T>::to_f32(v[e]);
           const float f0 = Low<T>::to_f32(v[0]), f7 = Low<T>::to_f32(v[7]);
           const float full = inner + f0 + f7;
-          sum_t[dyv * 3 + 0] = fmaf(tau, inner + f7 + (xq0 == 0 ? 0.f : f0), sum_t[dyv * 3 + 0]);      // dx = -1
+          const float left = inner + f7 + (xq0 == 0 ? 0.f : f0);       // dx = -1
+          const float right = inner + f0 + (xq0 == W - 8 ? 0.f : f7);  // dx = +1
+          sum_t[dyv * 3 + 0] = fmaf(tau, left, sum_t[dyv * 3 + 0]);
           sum_t[dyv * 3 + 1] = fmaf(tau, full, sum_t[dyv * 3 + 1]);
-          sum_t[dyv * 3 + 2] = fmaf(tau, inner + f0 + (xq0 == W - 8 ? 0.f : f7), sum_t[dyv * 3 + 2]);  // dx = +1
+          sum_t[dyv * 3 + 2] = fmaf(tau, right, sum_t[dyv * 3 + 2]);
+          if (tsums) {
+            sum_1[dyv * 3 + 0] += left;
+            sum_1[dyv * 3 + 1] += full;
+            sum_1[dyv * 3 + 2] += right;
+            sum_c[dyv * 3 + 0] = fmaf(cj, left, sum_c[dyv * 3 + 0]);
+            sum_c[dyv * 3 + 1] = fmaf(cj, full, sum_c[dyv * 3 + 1]);
+            sum_c[dyv * 3 + 2] = fmaf(cj, right, sum_c[dyv * 3 + 2]);
+          }
           if (dyv == 1) sum_b += full;
         }
       }
@@ -543,6 +563,19 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
 #pragma unroll
         for (int t = 0; t < 9; ++t) unsafeAtomicAdd(&g.gwt[(size_t)na * g.wt_stride + t], scale * sum_t[t]);
       }
+    }
+    if (tsums) {
+      // this thread's quarter of its channel's rows: contract the tap sums with the time weights
+      float p0 = 0.f, p1 = 0.f;
+      if (na < g.Na) {
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+          const float wv = g.wt[t * g.ldwt + na];
+          p0 = fmaf(wv, sum_1[t] - sum_c[t], p0);
+          p1 = fmaf(wv, sum_c[t], p1);
+        }
+      }
+      block_sum2(scale * p0, scale * p1, g.tpart);
     }
   }
   // plain read-modify-write: the slot belongs to this workgroup for the whole backward pass

@@ -717,7 +717,7 @@ struct Runner {
   // one step of the adjoint recursion: recompute, cotangent chain, decision, fp32 updates
   void backward_step(int i, const double* tgrid, const rampde_tableau* tab, const rampde_policy* pol,
                      const uint16_t* ckpt, float* a, const float* gys_i, float* grad_theta, int dynamic, int detect,
-                     bool recompute) {
+                     bool recompute, float* tpart_i) {
     const int s = p.s;
     const float h = (float)(tgrid[i + 1] - tgrid[i]);
     Coefs taus{};
@@ -771,7 +771,20 @@ struct Runner {
       }
     }
     chain_decide<<<1, 1, 0, st>>>(ctl, i, detect);
-    param_grads(h, taus, grad_theta);
+    Coefs cs{};
+    for (int j = 0; j < s; ++j) cs.v[j] = (float)tab->c[j];
+    if (tpart_i) {
+      // state-shaped terms of the time-grid gradient, with the adjoint as it is before this step's update
+      Coefs bw{};
+      CoefMat am{};
+      for (int j = 0; j < s; ++j) {
+        bw.v[j] = (float)tab->b[j];
+        for (int l = 0; l < j; ++l) am.v[j * kMaxStages + l] = (float)tab->A[j * s + l];
+      }
+      time_grid_terms<T><<<stream_blocks(p.n, 1024), 256, 0, st>>>(a, p.d, u16(p.K), u16(p.ZBAR), p.stage_stride, s, bw,
+                                                                   am, h, p.dpad, p.R, ctl, tpart_i);
+    }
+    param_grads(h, taus, grad_theta, cs, tpart_i);
     {
       // bytes per state element: read a (4) + s stage cotangents (2 each) + write a (4)
       TimeScope ts(RAMPDE_K_ADJOINT_UPDATE, (double)p.n * (8.0 + 2.0 * s), st);
@@ -788,7 +801,7 @@ struct Runner {
 
   // parameter gradient of one accepted step: contraction over all stages and rows at once,
   // scaled by h / S_step and accumulated in fp32 (paper Sec. 3, update of g)
-  void param_grads(float h, const Coefs& taus, float* grad_theta) {
+  void param_grads(float h, const Coefs& taus, float* grad_theta, const Coefs& cs, float* tpart_i) {
     const int s = p.s;
     const int64_t rows = (int64_t)s * p.R;
     for (int l = 0; l < p.L; ++l) {
@@ -812,7 +825,13 @@ struct Runner {
         c.wt_stride = y.in_full * 9;
         c.Na = y.out;
         c.R = p.R;
-        for (int j = 0; j < kMaxStages; ++j) c.taus[j] = j < s ? taus.v[j] : 0.f;
+        for (int j = 0; j < kMaxStages; ++j) {
+          c.taus[j] = j < s ? taus.v[j] : 0.f;
+          c.cs[j] = j < s ? cs.v[j] : 0.f;
+        }
+        c.wt = y.has_time ? f32(y.wt_f) : nullptr;
+        c.ldwt = y.Npad;
+        c.tpart = tpart_i;
         dim3 cgrid(y.Npad / 64, y.Kpad / 64, y.cw_splits);
         TimeScope ts(RAMPDE_K_WGRAD_GEMM, 2.0 * rows * (double)y.Npad * y.Kpad * 9, st);
         conv_wgrad<T><<<cgrid, 256, conv_wgrad_lds_bytes(p.Wd), st>>>(c);
@@ -854,10 +873,10 @@ struct Runner {
       float* gwt = y.has_time ? grad_theta + y.theta_w + (p.conv ? (size_t)y.in * 9 : (size_t)y.in) : nullptr;
       if (p.conv)
         column_sums<T, true><<<cgrid, 256, 0, st>>>(g.A, y.Npad, p.R, s, y.out, taus, h, gb, gwt, y.in_full * 9, p.H,
-                                                    p.Wd, rpb, ctl);
+                                                    p.Wd, rpb, ctl, y.has_time ? f32(y.wt_f) : nullptr, cs, tpart_i);
       else
         column_sums<T, false><<<cgrid, 256, 0, st>>>(g.A, y.Npad, p.R, s, y.out, taus, h, gb, gwt, y.in_full, p.H,
-                                                     p.Wd, rpb, ctl);
+                                                     p.Wd, rpb, ctl, y.has_time ? f32(y.wt_f) : nullptr, cs, tpart_i);
     }
   }
 
@@ -917,7 +936,6 @@ struct Runner {
                rampde_scaling scaling, const uint16_t* ckpt, const float* grad_yN, const float* grad_ys,
                float* grad_y0, float* grad_theta, float* grad_t, float* scale_hist, rampde_stats* stats) {
     const int dynamic = scaling == RAMPDE_SCALE_DYNAMIC;
-    if (grad_t && !use_fused) return RAMPDE_EUNSUPPORTED;  // (time-grid gradient: row-tile-persistent kernels only)
     if (grad_t) fill_zero_u32<<<1, 256, 0, st>>>((uint32_t*)(ws + p.tpart), 2 * (size_t)N);
     const int detect = dynamic || scaling == RAMPDE_SCALE_NONE_SAFE;
     const int k_max = pol->k_max > 0 ? pol->k_max : 16;
@@ -1044,7 +1062,7 @@ struct Runner {
           }
         } else {
           backward_step(i, tgrid, tab, pol, ckpt, a, gys_at(i), grad_theta, dynamic, detect,
-                        i == from ? recompute_first : true);
+                        i == from ? recompute_first : true, grad_t ? f32(p.tpart) + 2 * (size_t)i : nullptr);
         }
       }
       if (use_fused) {

@@ -76,3 +76,20 @@ def test_full_size_sampled_rows(name, tab):
     assert errs["yN_f64"] <= par.TOL_F64[cfg.low] and errs["grad_y0_f64"] <= par.TOL_F64[cfg.low]
     # stored trajectory = (N+1) low-precision states, half the bytes of an fp32 trajectory
     assert gpu["ckpt"].size == (cfg.N + 1) * cfg.B * cfg.d
+
+
+@pytest.mark.parametrize("name,steps", [("cfg2", 32), ("cfg3", 2), ("cfg4", 1), ("cfg5", 4)])
+def test_time_grid_gradient_full_batch(name, steps):
+    # dL/dt is a sum over the whole batch, so it is compared at the full batch size (the benchmark
+    # workload over all its steps, the larger ones over a few), beside the other outputs of that call
+    full = wl.CONFIGS[name]
+    cfg = full.with_(N=steps, t1=full.t0 + (full.t1 - full.t0) * steps / full.N)
+    theta, y0, target = par.make_inputs(cfg)
+    print(f"[case] dL/dt {cfg.name} full batch B={cfg.B}, {steps} of {full.N} steps", flush=True)
+    gpu = par.run_gpu(cfg, theta, y0, target, want_grad_t=True)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul")
+    e = par.rel_err(gpu["grad_t"], emu["grad_t"])
+    print(f"  dL/dt vs emul {e:.2e}", flush=True)
+    assert e <= par.TOL_EMUL, (e, gpu["grad_t"], emu["grad_t"])
+    par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])

@@ -153,9 +153,17 @@ def _time_grid_case(cfg, scaling=None, bias_std=0.1, grad_ys=None, flags=0):
     return gpu, emu
 
 
+@PATHS
 @pytest.mark.parametrize("tab", ["euler", "heun", "rk4", "kutta3"])
-def test_time_grid_gradient_small_mlp_all_tableaux(tab):
+def test_time_grid_gradient_small_mlp_all_tableaux(tab, flags):
     cfg = wl.CONFIGS["cfg1"].with_(name="dt" + tab, B=130, N=6, widths=(5, 40, 24, 5), tableau=tab)
+    _time_grid_case(cfg, flags=flags)
+
+
+@pytest.mark.parametrize("C,H,W,B,tab", [(64, 32, 32, 2, "rk4"), (5, 7, 6, 2, "kutta3"), (70, 4, 8, 3, "heun")])
+def test_time_grid_gradient_conv(C, H, W, B, tab):
+    # both convolutions carry a time channel; all-taps weight-gradient kernel and the generic one (W = 6)
+    cfg = wl.CONFIGS["cfg4"].with_(name=f"dtconv{C}x{H}x{W}", B=B, N=2, C=C, H=H, W=W, tableau=tab)
     _time_grid_case(cfg)
 
 

@@ -159,22 +159,15 @@ def test_gradient_is_accumulated_into_the_callers_vector():
 
 
 
+@PATHS
 @pytest.mark.parametrize("N,tabname", [(5, "euler"), (4, "rk4")])
-def test_time_grid_gradient_counts_a_retried_step_once(N, tabname):
+def test_time_grid_gradient_counts_a_retried_step_once(N, tabname, flags):
     # the sums of a step whose cotangent chain overflowed are discarded before the step is redone
     case = _linear_case(N)
     print(f"[case] dL/dt with overflow retry N={N} {tabname}", flush=True)
     gt = torch.full((N + 1,), 0.25, dtype=torch.float32, device="cuda:0")   # accumulated into
-    (gy0, gth, info), _ = _gpu_linear(*case, "dynamic", 16, 0, tabname, grad_t=gt)
+    (gy0, gth, info), _ = _gpu_linear(*case, "dynamic", 16, flags, tabname, grad_t=gt)
     ref = _oracle_linear(*case, "dynamic", 16, tabname)
     assert ref.retries >= 1 and info.retries == ref.retries
     assert par.rel_err(gt.cpu().numpy() - 0.25, ref.grad_t) <= par.TOL_EMUL, (gt.cpu().numpy() - 0.25, ref.grad_t)
     assert par.rel_err(gy0.cpu().numpy(), ref.grad_y0) <= par.TOL_EMUL
-
-
-def test_time_grid_gradient_is_refused_on_the_per_layer_path():
-    case = _linear_case(2)
-    gt = torch.zeros(3, dtype=torch.float32, device="cuda:0")
-    with pytest.raises(rb.RampdeError) as e:
-        _gpu_linear(*case, "dynamic", 16, rb.PER_LAYER_KERNELS, "euler", grad_t=gt)
-    assert e.value.code == rb.EUNSUPPORTED
