@@ -76,6 +76,9 @@ typedef enum {
 #define RAMPDE_ROUND_INCREMENT 1u /* round sum_j b_j k_j to `low` before the fp32 add (literal Alg. 1 line 4) */
 #define RAMPDE_GROW_RAW_NORM 2u   /* growth test on the unscaled norm ||a|| <= 1/(2 u_L) (literal Alg. 2)     */
 #define RAMPDE_PER_LAYER_KERNELS 4u /* dense networks: use one kernel per layer instead of the row-tile-persistent kernels */
+#define RAMPDE_NAIVE_STATE 8u       /* comparison baseline, not the paper's scheme: the state y and the adjoint a are
+                                     themselves kept in low precision (rounded after every update), i.e. without
+                                     the fp32 accumulators of Algorithms 1-2 (the "naive" rows of the paper's Table 5) */
 
 /* Explicit Butcher tableau, host memory, fp64.  A is s*s row-major; only the strictly
  * lower triangle may be non-zero (checked).  Consistency (sum b = 1, ...) is not checked. */

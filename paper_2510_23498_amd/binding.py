@@ -28,7 +28,7 @@ EXPORTS = ("rampde_num_params", "rampde_workspace_bytes", "rampde_odeint_fwd", "
            "rampde_odeint_bwd_tgrid", "rampde_strerror", "rampde_version", "rampde_timing_enable", "rampde_timing_read")
 
 K_VELOCITY_GEMM, K_WGRAD_GEMM, K_COMBINE_STORE, K_ADJOINT_UPDATE, K_FUSED_FORWARD, K_FUSED_ADJOINT_STEP = range(6)
-ROUND_INCREMENT, GROW_RAW_NORM, PER_LAYER_KERNELS = 1, 2, 4
+ROUND_INCREMENT, GROW_RAW_NORM, PER_LAYER_KERNELS, NAIVE_STATE = 1, 2, 4, 8
 
 
 class _Tableau(C.Structure):

@@ -80,13 +80,17 @@ __global__ void rows_to_nchw(const float* __restrict__ src, float* __restrict__ 
 
 // y <- y0 (fp32), ckpt[0] <- Q(y0)     (paper Alg. 1: initialisation and first stored state)
 template <class T>
+// naive: the low-precision baseline that keeps the state itself in low precision (paper Table 5,
+// "naive" rows): y <- Q(y0) as well
 __global__ void init_state(const float* __restrict__ y0, float* __restrict__ y, uint16_t* __restrict__ ck0,
-                           int64_t n, int copy_y) {
+                           int64_t n, int copy_y, int naive) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   float v = y0[i];
-  if (copy_y) y[i] = v;
-  ck0[i] = Low<T>::from_f32(v);
+  const uint16_t q = Low<T>::from_f32(v);
+  if (naive) v = Low<T>::to_f32(q);
+  if (copy_y || naive) y[i] = v;
+  ck0[i] = q;
 }
 
 // Stage input  z_j = Q( yhat + h * sum_{l<j} a_jl k_l ),  yhat = stored checkpoint.
@@ -124,10 +128,12 @@ __global__ void combine_store(float* __restrict__ y, const uint16_t* __restrict_
   int c = (int)(i % d);
   float incr = 0.f;
   for (int j = 0; j < s; ++j) incr = fmaf(b.v[j], Low<T>::to_f32(K[j * stage_stride + r * ld + c]), incr);
-  if (round_incr) incr = Low<T>::to_f32(Low<T>::from_f32(incr));
+  if (round_incr & 1) incr = Low<T>::to_f32(Low<T>::from_f32(incr));
   float v = fmaf(h, incr, y[i]);
+  const uint16_t q = Low<T>::from_f32(v);
+  if (round_incr & 2) v = Low<T>::to_f32(q);  // naive baseline: the state is kept in low precision
   y[i] = v;
-  ck_next[i] = Low<T>::from_f32(v);
+  ck_next[i] = q;
 }
 
 // ------------------------------------------------------------------------- backward
@@ -140,14 +146,17 @@ __global__ void ctl_reset(Ctl* ctl, float* scale_hist, int N) {
 }
 
 // a <- dL/dy_N (+ running-cost cotangent), max|a|   (paper Alg. 2, initialisation)
+// naive_low: 0, or the low precision (1 fp16, 2 bf16) in which the naive baseline keeps the adjoint
 __global__ void init_adjoint(const float* __restrict__ gyN, const float* __restrict__ gys_last,
-                             float* __restrict__ a, int64_t n, Ctl* ctl, int copy) {
+                             float* __restrict__ a, int64_t n, Ctl* ctl, int copy, int naive_low) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   unsigned bits = 0;
   if (i < n) {
     float v = gyN[i];
     if (gys_last) v += gys_last[i];
-    if (copy || gys_last) a[i] = v;
+    if (naive_low == 1) v = Low<F16>::to_f32(Low<F16>::from_f32(v));
+    if (naive_low == 2) v = Low<BF16>::to_f32(Low<BF16>::from_f32(v));
+    if (copy || gys_last || naive_low) a[i] = v;
     bits = __builtin_bit_cast(unsigned, fabsf(v));
   }
   block_amax(bits, &ctl->amax_bits);
@@ -239,7 +248,7 @@ __global__ void fold_time_sums(float* __restrict__ grad_t, const float* __restri
 template <class T>
 __global__ void adjoint_update(float* __restrict__ a, int d, const uint16_t* __restrict__ zbar,
                                int64_t stage_stride, int s, float h, const float* __restrict__ gys_i, int ld,
-                               int64_t R, Ctl* ctl) {
+                               int64_t R, Ctl* ctl, int naive) {
   if (ctl->poison) return;
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   unsigned bits = 0;
@@ -250,6 +259,7 @@ __global__ void adjoint_update(float* __restrict__ a, int d, const uint16_t* __r
     for (int j = 0; j < s; ++j) da += Low<T>::to_f32(zbar[j * stage_stride + r * ld + c]);
     float v = fmaf(h / ctl->S, da, a[i]);
     if (gys_i) v += gys_i[i];
+    if (naive) v = Low<T>::to_f32(Low<T>::from_f32(v));  // naive baseline: adjoint kept in low precision
     a[i] = v;
     bits = __builtin_bit_cast(unsigned, fabsf(v));
   }
@@ -493,11 +503,13 @@ __global__ __launch_bounds__(256) void combine_store_v8(float* __restrict__ y, c
     load8f(y + r * d + c, yv);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      if (round_incr) incr[e] = Low<T>::to_f32(Low<T>::from_f32(incr[e]));
+      if (round_incr & 1) incr[e] = Low<T>::to_f32(Low<T>::from_f32(incr[e]));
       yv[e] = fmaf(h, incr[e], yv[e]);
     }
+    const u16x8 q = pack8<T>(yv);
+    if (round_incr & 2) unpack8<T>(q, yv);  // naive baseline: the state is kept in low precision
     store8f(y + r * d + c, yv);
-    *reinterpret_cast<u16x8*>(ck_next + r * d + c) = pack8<T>(yv);
+    *reinterpret_cast<u16x8*>(ck_next + r * d + c) = q;
   }
 }
 
@@ -545,7 +557,7 @@ template <class T>
 __global__ __launch_bounds__(256) void adjoint_update_v8(float* __restrict__ a, int d,
                                                          const uint16_t* __restrict__ zbar, int64_t stage_stride, int s,
                                                          float h, const float* __restrict__ gys_i, int ld, int64_t R,
-                                                         Ctl* ctl) {
+                                                         Ctl* ctl, int naive) {
   if (ctl->poison) return;
   const int gpr = d >> 3;
   const int64_t G = R * gpr;
@@ -570,6 +582,7 @@ __global__ __launch_bounds__(256) void adjoint_update_v8(float* __restrict__ a, 
 #pragma unroll
       for (int e = 0; e < 8; ++e) av[e] = fmaf(hs, da[e], av[e]);
     }
+    if (naive) unpack8<T>(pack8<T>(av), av);
     store8f(a + r * d + c, av);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {

@@ -82,7 +82,8 @@ struct FusedArgs {
   const float* y0;
   float* y;
   uint16_t* ckpt;
-  int round_incr;
+  int round_incr;        // bit 0: round sum_j b_j k_j to low before the fp32 add; bit 1: naive baseline,
+                         // the state (y, and the adjoint a) is itself kept in low precision
   uint16_t* K;  // [s][R][dpad] slopes (used when they do not fit in LDS)
   // one adjoint step
   int step;
@@ -650,6 +651,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_forward_fused(FusedArgs g) {
         const int n = eng.state_col(nt, lq), m = mt * 16 + lm;
         load4f(g.y0, row0 + m, g.R, n, g.d, yv[nt][mt]);
         const uint2 q = pack4<T>(yv[nt][mt]);
+        if (g.round_incr & 2) unpack4<T>(q, yv[nt][mt]);
         store4h(g.ckpt, row0 + m, g.R, n, g.d, q);
         lds_store_u2(&lds.zbuf[m * lds.ldz + n], q);
       }
@@ -712,10 +714,11 @@ __global__ __launch_bounds__(64 * NW) void mlp_forward_fused(FusedArgs g) {
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
                 incr[r] = fmaf(g.b[j], kf[r], incr[r]);
-                if (g.round_incr) incr[r] = Low<T>::to_f32(Low<T>::from_f32(incr[r]));
+                if (g.round_incr & 1) incr[r] = Low<T>::to_f32(Low<T>::from_f32(incr[r]));
                 y[r] = fmaf(h, incr[r], y[r]);
               }
               zq = pack4<T>(y);
+              if (g.round_incr & 2) unpack4<T>(zq, y);
               store4h(ck_next, row0 + m, g.R, n, g.d, zq);
             }
             lds_store_u2(&lds.zbuf[m * lds.ldz + n], zq);
@@ -1018,6 +1021,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           av[nt][mt][r] = fmaf(hs, da[nt][mt][r], av[nt][mt][r]) + gy[r];
+          if (g.round_incr & 2) av[nt][mt][r] = Low<T>::to_f32(Low<T>::from_f32(av[nt][mt][r]));
           const unsigned bb = __builtin_bit_cast(unsigned, fabsf(av[nt][mt][r]));
           if (row0 + m < g.R && n + r < g.d) bits = bb > bits ? bb : bits;
         }

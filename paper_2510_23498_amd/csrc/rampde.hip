@@ -664,7 +664,7 @@ struct Runner {
     a.y0 = y0;
     a.y = yN;
     a.ckpt = ckpt;
-    a.round_incr = (pol->flags & RAMPDE_ROUND_INCREMENT) ? 1 : 0;
+    a.round_incr = ((pol->flags & RAMPDE_ROUND_INCREMENT) ? 1 : 0) | ((pol->flags & RAMPDE_NAIVE_STATE) ? 2 : 0);
     int rc;
     {
       TimeScope ts(RAMPDE_K_FUSED_FORWARD, step_flops() * p.s * N, st);
@@ -684,13 +684,15 @@ struct Runner {
               const rampde_policy* pol, uint16_t* ckpt, float* yN) {
     if (use_fused) return forward_fused(theta, y0, tgrid, N, tab, pol, ckpt, yN);
     cast_weights(theta);
+    const int naive = (pol->flags & RAMPDE_NAIVE_STATE) ? 1 : 0;
+    const int incr_mode = ((pol->flags & RAMPDE_ROUND_INCREMENT) ? 1 : 0) | (naive ? 2 : 0);
     float* y = yN;
     if (p.conv) {
       y = f32(p.y_rows);
       nchw_to_rows<<<blocks_for(p.n, 256), 256, 0, st>>>(y0, y, p.R, p.d, p.H * p.Wd);
-      init_state<T><<<blocks_for(p.n, 256), 256, 0, st>>>(y, y, ckpt, p.n, 0);
+      init_state<T><<<blocks_for(p.n, 256), 256, 0, st>>>(y, y, ckpt, p.n, 0, naive);
     } else {
-      init_state<T><<<blocks_for(p.n, 256), 256, 0, st>>>(y0, y, ckpt, p.n, 1);
+      init_state<T><<<blocks_for(p.n, 256), 256, 0, st>>>(y0, y, ckpt, p.n, 1, naive);
     }
     Coefs bw{};
     for (int j = 0; j < p.s; ++j) bw.v[j] = (float)tab->b[j];
@@ -701,12 +703,10 @@ struct Runner {
       // bytes per state element: read y (4) + s slopes (2 each) + write y (4) + write checkpoint (2)
       TimeScope ts(RAMPDE_K_COMBINE_STORE, (double)p.n * (10.0 + 2.0 * p.s), st);
       if (vec8())
-        combine_store_v8<T><<<stream_blocks(p.n / 8), 256, 0, st>>>(y, u16(p.K), p.stage_stride, p.s, bw, h,
-                                                                   (pol->flags & RAMPDE_ROUND_INCREMENT) ? 1 : 0,
+        combine_store_v8<T><<<stream_blocks(p.n / 8), 256, 0, st>>>(y, u16(p.K), p.stage_stride, p.s, bw, h, incr_mode,
                                                                    ckpt + (size_t)(i + 1) * p.n, p.d, p.dpad, p.R);
       else
-        combine_store<T><<<blocks_for(p.n, 256), 256, 0, st>>>(y, u16(p.K), p.stage_stride, p.s, bw, h,
-                                                              (pol->flags & RAMPDE_ROUND_INCREMENT) ? 1 : 0,
+        combine_store<T><<<blocks_for(p.n, 256), 256, 0, st>>>(y, u16(p.K), p.stage_stride, p.s, bw, h, incr_mode,
                                                               ckpt + (size_t)(i + 1) * p.n, p.d, p.dpad, p.R);
     }
     if (p.conv) rows_to_nchw<<<blocks_for(p.n, 256), 256, 0, st>>>(y, yN, p.R, p.d, p.H * p.Wd, nullptr, 0);
@@ -719,6 +719,7 @@ struct Runner {
                      const uint16_t* ckpt, float* a, const float* gys_i, float* grad_theta, int dynamic, int detect,
                      bool recompute, float* tpart_i) {
     const int s = p.s;
+    const int naive = (pol->flags & RAMPDE_NAIVE_STATE) ? 1 : 0;
     const float h = (float)(tgrid[i + 1] - tgrid[i]);
     Coefs taus{};
     if (recompute) {
@@ -790,10 +791,10 @@ struct Runner {
       TimeScope ts(RAMPDE_K_ADJOINT_UPDATE, (double)p.n * (8.0 + 2.0 * s), st);
       if (vec8())
         adjoint_update_v8<T><<<stream_blocks(p.n / 8, 1024), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, s, h, gys_i,
-                                                                    p.dpad, p.R, ctl);
+                                                                    p.dpad, p.R, ctl, naive);
       else
         adjoint_update<T><<<blocks_for(p.n, 256), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, s, h, gys_i,
-                                                               p.dpad, p.R, ctl);
+                                                               p.dpad, p.R, ctl, naive);
     }
     scale_grow<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), i, Low<T>::p_bits, dynamic,
                                 (pol->flags & RAMPDE_GROW_RAW_NORM) ? 1 : 0);
@@ -976,6 +977,7 @@ struct Runner {
       fa.set_stride = (int64_t)(p.fm_stride / 2);
       fa.nsteps = 1;
       fa.tpart = grad_t ? f32(p.tpart) : nullptr;
+      fa.round_incr = (pol->flags & RAMPDE_NAIVE_STATE) ? 2 : 0;
       fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + p.gpart), (size_t)p.ksplits * p.P);
       if (p.Rp != p.R) {
         // rows R..Rp of every stage are padding of the contraction: they must read as zero
@@ -988,6 +990,7 @@ struct Runner {
       fa.raw_norm = (pol->flags & RAMPDE_GROW_RAW_NORM) ? 1 : 0;
     }
     float* a = use_fused ? a_buf(N) : grad_y0;
+    const int naive_low = (pol->flags & RAMPDE_NAIVE_STATE) ? (std::is_same<T, BF16>::value ? 2 : 1) : 0;
     float* gys_rows = nullptr;
     auto gys_at = [&](int i) -> const float* {
       if (!grad_ys) return nullptr;
@@ -1000,9 +1003,9 @@ struct Runner {
       a = f32(p.a_rows);
       gys_rows = f32(p.gys_rows);
       nchw_to_rows<<<blocks_for(p.n, 256), 256, 0, st>>>(grad_yN, a, p.R, p.d, HW);
-      init_adjoint<<<blocks_for(p.n, 256), 256, 0, st>>>(a, gys_at(N), a, p.n, ctl, 0);
+      init_adjoint<<<blocks_for(p.n, 256), 256, 0, st>>>(a, gys_at(N), a, p.n, ctl, 0, naive_low);
     } else {
-      init_adjoint<<<blocks_for(p.n, 256), 256, 0, st>>>(grad_yN, gys_at(N), a, p.n, ctl, 1);
+      init_adjoint<<<blocks_for(p.n, 256), 256, 0, st>>>(grad_yN, gys_at(N), a, p.n, ctl, 1, naive_low);
     }
     scale_init<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), N, Low<T>::p_bits, dynamic);
 

@@ -184,3 +184,57 @@ def test_time_grid_gradient_wide_and_single_layer_networks():
     _time_grid_case(wl.CONFIGS["cfg5"].with_(name="dt5", B=96, N=4))
     _time_grid_case(wl.CONFIGS["cfg3"].with_(name="dt3", B=300, N=3))
     _time_grid_case(wl.CONFIGS["cfg1"].with_(name="dtlin", B=40, N=5, widths=(12, 12)))
+
+
+# ------------------------------------------------------------------ naive low-precision baseline (Table 5)
+NAIVE = 8  # policy flag: state and adjoint kept in low precision (no fp32 accumulators)
+
+
+@PATHS
+@pytest.mark.parametrize("low", ["f16", "bf16"])
+def test_naive_state_baseline_matches_oracle(low, flags):
+    cfg = wl.CONFIGS["cfg1"].with_(name="naive" + low, B=70, N=12, widths=(6, 40, 6), low=low)
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    print(f"[case] naive baseline {low} flags={flags}", flush=True)
+    gpu = par.run_gpu(cfg, theta, y0, target, scaling="none", flags=flags | NAIVE)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul", scaling="none", flags=dict(naive_state=True))
+    tol = par.TOL_EMUL
+    for k in ("yN", "ckpt", "grad_y0", "grad_theta"):
+        e = par.rel_err(gpu[k].reshape(emu[k].shape), emu[k])
+        print(f"  {k}: {e:.2e}", flush=True)
+        assert e <= tol, (k, e)
+    # and it is a different computation from the scheme's
+    good = par.run_gpu(cfg, theta, y0, target, scaling="none", flags=flags)
+    assert par.rel_err(good["yN"], gpu["yN"]) > 0
+
+
+def test_fp32_accumulator_beats_naive_low_precision_state_on_the_gpu():
+    # many small steps of a contractive linear problem: rounding the state after every step loses the
+    # increments (paper Sec. 4 discussion of Table 5); the scheme's fp32 accumulator does not
+    import torch
+    from paper_2510_23498_amd import binding as rb
+    from oracle import rampde_oracle as orc
+    rng = np.random.default_rng(11)
+    d, B, N = 8, 4, 1000
+    M = rng.normal(size=(d, d))
+    A = -(M @ M.T) / d
+    theta = np.concatenate([A.ravel(), np.zeros(d)])
+    y0 = rng.normal(size=(B, d))
+    rho = np.max(np.abs(np.linalg.eigvalsh(A)))
+    tg = np.arange(N + 1) * (0.5 * 2.0 / rho) * 0.05
+    t = wl.TABLEAUX["euler"]
+    ref = orc.odeint_fwd(orc.MLPVelocity((d, d), time_input=False, activation="identity"), theta, y0, tg, t,
+                         orc.Policy(low="f64"))[0]
+    dev = torch.device("cuda:0")
+    vel = rb.Velocity.mlp((d, d), time_input=False)
+    tab = rb.Tableau(t.A, t.b, t.c)
+    th = torch.from_numpy(theta.astype(np.float32)).to(dev)
+    y0d = torch.from_numpy(y0.astype(np.float32)).to(dev)
+    for low in ("f16", "bf16"):
+        errs = {}
+        for name, fl in (("scheme", 0), ("naive", NAIVE)):
+            yN, _ = rb.rampde_odeint_fwd(vel, th, y0d, tg, tab, rb.Policy(low=low, scaling="none", flags=fl))
+            torch.cuda.synchronize()
+            errs[name] = par.rel_err(yN.cpu().numpy(), ref)
+        print(f"[case] naive vs scheme {low}: {errs}", flush=True)
+        assert errs["naive"] > 10.0 * errs["scheme"], (low, errs)
