@@ -383,7 +383,8 @@ struct ConvWgrad {
 constexpr int CW_PA = BK + 8;   // LDS pitch of the cotangent copies (elements)
 inline size_t conv_wgrad_lds_bytes(int Wd) { return (size_t)(3 * 64 * CW_PA + 3 * 64 * (64 + 2 * Wd + 8)) * 2; }
 
-template <class T>
+// TS: also form the time cotangent sums for the time-grid gradient (g.tpart, g.wt non-null).
+template <class T, bool TS>
 __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
   if (g.ctl->poison) return;
   extern __shared__ __attribute__((aligned(16))) uint16_t cw_smem[];
@@ -480,7 +481,7 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
 
   const int frow = lane & 31, fk = (lane >> 5) * 8;
   const bool sums = blockIdx.y == 0 && g.gb != nullptr;
-  const bool tsums = g.tpart != nullptr && g.wt != nullptr;
+  constexpr bool tsums = TS;
   float sum_b = 0.f, sum_t[9], sum_1[9], sum_c[9];  // tau-, un- and c_j-weighted tap sums
 #pragma unroll
   for (int t = 0; t < 9; ++t) sum_t[t] = sum_1[t] = sum_c[t] = 0.f;

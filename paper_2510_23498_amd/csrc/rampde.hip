@@ -835,7 +835,10 @@ struct Runner {
         c.tpart = tpart_i;
         dim3 cgrid(y.Npad / 64, y.Kpad / 64, y.cw_splits);
         TimeScope ts(RAMPDE_K_WGRAD_GEMM, 2.0 * rows * (double)y.Npad * y.Kpad * 9, st);
-        conv_wgrad<T><<<cgrid, 256, conv_wgrad_lds_bytes(p.Wd), st>>>(c);
+        if (c.tpart && c.wt)
+          conv_wgrad<T, true><<<cgrid, 256, conv_wgrad_lds_bytes(p.Wd), st>>>(c);
+        else
+          conv_wgrad<T, false><<<cgrid, 256, conv_wgrad_lds_bytes(p.Wd), st>>>(c);
         continue;  // (bias and time-channel gradients included)
       } else {
         // split the contraction so that about 1024 workgroups are in flight
@@ -941,9 +944,12 @@ struct Runner {
     const int detect = dynamic || scaling == RAMPDE_SCALE_NONE_SAFE;
     const int k_max = pol->k_max > 0 ? pol->k_max : 16;
     const int HW = p.H * p.Wd;
-    if (conv_wgrad_applies(p))
-      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T>),
+    if (conv_wgrad_applies(p)) {
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_wgrad_lds_bytes(p.Wd)));
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_wgrad_lds_bytes(p.Wd)));
+    }
     ctl_reset<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), N);
     if (conv_wgrad_applies(p))
       for (auto& y : p.layers)
