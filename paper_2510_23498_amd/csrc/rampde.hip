@@ -20,6 +20,7 @@
 #include "elementwise.hpp"
 #include "fused_launch.hpp"
 #include "gemm.hpp"
+#include "conv.hpp"
 
 namespace rampde {
 
@@ -467,9 +468,20 @@ struct Runner {
     }
   }
 
+  // the convolution tile kernel keeps a layer's weights in LDS: more than the default limit
+  hipError_t allow_conv_tile_lds() {
+    if (p.Wd < 8 || p.Wd > 64) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3x3_tile<T>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_tile_lds_bytes(p.Wd));
+  }
+
   void launch_nt(const GemmNT& g) {
     TimeScope ts(RAMPDE_K_VELOCITY_GEMM, 2.0 * g.M * (double)g.N * g.K, st);
-    if (p.conv) {
+    if (p.conv && conv_tile_applies(g.Cpad, g.N, g.H, g.Wd, g.M)) {
+      // persistent: one workgroup per CU (its LDS holds the layer's weights), tiles of 256 pixels
+      const int ntiles = (int)(g.M / CT_TILE);
+      conv3x3_tile<T><<<std::min(ntiles, 256), 256, conv_tile_lds_bytes(g.Wd), st>>>(g);
+    } else if (p.conv) {
       dim3 grid(blocks_for(g.M, 128), g.N / 64);
       gemm_nt<T, 2, 1, true><<<grid, 256, 0, st>>>(g);
     } else if (g.N % 128 == 0 && g.M >= 2048) {
@@ -683,6 +695,7 @@ struct Runner {
   int forward(const float* theta, const float* y0, const double* tgrid, int N, const rampde_tableau* tab,
               const rampde_policy* pol, uint16_t* ckpt, float* yN) {
     if (use_fused) return forward_fused(theta, y0, tgrid, N, tab, pol, ckpt, yN);
+    if (p.conv) HIP_TRY(allow_conv_tile_lds());
     cast_weights(theta);
     const int naive = (pol->flags & RAMPDE_NAIVE_STATE) ? 1 : 0;
     const int incr_mode = ((pol->flags & RAMPDE_ROUND_INCREMENT) ? 1 : 0) | (naive ? 2 : 0);
@@ -944,6 +957,7 @@ struct Runner {
     const int detect = dynamic || scaling == RAMPDE_SCALE_NONE_SAFE;
     const int k_max = pol->k_max > 0 ? pol->k_max : 16;
     const int HW = p.H * p.Wd;
+    if (p.conv) HIP_TRY(allow_conv_tile_lds());
     if (conv_wgrad_applies(p)) {
       HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_wgrad_lds_bytes(p.Wd)));
