@@ -41,7 +41,7 @@ def oracle_velocity(cfg: wl.Config):
 
 
 def run_oracle(cfg: wl.Config, theta, y0, target, mode: str, scaling: str = None, k_max: int = 16,
-               flags: dict = None, grad_ys=None):
+               flags: dict = None, grad_ys=None, tgrid=None):
     """mode: 'emul' (round like the scheme, cfg.low) or 'f64'.  Returns a dict of fp64 arrays."""
     from oracle import rampde_oracle as orc
     vel = oracle_velocity(cfg)
@@ -49,7 +49,7 @@ def run_oracle(cfg: wl.Config, theta, y0, target, mode: str, scaling: str = None
     low = cfg.low if mode == "emul" else "f64"
     scaling = scaling or wl.resolve_scaling(cfg)
     pol = orc.Policy(low=low, scaling=scaling, k_max=k_max, **(flags or {}))
-    tgrid = cfg.tgrid()
+    tgrid = cfg.tgrid() if tgrid is None else np.asarray(tgrid, dtype=np.float64)
     y0f = y0.reshape(cfg.B, -1)
     yN, ckpt = orc.odeint_fwd(vel, theta, y0f, tgrid, tab, pol)
     yN32 = yN.astype(np.float32).reshape(cfg.state_shape)
@@ -106,14 +106,14 @@ def ckpt_to_boundary_layout(cfg: wl.Config, ckpt_np: np.ndarray) -> np.ndarray:
 
 
 def run_gpu(cfg: wl.Config, theta, y0, target, scaling: str = None, k_max: int = 16, flags: int = 0,
-            grad_ys=None, expect_error: bool = False, want_grad_t: bool = False):
+            grad_ys=None, expect_error: bool = False, want_grad_t: bool = False, tgrid=None):
     import torch
     from paper_2510_23498_amd import binding as rb
     vel, tab, pol = gpu_descriptors(cfg, scaling, k_max, flags)
     dev = torch.device("cuda:0")
     th = torch.from_numpy(theta).to(dev)
     y0d = torch.from_numpy(np.ascontiguousarray(y0)).to(dev)
-    tgrid = cfg.tgrid()
+    tgrid = cfg.tgrid() if tgrid is None else np.asarray(tgrid, dtype=np.float64)
     yN, ckpt = rb.rampde_odeint_fwd(vel, th, y0d, tgrid, tab, pol)
     torch.cuda.synchronize()
     yN_np = yN.cpu().numpy()

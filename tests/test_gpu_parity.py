@@ -238,3 +238,40 @@ def test_fp32_accumulator_beats_naive_low_precision_state_on_the_gpu():
             errs[name] = par.rel_err(yN.cpu().numpy(), ref)
         print(f"[case] naive vs scheme {low}: {errs}", flush=True)
         assert errs["naive"] > 10.0 * errs["scheme"], (low, errs)
+
+
+# ------------------------------------------------------------------ non-uniform time grids
+def _nonuniform_grid(N, t0=0.0, t1=1.0, seed=3):
+    w = 0.25 + wl.normals(seed, "grid", (N,), 1.0) ** 2       # step lengths differing by up to ~20x
+    return t0 + (t1 - t0) * np.concatenate([[0.0], np.cumsum(w) / np.sum(w)])
+
+
+@PATHS
+@pytest.mark.parametrize("low,scaling,group", [("f16", "dynamic", 0), ("bf16", "none", 64), ("bf16", "none", 3)])
+def test_nonuniform_time_grid(low, scaling, group, flags, monkeypatch):
+    # every step has its own h (and, with fixed scale, the groups-of-steps contraction rescales its
+    # running sums by h_i / h_{i+1} at the step boundaries); dL/dt rides along
+    if group:
+        monkeypatch.setenv("RAMPDE_STEP_GROUP", str(group))
+    cfg = wl.CONFIGS["cfg2"].with_(name=f"nonuni{low}{group}", B=150, N=10, widths=(20, 256, 256, 20), low=low)
+    tg = _nonuniform_grid(cfg.N)
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    print(f"[case] non-uniform grid {low} {scaling} group={group} flags={flags} h in [{np.diff(tg).min():.3f}, "
+          f"{np.diff(tg).max():.3f}]", flush=True)
+    gpu = par.run_gpu(cfg, theta, y0, target, scaling=scaling, flags=flags, tgrid=tg, want_grad_t=True)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul", scaling=scaling, tgrid=tg)
+    e = par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
+    et = par.rel_err(gpu["grad_t"], emu["grad_t"])
+    print("  vs emul:", {k: f"{v:.2e}" for k, v in e.items()}, f"dL/dt {et:.2e}", flush=True)
+    assert et <= par.TOL_EMUL
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
+
+
+def test_nonuniform_time_grid_conv():
+    cfg = wl.CONFIGS["cfg4"].with_(name="nonuniconv", B=2, N=4)
+    tg = _nonuniform_grid(cfg.N, seed=4)
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    gpu = par.run_gpu(cfg, theta, y0, target, tgrid=tg)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul", tgrid=tg)
+    par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
