@@ -72,6 +72,8 @@ struct FusedArgs {
   int wt_off;            // offset (floats) of the time-column weights in the LDS parameter block
   int nparam;            // floats in the LDS parameter block (multiple of 4)
   int k_in_lds;          // slopes / stage cotangents of a step are kept in LDS
+  int act_lds_off;       // adjoint kernel: > 0 = offset (16-bit elements) in LDS of a copy of the step's hidden
+                         // activations [s][L - 1][TM][ldp], which the tanh' factors then read instead of HBM
   int64_t R;
   int64_t stage_stride;  // R * dpad
   float A[kMaxStages * kMaxStages];
@@ -526,6 +528,7 @@ struct TileLds {
   lds_u16* buf0;    // [TM][ldp]
   lds_u16* buf1;    // [TM][ldp]
   lds_u16* kl;      // [s][TM][dpad] slopes or stage cotangents (when k_in_lds)
+  lds_u16* act;     // [s][L - 1][TM][ldp] hidden activations of the step (adjoint kernel, when they fit) or null
   int ldz, ldp;
   __device__ __forceinline__ TileLds(lds_u16* smem, const FusedArgs& g) {
     param = (lds_f32*)smem;
@@ -535,7 +538,9 @@ struct TileLds {
     buf0 = zbuf + TM * ldz;
     buf1 = buf0 + TM * ldp;
     kl = buf1 + TM * ldp;
+    act = g.act_lds_off > 0 ? smem + g.act_lds_off : nullptr;
   }
+  __device__ inline lds_u16* act_tile(int j, int l, int L) const { return act + (size_t)(j * (L - 1) + l) * TM * ldp; }
   // tile that layer / transposed pass number q (0 = first of its chain) reads and writes
   __device__ inline const lds_u16* in(int q) const { return q == 0 ? zbuf : (((q - 1) & 1) ? buf1 : buf0); }
   __device__ inline int ld_in(int q) const { return q == 0 ? ldz : ldp; }
@@ -598,6 +603,7 @@ __device__ __forceinline__ void hidden_layers(TileEngine<T, MT, NTL, NW, HP>& en
       for (int r = 0; r < 4; ++r) v[r] = tanh_fast(v[r]);
       const uint2 q = pack4<T>(v);
       lds_store_u2(&out[m * ldp + n], q);
+      if (KEEP && lds.act) lds_store_u2(&lds.act_tile(j, l, g.L)[m * ldp + n], q);
       if (KEEP && row0 + m < g.R) RAMPDE_STORE_G4(group4(goutT, g.ldk, kj + m, n), q);
     };
     auto nxt = [&]() {
@@ -944,7 +950,10 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
         const int64_t kj = (int64_t)j * g.Rp + row0;
         lds_u16* out = lds.out(q);
         const int ldp = lds.ldp;
+        // (a retry launch that skips the recomputation has no LDS copy: it reads the stored one)
+        const lds_u16* act_lds = (lds.act && !g.skip_recompute) ? lds.act_tile(j, l - 1, g.L) : nullptr;
         auto pre_act = [&](int n, int m) {
+                  if (act_lds) return lds_load_u2(&act_lds[m * ldp + n]);
                   return (row0 + m < g.R) ? *group4(actT, g.ldk, kj + m, n) : make_uint2(0u, 0u);
                 };
         auto epi_delta = [&](const f32x4& acc, uint2 pf, int, int, int n, int m) {

@@ -88,6 +88,7 @@ struct Plan {
   size_t gpart = 0;                 // ksplits copies of the gradient vector
   size_t ZT = 0, KBART = 0;
   size_t fm_stride = 0;             // distance between the sets of feature-group-major buffers
+  int act_lds_off = 0;              // adjoint kernel: LDS offset (16-bit elements) of the activation copy, 0 = none
   int nsets = 2;                    // sets: step i uses set i % nsets
   int step_group = 1;               // adjoint steps per kernel launch (> 1: fixed scale, no detection)
   std::vector<size_t> ACTT, DELTAT;
@@ -152,6 +153,7 @@ static bool build_layers(const rampde_velocity* vel, Plan& p, int hidden_pad = k
 
 static int wgrad_target_blocks();
 static int step_group_cap();
+static bool act_in_lds_enabled();
 static rampde_scaling resolve_scaling(const rampde_policy* pol);
 struct Plan;
 // the all-taps convolution weight-gradient kernel: image lines of a multiple of 8 pixels, at most
@@ -216,6 +218,14 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
       p.k_in_lds = lds_need(mt, true) <= lds_limit;
       p.overlap_wgrad = (mt == 1 && maxw <= 256);
       p.lds_bytes = lds_need(mt, p.k_in_lds);
+      if (is_backward && p.L > 1) {
+        // a copy of the step's hidden activations for the tanh' factors, when it still fits
+        const size_t act_bytes = (size_t)p.s * (p.L - 1) * 16 * mt * p.ldp * 2;
+        if (p.lds_bytes + act_bytes <= lds_limit && act_in_lds_enabled()) {
+          p.act_lds_off = (int)(p.lds_bytes / 2);
+          p.lds_bytes += act_bytes;
+        }
+      }
       for (auto& y : p.layers) {
         y.Wf = take((size_t)y.Npad * y.Kpad * 2);
         y.WTf = take((size_t)y.Npad * y.Kpad * 2);
@@ -324,6 +334,12 @@ static int step_group_cap() {
   const char* e = getenv("RAMPDE_STEP_GROUP");
   const int x = e ? atoi(e) : 0;
   return x > 0 ? x : kMaxWgradSteps;
+}
+
+// (environment RAMPDE_NO_ACT_LDS=1 keeps the activations out of LDS: for experiments)
+static bool act_in_lds_enabled() {
+  const char* e = getenv("RAMPDE_NO_ACT_LDS");
+  return !(e && atoi(e) > 0);
 }
 
 static bool conv_wgrad_applies(const Plan& p) { return p.conv && !p.fused && p.Wd % 8 == 0 && p.Wd <= 64 && p.R % 64 == 0; }
@@ -613,6 +629,7 @@ struct Runner {
     a.wt_off = p.wt_off;
     a.nparam = p.nparam;
     a.k_in_lds = p.k_in_lds ? 1 : 0;
+    a.act_lds_off = p.act_lds_off;
     a.L = p.L;
     a.s = p.s;
     a.N = N;
