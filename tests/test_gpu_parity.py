@@ -275,3 +275,17 @@ def test_nonuniform_time_grid_conv():
     emu = par.run_oracle(cfg, theta, y0, target, "emul", tgrid=tg)
     par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
     np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
+
+
+def test_fixed_scale_many_steps_default_group_length():
+    # 130 steps without an environment override: groups of 64, 64 and 2 steps
+    cfg = wl.CONFIGS["cfg2"].with_(name="grp130", B=48, N=130, widths=(8, 256, 256, 8), tableau="heun")
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    print(f"[case] {cfg.name}", flush=True)
+    gpu = par.run_gpu(cfg, theta, y0, target, scaling="none", want_grad_t=True)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul", scaling="none")
+    e = par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
+    et = par.rel_err(gpu["grad_t"], emu["grad_t"])
+    print("  vs emul:", {k: f"{v:.2e}" for k, v in e.items()}, f"dL/dt {et:.2e}", flush=True)
+    assert et <= par.TOL_EMUL
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
