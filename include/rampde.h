@@ -73,7 +73,7 @@ typedef enum {
 } rampde_status;
 
 /* policy.flags */
-#define RAMPDE_ROUND_INCREMENT 1u /* round sum_j b_j k_j to `low` before the fp32 add (literal Alg. 1 line 4) */
+#define RAMPDE_ROUND_INCREMENT 1u /* round sum_j b_j k_j to `low` before the fp32 add (the literal update line of Alg. 1) */
 #define RAMPDE_GROW_RAW_NORM 2u   /* growth test on the unscaled norm ||a|| <= 1/(2 u_L) (literal Alg. 2)     */
 #define RAMPDE_PER_LAYER_KERNELS 4u /* dense networks: use one kernel per layer instead of the row-tile-persistent kernels */
 #define RAMPDE_NAIVE_STATE 8u       /* comparison baseline, not the paper's scheme: the state y and the adjoint a are
@@ -123,7 +123,7 @@ size_t rampde_workspace_bytes(const rampde_velocity *vel, int64_t B, int N,
                               int is_backward);
 
 /* Forward pass, Algorithm 1.
- *   theta   dev, P fp32 (master weights; rounded to `low` once inside, Alg. 1 line 4)
+ *   theta   dev, P fp32 (master weights; rounded to `low` once inside: the weight rounding of Alg. 1)
  *   y0      dev, B*d fp32
  *   tgrid   host, N+1 strictly increasing fp64
  *   ckpt    dev, (N+1)*B*d elements of `low`, written: ckpt[i] = Q_low(y_i)
@@ -192,9 +192,9 @@ int rampde_version(void);
  *                     s slopes (2 each), writes y (4) and the checkpoint (2); adjoint update
  *                     reads a (4), s stage cotangents (2 each), writes a (4)).            */
 typedef enum {
-  RAMPDE_K_VELOCITY_GEMM = 0,  /* forward layers, recomputation and input-cotangent products (Alg. 1 line 4, eq. (vjp)) */
+  RAMPDE_K_VELOCITY_GEMM = 0,  /* forward layers, recomputation and input-cotangent products (Alg. 1: low-precision evaluation of Phi; eq. (vjp)) */
   RAMPDE_K_WGRAD_GEMM = 1,     /* parameter-gradient contractions over the batch (update of g, Sec. 3) */
-  RAMPDE_K_COMBINE_STORE = 2,  /* fp32 solution update + low-precision checkpoint store (Alg. 1 lines 5-6) */
+  RAMPDE_K_COMBINE_STORE = 2,  /* fp32 solution update + low-precision checkpoint store (Alg. 1: accumulate and store) */
   RAMPDE_K_ADJOINT_UPDATE = 3, /* fp32 adjoint update + max-norm (Alg. 2, update of a) */
   RAMPDE_K_FUSED_FORWARD = 4,  /* dense networks: whole forward pass of a row tile, all steps, one launch (Alg. 1);
                                   work = flops of all its layer contractions */

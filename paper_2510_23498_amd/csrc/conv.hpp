@@ -1,7 +1,7 @@
 // 3x3 zero-padded convolution (and its transpose: the same kernel with the flipped, transposed
 // weights) on channels-last rows, for at most 64 channels: the velocity evaluations, their
-// recomputation and the input-cotangent products of the convolutional velocity (paper Alg. 1 line 4,
-// eq. (vjp)) as one persistent kernel per call.
+// recomputation and the input-cotangent products of the convolutional velocity (paper Alg. 1, the
+// low-precision evaluation of Phi; eq. (vjp)) as one persistent kernel per call.
 //
 // A workgroup keeps the whole weight tensor of the layer (9 taps x 64 x 64, low precision) in LDS
 // for as long as it lives and walks over tiles of 256 pixels (whole image lines).  Per tile the
