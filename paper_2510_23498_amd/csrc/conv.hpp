@@ -34,8 +34,11 @@ inline size_t conv_tile_lds_bytes(int Wd) {
   return (size_t)(9 * 64 * CT_PITCH + lines * (Wd + 2) * CT_PITCH) * 2 + 16 * 64 * 4;
 }
 
-template <class T>
-__global__ __launch_bounds__(256) void conv3x3_tile(GemmNT g) {
+// NWV wavefronts per workgroup (4 or 8): a wavefront owns 256 / NWV pixels of the tile x all 64 output channels.
+template <class T, int NWV>
+__global__ __launch_bounds__(64 * NWV) void conv3x3_tile(GemmNT g) {
+  constexpr int NT = 64 * NWV;        // threads
+  constexpr int NB = 8 / NWV;         // 32-pixel blocks per wavefront (2 or 1)
   if (g.ctl && g.ctl->poison) return;
   extern __shared__ __attribute__((aligned(16))) uint16_t ct_smem[];
   const int W = g.Wd, H = g.H;
@@ -51,28 +54,28 @@ __global__ __launch_bounds__(256) void conv3x3_tile(GemmNT g) {
   // ---- once per workgroup: weights, zero halo columns, time-term table
   {
     // (all 18 loads of a thread are issued before the first is stored: one memory latency, not 18)
-    constexpr int NWC = 9 * 64 * 8 / 256;
+    constexpr int NWC = 9 * 64 * 8 / NT;
     u16x8 wr[NWC];
 #pragma unroll
     for (int i = 0; i < NWC; ++i) {
-      const int id = tid + 256 * i;
+      const int id = tid + NT * i;
       const int c8 = id & 7, co = (id >> 3) & 63, tap = id >> 9;
       wr[i] = *reinterpret_cast<const u16x8*>(g.W + (size_t)co * g.ldw + tap * 64 + c8 * 8);
     }
 #pragma unroll
     for (int i = 0; i < NWC; ++i) {
-      const int id = tid + 256 * i;
+      const int id = tid + NT * i;
       const int c8 = id & 7, co = (id >> 3) & 63, tap = id >> 9;
       *reinterpret_cast<u16x8*>(&sW[(tap * 64 + co) * CT_PITCH + c8 * 8]) = wr[i];
     }
   }
-  for (int id = tid; id < (PR + 2) * 2 * 8; id += 256) {
+  for (int id = tid; id < (PR + 2) * 2 * 8; id += NT) {
     const int c8 = id & 7, side = (id >> 3) & 1, ly = id >> 4;
     const u16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
     *reinterpret_cast<u16x8*>(&sIn[(ly * LW + (side ? W + 1 : 0)) * CT_PITCH + c8 * 8]) = z;
   }
   if (g.wt) {
-    for (int i = tid; i < 16 * 64; i += 256) {
+    for (int i = tid; i < 16 * 64; i += NT) {
       const int combo = i >> 6, n = i & 63;
       float sum = 0.f;
 #pragma unroll
@@ -88,13 +91,14 @@ __global__ __launch_bounds__(256) void conv3x3_tile(GemmNT g) {
 
   // ---- input chunks of a tile: chunk id -> (staged line ly, pixel x, 8 channels c8)
   const int nchunk = (PR + 2) * W * 8;
-  u16x8 reg[CT_MAXCHUNK];
+  constexpr int MAXC = CT_MAXCHUNK * 256 / NT;
+  u16x8 reg[MAXC];
   auto load_tile = [&](int t) __attribute__((always_inline)) {
     const int64_t row0 = (int64_t)t * CT_TILE;          // first pixel row of the tile
     const int y0 = (int)((row0 >> wshift) % H);         // its image line
 #pragma unroll
-    for (int i = 0; i < CT_MAXCHUNK; ++i) {
-      const int id = tid + 256 * i;
+    for (int i = 0; i < MAXC; ++i) {
+      const int id = tid + NT * i;
       u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
       if (id < nchunk) {
         const int c8 = id & 7, px = id >> 3;
@@ -108,8 +112,8 @@ __global__ __launch_bounds__(256) void conv3x3_tile(GemmNT g) {
   };
   auto store_tile = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < CT_MAXCHUNK; ++i) {
-      const int id = tid + 256 * i;
+    for (int i = 0; i < MAXC; ++i) {
+      const int id = tid + NT * i;
       if (id < nchunk) {
         const int c8 = id & 7, px = id >> 3;
         const int x = px & (W - 1), ly = px >> wshift;
@@ -122,10 +126,10 @@ __global__ __launch_bounds__(256) void conv3x3_tile(GemmNT g) {
 
   // this lane's two pixel columns (operand B) and weight rows (operand A)
   const int fk = (lane >> 5) * 8;
-  int in_base[2];
+  int in_base[NB];
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    const int p = wave * 64 + nb * 32 + (lane & 31);
+  for (int nb = 0; nb < NB; ++nb) {
+    const int p = wave * (32 * NB) + nb * 32 + (lane & 31);
     const int x = p & (W - 1), ly = p >> wshift;        // line within the tile, 0-based
     in_base[nb] = ((ly + 1) * LW + x + 1) * CT_PITCH + fk;
   }
@@ -139,26 +143,26 @@ __global__ __launch_bounds__(256) void conv3x3_tile(GemmNT g) {
     __syncthreads();
     if (t + (int)gridDim.x < ntiles) load_tile(t + gridDim.x);
 
-    f32x16 acc[2][2];
+    f32x16 acc[2][NB];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.f;
     // 36 k-blocks of 16 (9 taps x 64 channels); the fragments of block i + 1 are read from LDS
     // before the MFMAs of block i are issued (a workgroup is alone on its CU: nothing else hides
     // the LDS latency)
-    auto load_frags = [&](int it, u16x8 (&fa)[2], u16x8 (&fb)[2]) __attribute__((always_inline)) {
+    auto load_frags = [&](int it, u16x8 (&fa)[2], u16x8 (&fb)[NB]) __attribute__((always_inline)) {
       const int tap = it >> 2, kk = it & 3;
       const int shift = ((tap / 3 - 1) * LW + (tap % 3 - 1)) * CT_PITCH;
 #pragma unroll
       for (int a = 0; a < 2; ++a)
         fa[a] = *reinterpret_cast<const u16x8*>(&sW[(tap * 64 + a * 32) * CT_PITCH + w_base + kk * 16]);
 #pragma unroll
-      for (int b = 0; b < 2; ++b) fb[b] = *reinterpret_cast<const u16x8*>(&sIn[in_base[b] + shift + kk * 16]);
+      for (int b = 0; b < NB; ++b) fb[b] = *reinterpret_cast<const u16x8*>(&sIn[in_base[b] + shift + kk * 16]);
     };
-    u16x8 fa[2][2], fb[2][2];
+    u16x8 fa[2][2], fb[2][NB];
     load_frags(0, fa[0], fb[0]);
 #pragma unroll
     for (int it = 0; it < 36; ++it) {
@@ -167,15 +171,15 @@ __global__ __launch_bounds__(256) void conv3x3_tile(GemmNT g) {
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = Low<T>::mfma32(fa[it & 1][a], fb[it & 1][b], acc[a][b]);
+        for (int b = 0; b < NB; ++b) acc[a][b] = Low<T>::mfma32(fa[it & 1][a], fb[it & 1][b], acc[a][b]);
       __builtin_amdgcn_sched_barrier(0);
     }
 
     // ---- epilogue: accumulator row = output channel 8 (q / 4) + 4 (lane / 32) + q % 4 of block a,
     //      column = pixel lane % 32 of block b
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const int p = wave * 64 + b * 32 + (lane & 31);
+    for (int b = 0; b < NB; ++b) {
+      const int p = wave * (32 * NB) + b * 32 + (lane & 31);
       const int64_t m = (int64_t)t * CT_TILE + p;
       int combo = 0;
       if (g.wt) {

@@ -154,6 +154,7 @@ static bool build_layers(const rampde_velocity* vel, Plan& p, int hidden_pad = k
 static int wgrad_target_blocks();
 static int step_group_cap();
 static bool act_in_lds_enabled();
+static int conv_tile_waves();
 static rampde_scaling resolve_scaling(const rampde_policy* pol);
 struct Plan;
 // the all-taps convolution weight-gradient kernel: image lines of a multiple of 8 pixels, at most
@@ -342,6 +343,12 @@ static bool act_in_lds_enabled() {
   return !(e && atoi(e) > 0);
 }
 
+// wavefronts per workgroup of the convolution tile kernel (environment RAMPDE_CONV_WAVES=4: for experiments)
+static int conv_tile_waves() {
+  const char* e = getenv("RAMPDE_CONV_WAVES");
+  return (e && atoi(e) == 4) ? 4 : 8;
+}
+
 static bool conv_wgrad_applies(const Plan& p) { return p.conv && !p.fused && p.Wd % 8 == 0 && p.Wd <= 64 && p.R % 64 == 0; }
 
 static int check_common(const rampde_velocity* vel, const double* tgrid, int N, const rampde_tableau* tab,
@@ -487,7 +494,10 @@ struct Runner {
   // the convolution tile kernel keeps a layer's weights in LDS: more than the default limit
   hipError_t allow_conv_tile_lds() {
     if (p.Wd < 8 || p.Wd > 64) return hipSuccess;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3x3_tile<T>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3x3_tile<T, 4>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_tile_lds_bytes(p.Wd));
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3x3_tile<T, 8>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_tile_lds_bytes(p.Wd));
   }
 
@@ -496,7 +506,10 @@ struct Runner {
     if (p.conv && conv_tile_applies(g.Cpad, g.N, g.H, g.Wd, g.M)) {
       // persistent: one workgroup per CU (its LDS holds the layer's weights), tiles of 256 pixels
       const int ntiles = (int)(g.M / CT_TILE);
-      conv3x3_tile<T><<<std::min(ntiles, 256), 256, conv_tile_lds_bytes(g.Wd), st>>>(g);
+      if (conv_tile_waves() == 4)
+        conv3x3_tile<T, 4><<<std::min(ntiles, 256), 256, conv_tile_lds_bytes(g.Wd), st>>>(g);
+      else
+        conv3x3_tile<T, 8><<<std::min(ntiles, 256), 512, conv_tile_lds_bytes(g.Wd), st>>>(g);
     } else if (p.conv) {
       dim3 grid(blocks_for(g.M, 128), g.N / 64);
       gemm_nt<T, 2, 1, true><<<grid, 256, 0, st>>>(g);
