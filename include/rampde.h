@@ -117,7 +117,12 @@ typedef struct {
 /* Number of parameters P implied by a velocity descriptor (0 if invalid). */
 int64_t rampde_num_params(const rampde_velocity *vel);
 
-/* Bytes of device workspace needed by fwd (is_backward = 0) or bwd (= 1). 0 if invalid. */
+/* Bytes of device workspace needed by fwd (is_backward = 0) or bwd (= 1). 0 if invalid.
+ * The size depends on the policy: with a fixed scale (SCALE_NONE) the backward pass of a dense
+ * network keeps the low-precision stage inputs, activations and cotangents of a whole group of
+ * steps (up to 64 steps or about 4 GiB) so that their parameter gradients are one contraction;
+ * with overflow detection it keeps those of two steps.  Pass the same policy to the query and
+ * to the call. */
 size_t rampde_workspace_bytes(const rampde_velocity *vel, int64_t B, int N,
                               const rampde_tableau *tab, const rampde_policy *pol,
                               int is_backward);
