@@ -149,15 +149,15 @@ __global__ void ctl_reset(Ctl* ctl, float* scale_hist, int N) {
 // naive_low: 0, or the low precision (1 fp16, 2 bf16) in which the naive baseline keeps the adjoint
 __global__ void init_adjoint(const float* __restrict__ gyN, const float* __restrict__ gys_last,
                              float* __restrict__ a, int64_t n, Ctl* ctl, int copy, int naive_low) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  unsigned bits = 0;
-  if (i < n) {
+  unsigned bits = 0;  // (grid-stride: one atomic per workgroup, and few workgroups)
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
     float v = gyN[i];
     if (gys_last) v += gys_last[i];
     if (naive_low == 1) v = Low<F16>::to_f32(Low<F16>::from_f32(v));
     if (naive_low == 2) v = Low<BF16>::to_f32(Low<BF16>::from_f32(v));
     if (copy || gys_last || naive_low) a[i] = v;
-    bits = __builtin_bit_cast(unsigned, fabsf(v));
+    const unsigned bb = __builtin_bit_cast(unsigned, fabsf(v));
+    bits = bb > bits ? bb : bits;
   }
   block_amax(bits, &ctl->amax_bits);
 }

@@ -1053,9 +1053,9 @@ struct Runner {
       a = f32(p.a_rows);
       gys_rows = f32(p.gys_rows);
       nchw_to_rows<<<blocks_for(p.n, 256), 256, 0, st>>>(grad_yN, a, p.R, p.d, HW);
-      init_adjoint<<<blocks_for(p.n, 256), 256, 0, st>>>(a, gys_at(N), a, p.n, ctl, 0, naive_low);
+      init_adjoint<<<stream_blocks(p.n, 512), 256, 0, st>>>(a, gys_at(N), a, p.n, ctl, 0, naive_low);
     } else {
-      init_adjoint<<<blocks_for(p.n, 256), 256, 0, st>>>(grad_yN, gys_at(N), a, p.n, ctl, 1, naive_low);
+      init_adjoint<<<stream_blocks(p.n, 512), 256, 0, st>>>(grad_yN, gys_at(N), a, p.n, ctl, 1, naive_low);
     }
     scale_init<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), N, Low<T>::p_bits, dynamic);
 
