@@ -24,6 +24,12 @@ hipError_t launch_kernel(Kern kern, int waves, const FusedLaunch& l, const Fused
 
 template <class T, int MT, int NTL>
 hipError_t pick_kernel(const FusedLaunch& l, const FusedArgs& a) {
+  // forward pass of 16-row tiles: 16 wavefronts (four per SIMD, under 128 registers each) hide more of
+  // the per-pass latencies than 8; the adjoint kernel does not fit that register budget
+  if constexpr (MT == 1) {
+    if (!l.adjoint && l.waves == 16)
+      return launch_kernel(mlp_forward_fused<T, MT, NTL, 16, RAMPDE_INST_HP>, 16, l, a);
+  }
   if (l.adjoint) {
     // (the host caps the adjoint's row tile at 32 rows: 64-row tiles spill; several steps per launch
     // only with 8 wavefronts)

@@ -675,6 +675,7 @@ struct Runner {
     FusedLaunch l{};
     l.adjoint = adjoint ? 1 : 0;
     l.waves = p.overlap_wgrad ? 4 : 8;
+    if (p.MT == 1 && !adjoint) l.waves = 16;
     l.bf16 = std::is_same<T, BF16>::value ? 1 : 0;
     l.MT = p.MT;
     l.NTL = p.dpad / 64;
