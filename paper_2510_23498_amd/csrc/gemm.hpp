@@ -384,7 +384,9 @@ constexpr int CW_PA = BK + 8;   // LDS pitch of the cotangent copies (elements)
 inline size_t conv_wgrad_lds_bytes(int Wd) { return (size_t)(3 * 64 * CW_PA + 3 * 64 * (64 + 2 * Wd + 8)) * 2; }
 
 // TS: also form the time cotangent sums for the time-grid gradient (g.tpart, g.wt non-null).
-template <class T, bool TS>
+// MAXI: loader items per thread: 2 cover image lines of up to 32 pixels (and keep the kernel free of
+// register spills), 3 are needed for lines of 64.
+template <class T, bool TS, int MAXI>
 __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
   if (g.ctl->poison) return;
   extern __shared__ __attribute__((aligned(16))) uint16_t cw_smem[];
@@ -401,7 +403,6 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
 
   // work items of the transposing loaders: 8 rows x 8 channels each.  Items [0, 3 nXb): input
   // copies (copy, 8-row block, channel group); then 64 items of the cotangent tile.
-  constexpr int MAXI = 3;
   const int nXb = XR;  // (XR / 8) row blocks x 8 channel groups
   const int nI = 3 * nXb + 64;
   bool it_on[MAXI], it_isA[MAXI];

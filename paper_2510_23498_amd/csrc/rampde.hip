@@ -879,10 +879,15 @@ struct Runner {
         c.tpart = tpart_i;
         dim3 cgrid(y.Npad / 64, y.Kpad / 64, y.cw_splits);
         TimeScope ts(RAMPDE_K_WGRAD_GEMM, 2.0 * rows * (double)y.Npad * y.Kpad * 9, st);
-        if (c.tpart && c.wt)
-          conv_wgrad<T, true><<<cgrid, 256, conv_wgrad_lds_bytes(p.Wd), st>>>(c);
-        else
-          conv_wgrad<T, false><<<cgrid, 256, conv_wgrad_lds_bytes(p.Wd), st>>>(c);
+        const size_t lds = conv_wgrad_lds_bytes(p.Wd);
+        const bool tsum = c.tpart && c.wt;
+        if (p.Wd <= 32) {
+          if (tsum) conv_wgrad<T, true, 2><<<cgrid, 256, lds, st>>>(c);
+          else conv_wgrad<T, false, 2><<<cgrid, 256, lds, st>>>(c);
+        } else {
+          if (tsum) conv_wgrad<T, true, 3><<<cgrid, 256, lds, st>>>(c);
+          else conv_wgrad<T, false, 3><<<cgrid, 256, lds, st>>>(c);
+        }
         continue;  // (bias and time-channel gradients included)
       } else {
         // split the contraction so that about 1024 workgroups are in flight
@@ -990,10 +995,15 @@ struct Runner {
     const int HW = p.H * p.Wd;
     if (p.conv) HIP_TRY(allow_conv_tile_lds());
     if (conv_wgrad_applies(p)) {
-      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_wgrad_lds_bytes(p.Wd)));
-      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_wgrad_lds_bytes(p.Wd)));
+      const int lds = (int)conv_wgrad_lds_bytes(p.Wd);
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false, 2>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, true, 2>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false, 3>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, true, 3>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     }
     ctl_reset<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), N);
     if (conv_wgrad_applies(p))
