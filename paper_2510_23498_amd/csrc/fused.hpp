@@ -55,7 +55,10 @@ __device__ inline float4 lds_load_f4(const lds_f32* p) {
 typedef __attribute__((address_space(1))) u16x8 glb_u16x8;  // weight fragments: always global memory
 
 constexpr int kMaxLayers = 8;
-constexpr int PD = 4;  // k-blocks (of 32) of weight fragments kept in flight per wavefront
+// k-blocks (of 32) of weight fragments kept in flight per wavefront.  Four, except for hidden width
+// 512, where the adjoint kernel of 32-row tiles would spill registers (two then measure faster).
+template <int HP>
+constexpr int kPipelineDepth = (HP == 512) ? 2 : 4;
 
 struct FusedLayer {
   const u16x8* Wf;    // forward fragments  [Kpad/32][Npad/16][64 lanes]: lane -> W[nt*16 + lane%16][kb*32 + (lane/16)*8 + 0..7]
@@ -277,7 +280,7 @@ struct PassDesc {
 // KBC / NTC > 0: the pass's k-blocks and column tiles are compile-time constants (kernels
 // specialised for a network shape): the whole pipeline unrolls into straight-line code with
 // immediate offsets.  KBC = 0: both are taken from the descriptor at run time.
-template <int NTG, int RW, int KBC, int NTC>
+template <int PD, int NTG, int RW, int KBC, int NTC>
 __device__ inline void ring_preload(u16x8 (&ring)[PD][RW], const PassDesc& p, int nt0, int lane) {
   const glb_u16x8* base = p.Wf + (size_t)nt0 * 64 + lane;
   if constexpr (KBC > 0) {
@@ -299,7 +302,7 @@ __device__ inline void ring_preload(u16x8 (&ring)[PD][RW], const PassDesc& p, in
   }
 }
 
-template <class T, int MT, int NTG, int RW, int KBC, int NTC>
+template <class T, int PD, int MT, int NTG, int RW, int KBC, int NTC>
 __device__ inline void tile_mma(f32x4 (&acc)[RW][MT], u16x8 (&ring)[PD][RW], const PassDesc& p, int nt0,
                                 const lds_u16* in, int ldp, int lane) {
   static_assert(PD % 2 == 0, "activation fragments are double-buffered by k-block parity");
@@ -439,6 +442,7 @@ template <class T, int MT, int NTL, int NW, int HP>
 struct TileEngine {
   using Sh = Shape<NTL, NW, HP>;
   static constexpr int NTH = Sh::NTH, NTS = Sh::NTS, ACTIVE = Sh::ACTIVE, RW = Sh::RW;
+  static constexpr int PD = kPipelineDepth<HP>;
   u16x8 ring[PD][RW];
   int lane, wave;
 
@@ -451,12 +455,12 @@ struct TileEngine {
   __device__ inline void preload_hidden(const PassDesc& p, int g) {
     constexpr int KBC = FROM_STATE ? Sh::KB_S : Sh::KB_H;
     const int ntw = HP > 0 ? Sh::NT_H / NW : p.NT16 / NW;
-    ring_preload<NTH, RW, KBC, Sh::NT_H>(ring, p, wave * ntw + g * NTH, lane);
+    ring_preload<PD, NTH, RW, KBC, Sh::NT_H>(ring, p, wave * ntw + g * NTH, lane);
   }
   template <bool FROM_STATE>
   __device__ inline void preload_state(const PassDesc& p) {
     constexpr int KBC = FROM_STATE ? Sh::KB_S : Sh::KB_H;
-    if (state_wave()) ring_preload<NTS, RW, KBC, Sh::NT_S>(ring, p, wave * NTS, lane);
+    if (state_wave()) ring_preload<PD, NTS, RW, KBC, Sh::NT_S>(ring, p, wave * NTS, lane);
   }
 
   template <int NTG, int KBC, int NTC, class Pre, class Epi, class Nxt>
@@ -469,7 +473,7 @@ struct TileEngine {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) pf[nt][mt] = pre((nt0 + nt) * 16 + lq * 4, mt * 16 + lm);
     f32x4 acc[RW][MT];
-    tile_mma<T, MT, NTG, RW, KBC, NTC>(acc, ring, p, nt0, in, ld_in, lane);
+    tile_mma<T, PD, MT, NTG, RW, KBC, NTC>(acc, ring, p, nt0, in, ld_in, lane);
     nxt();
     if (sync_before_epi) __syncthreads();
 #pragma unroll
