@@ -380,8 +380,12 @@ struct ConvWgrad {
   float cs[kMaxStages];         // c_j
 };
 
-constexpr int CW_PA = BK + 8;   // LDS pitch of the cotangent copies (elements)
-inline size_t conv_wgrad_lds_bytes(int Wd) { return (size_t)(3 * 64 * CW_PA + 3 * 64 * (64 + 2 * Wd + 8)) * 2; }
+constexpr int CW_KS = 128;          // pixels (rows) per k-step
+constexpr int CW_PA = CW_KS + 8;    // LDS pitch of the cotangent copies (elements)
+// loader items (8 rows x 8 channels) per thread for image lines of up to 32 / up to 64 pixels
+constexpr int CW_MAXI_LO = (3 * (CW_KS + 64) + CW_KS + 255) / 256;
+constexpr int CW_MAXI_HI = (3 * (CW_KS + 128) + CW_KS + 255) / 256;
+inline size_t conv_wgrad_lds_bytes(int Wd) { return (size_t)(3 * 64 * CW_PA + 3 * 64 * (CW_KS + 2 * Wd + 8)) * 2; }
 
 // TS: also form the time cotangent sums for the time-grid gradient (g.tpart, g.wt non-null).
 // MAXI: loader items per thread: 2 cover image lines of up to 32 pixels (and keep the kernel free of
@@ -390,7 +394,7 @@ template <class T, bool TS, int MAXI>
 __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
   if (g.ctl->poison) return;
   extern __shared__ __attribute__((aligned(16))) uint16_t cw_smem[];
-  const int W = g.Wd, XR = 64 + 2 * W, PX = XR + 8;
+  const int W = g.Wd, XR = CW_KS + 2 * W, PX = XR + 8;
   uint16_t* sA = cw_smem;                 // [3 (dy)][64 co][CW_PA]
   uint16_t* sX = cw_smem + 3 * 64 * CW_PA;  // [3 (dx)][64 ci][PX]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -401,73 +405,115 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
   if (k_end > g.rows) k_end = g.rows;
   if (k_begin >= k_end) return;
 
-  // work items of the transposing loaders: 8 rows x 8 channels each.  Items [0, 3 nXb): input
-  // copies (copy, 8-row block, channel group); then 64 items of the cotangent tile.
+  // work items of the transposing loaders: 8 rows x 8 channels each.  Items [0, CW_KS): the
+  // cotangent tile (8-row block, channel group) - only a thread's first item can be one, and it is
+  // one for whole wavefronts; then 3 XR items of the input copies (copy, 8-row block, channel group).
+  // The pixel coordinates of an item (x of its first row; image line y for cotangent items) are
+  // stepped from k-step to k-step: no division inside the loop.
   const int nXb = XR;  // (XR / 8) row blocks x 8 channel groups
-  const int nI = 3 * nXb + 64;
-  bool it_on[MAXI], it_isA[MAXI];
-  int it_rel[MAXI], it_dx[MAXI], it_fg[MAXI], it_dst[MAXI];
+  const int nI = 3 * nXb + CW_KS;
+  const int ksx = CW_KS % W, dlm = (CW_KS / W) % g.H;
+  bool it_on[MAXI];
+  int it_rel[MAXI], it_dx[MAXI], it_fg[MAXI], it_dst[MAXI], it_x[MAXI];
+  const bool isA0 = tid < CW_KS;
+  int yA = 0;
 #pragma unroll
   for (int j = 0; j < MAXI; ++j) {
     const int id = tid + 256 * j;
     it_on[j] = id < nI;
-    it_isA[j] = id >= 3 * nXb;
-    if (!it_isA[j]) {
-      const int v = id / nXb, r = id - v * nXb;
-      it_fg[j] = r & 7;
-      it_rel[j] = -W + (r >> 3) * 8;
-      it_dx[j] = v - 1;
-      it_dst[j] = (v * 64 + it_fg[j] * 8) * PX + (r >> 3) * 8;
-    } else {
-      const int r = id - 3 * nXb;
-      it_fg[j] = r & 7;
-      it_rel[j] = (r >> 3) * 8;
+    // (consecutive lanes take consecutive 8-row blocks of one channel group: their 16-byte LDS
+    // writes then fall into different banks; with the channel group in the low lane bits they
+    // would all hit the same ones)
+    if (j == 0 && isA0) {
+      const int rb = id & (CW_KS / 8 - 1);
+      it_fg[j] = id / (CW_KS / 8);
+      it_rel[j] = rb * 8;
       it_dx[j] = 0;
-      it_dst[j] = it_fg[j] * 8 * CW_PA + (r >> 3) * 8;
+      it_dst[j] = it_fg[j] * 8 * CW_PA + rb * 8;
+      yA = (int)(((k_begin + it_rel[j]) / W) % g.H);
+    } else {
+      const int nrb = XR / 8;
+      const int idx = it_on[j] ? id - CW_KS : 0;
+      const int v = idx / nXb, r = idx - v * nXb;
+      const int rb = r % nrb;
+      it_fg[j] = r / nrb;
+      it_rel[j] = -W + rb * 8;
+      it_dx[j] = v - 1;
+      it_dst[j] = (v * 64 + it_fg[j] * 8) * PX + rb * 8;
     }
+    it_x[j] = (int)((k_begin + W + it_rel[j]) % W);
   }
+  auto advance_items = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < MAXI; ++j) {
+      int x = it_x[j] + ksx;
+      const int carry = x >= W ? 1 : 0;
+      it_x[j] = x - (carry ? W : 0);
+      if (j == 0) {
+        const int y = yA + dlm + carry;
+        yA = y >= g.H ? y - g.H : y;
+      }
+    }
+  };
   u16x8 reg[MAXI][8];
-  auto load_items = [&](int64_t k0) {
+  auto load_items = [&](int64_t k0) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < MAXI; ++j) {
       if (!it_on[j]) continue;
       const int64_t qb = k0 + it_rel[j];
-      if (it_isA[j]) {
+      if (j == 0 && isA0) {
+        const uint16_t* src = g.A + (size_t)qb * g.lda + a0 + it_fg[j] * 8;
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-          reg[j][i] = *reinterpret_cast<const u16x8*>(g.A + (size_t)(qb + i) * g.lda + a0 + it_fg[j] * 8);
+        for (int i = 0; i < 8; ++i) reg[j][i] = *reinterpret_cast<const u16x8*>(src + (size_t)i * g.lda);
       } else {
         const bool inside = qb >= 0 && qb < g.rows;
-        const int xq0 = inside ? (int)(qb % W) : 0;
+        const uint16_t* src = g.B + ((int64_t)qb + it_dx[j]) * g.ldb + b0 + it_fg[j] * 8;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          const int xi = xq0 + i + it_dx[j];
-          u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-          if (inside && xi >= 0 && xi < W)
-            v = *reinterpret_cast<const u16x8*>(g.B + (size_t)(qb + i + it_dx[j]) * g.ldb + b0 + it_fg[j] * 8);
-          reg[j][i] = v;
+          const int xi = it_x[j] + i + it_dx[j];
+          // (branch-free: a row that falls off the image line is read from a valid address here and
+          // zeroed when it is written to LDS)
+          const bool ok = inside && xi >= 0 && xi < W;
+          reg[j][i] = *reinterpret_cast<const u16x8*>(ok ? src + (int64_t)i * g.ldb : g.B);
         }
       }
     }
   };
-  auto store_items = [&](int64_t k0) {
+  auto store_items = [&](int64_t k0) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < MAXI; ++j) {
       if (!it_on[j]) continue;
-      int y = 0;
-      if (it_isA[j]) y = (int)(((k0 + it_rel[j]) / W) % g.H);
+      if (j == 0 && isA0) {
+        // copies for dy = -1 / +1: rows of the first / last image line zeroed
+        const uint16_t m_top = yA == 0 ? 0 : 0xffff, m_bot = yA == g.H - 1 ? 0 : 0xffff;
 #pragma unroll
-      for (int f = 0; f < 8; ++f) {
-        u16x8 o;
+        for (int f = 0; f < 8; ++f) {
+          u16x8 o, ot, ob;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = reg[j][i][f];
-        if (it_isA[j]) {
-          const u16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+          for (int i = 0; i < 8; ++i) {
+            o[i] = reg[j][i][f];
+            ot[i] = o[i] & m_top;
+            ob[i] = o[i] & m_bot;
+          }
           uint16_t* d = sA + it_dst[j] + f * CW_PA;
-          *reinterpret_cast<u16x8*>(d) = (y == 0) ? z : o;                        // dy = -1
-          *reinterpret_cast<u16x8*>(d + 64 * CW_PA) = o;                          // dy = 0
-          *reinterpret_cast<u16x8*>(d + 2 * 64 * CW_PA) = (y == g.H - 1) ? z : o;  // dy = +1
-        } else {
+          *reinterpret_cast<u16x8*>(d) = ot;
+          *reinterpret_cast<u16x8*>(d + 64 * CW_PA) = o;
+          *reinterpret_cast<u16x8*>(d + 2 * 64 * CW_PA) = ob;
+        }
+      } else {
+        const int64_t qb = k0 + it_rel[j];
+        const bool inside = qb >= 0 && qb < g.rows;
+        uint16_t m[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int xi = it_x[j] + i + it_dx[j];
+          m[i] = (inside && xi >= 0 && xi < W) ? 0xffff : 0;
+        }
+#pragma unroll
+        for (int f = 0; f < 8; ++f) {
+          u16x8 o;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) o[i] = reg[j][i][f] & m[i];
           *reinterpret_cast<u16x8*>(sX + it_dst[j] + f * PX) = o;
         }
       }
@@ -486,16 +532,24 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
   float sum_b = 0.f, sum_t[9], sum_1[9], sum_c[9];  // tau-, un- and c_j-weighted tap sums
 #pragma unroll
   for (int t = 0; t < 9; ++t) sum_t[t] = sum_1[t] = sum_c[t] = 0.f;
+  // sums: thread -> (channel tid / 4, quarter tid % 4 of the k-step's rows, in 8-row blocks); a block
+  // lies in one image line: only its first row can have x = 0, only its last x = W - 1
+  int sx[CW_KS / 32];
+#pragma unroll
+  for (int b = 0; b < CW_KS / 32; ++b) sx[b] = (int)((k_begin + (tid & 3) * (CW_KS / 4) + b * 8) % W);
+  int jst = (int)(k_begin / g.R);
+  int64_t stage_end = (int64_t)(jst + 1) * g.R;
   load_items(k_begin);
-  for (int64_t k0 = k_begin; k0 < k_end; k0 += 64) {
+  for (int64_t k0 = k_begin; k0 < k_end; k0 += CW_KS) {
     store_items(k0);
     __syncthreads();
-    if (k0 + 64 < k_end) load_items(k0 + 64);
     if (sums) {
-      // thread -> (channel tid / 4, quarter tid % 4 of the 64 rows = two 8-row blocks); a block lies in
-      // one image line: only its first row can have x = 0, only its last x = W - 1
       const int co = tid >> 2, qt = tid & 3;
-      const int j = (int)(k0 / g.R);
+      if (k0 >= stage_end) {
+        ++jst;
+        stage_end += g.R;
+      }
+      const int j = jst;
       float tau = 0.f, cj = 0.f;
 #pragma unroll
       for (int q = 0; q < kMaxStages; ++q) {
@@ -503,9 +557,10 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
         cj = (q == j) ? g.cs[q] : cj;
       }
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const int kq = qt * 16 + b * 8;
-        const int xq0 = (int)((k0 + kq) % W);
+      for (int b = 0; b < CW_KS / 32; ++b) {
+        const int kq = qt * (CW_KS / 4) + b * 8;
+        const int xq0 = sx[b];
+        sx[b] = xq0 + ksx >= W ? xq0 + ksx - W : xq0 + ksx;
 #pragma unroll
         for (int dyv = 0; dyv < 3; ++dyv) {
           const u16x8 v = *reinterpret_cast<const u16x8*>(&sA[(dyv * 64 + co) * CW_PA + kq]);
@@ -531,20 +586,33 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
         }
       }
     }
+    // the next k-step's rows are fetched into registers while this one is multiplied
+    advance_items();
+    if (k0 + CW_KS < k_end) load_items(k0 + CW_KS);
+    // (kk, dy) steps of 3 MFMAs; the 4 operand fragments of step i + 2 are read from LDS before the
+    // MFMAs of step i are issued (one wavefront per SIMD: nothing else hides the LDS latency)
+    {
+      constexpr int NST = (CW_KS / 16) * 3;
+      auto load_frags = [&](int st, u16x8& fa, u16x8(&fb)[3]) __attribute__((always_inline)) {
+        const int kk = st / 3, dyv = st % 3;
+        fa = *reinterpret_cast<const u16x8*>(&sA[(dyv * 64 + wm * 32 + frow) * CW_PA + kk * 16 + fk]);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      u16x8 fa[3];
+        for (int dxv = 0; dxv < 3; ++dxv)
+          fb[dxv] = *reinterpret_cast<const u16x8*>(&sX[(dxv * 64 + wn * 32 + frow) * PX + dyv * W + kk * 16 + fk]);
+      };
+      u16x8 fa[3], fb[3][3];
+      load_frags(0, fa[0], fb[0]);
+      load_frags(1, fa[1], fb[1]);
 #pragma unroll
-      for (int dyv = 0; dyv < 3; ++dyv)
-        fa[dyv] = *reinterpret_cast<const u16x8*>(&sA[(dyv * 64 + wm * 32 + frow) * CW_PA + kk * 16 + fk]);
+      for (int st = 0; st < NST; ++st) {
+        if (st + 2 < NST) load_frags(st + 2, fa[(st + 2) % 3], fb[(st + 2) % 3]);
+        __builtin_amdgcn_sched_barrier(0);
+        const int dyv = st % 3;
 #pragma unroll
-      for (int dyv = 0; dyv < 3; ++dyv)
-#pragma unroll
-        for (int dxv = 0; dxv < 3; ++dxv) {
-          const u16x8 fb =
-              *reinterpret_cast<const u16x8*>(&sX[(dxv * 64 + wn * 32 + frow) * PX + dyv * W + kk * 16 + fk]);
-          acc[dyv * 3 + dxv] = Low<T>::mfma32(fa[dyv], fb, acc[dyv * 3 + dxv]);
-        }
+        for (int dxv = 0; dxv < 3; ++dxv)
+          acc[dyv * 3 + dxv] = Low<T>::mfma32(fa[st % 3], fb[st % 3][dxv], acc[dyv * 3 + dxv]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     __syncthreads();
   }

@@ -315,8 +315,8 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
         for (auto& y : p.layers) {
           const int tiles = (y.Npad / 64) * (y.Kpad / 64);
           const int64_t want = std::max(1, 512 / tiles);
-          int64_t per = ((rows + want - 1) / want + 63) / 64 * 64;
-          if (per < 4 * 64) per = 4 * 64;
+          int64_t per = ((rows + want - 1) / want + CW_KS - 1) / CW_KS * CW_KS;
+          if (per < 4 * CW_KS) per = 4 * CW_KS;
           y.cw_per = (int)per;
           y.cw_splits = (int)((rows + per - 1) / per);
           y.cw_part = take(sizeof(float) * (size_t)y.cw_splits * tiles * 9 * 4096);
@@ -349,7 +349,7 @@ static int conv_tile_waves() {
   return (e && atoi(e) == 4) ? 4 : 8;
 }
 
-static bool conv_wgrad_applies(const Plan& p) { return p.conv && !p.fused && p.Wd % 8 == 0 && p.Wd <= 64 && p.R % 64 == 0; }
+static bool conv_wgrad_applies(const Plan& p) { return p.conv && !p.fused && p.Wd % 8 == 0 && p.Wd <= 64 && p.R % CW_KS == 0; }
 
 static int check_common(const rampde_velocity* vel, const double* tgrid, int N, const rampde_tableau* tab,
                         const rampde_policy* pol) {
@@ -882,11 +882,11 @@ struct Runner {
         const size_t lds = conv_wgrad_lds_bytes(p.Wd);
         const bool tsum = c.tpart && c.wt;
         if (p.Wd <= 32) {
-          if (tsum) conv_wgrad<T, true, 2><<<cgrid, 256, lds, st>>>(c);
-          else conv_wgrad<T, false, 2><<<cgrid, 256, lds, st>>>(c);
+          if (tsum) conv_wgrad<T, true, CW_MAXI_LO><<<cgrid, 256, lds, st>>>(c);
+          else conv_wgrad<T, false, CW_MAXI_LO><<<cgrid, 256, lds, st>>>(c);
         } else {
-          if (tsum) conv_wgrad<T, true, 3><<<cgrid, 256, lds, st>>>(c);
-          else conv_wgrad<T, false, 3><<<cgrid, 256, lds, st>>>(c);
+          if (tsum) conv_wgrad<T, true, CW_MAXI_HI><<<cgrid, 256, lds, st>>>(c);
+          else conv_wgrad<T, false, CW_MAXI_HI><<<cgrid, 256, lds, st>>>(c);
         }
         continue;  // (bias and time-channel gradients included)
       } else {
@@ -996,13 +996,13 @@ struct Runner {
     if (p.conv) HIP_TRY(allow_conv_tile_lds());
     if (conv_wgrad_applies(p)) {
       const int lds = (int)conv_wgrad_lds_bytes(p.Wd);
-      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false, 2>),
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false, CW_MAXI_LO>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, true, 2>),
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, true, CW_MAXI_LO>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false, 3>),
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false, CW_MAXI_HI>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, true, 3>),
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, true, CW_MAXI_HI>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     }
     ctl_reset<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), N);
