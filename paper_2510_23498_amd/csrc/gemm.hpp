@@ -360,15 +360,16 @@ struct ConvWgrad {
   const uint16_t* B; int ldb;   // [rows, >= 64 gridDim.y] the layer's input
   int64_t rows;                 // stages * batch * H * W
   int rows_per_split;           // multiple of 64
-  float* part;                  // [gridDim.z][gridDim.x][gridDim.y][9 taps][64 co][64 ci] fp32: the private
+  float* part;                  // [gridDim.z][gridDim.x][gridDim.y][CW_SLOT] fp32 (tap blocks in register order): the private
                                 // accumulators of every (K-chunk, channel block), summed at the end of the pass
   float h;                      // scale = h / ctl->S_step
   const Ctl* ctl;
   int H, Wd;
   // bias and time-channel gradients (folded into the workgroups of the first input-channel block):
   //   db[co] += scale * sum_k delta[k][co];   dwt[co][tap] += scale * sum_k tau(k) delta[k][co] * [tap inside]
-  float* gb;                    // db, or null
-  float* gwt; int wt_stride;    // dwt: element (co, tap) at co * wt_stride + tap, or null
+  // (accumulated in the tail of the private copy: atomics on these few addresses from every workgroup
+  // would serialise in the L2)
+  bool want_sums;
   int Na;                       // valid output channels
   int64_t R;                    // rows per stage (a multiple of 64)
   float taus[kMaxStages];       // stage times
@@ -381,6 +382,8 @@ struct ConvWgrad {
 };
 
 constexpr int CW_KS = 128;          // pixels (rows) per k-step
+constexpr int CW_SLOT = 9 * 4096 + 64 * 16;  // floats of a workgroup's private copy: 9 tap blocks, then per output
+                                             // channel [db, dwt[9 taps], 6 unused]
 constexpr int CW_PA = CW_KS + 8;    // LDS pitch of the cotangent copies (elements)
 // loader items (8 rows x 8 channels) per thread for image lines of up to 32 / up to 64 pixels
 constexpr int CW_MAXI_LO = (3 * (CW_KS + 64) + CW_KS + 255) / 256;
@@ -527,7 +530,7 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
     for (int q = 0; q < 16; ++q) acc[t][q] = 0.f;
 
   const int frow = lane & 31, fk = (lane >> 5) * 8;
-  const bool sums = blockIdx.y == 0 && g.gb != nullptr;
+  const bool sums = blockIdx.y == 0 && g.want_sums;
   constexpr bool tsums = TS;
   float sum_b = 0.f, sum_t[9], sum_1[9], sum_c[9];  // tau-, un- and c_j-weighted tap sums
 #pragma unroll
@@ -556,14 +559,21 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
         tau = (q == j) ? g.taus[q] : tau;
         cj = (q == j) ? g.cs[q] : cj;
       }
+      // (all reads first: the loader registers are free at this point)
+      u16x8 sv[CW_KS / 32][3];
+#pragma unroll
+      for (int b = 0; b < CW_KS / 32; ++b)
+#pragma unroll
+        for (int dyv = 0; dyv < 3; ++dyv)
+          sv[b][dyv] = *reinterpret_cast<const u16x8*>(&sA[(dyv * 64 + co) * CW_PA + qt * (CW_KS / 4) + b * 8]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int b = 0; b < CW_KS / 32; ++b) {
-        const int kq = qt * (CW_KS / 4) + b * 8;
         const int xq0 = sx[b];
         sx[b] = xq0 + ksx >= W ? xq0 + ksx - W : xq0 + ksx;
 #pragma unroll
         for (int dyv = 0; dyv < 3; ++dyv) {
-          const u16x8 v = *reinterpret_cast<const u16x8*>(&sA[(dyv * 64 + co) * CW_PA + kq]);
+          const u16x8 v = sv[b][dyv];
           float inner = 0.f;
 #pragma unroll
           for (int e = 1; e < 7; ++e) inner += Low<T>::to_f32(v[e]);
@@ -618,6 +628,7 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
   }
 
   const float scale = g.h / g.ctl->S_step;
+  float* slotf = g.part + ((size_t)(blockIdx.z * gridDim.x + blockIdx.x) * gridDim.y + blockIdx.y) * CW_SLOT;
   if (sums) {
     sum_b += __shfl_xor(sum_b, 1);
     sum_b += __shfl_xor(sum_b, 2);
@@ -627,12 +638,15 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
       sum_t[t] += __shfl_xor(sum_t[t], 2);
     }
     const int na = a0 + (tid >> 2);
-    if ((tid & 3) == 0 && na < g.Na) {
-      unsafeAtomicAdd(&g.gb[na], scale * sum_b);
-      if (g.gwt) {
-#pragma unroll
-        for (int t = 0; t < 9; ++t) unsafeAtomicAdd(&g.gwt[(size_t)na * g.wt_stride + t], scale * sum_t[t]);
-      }
+    if ((tid & 3) == 0) {
+      float4* tail = reinterpret_cast<float4*>(slotf + 9 * 4096 + (tid >> 2) * 16);
+      float4 v0 = tail[0], v1 = tail[1], v2 = tail[2];
+      v0.x = fmaf(scale, sum_b, v0.x);
+      v0.y = fmaf(scale, sum_t[0], v0.y); v0.z = fmaf(scale, sum_t[1], v0.z); v0.w = fmaf(scale, sum_t[2], v0.w);
+      v1.x = fmaf(scale, sum_t[3], v1.x); v1.y = fmaf(scale, sum_t[4], v1.y);
+      v1.z = fmaf(scale, sum_t[5], v1.z); v1.w = fmaf(scale, sum_t[6], v1.w);
+      v2.x = fmaf(scale, sum_t[7], v2.x); v2.y = fmaf(scale, sum_t[8], v2.y);
+      tail[0] = v0; tail[1] = v1; tail[2] = v2;
     }
     if (tsums) {
       // this thread's quarter of its channel's rows: contract the tap sums with the time weights
@@ -648,30 +662,60 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
       block_sum2(scale * p0, scale * p1, g.tpart);
     }
   }
-  // plain read-modify-write: the slot belongs to this workgroup for the whole backward pass
-  float* slot = g.part + ((size_t)(blockIdx.z * gridDim.x + blockIdx.x) * gridDim.y + blockIdx.y) * (9 * 4096);
-  const int nb = wn * 32 + (lane & 31);
+  // plain read-modify-write: the slot belongs to this workgroup for the whole backward pass.  Its
+  // layout follows the accumulator registers: float4 number ((tap * 4 + q / 4) * 256 + thread) holds
+  // rows (co) wm * 32 + 8 (q / 4) + 4 (lane / 32) + 0..3 of column (ci) wn * 32 + lane % 32.  The old
+  // values of three taps are fetched together (one memory latency per group, not one per value).
+  float4* slot = reinterpret_cast<float4*>(slotf);
 #pragma unroll
-  for (int t = 0; t < 9; ++t)
+  for (int t0 = 0; t0 < 9; t0 += 3) {
+    float4 old[3][4];
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const int na = wm * 32 + 8 * (q >> 2) + 4 * (lane >> 5) + (q & 3);
-      float* dst = slot + (t * 64 + na) * 64 + nb;
-      *dst = fmaf(scale, acc[t][q], *dst);
-    }
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) old[t][q4] = slot[((t0 + t) * 4 + q4) * 256 + tid];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        float4 v = old[t][q4];
+        v.x = fmaf(scale, acc[t0 + t][q4 * 4 + 0], v.x);
+        v.y = fmaf(scale, acc[t0 + t][q4 * 4 + 1], v.y);
+        v.z = fmaf(scale, acc[t0 + t][q4 * 4 + 2], v.z);
+        v.w = fmaf(scale, acc[t0 + t][q4 * 4 + 3], v.w);
+        slot[((t0 + t) * 4 + q4) * 256 + tid] = v;
+      }
+  }
 }
 
-// dW[co][ci][tap] += sum over K-chunks of the private accumulators (end of the backward pass)
+// dW[co][ci][tap], db[co] and dwt[co][tap] += sum over K-chunks of the private accumulators (end of the
+// backward pass).  gb / gwt null: no bias / no time channel; element (co, tap) of dwt at co * wt_stride + tap.
 __global__ void conv_wgrad_reduce(float* __restrict__ G, int ldg, const float* __restrict__ part, int splits,
-                                  int tiles_a, int tiles_b, int Na, int Nb, const Ctl* ctl) {
+                                  int tiles_a, int tiles_b, int Na, int Nb, float* __restrict__ gb,
+                                  float* __restrict__ gwt, int wt_stride, const Ctl* ctl) {
   if (ctl->poison) return;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)Na * Nb * 9) return;
+  const int64_t nW = (int64_t)Na * Nb * 9;
+  if (i >= nW + (int64_t)Na * 10) return;
+  if (i >= nW) {
+    const int na = (int)((i - nW) / 10), e = (int)((i - nW) % 10);
+    float* dst = e == 0 ? (gb ? gb + na : nullptr) : (gwt ? gwt + (size_t)na * wt_stride + (e - 1) : nullptr);
+    if (!dst) return;
+    const size_t off = (size_t)(na >> 6) * tiles_b * CW_SLOT + 9 * 4096 + (na & 63) * 16 + e;
+    float acc = 0.f;
+    for (int c = 0; c < splits; ++c) acc += part[(size_t)c * tiles_a * tiles_b * CW_SLOT + off];
+    *dst += acc;
+    return;
+  }
   const int nb = (int)(i % Nb), t = (int)((i / Nb) % 9), na = (int)(i / ((int64_t)Nb * 9));
-  const size_t in_tile = ((size_t)t * 64 + (na & 63)) * 64 + (nb & 63);
+  // (position of element (tap, co, ci) in a workgroup's copy: see the epilogue of conv_wgrad)
+  const int r = na & 31, c = nb & 31;
+  const int thread = (((na >> 5) & 1) * 2 + ((nb >> 5) & 1)) * 64 + ((r >> 2) & 1) * 32 + c;
+  const size_t in_tile = ((size_t)(t * 4 + (r >> 3)) * 256 + thread) * 4 + (r & 3);
   const size_t tile = (size_t)(na >> 6) * tiles_b + (nb >> 6);
   float acc = 0.f;
-  for (int c = 0; c < splits; ++c) acc += part[((size_t)c * tiles_a * tiles_b + tile) * (9 * 4096) + in_tile];
+  for (int c2 = 0; c2 < splits; ++c2) acc += part[((size_t)c2 * tiles_a * tiles_b + tile) * CW_SLOT + in_tile];
   G[(size_t)na * ldg + (size_t)nb * 9 + t] += acc;
 }
 

@@ -160,6 +160,15 @@ struct Plan;
 // the all-taps convolution weight-gradient kernel: image lines of a multiple of 8 pixels, at most
 // 64, and whole 64-row k-steps
 static bool conv_wgrad_applies(const Plan& p);
+// workgroups per launch of the conv weight-gradient kernel (env RAMPDE_CONV_WGRAD_BLOCKS overrides)
+static int conv_wgrad_blocks() {
+  static const int v = [] {
+    const char* e = std::getenv("RAMPDE_CONV_WGRAD_BLOCKS");
+    const int n = e ? std::atoi(e) : 0;
+    return n > 0 ? n : 256;
+  }();
+  return v;
+}
 
 static bool fused_candidate(const rampde_velocity* vel, const rampde_policy* pol) {
   if (!vel || vel->kind != RAMPDE_VEL_MLP || (pol && (pol->flags & RAMPDE_PER_LAYER_KERNELS))) return false;
@@ -310,16 +319,18 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
       for (int l = 0; l + 1 < p.L; ++l) p.DELTA.push_back(take((size_t)p.s * p.R * p.layers[l].Npad * 2));
       if (conv_wgrad_applies(p)) {
         // every (K-chunk, 64 x 64 channel block) accumulates its 9 tap blocks over all steps in a
-        // copy of its own; about 512 workgroups per launch, at least 4 k-steps each
+        // copy of its own; one workgroup per compute unit (its LDS holds one), at least 4 k-steps
+        // each: fewer, longer chunks keep the read-modify-write of the copies and the pipeline
+        // fill small against the multiplication
         const int64_t rows = (int64_t)p.s * p.R;
         for (auto& y : p.layers) {
           const int tiles = (y.Npad / 64) * (y.Kpad / 64);
-          const int64_t want = std::max(1, 512 / tiles);
+          const int64_t want = std::max<int64_t>(1, conv_wgrad_blocks() / tiles);
           int64_t per = ((rows + want - 1) / want + CW_KS - 1) / CW_KS * CW_KS;
           if (per < 4 * CW_KS) per = 4 * CW_KS;
           y.cw_per = (int)per;
           y.cw_splits = (int)((rows + per - 1) / per);
-          y.cw_part = take(sizeof(float) * (size_t)y.cw_splits * tiles * 9 * 4096);
+          y.cw_part = take(sizeof(float) * (size_t)y.cw_splits * tiles * CW_SLOT);
         }
       }
     }
@@ -865,9 +876,7 @@ struct Runner {
         c.rows_per_split = y.cw_per;
         c.part = f32(y.cw_part);
         c.h = h; c.ctl = ctl; c.H = p.H; c.Wd = p.Wd;
-        c.gb = grad_theta + y.theta_b;
-        c.gwt = y.has_time ? grad_theta + y.theta_w + (size_t)y.in * 9 : nullptr;
-        c.wt_stride = y.in_full * 9;
+        c.want_sums = true;
         c.Na = y.out;
         c.R = p.R;
         for (int j = 0; j < kMaxStages; ++j) {
@@ -1009,7 +1018,7 @@ struct Runner {
     if (conv_wgrad_applies(p))
       for (auto& y : p.layers)
         fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + y.cw_part),
-                                            (size_t)y.cw_splits * (y.Npad / 64) * (y.Kpad / 64) * 9 * 4096);
+                                            (size_t)y.cw_splits * (y.Npad / 64) * (y.Kpad / 64) * CW_SLOT);
     if (!use_fused) cast_weights(theta);
     SideStream& side = SideStream::get();
     if (use_fused && p.overlap_wgrad) {
@@ -1137,9 +1146,10 @@ struct Runner {
       if (grad_t) fold_time_sums<<<blocks_for(N + 1, 256), 256, 0, st>>>(grad_t, f32(p.tpart), N, ctl);
       if (conv_wgrad_applies(p))
         for (auto& y : p.layers) {
-          const int64_t n = (int64_t)y.out * y.in * 9;
-          conv_wgrad_reduce<<<blocks_for(n, 256), 256, 0, st>>>(grad_theta + y.theta_w, y.in_full * 9, f32(y.cw_part),
-                                                                y.cw_splits, y.Npad / 64, y.Kpad / 64, y.out, y.in, ctl);
+          const int64_t n = (int64_t)y.out * y.in * 9 + (int64_t)y.out * 10;
+          conv_wgrad_reduce<<<blocks_for(n, 256), 256, 0, st>>>(
+              grad_theta + y.theta_w, y.in_full * 9, f32(y.cw_part), y.cw_splits, y.Npad / 64, y.Kpad / 64, y.out, y.in,
+              grad_theta + y.theta_b, y.has_time ? grad_theta + y.theta_w + (size_t)y.in * 9 : nullptr, y.in_full * 9, ctl);
         }
       HIP_TRY(hipGetLastError());
       if (!must_sync) break;
