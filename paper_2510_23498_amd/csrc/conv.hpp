@@ -31,7 +31,7 @@ inline bool conv_tile_applies(int Cpad, int N, int H, int Wd, int64_t M) {
 }
 inline size_t conv_tile_lds_bytes(int Wd) {
   const int lines = CT_TILE / Wd + 2;
-  return (size_t)(9 * 64 * CT_PITCH + lines * (Wd + 2) * CT_PITCH) * 2 + 16 * 64 * 4;
+  return (size_t)(9 * 64 * CT_PITCH + lines * (Wd + 2) * CT_PITCH) * 2 + (16 * 64 + 10 * 64) * 4;
 }
 
 // NWV wavefronts per workgroup (4 or 8): a wavefront owns 256 / NWV pixels of the tile x all 64 output channels.
@@ -47,47 +47,10 @@ __global__ __launch_bounds__(64 * NWV) void conv3x3_tile(GemmNT g) {
   const int wshift = 31 - __builtin_clz(W);
   uint16_t* sW = ct_smem;                              // [9][64 co][CT_PITCH]
   uint16_t* sIn = ct_smem + 9 * 64 * CT_PITCH;         // [PR + 2][W + 2][CT_PITCH]
-  float* s_tt = reinterpret_cast<float*>(sIn + (PR + 2) * LW * CT_PITCH);  // [16][64]
+  float* s_tt = reinterpret_cast<float*>(sIn + (PR + 2) * LW * CT_PITCH);  // [16][64]: bias + time term by border class
+  float* s_wt = s_tt + 16 * 64;                                            // [9][64] time-channel weights, [64] bias
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ntiles = (int)(g.M / CT_TILE);
-
-  // ---- once per workgroup: weights, zero halo columns, time-term table
-  {
-    // (all 18 loads of a thread are issued before the first is stored: one memory latency, not 18)
-    constexpr int NWC = 9 * 64 * 8 / NT;
-    u16x8 wr[NWC];
-#pragma unroll
-    for (int i = 0; i < NWC; ++i) {
-      const int id = tid + NT * i;
-      const int c8 = id & 7, co = (id >> 3) & 63, tap = id >> 9;
-      wr[i] = *reinterpret_cast<const u16x8*>(g.W + (size_t)co * g.ldw + tap * 64 + c8 * 8);
-    }
-#pragma unroll
-    for (int i = 0; i < NWC; ++i) {
-      const int id = tid + NT * i;
-      const int c8 = id & 7, co = (id >> 3) & 63, tap = id >> 9;
-      *reinterpret_cast<u16x8*>(&sW[(tap * 64 + co) * CT_PITCH + c8 * 8]) = wr[i];
-    }
-  }
-  for (int id = tid; id < (PR + 2) * 2 * 8; id += NT) {
-    const int c8 = id & 7, side = (id >> 3) & 1, ly = id >> 4;
-    const u16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-    *reinterpret_cast<u16x8*>(&sIn[(ly * LW + (side ? W + 1 : 0)) * CT_PITCH + c8 * 8]) = z;
-  }
-  if (g.wt) {
-    for (int i = tid; i < 16 * 64; i += NT) {
-      const int combo = i >> 6, n = i & 63;
-      float sum = 0.f;
-#pragma unroll
-      for (int t = 0; t < 9; ++t) {
-        const int dy = t / 3 - 1, dx = t % 3 - 1;
-        const bool ok = (dy >= 0 || (combo & 8)) && (dy <= 0 || (combo & 4)) && (dx >= 0 || (combo & 2)) &&
-                        (dx <= 0 || (combo & 1));
-        if (ok) sum += g.wt[t * g.N + n] * g.tau;
-      }
-      s_tt[i] = sum;
-    }
-  }
 
   // ---- input chunks of a tile: chunk id -> (staged line ly, pixel x, 8 channels c8)
   const int nchunk = (PR + 2) * W * 8;
@@ -122,7 +85,57 @@ __global__ __launch_bounds__(64 * NWV) void conv3x3_tile(GemmNT g) {
     }
   };
 
+  // (the first tile's input is requested before the weights: both are in flight together)
   if ((int)blockIdx.x < ntiles) load_tile(blockIdx.x);
+
+  // ---- once per workgroup: weights, zero halo columns, time-term table
+  {
+    // (all 18 loads of a thread are issued before the first is stored: one memory latency, not 18)
+    constexpr int NWC = 9 * 64 * 8 / NT;
+    u16x8 wr[NWC];
+#pragma unroll
+    for (int i = 0; i < NWC; ++i) {
+      const int id = tid + NT * i;
+      const int c8 = id & 7, co = (id >> 3) & 63, tap = id >> 9;
+      wr[i] = *reinterpret_cast<const u16x8*>(g.W + (size_t)co * g.ldw + tap * 64 + c8 * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < NWC; ++i) {
+      const int id = tid + NT * i;
+      const int c8 = id & 7, co = (id >> 3) & 63, tap = id >> 9;
+      *reinterpret_cast<u16x8*>(&sW[(tap * 64 + co) * CT_PITCH + c8 * 8]) = wr[i];
+    }
+  }
+  for (int id = tid; id < (PR + 2) * 2 * 8; id += NT) {
+    const int c8 = id & 7, side = (id >> 3) & 1, ly = id >> 4;
+    const u16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+    *reinterpret_cast<u16x8*>(&sIn[(ly * LW + (side ? W + 1 : 0)) * CT_PITCH + c8 * 8]) = z;
+  }
+  // (one global load per thread, then the table from LDS: a chain of dependent global loads per
+  // table entry would cost more than the tile's multiplication)
+  for (int i = tid; i < 10 * 64; i += NT) {
+    float v = 0.f;
+    if (i < 9 * 64) {
+      if (g.wt) v = g.wt[(i >> 6) * g.N + (i & 63)];
+    } else if (g.bias) {
+      v = g.bias[i & 63];
+    }
+    s_wt[i] = v;
+  }
+  __syncthreads();
+  for (int i = tid; i < 16 * 64; i += NT) {
+    const int combo = i >> 6, n = i & 63;
+    float sum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+      const int dy = t / 3 - 1, dx = t % 3 - 1;
+      const bool ok = (dy >= 0 || (combo & 8)) && (dy <= 0 || (combo & 4)) && (dx >= 0 || (combo & 2)) &&
+                      (dx <= 0 || (combo & 1));
+      sum += ok ? s_wt[t * 64 + n] * g.tau : 0.f;
+    }
+    s_tt[i] = s_wt[9 * 64 + n] + sum;
+  }
+
 
   // this lane's two pixel columns (operand B) and weight rows (operand A)
   const int fk = (lane >> 5) * 8;
@@ -150,6 +163,21 @@ __global__ __launch_bounds__(64 * NWV) void conv3x3_tile(GemmNT g) {
       for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.f;
+    // the stored activations for the tanh' factor of this lane's outputs: in flight during the
+    // multiplication
+    uint2 dv[NB][2][4];
+    if (g.dact) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const int64_t m = (int64_t)t * CT_TILE + wave * (32 * NB) + b * 32 + (lane & 31);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4)
+            dv[b][a][q4] =
+                *reinterpret_cast<const uint2*>(g.dact + (size_t)m * g.ldd + a * 32 + 8 * q4 + 4 * (lane >> 5));
+      }
+    }
     // 36 k-blocks of 16 (9 taps x 64 channels); the fragments of block i + 1 are read from LDS
     // before the MFMAs of block i are issued (a workgroup is alone on its CU: nothing else hides
     // the LDS latency)
@@ -187,6 +215,12 @@ __global__ __launch_bounds__(64 * NWV) void conv3x3_tile(GemmNT g) {
         const int y = (int)((m >> wshift) % H);
         combo = ((y > 0) << 3) | ((y < H - 1) << 2) | ((x > 0) << 1) | (x < W - 1 ? 1 : 0);
       }
+      float4 tv[2][4];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+          tv[a][q4] = *reinterpret_cast<const float4*>(&s_tt[combo * 64 + a * 32 + 8 * q4 + 4 * (lane >> 5)]);
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
 #pragma unroll
@@ -195,21 +229,14 @@ __global__ __launch_bounds__(64 * NWV) void conv3x3_tile(GemmNT g) {
           float v[4];
 #pragma unroll
           for (int r = 0; r < 4; ++r) v[r] = acc[a][b][q4 * 4 + r];
-          if (g.bias) {
-            const float4 bv = *reinterpret_cast<const float4*>(g.bias + n);
-            v[0] += bv.x; v[1] += bv.y; v[2] += bv.z; v[3] += bv.w;
-          }
-          if (g.wt) {
-            const float4 tv = *reinterpret_cast<const float4*>(&s_tt[combo * 64 + n]);
-            v[0] += tv.x; v[1] += tv.y; v[2] += tv.z; v[3] += tv.w;
-          }
+          v[0] += tv[a][q4].x; v[1] += tv[a][q4].y; v[2] += tv[a][q4].z; v[3] += tv[a][q4].w;
           if (g.act_tanh) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[r] = tanh_fast(v[r]);
           }
           if (g.dact) {
             float av[4];
-            unpack4<T>(*reinterpret_cast<const uint2*>(g.dact + (size_t)m * g.ldd + n), av);
+            unpack4<T>(dv[b][a][q4], av);
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[r] = v[r] * (1.f - av[r] * av[r]);
           }
