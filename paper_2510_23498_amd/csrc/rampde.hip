@@ -165,7 +165,13 @@ static int conv_wgrad_blocks() {
   static const int v = [] {
     const char* e = std::getenv("RAMPDE_CONV_WGRAD_BLOCKS");
     const int n = e ? std::atoi(e) : 0;
-    return n > 0 ? n : 256;
+    if (n > 0) return n;
+    // one workgroup per compute unit of the current device (256 on MI355X)
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+    return cus;
   }();
   return v;
 }

@@ -84,10 +84,11 @@ def test_cfg4_conv_shape_reduced():
     _both(wl.CONFIGS["cfg4"].with_(name="cfg4s", B=3, N=3), bias_std=0.1)
 
 
-@pytest.mark.parametrize("C,H,W,B", [(96, 4, 8, 4), (8, 8, 16, 2), (70, 2, 64, 1)])
+@pytest.mark.parametrize("C,H,W,B", [(96, 4, 8, 4), (8, 8, 16, 2), (70, 2, 64, 1), (8, 16, 24, 1), (16, 8, 40, 2)])
 def test_conv_weight_gradient_all_taps_kernel(C, H, W, B):
     # image lines of 8 k pixels: the convolution weight gradient runs in the kernel that handles all
-    # nine taps per workgroup (several channel blocks, a halo wider than the k-step, one-line images)
+    # nine taps per workgroup (several channel blocks, a halo wider than the k-step, one-line images,
+    # lines of 24 and 40 pixels: a k-step of 128 pixels then starts at a different column each time)
     cfg = wl.CONFIGS["cfg4"].with_(name=f"convw{C}x{H}x{W}", B=B, N=2, C=C, H=H, W=W, tableau="kutta3")
     _both(cfg, bias_std=0.1)
 
@@ -160,7 +161,8 @@ def test_time_grid_gradient_small_mlp_all_tableaux(tab, flags):
     _time_grid_case(cfg, flags=flags)
 
 
-@pytest.mark.parametrize("C,H,W,B,tab", [(64, 32, 32, 2, "rk4"), (5, 7, 6, 2, "kutta3"), (70, 4, 8, 3, "heun")])
+@pytest.mark.parametrize("C,H,W,B,tab", [(64, 32, 32, 2, "rk4"), (5, 7, 6, 2, "kutta3"), (70, 4, 8, 4, "heun"),
+                                          (70, 4, 8, 3, "heun"), (8, 16, 24, 1, "kutta3")])
 def test_time_grid_gradient_conv(C, H, W, B, tab):
     # both convolutions carry a time channel; all-taps weight-gradient kernel and the generic one (W = 6)
     cfg = wl.CONFIGS["cfg4"].with_(name=f"dtconv{C}x{H}x{W}", B=B, N=2, C=C, H=H, W=W, tableau=tab)
