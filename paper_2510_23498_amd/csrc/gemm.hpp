@@ -719,6 +719,36 @@ __global__ void conv_wgrad_reduce(float* __restrict__ G, int ldg, const float* _
   G[(size_t)na * ldg + (size_t)nb * 9 + t] += acc;
 }
 
+// The MFMAs of one k-step of 64 on a wavefront's 64 x 64 output block: operand fragments of k-block
+// kk + 1 are read from LDS before the MFMAs of k-block kk are issued (left to itself the compiler
+// puts a full wait between every fragment read and its MFMA).  pa / pb: this lane's first fragment
+// of the two operand tiles (row (lane % 32), k offset 8 (lane / 32)).
+template <class T, int PITCH>
+__device__ __forceinline__ void mma_k64(const uint16_t* pa, const uint16_t* pb, f32x16 (&acc)[2][2]) {
+  u16x8 fa[2][2], fb[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a) fa[0][a] = *reinterpret_cast<const u16x8*>(pa + a * 32 * PITCH);
+#pragma unroll
+  for (int b = 0; b < 2; ++b) fb[0][b] = *reinterpret_cast<const u16x8*>(pb + b * 32 * PITCH);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    if (kk + 1 < 4) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+        fa[(kk + 1) & 1][a] = *reinterpret_cast<const u16x8*>(pa + a * 32 * PITCH + (kk + 1) * 16);
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+        fb[(kk + 1) & 1][b] = *reinterpret_cast<const u16x8*>(pb + b * 32 * PITCH + (kk + 1) * 16);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) acc[a][b] = Low<T>::mfma32(fa[kk & 1][a], fb[kk & 1][b], acc[a][b]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 // ------------------------------------------------------------------------------------
 // Parameter gradients of one adjoint step for dense networks whose cotangents and layer
 // inputs were stored FEATURE-GROUP-MAJOR by the row-tile-persistent adjoint kernel: element
@@ -1038,6 +1068,9 @@ __global__ __launch_bounds__(256, 2) void wgrad_feature_major_steps(WgradArgs g)
 #pragma unroll
   for (int u = 0; u < WG_STAGES; ++u) load_tiles(ra[u], rb[u]);
   int it = 0, kk = 0;  // position of the tile being consumed
+  const int j_first = (int)(k_begin / g.Rp);
+  int jst = j_first;
+  int64_t stage_end = (int64_t)(j_first + 1) * g.Rp;
   auto k_step = [&](auto sums, u16x8 (&qa)[4], u16x8 (&qb)[4]) __attribute__((always_inline)) {
     __builtin_amdgcn_sched_barrier(0);
     regroup_store(sA, qa);
@@ -1046,8 +1079,15 @@ __global__ __launch_bounds__(256, 2) void wgrad_feature_major_steps(WgradArgs g)
     load_tiles(qa, qb);
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (decltype(sums)::value) {
-      const int j = (int)((k_begin + (int64_t)kk * BK) / g.Rp);
-      const float tau = s_tau[it][j];
+      if (kk == 0) {  // (a new step starts over at the chunk's first stage; no division per k-step)
+        jst = j_first;
+        stage_end = (int64_t)(j_first + 1) * g.Rp;
+      }
+      if (k_begin + (int64_t)kk * BK >= stage_end) {
+        ++jst;
+        stage_end += g.Rp;
+      }
+      const float tau = s_tau[it][jst];
       float part = 0.f;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
@@ -1058,20 +1098,8 @@ __global__ __launch_bounds__(256, 2) void wgrad_feature_major_steps(WgradArgs g)
       sum_b += part;
       sum_t = fmaf(tau, part, sum_t);
     }
-#pragma unroll
-    for (int q4 = 0; q4 < BK / 16; ++q4) {
-      u16x8 fa[2], fb[2];
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-        fa[a] = *reinterpret_cast<const u16x8*>(&sA[(wm * 64 + a * 32 + frow) * LDS_PITCH + q4 * 16 + fk]);
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-        fb[b] = *reinterpret_cast<const u16x8*>(&sB[(wn * 64 + b * 32 + frow) * LDS_PITCH + q4 * 16 + fk]);
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = Low<T>::mfma32(fa[a], fb[b], acc[a][b]);
-    }
+    static_assert(BK == 64, "mma_k64 covers a k-step of 64");
+    mma_k64<T, LDS_PITCH>(&sA[(wm * 64 + frow) * LDS_PITCH + fk], &sB[(wn * 64 + frow) * LDS_PITCH + fk], acc);
     if (kk == nk - 1) {
       // the step's partial sums are complete: rescale the running sums for the next step
       const float sc = s_scale[it];
