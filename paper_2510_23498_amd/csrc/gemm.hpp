@@ -347,19 +347,19 @@ __global__ __launch_bounds__(256) void gemm_tn(GemmTN g) {
 // of g, for the convolutional velocity):
 //   dW[co][ci][tap] += scale * sum_k delta[k][co] * x[k + dy W + dx][ci] * [pixel (y+dy, x+dx) inside]
 // over the rows k (pixels of all samples and stages) of one K-chunk, all 9 taps in one workgroup.
-// A workgroup owns a 64 (co) x 64 (ci) block.  Per k-step of 64 rows it transposes into LDS
+// A workgroup owns a 64 (co) x 64 (ci) block.  Per k-step of CW_KS = 128 rows it transposes into LDS
 //   - the cotangent tile, in 3 copies: as is, and with the rows of the first / last image line
 //     zeroed (taps with dy = -1 / +1: the line above / below does not exist),
-//   - the input tile with a halo of one image line on both sides (64 + 2 W rows), in 3 copies
+//   - the input tile with a halo of one image line on both sides (CW_KS + 2 W rows), in 3 copies
 //     shifted by dx = -1, 0, +1 rows with the pixels that fall off the line zeroed,
 // so that the operand fragment of tap (dy, dx) is an aligned read at row offset (1 + dy) W of copy
-// dx, and every tap is one MFMA per 16 k.  Needs W % 8 == 0, W <= 64 and rows % 64 == 0 (the
-// 8-row blocks a thread transposes then lie within one image line).
+// dx, and every tap is one MFMA per 16 k.  Needs W % 8 == 0 (the 8-row blocks a thread transposes
+// then lie within one image line), W <= 64 and rows per stage % CW_KS == 0 (a k-step lies within one stage).
 struct ConvWgrad {
   const uint16_t* A; int lda;   // [rows, >= 64 gridDim.x] cotangents of the layer's output
   const uint16_t* B; int ldb;   // [rows, >= 64 gridDim.y] the layer's input
   int64_t rows;                 // stages * batch * H * W
-  int rows_per_split;           // multiple of 64
+  int rows_per_split;           // multiple of CW_KS
   float* part;                  // [gridDim.z][gridDim.x][gridDim.y][CW_SLOT] fp32 (tap blocks in register order): the private
                                 // accumulators of every (K-chunk, channel block), summed at the end of the pass
   float h;                      // scale = h / ctl->S_step
@@ -371,7 +371,7 @@ struct ConvWgrad {
   // would serialise in the L2)
   bool want_sums;
   int Na;                       // valid output channels
-  int64_t R;                    // rows per stage (a multiple of 64)
+  int64_t R;                    // rows per stage (a multiple of CW_KS)
   float taus[kMaxStages];       // stage times
   // time-grid gradient (paper Sec. 3, update lines of t'): the time cotangent of stage j is
   // taubar_j = sum_{k, co, tap} delta[k][co] * wt[tap][co] * [tap inside]; the step's sums get
@@ -391,8 +391,8 @@ constexpr int CW_MAXI_HI = (3 * (CW_KS + 128) + CW_KS + 255) / 256;
 inline size_t conv_wgrad_lds_bytes(int Wd) { return (size_t)(3 * 64 * CW_PA + 3 * 64 * (CW_KS + 2 * Wd + 8)) * 2; }
 
 // TS: also form the time cotangent sums for the time-grid gradient (g.tpart, g.wt non-null).
-// MAXI: loader items per thread: 2 cover image lines of up to 32 pixels (and keep the kernel free of
-// register spills), 3 are needed for lines of 64.
+// MAXI: loader items (8 rows x 8 channels) per thread: CW_MAXI_LO = 3 cover image lines of up to 32
+// pixels, CW_MAXI_HI = 4 are needed for lines of 64 (that instance spills a few registers).
 template <class T, bool TS, int MAXI>
 __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
   if (g.ctl->poison) return;
