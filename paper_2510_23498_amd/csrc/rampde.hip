@@ -158,7 +158,7 @@ static int conv_tile_waves();
 static rampde_scaling resolve_scaling(const rampde_policy* pol);
 struct Plan;
 // the all-taps convolution weight-gradient kernel: image lines of a multiple of 8 pixels, at most
-// 64, and whole 64-row k-steps
+// 64, and whole 128-row k-steps within a stage
 static bool conv_wgrad_applies(const Plan& p);
 // workgroups per launch of the conv weight-gradient kernel (env RAMPDE_CONV_WGRAD_BLOCKS overrides)
 static int conv_wgrad_blocks() {
