@@ -103,6 +103,13 @@ typedef struct {
   rampde_scaling scaling;
   int k_max;              /* max attempts per step under DYNAMIC (Alg. 2); <= 0 means 16     */
   unsigned flags;
+  /* Launch-shape choices; 0 = let the library choose.  They change how the work is cut into
+   * kernels, never what is computed (results agree to fp32 summation order). */
+  int step_group;         /* dense networks, fixed scale (SCALE_NONE): cap on the adjoint steps that one
+                             launch runs (default: as many as about 4 GiB of workspace hold, at most 64) */
+  int row_tile;           /* dense networks: batch rows per workgroup of the row-tile kernels: 16, 32 or 64.
+                             64 selects the kernels built for 512-wide networks (state width 128) where
+                             they apply; values that do not apply fall back to the automatic choice  */
 } rampde_policy;
 
 typedef struct {

@@ -42,7 +42,8 @@ class _Velocity(C.Structure):
 
 
 class _Policy(C.Structure):
-    _fields_ = [("low", C.c_int), ("scaling", C.c_int), ("k_max", C.c_int), ("flags", C.c_uint)]
+    _fields_ = [("low", C.c_int), ("scaling", C.c_int), ("k_max", C.c_int), ("flags", C.c_uint),
+                ("step_group", C.c_int), ("row_tile", C.c_int)]
 
 
 class _Stats(C.Structure):
@@ -159,10 +160,13 @@ class Policy:
     scaling: str = "auto"
     k_max: int = 16
     flags: int = 0
+    step_group: int = 0
+    row_tile: int = 0
 
     @property
     def c(self):
-        return _Policy(_LOW[self.low], _SCALING[self.scaling], int(self.k_max), int(self.flags))
+        return _Policy(_LOW[self.low], _SCALING[self.scaling], int(self.k_max), int(self.flags),
+                       int(self.step_group), int(self.row_tile))
 
     @property
     def torch_low(self):

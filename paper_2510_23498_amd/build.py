@@ -24,7 +24,7 @@ def hipcc_path() -> str:
     return cand
 
 
-FUSED_HIDDEN_WIDTHS = (0, 256, 512, 1024)  # one translation unit of fused_inst.hip per width
+FUSED_HIDDEN_WIDTHS = (0, 256, 512, 1024)  # translation units of fused_inst.hip: one per width and precision
 
 COMPILE_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wno-pass-failed",
                  "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -43,10 +43,14 @@ def build_library(verbose: bool = False, jobs: int = 0) -> str:
     from concurrent.futures import ThreadPoolExecutor
     objdir = os.path.join(PKG_DIR, "_build")
     os.makedirs(objdir, exist_ok=True)
-    units = [(os.path.join(CSRC, "rampde.hip"), os.path.join(objdir, "rampde.o"), [])]
+    units = [(os.path.join(CSRC, "rampde.hip"), os.path.join(objdir, "rampde.o"), []),
+             (os.path.join(CSRC, "wide_inst.hip"), os.path.join(objdir, "wide.o"), [])]
     for hp in FUSED_HIDDEN_WIDTHS:
-        units.append((os.path.join(CSRC, "fused_inst.hip"), os.path.join(objdir, f"fused_hp{hp}.o"),
-                      [f"-DRAMPDE_INST_HP={hp}"]))
+        for bf16 in (0, 1):
+            units.append((os.path.join(CSRC, "fused_inst.hip"), os.path.join(objdir, f"fused_hp{hp}_{bf16}.o"),
+                          [f"-DRAMPDE_INST_HP={hp}", f"-DRAMPDE_INST_BF16={bf16}"]))
+    # (longest first: the widest instantiations take the longest to compile)
+    units.sort(key=lambda u: -int(u[2][0].split("=")[1]) if u[2] else 1)
     jobs = jobs or min(len(units), os.cpu_count() or 1, 16)
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         results = list(pool.map(_compile, units))

@@ -163,12 +163,17 @@ __global__ void init_adjoint(const float* __restrict__ gyN, const float* __restr
 }
 
 // S_N = 2^floor(-log2(u_L * max|a|)) from the exponent of max|a|; exact in integers.
-__global__ void scale_init(Ctl* ctl, float* scale_hist, int N, int p_bits, int dynamic) {
+// A non-finite dL/dy_N is a range event only for the variants that check for them (detect: dynamic
+// scaling reports a failure at step N, unscaled-safe returns infinite gradients); the plain unscaled
+// variant has no checks (paper Sec. 5) and lets the NaN / inf run through the ordinary arithmetic.
+__global__ void scale_init(Ctl* ctl, float* scale_hist, int N, int p_bits, int dynamic, int detect) {
   unsigned bits = ctl->amax_bits;
   float S = 1.f;
   if (bits >= 0x7F800000u) {  // non-finite dL/dy_N
-    ctl->poison = 1;
-    ctl->failed_step = N;
+    if (detect) {
+      ctl->poison = 1;
+      ctl->failed_step = N;
+    }
   } else if (dynamic && bits != 0) {
     int e;
     float m = frexpf(__builtin_bit_cast(float, bits), &e);  // amax = m * 2^e, m in [0.5, 1)

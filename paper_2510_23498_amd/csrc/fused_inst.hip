@@ -1,8 +1,9 @@
-// One translation unit per hidden width: compile with -DRAMPDE_INST_HP={0,256,512,1024}.
+// One translation unit per hidden width and precision: compile with
+// -DRAMPDE_INST_HP={0,256,512,1024} -DRAMPDE_INST_BF16={0,1}.
 #include "fused_launch.hpp"
 
-#ifndef RAMPDE_INST_HP
-#error "define RAMPDE_INST_HP"
+#if !defined(RAMPDE_INST_HP) || !defined(RAMPDE_INST_BF16)
+#error "define RAMPDE_INST_HP and RAMPDE_INST_BF16"
 #endif
 #define RAMPDE_CAT2(a, b) a##b
 #define RAMPDE_CAT(a, b) RAMPDE_CAT2(a, b)
@@ -71,8 +72,14 @@ hipError_t pick_mt(const FusedLaunch& l, const FusedArgs& a) {
 
 }  // namespace
 
-hipError_t RAMPDE_CAT(fused_launch_hp, RAMPDE_INST_HP)(const FusedLaunch& l, const FusedArgs& a) {
-  return l.bf16 ? pick_mt<BF16>(l, a) : pick_mt<F16>(l, a);
+#if RAMPDE_INST_BF16
+hipError_t RAMPDE_CAT(RAMPDE_CAT(fused_launch_hp, RAMPDE_INST_HP), _bf16)(const FusedLaunch& l, const FusedArgs& a) {
+  return pick_mt<BF16>(l, a);
 }
+#else
+hipError_t RAMPDE_CAT(RAMPDE_CAT(fused_launch_hp, RAMPDE_INST_HP), _f16)(const FusedLaunch& l, const FusedArgs& a) {
+  return pick_mt<F16>(l, a);
+}
+#endif
 
 }  // namespace rampde

@@ -24,10 +24,21 @@ struct FusedLaunch {
   hipStream_t stream;
 };
 
-// Each returns hipSuccess or the error of the attribute call / launch.
-hipError_t fused_launch_hp0(const FusedLaunch& l, const FusedArgs& a);
-hipError_t fused_launch_hp256(const FusedLaunch& l, const FusedArgs& a);
-hipError_t fused_launch_hp512(const FusedLaunch& l, const FusedArgs& a);
-hipError_t fused_launch_hp1024(const FusedLaunch& l, const FusedArgs& a);
+// Each returns hipSuccess or the error of the attribute call / launch.  One function per hidden
+// width and precision, each in a translation unit of its own (they compile in parallel).
+#define RAMPDE_DECLARE_FUSED(hp)                                                   \
+  hipError_t fused_launch_hp##hp##_f16(const FusedLaunch& l, const FusedArgs& a);  \
+  hipError_t fused_launch_hp##hp##_bf16(const FusedLaunch& l, const FusedArgs& a); \
+  inline hipError_t fused_launch_hp##hp(const FusedLaunch& l, const FusedArgs& a) { \
+    return l.bf16 ? fused_launch_hp##hp##_bf16(l, a) : fused_launch_hp##hp##_f16(l, a); \
+  }
+RAMPDE_DECLARE_FUSED(0)
+RAMPDE_DECLARE_FUSED(256)
+RAMPDE_DECLARE_FUSED(512)
+RAMPDE_DECLARE_FUSED(1024)
+#undef RAMPDE_DECLARE_FUSED
+
+// the 64-row-tile kernels for 512-wide networks (wide.hpp): state width 128; l.MT, l.NTL and l.waves are not used
+hipError_t wide_launch(const FusedLaunch& l, const FusedArgs& a);
 
 }  // namespace rampde

@@ -19,6 +19,7 @@
 #include "common.hpp"
 #include "elementwise.hpp"
 #include "fused_launch.hpp"
+#include "wide.hpp"
 #include "gemm.hpp"
 #include "conv.hpp"
 
@@ -76,6 +77,7 @@ struct Plan {
   // row-tile-persistent path (dense networks whose widest layer fits the LDS tiles)
   bool fused = false;
   int MT = 1;          // row tile = 16 * MT
+  bool wide = false;   // 64-row tiles of the kernels for 512-wide networks (wide.hpp)
   int ldp = 0;         // LDS row pitch (elements)
   size_t lds_bytes = 0;
   size_t steptab = 0, a_alt = 0;
@@ -151,29 +153,19 @@ static bool build_layers(const rampde_velocity* vel, Plan& p, int hidden_pad = k
   return true;
 }
 
-static int wgrad_target_blocks();
-static int step_group_cap();
-static bool act_in_lds_enabled();
-static int conv_tile_waves();
 static rampde_scaling resolve_scaling(const rampde_policy* pol);
 struct Plan;
 // the all-taps convolution weight-gradient kernel: image lines of a multiple of 8 pixels, at most
 // 64, and whole 128-row k-steps within a stage
 static bool conv_wgrad_applies(const Plan& p);
-// workgroups per launch of the conv weight-gradient kernel (env RAMPDE_CONV_WGRAD_BLOCKS overrides)
-static int conv_wgrad_blocks() {
-  static const int v = [] {
-    const char* e = std::getenv("RAMPDE_CONV_WGRAD_BLOCKS");
-    const int n = e ? std::atoi(e) : 0;
-    if (n > 0) return n;
-    // one workgroup per compute unit of the current device (256 on MI355X)
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-      cus = 256;
-    return cus;
-  }();
-  return v;
+// compute units of the current device (256 on MI355X; also the answer when no device is visible,
+// e.g. a workspace query on a host without a GPU)
+static int device_compute_units() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    cus = 256;
+  return cus;
 }
 
 static bool fused_candidate(const rampde_velocity* vel, const rampde_policy* pol) {
@@ -183,8 +175,10 @@ static bool fused_candidate(const rampde_velocity* vel, const rampde_policy* pol
   return dp == 64 || dp == 128 || dp == 256;
 }
 
+// allow_wide = false: never the kernels of wide.hpp (the backward pass that also forms the time-grid
+// gradient runs on the other row-tile kernels)
 static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde_tableau* tab,
-                      const rampde_policy* pol, int is_backward) {
+                      const rampde_policy* pol, int is_backward, bool allow_wide = true) {
   Plan p;
   const bool allow_fused = fused_candidate(vel, pol);
   if (!build_layers(vel, p, allow_fused ? 256 : kPad)) return p;
@@ -226,18 +220,34 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
     };
     // (the adjoint kernel carries more per-tile state in registers: it spills beyond 32-row tiles)
     int mt = is_backward ? 2 : 4;
+    const int want_rows = pol ? pol->row_tile : 0;
+    if (want_rows == 16 || want_rows == 32 || (want_rows == 64 && !is_backward)) mt = want_rows / 16;
     // largest row tile that still gives every compute unit a workgroup and fits the LDS tiles
-    while (mt > 1 && ((p.R + 16 * mt - 1) / (16 * mt) < 256 || lds_need(mt, false) > lds_limit)) mt >>= 1;
-    if (lds_need(mt, false) <= lds_limit) {
+    while (mt > 1 && ((want_rows == 0 && (p.R + 16 * mt - 1) / (16 * mt) < 256) || lds_need(mt, false) > lds_limit)) mt >>= 1;
+    // Networks with 512-wide hidden layers and a 128-wide state: the 64-row-tile kernels of wide.hpp,
+    // forward and adjoint, when the batch gives at least half of the compute units a tile (or on
+    // request).  Not for the time-grid gradient, and not where a fixed scale lets the other adjoint
+    // kernel run groups of steps per launch.
+    bool all512 = p.L >= 2;
+    for (int l = 0; l + 1 < p.L; ++l) all512 = all512 && p.layers[l].Npad == 512;
+    const bool fixed_scale = pol && resolve_scaling(pol) == RAMPDE_SCALE_NONE;
+    if (allow_wide && all512 && p.d == 128 && !(is_backward && fixed_scale) &&
+        (want_rows == 64 || (want_rows == 0 && (p.R + 63) / 64 >= 128)) &&
+        (size_t)p.nparam * 4 + 64 * (size_t)(128 + 8) * 2 + 2 * 64 * (size_t)(512 + 8) * 2 <= lds_limit) {
+      p.wide = true;
+      mt = 4;
+    }
+    if (p.wide || lds_need(mt, false) <= lds_limit) {
       p.fused = true;
       p.MT = mt;
-      p.k_in_lds = lds_need(mt, true) <= lds_limit;
+      p.k_in_lds = !p.wide && lds_need(mt, true) <= lds_limit;
       p.overlap_wgrad = (mt == 1 && maxw <= 256);
-      p.lds_bytes = lds_need(mt, p.k_in_lds);
-      if (is_backward && p.L > 1) {
+      p.lds_bytes = p.wide ? (size_t)p.nparam * 4 + 64 * (size_t)(128 + 8) * 2 + 2 * 64 * (size_t)(512 + 8) * 2
+                           : lds_need(mt, p.k_in_lds);
+      if (is_backward && p.L > 1 && !p.wide) {
         // a copy of the step's hidden activations for the tanh' factors, when it still fits
         const size_t act_bytes = (size_t)p.s * (p.L - 1) * 16 * mt * p.ldp * 2;
-        if (p.lds_bytes + act_bytes <= lds_limit && act_in_lds_enabled()) {
+        if (p.lds_bytes + act_bytes <= lds_limit) {
           p.act_lds_off = (int)(p.lds_bytes / 2);
           p.lds_bytes += act_bytes;
         }
@@ -252,7 +262,7 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
       // the tiles do not fit in LDS: fall back to the per-layer kernels with their own padding
       rampde_policy pl = pol ? *pol : rampde_policy{};
       pl.flags |= RAMPDE_PER_LAYER_KERNELS;
-      return make_plan(vel, B, N, tab, &pl, is_backward);
+      return make_plan(vel, B, N, tab, &pl, is_backward, allow_wide);
     }
   }
   const int sbuf = is_backward ? p.s : 1;  // forward keeps one stage of inputs/activations
@@ -280,7 +290,8 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
         size_t per_set = 2 * (size_t)p.dpad * p.ldk * 2;
         for (int l = 0; l + 1 < p.L; ++l) per_set += 2 * (size_t)p.layers[l].Npad * p.ldk * 2;
         const int64_t fit = (int64_t)((size_t(4) << 30) / per_set);
-        const int64_t cap = std::min<int64_t>(step_group_cap(), std::min<int64_t>(fit, kMaxWgradSteps));
+        const int64_t want_group = (pol && pol->step_group > 0) ? pol->step_group : kMaxWgradSteps;
+        const int64_t cap = std::min<int64_t>(want_group, std::min<int64_t>(fit, kMaxWgradSteps));
         if (pol && resolve_scaling(pol) == RAMPDE_SCALE_NONE && cap >= 2) {
           p.step_group = (int)std::min<int64_t>(N, cap);
           p.nsets = p.step_group;
@@ -293,7 +304,7 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
         // K-chunks: as many workgroups as are resident at once (two per CU; one when the kernel
         // shares the CUs with the adjoint kernel) and no more -- a second, partial round of
         // workgroups costs more than it spreads --, but at least 256 k per chunk
-        const int resident = wgrad_target_blocks() * (p.overlap_wgrad ? 1 : 2);
+        const int resident = device_compute_units() * (p.overlap_wgrad ? 1 : 2);
         int64_t ks = std::max(1, resident / tiles);
         // (a group of steps multiplies a workgroup's k-steps: chunks can be shorter)
         const int64_t min_chunk = p.step_group > 1 ? 128 : 256;
@@ -331,7 +342,7 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
         const int64_t rows = (int64_t)p.s * p.R;
         for (auto& y : p.layers) {
           const int tiles = (y.Npad / 64) * (y.Kpad / 64);
-          const int64_t want = std::max<int64_t>(1, conv_wgrad_blocks() / tiles);
+          const int64_t want = std::max<int64_t>(1, device_compute_units() / tiles);
           int64_t per = ((rows + want - 1) / want + CW_KS - 1) / CW_KS * CW_KS;
           if (per < 4 * CW_KS) per = 4 * CW_KS;
           y.cw_per = (int)per;
@@ -345,25 +356,6 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
   p.total = off;
   p.ok = true;
   return p;
-}
-
-// upper limit of the adjoint steps per launch (environment RAMPDE_STEP_GROUP, for experiments and tests)
-static int step_group_cap() {
-  const char* e = getenv("RAMPDE_STEP_GROUP");
-  const int x = e ? atoi(e) : 0;
-  return x > 0 ? x : kMaxWgradSteps;
-}
-
-// (environment RAMPDE_NO_ACT_LDS=1 keeps the activations out of LDS: for experiments)
-static bool act_in_lds_enabled() {
-  const char* e = getenv("RAMPDE_NO_ACT_LDS");
-  return !(e && atoi(e) > 0);
-}
-
-// wavefronts per workgroup of the convolution tile kernel (environment RAMPDE_CONV_WAVES=4: for experiments)
-static int conv_tile_waves() {
-  const char* e = getenv("RAMPDE_CONV_WAVES");
-  return (e && atoi(e) == 4) ? 4 : 8;
 }
 
 static bool conv_wgrad_applies(const Plan& p) { return p.conv && !p.fused && p.Wd % 8 == 0 && p.Wd <= 64 && p.R % CW_KS == 0; }
@@ -397,17 +389,6 @@ static int hip_fail(hipError_t e, const char* where) {
   } while (0)
 
 static inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
-
-// workgroups of the parameter-gradient kernel per resident slot of the chip: one per CU
-// (tunable for experiments)
-static int wgrad_target_blocks() {
-  static int v = [] {
-    const char* e = getenv("RAMPDE_WGRAD_BLOCKS");
-    const int x = e ? atoi(e) : 0;
-    return x > 0 ? x : 256;
-  }();
-  return v;
-}
 
 __global__ void fill_zero_u32(uint32_t* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
@@ -511,9 +492,6 @@ struct Runner {
   // the convolution tile kernel keeps a layer's weights in LDS: more than the default limit
   hipError_t allow_conv_tile_lds() {
     if (p.Wd < 8 || p.Wd > 64) return hipSuccess;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3x3_tile<T, 4>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_tile_lds_bytes(p.Wd));
-    if (e != hipSuccess) return e;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3x3_tile<T, 8>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_tile_lds_bytes(p.Wd));
   }
@@ -523,10 +501,7 @@ struct Runner {
     if (p.conv && conv_tile_applies(g.Cpad, g.N, g.H, g.Wd, g.M)) {
       // persistent: one workgroup per CU (its LDS holds the layer's weights), tiles of 256 pixels
       const int ntiles = (int)(g.M / CT_TILE);
-      if (conv_tile_waves() == 4)
-        conv3x3_tile<T, 4><<<std::min(ntiles, 256), 256, conv_tile_lds_bytes(g.Wd), st>>>(g);
-      else
-        conv3x3_tile<T, 8><<<std::min(ntiles, 256), 512, conv_tile_lds_bytes(g.Wd), st>>>(g);
+      conv3x3_tile<T, 8><<<std::min(ntiles, device_compute_units()), 512, conv_tile_lds_bytes(g.Wd), st>>>(g);
     } else if (p.conv) {
       dim3 grid(blocks_for(g.M, 128), g.N / 64);
       gemm_nt<T, 2, 1, true><<<grid, 256, 0, st>>>(g);
@@ -622,7 +597,10 @@ struct Runner {
       nfrag += (y.Kpad / 32) * (y.Npad / 16) + (y.Npad / 32) * (y.Kpad / 16);
     }
     c.nfrag = nfrag;
-    cast_dense_fragments<T><<<blocks_for(nfrag, 4), 256, 0, st>>>(c);
+    if (p.wide)
+      cast_dense_fragments_wide<T><<<blocks_for(nfrag, 4), 256, 0, st>>>(c);
+    else
+      cast_dense_fragments<T><<<blocks_for(nfrag, 4), 256, 0, st>>>(c);
   }
 
   // per step: h_i, then the stage times rounded to low precision
@@ -700,6 +678,11 @@ struct Runner {
     l.lds_bytes = p.lds_bytes;
     l.stream = st;
     hipError_t e;
+    if (p.wide) {
+      e = wide_launch(l, a);
+      if (e != hipSuccess) return hip_fail(e, "wide row-tile kernel launch");
+      return RAMPDE_OK;
+    }
     switch (static_hidden_width()) {
       case 256: e = fused_launch_hp256(l, a); break;
       case 512: e = fused_launch_hp512(l, a); break;
@@ -1083,7 +1066,7 @@ struct Runner {
     } else {
       init_adjoint<<<stream_blocks(p.n, 512), 256, 0, st>>>(grad_yN, gys_at(N), a, p.n, ctl, 1, naive_low);
     }
-    scale_init<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), N, Low<T>::p_bits, dynamic);
+    scale_init<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), N, Low<T>::p_bits, dynamic, detect);
 
     Ctl hctl;
     memset(&hctl, 0, sizeof hctl);
@@ -1185,22 +1168,21 @@ struct Runner {
     }
     if (p.conv) rows_to_nchw<<<blocks_for(p.n, 256), 256, 0, st>>>(a, grad_y0, p.R, p.d, HW, nullptr, 0);
     HIP_TRY(hipGetLastError());
-    if (scale_hist) {
-      HIP_TRY(hipMemcpyAsync(scale_hist, f32(p.scale_hist), sizeof(float) * (size_t)(N + 1), hipMemcpyDeviceToHost, st));
+    std::vector<float> hist;
+    if (scale_hist || stats) {
+      hist.resize((size_t)N + 1);
+      HIP_TRY(hipMemcpyAsync(hist.data(), f32(p.scale_hist), sizeof(float) * (size_t)(N + 1), hipMemcpyDeviceToHost, st));
     }
     if (must_sync) HIP_TRY(hipStreamSynchronize(st));
+    if (scale_hist) memcpy(scale_hist, hist.data(), sizeof(float) * (size_t)(N + 1));
     if (stats) {
       stats->status = st_code;
       stats->failed_step = hctl.poison ? hctl.failed_step : -1;
       stats->retries = hctl.retries;
       stats->s_min = hctl.s_min;
       stats->s_max = hctl.s_max;
-      stats->s_first = 0.f;
-      stats->s_last = 0.f;
-      if (scale_hist) {
-        stats->s_first = scale_hist[N];
-        stats->s_last = scale_hist[0];
-      }
+      stats->s_first = hist[N];
+      stats->s_last = hist[0];
     }
     return status;
   }
@@ -1226,7 +1208,14 @@ int64_t rampde_num_params(const rampde_velocity* vel) {
 size_t rampde_workspace_bytes(const rampde_velocity* vel, int64_t B, int N, const rampde_tableau* tab,
                               const rampde_policy* pol, int is_backward) {
   Plan p = make_plan(vel, B, N, tab, pol, is_backward);
-  return p.ok ? p.total : 0;
+  if (!p.ok) return 0;
+  size_t total = p.total;
+  if (is_backward && p.wide) {
+    // the backward pass with the time-grid gradient uses the other row-tile kernels: room for either
+    Plan q = make_plan(vel, B, N, tab, pol, is_backward, false);
+    if (q.ok) total = std::max(total, q.total);
+  }
+  return total;
 }
 
 int rampde_odeint_fwd(const rampde_velocity* vel, const float* theta, const float* y0, int64_t B,
@@ -1266,7 +1255,7 @@ int rampde_odeint_bwd_tgrid(const rampde_velocity* vel, const float* theta, int6
   int rc = check_common(vel, tgrid, N, tab, pol);
   if (rc) return rc;
   if (!theta || !ckpt || !grad_yN || !grad_y0 || !grad_theta || !workspace || B < 1) return RAMPDE_EINVAL;
-  Plan p = make_plan(vel, B, N, tab, pol, 1);
+  Plan p = make_plan(vel, B, N, tab, pol, 1, grad_t == nullptr);
   if (!p.ok) return RAMPDE_EINVAL;
   if (workspace_bytes < p.total || ((uintptr_t)workspace & 255)) return RAMPDE_EWORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;

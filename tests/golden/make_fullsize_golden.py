@@ -1,0 +1,101 @@
+#!/usr/bin/env python3
+"""Writes tests/golden/fullsize_<workload>.npz: what the CPU oracle (rounding-emulation mode)
+gives for a workload at its FULL batch size over ALL its time steps.
+
+    python tests/golden/make_fullsize_golden.py cfg3 cfg4 cfg5 cfg5:heun cfg5:euler
+
+The parameter gradient is a sum over every sample, stage and step, so the oracle cannot form single
+entries of it more cheaply than the whole: this script runs the whole pass once (minutes per
+workload) and keeps a digest that the GPU tests compare with:
+  * the adjoint scale history and the retry count (exact);
+  * grad_theta at a seeded sample of indices (plus the first and last entries of every tensor),
+    the sums of 512 contiguous blocks of grad_theta, the 2-norm of every parameter tensor;
+  * y_N and dL/dy_0 on a seeded sample of batch rows, and their overall 2-norms.
+Only oracle/ and the seeded input generators are used: nothing here touches the HIP library.
+"""
+import os
+import sys
+import time
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(HERE))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+from oracle import rampde_oracle as orc  # noqa: E402
+from paper_2510_23498_amd import workloads as wl  # noqa: E402
+
+N_SAMPLES = 8192
+N_BLOCKS = 512
+N_ROWS = 24
+
+
+def sample_indices(cfg: wl.Config, P: int):
+    """Seeded sample of parameter indices + the first / last 32 entries of every tensor."""
+    u = wl.uniforms(cfg.seed + 17, f"{cfg.name}.golden.theta_idx", N_SAMPLES)
+    idx = set((u * P).astype(np.int64).clip(0, P - 1).tolist())
+    for _, shp, off in wl.theta_layout(cfg):
+        cnt = int(np.prod(shp))
+        idx.update(range(off, off + min(32, cnt)))
+        idx.update(range(off + max(0, cnt - 32), off + cnt))
+    return np.array(sorted(idx), dtype=np.int64)
+
+
+def sample_rows(cfg: wl.Config):
+    u = wl.uniforms(cfg.seed + 17, f"{cfg.name}.golden.rows", N_ROWS)
+    rows = set((u * cfg.B).astype(np.int64).clip(0, cfg.B - 1).tolist())
+    rows.update([0, 15, 16, 63, 64, cfg.B - 1])
+    return np.array(sorted(r for r in rows if r < cfg.B), dtype=np.int64)
+
+
+def block_sums(g: np.ndarray) -> np.ndarray:
+    edges = np.linspace(0, g.size, N_BLOCKS + 1).astype(np.int64)
+    return np.array([g[edges[i]:edges[i + 1]].sum() for i in range(N_BLOCKS)], dtype=np.float64)
+
+
+def golden_path(name: str, tableau: str) -> str:
+    tag = name if tableau == wl.CONFIGS[name].tableau else f"{name}_{tableau}"
+    return os.path.join(HERE, f"fullsize_{tag}.npz")
+
+
+def run(name: str, tableau: str = None):
+    cfg = wl.CONFIGS[name]
+    if tableau:
+        cfg = cfg.with_(tableau=tableau)
+    theta = wl.make_theta(cfg)
+    y0 = wl.make_y0(cfg)
+    target = None if cfg.loss == "mean_sq" else wl.make_target(cfg)
+    vel = (orc.MLPVelocity(cfg.widths, time_input=True) if cfg.kind == "mlp"
+           else orc.Conv2Velocity(cfg.C, cfg.H, cfg.W, time_input=True))
+    tab = wl.TABLEAUX[cfg.tableau]
+    pol = orc.Policy(low=cfg.low, scaling=wl.resolve_scaling(cfg))
+    t0 = time.time()
+    yN, ckpt = orc.odeint_fwd(vel, theta, y0.reshape(cfg.B, -1), cfg.tgrid(), tab, pol)
+    print(f"[{name} {cfg.tableau}] oracle forward {time.time() - t0:.0f} s", flush=True)
+    yN32 = yN.astype(np.float32).reshape(cfg.state_shape)
+    _, gyN = wl.loss_and_grad(cfg, yN32, target)
+    res = orc.odeint_bwd(vel, theta, cfg.tgrid(), tab, pol, ckpt, gyN.reshape(cfg.B, -1))
+    print(f"[{name} {cfg.tableau}] oracle forward + adjoint {time.time() - t0:.0f} s, status {res.status}, "
+          f"retries {res.retries}", flush=True)
+    assert res.status == "ok"
+    g = res.grad_theta
+    idx = sample_indices(cfg, g.size)
+    rows = sample_rows(cfg)
+    norms = np.array([np.linalg.norm(g[off:off + int(np.prod(shp))]) for _, shp, off in wl.theta_layout(cfg)])
+    gy0 = res.grad_y0.reshape(cfg.B, -1)
+    out = golden_path(name, cfg.tableau)
+    np.savez_compressed(
+        out, scale_hist=res.scale_hist, retries=np.int64(res.retries), theta_idx=idx, grad_theta_at_idx=g[idx],
+        grad_theta_block_sums=block_sums(g), grad_theta_tensor_norms=norms, grad_theta_norm=np.linalg.norm(g),
+        rows=rows, yN_rows=yN.reshape(cfg.B, -1)[rows], grad_y0_rows=gy0[rows], yN_norm=np.linalg.norm(yN),
+        grad_y0_norm=np.linalg.norm(gy0), oracle_seconds=np.float64(time.time() - t0))
+    print(f"wrote {out} ({os.path.getsize(out)} bytes)", flush=True)
+
+
+if __name__ == "__main__":
+    for arg in sys.argv[1:] or ["cfg3", "cfg4", "cfg5"]:
+        nm, _, tb = arg.partition(":")
+        run(nm, tb or None)

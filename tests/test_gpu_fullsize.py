@@ -8,6 +8,8 @@ times (row-tile-persistent kernels for the dense networks, per-layer kernels for
   can compute those rows one by one.
 Tolerances as in test_gpu_parity.py.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -16,6 +18,8 @@ from paper_2510_23498_amd import workloads as wl
 import parity as par
 
 pytestmark = pytest.mark.gpu
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 
 def _rows(cfg, k=6):
@@ -93,3 +97,72 @@ def test_time_grid_gradient_full_batch(name, steps):
     assert e <= par.TOL_EMUL, (e, gpu["grad_t"], emu["grad_t"])
     par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
     np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
+
+
+def _golden(name, tab):
+    tag = name if tab == wl.CONFIGS[name].tableau else f"{name}_{tab}"
+    path = os.path.join(GOLDEN, f"fullsize_{tag}.npz")
+    assert os.path.exists(path), f"{path} is missing: run tests/golden/make_fullsize_golden.py {name}:{tab}"
+    return np.load(path)
+
+
+def _block_sums(g, nblocks):
+    edges = np.linspace(0, g.size, nblocks + 1).astype(np.int64)
+    return np.array([g[edges[i]:edges[i + 1]].sum(dtype=np.float64) for i in range(nblocks)])
+
+
+@pytest.mark.parametrize("name,tab", [("cfg3", "rk4"), ("cfg4", "rk4"), ("cfg5", "rk4"), ("cfg5", "heun"),
+                                       ("cfg5", "euler")])
+def test_full_size_all_steps_parameter_gradient(name, tab):
+    """Full batch x ALL time steps against the emulation oracle's stored digest (written by
+    tests/golden/make_fullsize_golden.py from oracle/ alone): the parameter gradient is an fp32 sum
+    over B * s * N rows, whose accumulation error a few-step run cannot show."""
+    cfg = wl.CONFIGS[name].with_(tableau=tab)
+    ref = _golden(name, tab)
+    theta, y0, target = par.make_inputs(cfg)
+    print(f"[case] {cfg.name} {tab} full size B={cfg.B} N={cfg.N} vs stored oracle digest", flush=True)
+    gpu = par.run_gpu(cfg, theta, y0, target)
+    assert gpu["status"] == 0
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), ref["scale_hist"])
+    assert gpu["retries"] == int(ref["retries"])
+    g = gpu["grad_theta"].astype(np.float64)
+    rows = ref["rows"]
+    tol, tol_max = par.TOL_EMUL, par.TOL_EMUL_MAX[cfg.low]
+    norms = np.array([np.linalg.norm(g[sl]) for _, sl in par.layer_slices(cfg)])
+    errs = {
+        "grad_theta_samples": par.rel_err(g[ref["theta_idx"]], ref["grad_theta_at_idx"]),
+        "grad_theta_block_sums": par.rel_err(_block_sums(g, ref["grad_theta_block_sums"].size),
+                                             ref["grad_theta_block_sums"]),
+        "grad_theta_norm": abs(np.linalg.norm(g) / float(ref["grad_theta_norm"]) - 1.0),
+        "grad_theta_tensor_norms": float(np.max(np.abs(norms / np.maximum(ref["grad_theta_tensor_norms"], 1e-300) - 1.0)
+                                                * (ref["grad_theta_tensor_norms"] > 0))),
+        "yN_rows": par.rel_err(gpu["yN"].reshape(cfg.B, -1)[rows], ref["yN_rows"]),
+        "grad_y0_rows": par.rel_err(gpu["grad_y0"].reshape(cfg.B, -1)[rows], ref["grad_y0_rows"]),
+        "yN_norm": abs(np.linalg.norm(gpu["yN"].astype(np.float64)) / float(ref["yN_norm"]) - 1.0),
+        "grad_y0_norm": abs(np.linalg.norm(gpu["grad_y0"].astype(np.float64)) / float(ref["grad_y0_norm"]) - 1.0),
+    }
+    emax = {
+        "max_grad_theta_samples": par.max_err(g[ref["theta_idx"]], ref["grad_theta_at_idx"]),
+        "max_grad_y0_rows": par.max_err(gpu["grad_y0"].reshape(cfg.B, -1)[rows], ref["grad_y0_rows"]),
+        "max_yN_rows": par.max_err(gpu["yN"].reshape(cfg.B, -1)[rows], ref["yN_rows"]),
+    }
+    print("  ", {k: f"{v:.2e}" for k, v in {**errs, **emax}.items()}, flush=True)
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    bad.update({k: v for k, v in emax.items() if not v <= tol_max})
+    assert not bad, bad
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg5"])
+def test_full_size_two_kernel_paths_agree(name):
+    """The row-tile-persistent kernels and the per-layer kernels are independent implementations:
+    at full size they must take the same scale decisions and agree on every output."""
+    cfg = wl.CONFIGS[name]
+    theta, y0, target = par.make_inputs(cfg)
+    print(f"[case] {cfg.name} full size, both kernel paths", flush=True)
+    a = par.run_gpu(cfg, theta, y0, target)
+    b = par.run_gpu(cfg, theta, y0, target, flags=4)
+    np.testing.assert_array_equal(a["scale_hist"], b["scale_hist"])
+    assert a["retries"] == b["retries"] and a["status"] == b["status"] == 0
+    errs = {k: par.rel_err(a[k], b[k]) for k in ("yN", "ckpt", "grad_y0", "grad_theta")}
+    print("  ", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert max(errs.values()) <= par.TOL_EMUL, errs

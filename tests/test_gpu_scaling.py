@@ -171,3 +171,128 @@ def test_time_grid_gradient_counts_a_retried_step_once(N, tabname, flags):
     assert ref.retries >= 1 and info.retries == ref.retries
     assert par.rel_err(gt.cpu().numpy() - 0.25, ref.grad_t) <= par.TOL_EMUL, (gt.cpu().numpy() - 0.25, ref.grad_t)
     assert par.rel_err(gy0.cpu().numpy(), ref.grad_y0) <= par.TOL_EMUL
+
+
+# ------------------------------------------------------------------ the state machine at multi-workgroup sizes
+def _gain_case(base, **kw):
+    """A workload whose LAST weight tensor is multiplied by `gain`: the cotangent chain then amplifies
+    the scaled adjoint beyond the fp16 range at the initial scale, and the adjoint itself grows from
+    step to step going backward, so that the scale has to be halved again in the middle of the pass."""
+    gain = kw.pop("gain")
+    cfg = wl.CONFIGS[base].with_(low="f16", **kw)
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    name, shp, off = [x for x in wl.theta_layout(cfg) if x[0].startswith("W")][-1]
+    theta = theta.copy()
+    theta[off:off + int(np.prod(shp))] *= gain
+    return cfg, theta, y0, target
+
+
+MULTI_WG = [
+    # the 8-wavefront adjoint kernel (wide network), several row tiles and a ragged tail
+    ("cfg3", dict(name="retry512", B=300, N=6, t1=0.09, gain=256.0, scaling="dynamic")),
+    # the 4-wavefront adjoint kernel with the parameter gradients on the helper stream
+    ("cfg2", dict(name="retry256", B=300, N=6, t1=0.09, gain=256.0, scaling="dynamic")),
+    # the convolution path (per-layer kernels)
+    ("cfg4", dict(name="retryconv", B=2, N=4, C=8, H=8, W=16, t1=0.02, gain=256.0, scaling="dynamic")),
+]
+
+
+@pytest.mark.parametrize("base,kw", MULTI_WG, ids=[k["name"] for _, k in MULTI_WG])
+@pytest.mark.parametrize("flags,row_tile", [(0, 0), (rb.PER_LAYER_KERNELS, 0), (0, 64)], ids=["tile", "layer", "wide"])
+def test_retry_in_the_middle_of_the_pass_many_workgroups(base, kw, flags, row_tile):
+    if base == "cfg4" and (flags or row_tile):
+        pytest.skip("the convolution has one path")
+    if base == "cfg2" and row_tile:
+        pytest.skip("the 64-row-tile kernels are for 512-wide networks")
+    cfg, theta, y0, target = _gain_case(base, **dict(kw))
+    print(f"[case] mid-pass retry {cfg.name} B={cfg.B} flags={flags}", flush=True)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul")
+    hist = emu["scale_hist"]
+    assert emu["status"] == "ok" and emu["retries"] >= 3
+    assert np.sum(hist[:-1] < hist[1:]) >= 2, "the scale must drop at more than one step"
+    gpu = par.run_gpu(cfg, theta, y0, target, flags=flags, row_tile=row_tile)
+    assert gpu["status"] == 0
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), hist)
+    assert gpu["retries"] == emu["retries"]
+    errs = par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
+    print("  vs emul:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+
+
+@pytest.mark.parametrize("base,kw", MULTI_WG, ids=[k["name"] for _, k in MULTI_WG])
+def test_scaling_failure_many_workgroups(base, kw):
+    cfg, theta, y0, target = _gain_case(base, **dict(kw))
+    emu = par.run_oracle(cfg, theta, y0, target, "emul", k_max=1)
+    assert emu["status"] == "scale_failed"
+    print(f"[case] scaling failure {cfg.name}: oracle fails at step {emu['failed_step']}", flush=True)
+    gpu = par.run_gpu(cfg, theta, y0, target, k_max=1, expect_error=True)
+    assert gpu.get("error") == rb.ESCALE
+    assert gpu["info"].failed_step == emu["failed_step"] and gpu["info"].status == 2
+
+
+@pytest.mark.parametrize("base,kw", MULTI_WG, ids=[k["name"] for _, k in MULTI_WG])
+def test_unscaled_safe_many_workgroups(base, kw):
+    # a loss gradient of order 1e3 overflows the unscaled fp16 chain of these amplifying networks
+    kw = dict(kw)
+    kw["scaling"] = "none_safe"
+    cfg, theta, y0, target = _gain_case(base, **kw)
+    cfg = cfg.with_(grad_scale=1e3 if cfg.loss == "half_sse" else 1e3 * cfg.B * cfg.d)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul")
+    assert emu["status"] == "overflow_inf"
+    print(f"[case] unscaled-safe overflow {cfg.name}: oracle overflows at step {emu['failed_step']}", flush=True)
+    gpu = par.run_gpu(cfg, theta, y0, target)
+    assert gpu["status"] == 1 and gpu["failed_step"] == emu["failed_step"]
+    assert np.all(np.isinf(gpu["grad_theta"])) and np.all(np.isinf(gpu["grad_y0"]))
+
+
+@PATHS
+@pytest.mark.parametrize("want_info", [True, False])
+def test_unscaled_variant_propagates_a_nonfinite_loss_gradient(flags, want_info):
+    # the plain unscaled variant has no range checks (paper Sec. 5): an inf in dL/dy_N is not an
+    # error and must come back as non-finite gradients, with or without the statistics block
+    cfg = wl.CONFIGS["cfg1"].with_(name="infgrad", B=40, N=5, widths=(6, 32, 6))
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    vel, tab, pol = par.gpu_descriptors(cfg, scaling="none", flags=flags)
+    dev = torch.device("cuda:0")
+    th = torch.from_numpy(theta).to(dev)
+    yN, ck = rb.rampde_odeint_fwd(vel, th, torch.from_numpy(y0).to(dev), cfg.tgrid(), tab, pol)
+    gyN = torch.ones_like(yN)
+    gyN[3, 2] = float("inf")
+    gy0 = torch.zeros_like(yN)
+    gth = torch.zeros(rb.rampde_num_params(vel), dtype=torch.float32, device=dev)
+    _, _, info = rb.rampde_odeint_bwd(vel, th, cfg.tgrid(), tab, pol, ck, gyN, grad_y0=gy0, grad_theta=gth,
+                                      want_info=want_info)
+    torch.cuda.synchronize()
+    assert not torch.isfinite(gy0).all() and not torch.isfinite(gth).all()
+    if want_info:
+        assert info.status == 0
+
+
+def _constant_adjoint_case(N):
+    """Zero velocity: the adjoint stays at 1.5 in every entry, nothing in the chain can overflow
+    except lambda = Q(S a) itself.  S_N = 2^10 (S_N * 1.5 = 1536 lies in (1024, 2048])."""
+    d = 4
+    theta = np.zeros(d * d + d, dtype=np.float32)
+    y0 = np.full((2, d), 0.5, dtype=np.float32)
+    tg = np.arange(N + 1, dtype=np.float64) / N
+    aN = np.full((2, d), 1.5, dtype=np.float32)
+    return d, theta, y0, tg, aN
+
+
+@PATHS
+def test_raw_norm_growth_rule_differs_from_the_default(flags):
+    # default rule: S ||a|| = 1536 > 1/(2 u) = 1024, the scale never grows: 2^10 throughout.
+    # literal rule (||a|| = 1.5 <= 1024 at every clean step): the scale doubles after every clean
+    # step, so step i is entered with 2^(10 + N-1-i), until lambda = 2^16 * 1.5 overflows fp16; that
+    # step halves back to 2^15 (one retry, and no growth after a retried step), the next one is
+    # entered with 2^15, is clean and doubles, the one after overflows again, and so on.
+    N = 10
+    d, theta, y0, tg, aN = _constant_adjoint_case(N)
+    expect_default = np.full(N + 1, 2.0 ** 10)
+    expect_raw = np.array([2.0 ** min(10 + (N - 1 - i), 15) for i in range(N)] + [2.0 ** 10])
+    first_overflow = N - 1 - 6
+    expect_retries = {0: 0, rb.GROW_RAW_NORM: (first_overflow + 2) // 2}
+    for gflag, want in ((0, expect_default), (rb.GROW_RAW_NORM, expect_raw)):
+        (gy0, gth, info), _ = _gpu_linear(d, theta, y0, tg, aN, "dynamic", 16, flags | gflag)
+        np.testing.assert_array_equal(info.scale_hist.astype(np.float64), want)
+        assert info.status == 0 and info.retries == expect_retries[gflag]
+        assert torch.equal(gy0.cpu(), torch.from_numpy(aN))

@@ -621,3 +621,45 @@ def test_literal_variants_are_close_to_default():
             base = (yN, res.grad_theta)
         else:
             assert rel(yN, base[0]) < 4 * 2.0 ** -11 and rel(res.grad_theta, base[1]) < 8 * 2.0 ** -11
+
+
+def test_growth_rules_closed_form_on_a_constant_adjoint():
+    # Zero velocity: the adjoint stays 1.5 everywhere and only lambda = Q(S a) can overflow.
+    # S_N = 2^10 (1536 in (1024, 2048]).  Default rule: S ||a|| = 1536 > 1/(2u) = 1024, no growth ever.
+    # Literal rule (||a|| = 1.5 <= 1024 after every clean step): step i is entered with
+    # 2^(10 + N-1-i) until 2^16 * 1.5 > 65504 overflows; that step halves once (accepted at 2^15,
+    # no growth after a retry), the next is entered with 2^15, is clean and doubles, and so on.
+    N, d = 10, 4
+    vel = orc.MLPVelocity((d, d), time_input=False, activation="identity")
+    theta = np.zeros(d * d + d)
+    y0 = np.full((2, d), 0.5)
+    tg = np.arange(N + 1) / N
+    aN = np.full((2, d), 1.5)
+    want = {False: (np.full(N + 1, 2.0 ** 10), 0),
+            True: (np.array([2.0 ** min(10 + (N - 1 - i), 15) for i in range(N)] + [2.0 ** 10]), (N - 1 - 6 + 2) // 2)}
+    for raw in (False, True):
+        pol = orc.Policy(low="f16", scaling="dynamic", k_max=16, grow_raw_norm=raw)
+        _, ck = orc.odeint_fwd(vel, theta, y0, tg, tab("euler"), pol)
+        res = orc.odeint_bwd(vel, theta, tg, tab("euler"), pol, ck, aN)
+        assert res.status == "ok"
+        np.testing.assert_array_equal(res.scale_hist, want[raw][0])
+        assert res.retries == want[raw][1]
+        np.testing.assert_array_equal(res.grad_y0, aN)
+
+
+def test_round_increment_closed_form():
+    # One Heun step of y' = 1 + 2^-10 t from y = 0 on [0, 1]: k1 = 1, k2 = 1 + 2^-10 (adjacent fp16
+    # numbers).  Default: the weighted sum 1 + 2^-11 is formed and added in fp32 -> y_1 = 1 + 2^-11.
+    # Literal Alg. 1 line: the sum is rounded to fp16 first, a tie that goes to the even neighbour 1.
+    d = 3
+    vel = orc.MLPVelocity((d, d), time_input=True)
+    W = np.zeros((d, d + 1))
+    W[:, -1] = 2.0 ** -10
+    theta = np.concatenate([W.ravel(), np.ones(d)])
+    y0 = np.zeros((2, d))
+    tg = np.array([0.0, 1.0])
+    for literal, want in ((False, 1.0 + 2.0 ** -11), (True, 1.0)):
+        pol = orc.Policy(low="f16", round_increment=literal)
+        yN, ck = orc.odeint_fwd(vel, theta, y0, tg, tab("heun"), pol)
+        np.testing.assert_array_equal(yN, np.full((2, d), want))
+        np.testing.assert_array_equal(ck[1], np.full((2, d), 1.0))   # the stored state is fp16 either way
