@@ -69,7 +69,7 @@ def round_bf16_from_f32(x32: np.ndarray) -> np.ndarray:
     return r.view(np.float32).reshape(shape)
 
 
-def make_quantisers(low: str, flush_subnormals: bool = False):
+def make_quantisers(low: str):
     """Return (Q, R32): Q rounds fp64 -> fp32 -> `low`; R32 rounds fp64 -> fp32.
 
     Both return fp64 arrays holding representable values.  In "f64" mode both
@@ -84,8 +84,6 @@ def make_quantisers(low: str, flush_subnormals: bool = False):
         def Q(x):
             with np.errstate(over="ignore"):
                 r = np.asarray(x, dtype=np.float64).astype(np.float32).astype(np.float16)
-            if flush_subnormals:
-                r = np.where(np.abs(r) < np.float16(2.0 ** -14), np.float16(0) * r, r)
             return r.astype(np.float64)
         return Q, round_f32
     if low == "bf16":
@@ -337,7 +335,6 @@ class Policy:
     round_increment: bool = False    # literal Alg. 1: round sum_j b_j k_j to low before the fp32 add
     grow_raw_norm: bool = False      # literal Alg. 2 growth test on the unscaled norm
     naive_state: bool = False        # oracle-only: keep y and a in low precision (no fp32 accumulator)
-    flush_subnormals: bool = False
 
 
 @dataclass
@@ -401,7 +398,7 @@ def odeint_fwd(vel, theta, y0, tgrid, tableau, policy: Policy):
     Returns (y_N in the accumulator precision, checkpoints [N+1, ...] in `low`),
     both as fp64 arrays holding representable values.
     """
-    Q, R32 = make_quantisers(policy.low, policy.flush_subnormals)
+    Q, R32 = make_quantisers(policy.low)
     A, b, c = tableau.A, tableau.b, tableau.c
     tgrid = np.asarray(tgrid, dtype=np.float64)
     N = len(tgrid) - 1
@@ -443,7 +440,7 @@ def odeint_bwd(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad_yN,
     dg), Phi = sum_j b_j k_j from the low-precision slopes, and a_{i+1} is the fp32
     adjoint before this step's update.  `grad_t_init` is the explicit dL/dt it starts from.
     """
-    Q, R32 = make_quantisers(policy.low, policy.flush_subnormals)
+    Q, R32 = make_quantisers(policy.low)
     A, b, c = tableau.A, tableau.b, tableau.c
     s = len(b)
     tgrid = np.asarray(tgrid, dtype=np.float64)

@@ -37,9 +37,27 @@ def _compile(args):
     return res.returncode, res.stdout + res.stderr, obj
 
 
-def build_library(verbose: bool = False, jobs: int = 0) -> str:
+# headers each translation unit includes (directly or not), for the incremental mode
+_DEPS = {
+    "rampde.hip": ("common.hpp", "elementwise.hpp", "fused.hpp", "fused_launch.hpp", "wide.hpp", "gemm.hpp", "conv.hpp",
+                   os.path.join("..", "..", "include", "rampde.h")),
+    "fused_inst.hip": ("common.hpp", "fused.hpp", "fused_launch.hpp"),
+    "wide_inst.hip": ("common.hpp", "fused.hpp", "fused_launch.hpp", "wide.hpp"),
+}
+
+
+def _up_to_date(src: str, obj: str) -> bool:
+    if not os.path.exists(obj):
+        return False
+    t = os.path.getmtime(obj)
+    deps = [src, os.path.abspath(__file__)] + [os.path.join(CSRC, d) for d in _DEPS[os.path.basename(src)]]
+    return all(os.path.getmtime(d) < t for d in deps)
+
+
+def build_library(verbose: bool = False, jobs: int = 0, incremental: bool = False) -> str:
     """Compile the translation units under csrc/ in parallel and link librampde.so next to this
-    file; returns its path."""
+    file; returns its path.  incremental: keep objects newer than their sources and headers (a
+    developer convenience; the default compiles everything)."""
     from concurrent.futures import ThreadPoolExecutor
     objdir = os.path.join(PKG_DIR, "_build")
     os.makedirs(objdir, exist_ok=True)
@@ -52,8 +70,10 @@ def build_library(verbose: bool = False, jobs: int = 0) -> str:
     # (longest first: the widest instantiations take the longest to compile)
     units.sort(key=lambda u: -int(u[2][0].split("=")[1]) if u[2] else 1)
     jobs = jobs or min(len(units), os.cpu_count() or 1, 16)
+    todo = [u for u in units if not (incremental and _up_to_date(u[0], u[1]))]
     with ThreadPoolExecutor(max_workers=jobs) as pool:
-        results = list(pool.map(_compile, units))
+        results = list(pool.map(_compile, todo))
+    results += [(0, "", u[1]) for u in units if u not in todo]
     for rc, out, obj in results:
         if rc != 0:
             sys.stderr.write(out)
@@ -71,4 +91,4 @@ def build_library(verbose: bool = False, jobs: int = 0) -> str:
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    print(build_library(verbose="--quiet" not in sys.argv, incremental="--incremental" in sys.argv))

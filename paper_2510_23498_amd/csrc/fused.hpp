@@ -80,6 +80,7 @@ struct FusedArgs {
   int64_t R;
   int64_t stage_stride;  // R * dpad
   float A[kMaxStages * kMaxStages];
+  int dense_tableau;     // some a_jl != 0 with l < j - 1 (beyond the sub-diagonal): not Euler, Heun, classic RK4
   float b[kMaxStages];
   float c[kMaxStages];
   const float* steptab;  // [N][1 + s]: h_i, tau_{i,1..s} (tau already rounded to low precision)
@@ -90,6 +91,7 @@ struct FusedArgs {
   int round_incr;        // bit 0: round sum_j b_j k_j to low before the fp32 add; bit 1: naive baseline,
                          // the state (y, and the adjoint a) is itself kept in low precision
   uint16_t* K;  // [s][R][dpad] slopes (used when they do not fit in LDS)
+  float* bsum;  // [R][dpad] fp32 (64-row-tile kernels): running sum over the stages of b_l k_l within a step
   // one adjoint step
   int step;
   // Everything the parameter-gradient contraction reads is stored "feature-group-major":

@@ -972,8 +972,8 @@ __global__ __launch_bounds__(256, 2) __attribute__((amdgpu_num_vgpr(104))) void 
 }
 
 
-// The same contraction over SEVERAL steps in one launch (no scale decisions between the steps:
-// every step of the range is accepted before the launch).  A workgroup keeps its (K-chunk, tile)
+// The same contraction over SEVERAL steps in one launch (steps step, step - 1, ... of which the
+// accepted ones at the head of the range are taken: see s_accepted).  A workgroup keeps its (K-chunk, tile)
 // and walks through the steps' buffer sets as one continuous sequence of k-steps, so the load
 // pipeline never drains at a step boundary; the per-step factor h_i / S_i is applied when a
 // step's partial sum is folded into the running total.  One launch then costs one epilogue and
@@ -1002,6 +1002,18 @@ __global__ __launch_bounds__(256, 2) void wgrad_feature_major_steps(WgradArgs g)
   __shared__ __attribute__((aligned(16))) uint16_t sB[128 * LDS_PITCH];
   __shared__ float s_scale[kMaxWgradSteps];
   __shared__ float s_tau[kMaxWgradSteps][kMaxStages];
+  // Steps whose cotangent chain was rejected (or that never ran because an earlier one was) have no
+  // recorded scale: the launch covers the accepted steps at the head of its range only.  The host
+  // redoes the rest, from the rejected step on, with launches of their own.
+  __shared__ int s_accepted;
+  if (tid == 0) {
+    int n = 0;
+    while (n < g.nsteps && g.scale_hist[g.step - n] != 0.f) ++n;
+    s_accepted = n;
+  }
+  __syncthreads();
+  g.nsteps = s_accepted;
+  if (g.nsteps == 0) return;
   // s_scale[i] = c_i / c_{i+1} with c_i = h / S of the launch's i-th step (the last: c_i itself):
   // multiplying the running sums by it when step i is complete leaves, at the end,
   // sum_i c_i * (partial sum of step i) without a second set of accumulators

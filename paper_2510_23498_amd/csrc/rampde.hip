@@ -80,7 +80,7 @@ struct Plan {
   bool wide = false;   // 64-row tiles of the kernels for 512-wide networks (wide.hpp)
   int ldp = 0;         // LDS row pitch (elements)
   size_t lds_bytes = 0;
-  size_t steptab = 0, a_alt = 0;
+  size_t steptab = 0, a_alt = 0, bsum = 0;
   size_t tpart = 0;                 // [N][2] fp32 per-step sums of the time-grid gradient
   int nparam = 0, wt_off = 0;
   bool k_in_lds = false;
@@ -278,6 +278,7 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
     // the adjoint stores everything the parameter-gradient contraction (and tanh') reads
     // feature-group-major
     p.K = take((size_t)p.s * p.R * p.dpad * 2);
+    if (p.wide && !is_backward) p.bsum = take(sizeof(float) * (size_t)p.R * p.dpad);
     if (is_backward) {
       p.ZBAR = take((size_t)p.s * p.R * p.dpad * 2);
       p.Rp = (p.R + 63) / 64 * 64;
@@ -649,10 +650,14 @@ struct Runner {
     for (int i = 0; i < p.s; ++i) {
       a.b[i] = (float)tab->b[i];
       a.c[i] = (float)tab->c[i];
-      for (int j = 0; j < p.s; ++j) a.A[i * p.s + j] = (float)tab->A[i * p.s + j];
+      for (int j = 0; j < p.s; ++j) {
+        a.A[i * p.s + j] = (float)tab->A[i * p.s + j];
+        if (j + 1 < i && tab->A[i * p.s + j] != 0.0) a.dense_tableau = 1;
+      }
     }
     a.steptab = f32(p.steptab);
     a.K = u16(p.K);
+    a.bsum = p.bsum ? f32(p.bsum) : nullptr;
     return a;
   }
 

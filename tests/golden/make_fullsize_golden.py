@@ -10,7 +10,8 @@ workload) and keeps a digest that the GPU tests compare with:
   * the adjoint scale history and the retry count (exact);
   * grad_theta at a seeded sample of indices (plus the first and last entries of every tensor),
     the sums of 512 contiguous blocks of grad_theta, the 2-norm of every parameter tensor;
-  * y_N and dL/dy_0 on a seeded sample of batch rows, and their overall 2-norms.
+  * y_N and dL/dy_0 on a seeded sample of batch rows (for states wider than 4096 elements: on a
+    seeded sample of 4096 of each row's elements), and their overall 2-norms.
 Only oracle/ and the seeded input generators are used: nothing here touches the HIP library.
 """
 import os
@@ -31,6 +32,7 @@ from paper_2510_23498_amd import workloads as wl  # noqa: E402
 N_SAMPLES = 8192
 N_BLOCKS = 512
 N_ROWS = 24
+N_COLS = 4096
 
 
 def sample_indices(cfg: wl.Config, P: int):
@@ -49,6 +51,15 @@ def sample_rows(cfg: wl.Config):
     rows = set((u * cfg.B).astype(np.int64).clip(0, cfg.B - 1).tolist())
     rows.update([0, 15, 16, 63, 64, cfg.B - 1])
     return np.array(sorted(r for r in rows if r < cfg.B), dtype=np.int64)
+
+
+def sample_cols(cfg: wl.Config):
+    """Elements of a state row that are kept: all of them up to 4096, else a seeded sample."""
+    d = cfg.d
+    if d <= N_COLS:
+        return np.arange(d, dtype=np.int64)
+    u = wl.uniforms(cfg.seed + 17, f"{cfg.name}.golden.cols", N_COLS)
+    return np.unique((u * d).astype(np.int64).clip(0, d - 1))
 
 
 def block_sums(g: np.ndarray) -> np.ndarray:
@@ -86,11 +97,13 @@ def run(name: str, tableau: str = None):
     rows = sample_rows(cfg)
     norms = np.array([np.linalg.norm(g[off:off + int(np.prod(shp))]) for _, shp, off in wl.theta_layout(cfg)])
     gy0 = res.grad_y0.reshape(cfg.B, -1)
+    cols = sample_cols(cfg)
     out = golden_path(name, cfg.tableau)
     np.savez_compressed(
         out, scale_hist=res.scale_hist, retries=np.int64(res.retries), theta_idx=idx, grad_theta_at_idx=g[idx],
         grad_theta_block_sums=block_sums(g), grad_theta_tensor_norms=norms, grad_theta_norm=np.linalg.norm(g),
-        rows=rows, yN_rows=yN.reshape(cfg.B, -1)[rows], grad_y0_rows=gy0[rows], yN_norm=np.linalg.norm(yN),
+        rows=rows, cols=cols, yN_rows=yN.reshape(cfg.B, -1)[np.ix_(rows, cols)], grad_y0_rows=gy0[np.ix_(rows, cols)],
+        yN_norm=np.linalg.norm(yN),
         grad_y0_norm=np.linalg.norm(gy0), oracle_seconds=np.float64(time.time() - t0))
     print(f"wrote {out} ({os.path.getsize(out)} bytes)", flush=True)
 

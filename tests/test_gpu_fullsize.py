@@ -126,7 +126,7 @@ def test_full_size_all_steps_parameter_gradient(name, tab):
     np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), ref["scale_hist"])
     assert gpu["retries"] == int(ref["retries"])
     g = gpu["grad_theta"].astype(np.float64)
-    rows = ref["rows"]
+    rows = np.ix_(ref["rows"], ref["cols"] if "cols" in ref.files else np.arange(cfg.d))
     tol, tol_max = par.TOL_EMUL, par.TOL_EMUL_MAX[cfg.low]
     norms = np.array([np.linalg.norm(g[sl]) for _, sl in par.layer_slices(cfg)])
     errs = {

@@ -86,19 +86,35 @@ def test_cfg3_shape_reduced_needs_dynamic_scaling(flags):
 
 @PATHS
 def test_unscaled_fp16_cotangents_in_the_subnormal_range_match_the_emulation(flags):
-    # With the 1e-6 loss gradient and NO scaling most cotangents sit in (or below) the fp16 subnormal
-    # range.  The oracle keeps gradual underflow; so must every conversion and matrix instruction of
-    # the device path, or the two would differ by O(1) here (the fp64 comparison above only shows
-    # that the unscaled result is useless, not that both sides agree on HOW it is useless).
-    cfg = wl.CONFIGS["cfg3"].with_(name="cfg3sub", B=200, N=6)
+    # With the 1e-6 loss gradient and NO scaling most cotangents are a few units of the smallest fp16
+    # subnormal (2^-24).  The oracle keeps gradual underflow; so must every conversion and matrix
+    # instruction of the device path, or the two would differ by O(1) here (the fp64 comparison in
+    # test_cfg3_shape_reduced_needs_dynamic_scaling only shows that the unscaled result is useless, not
+    # that both sides agree on HOW it is useless).
+    # ONE step of a network with ONE hidden layer: beyond that this regime is chaotic with respect to
+    # rounding -- every cotangent is the rounding of a value of about one unit, so the first entry that
+    # rounds the other way (the two sides sum their fp32 accumulators in different orders) moves a whole
+    # row of the next layer by a sizeable fraction of a unit, and so on.  Measured on both kernel paths
+    # alike: one RK4 step of 128-512-128 agrees to 7e-6 (one Euler step bit for bit); one step of the
+    # four-layer cfg3 network to 3e-4 in dL/dy_0 but only 1e-2 in the first layer's gradient; 6 steps 5e-2.
+    cfg = wl.CONFIGS["cfg3"].with_(name="cfg3sub", B=200, N=1, t1=2.0 / 64, widths=(128, 512, 128))
     theta, y0, target = par.make_inputs(cfg)
     print(f"[case] {cfg.name} scaling=none flags={flags}", flush=True)
     gpu = par.run_gpu(cfg, theta, y0, target, scaling="none", flags=flags)
     emu = par.run_oracle(cfg, theta, y0, target, "emul", scaling="none")
-    lam = np.abs(emu["grad_y0"])
-    assert np.median(lam[lam > 0]) < 2.0 ** -14, "the case must exercise subnormal cotangents"
-    errs = par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle (unscaled)", tol_max=None)
+    step = np.abs(emu["grad_y0"] - emu["grad_yN"])
+    assert 0 < np.median(step[step > 0]) < 2.0 ** -20, "the case must exercise subnormal cotangents"
+    # max-norm bound: a hidden cotangent here carries two or three significant bits, so ONE entry that
+    # rounds the other way moves that sample's term of a first-layer gradient entry by up to half of
+    # itself; the bound allows a handful of such entries (measured 4e-3), the 2-norm bound stays 1e-3.
+    errs = par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle (unscaled)", tol_max=1e-2)
     print("  vs emul:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    # the adjoint increment itself (not hidden behind the much larger dL/dy_N), in units of 2^-24: it is
+    # built from those two-or-three-bit cotangents alone, so the bound is 5 * TOL_EMUL (measured 1.2e-3);
+    # flushing subnormals anywhere on the way would leave O(1) here
+    inc_gpu = (gpu["grad_y0"].astype(np.float64) - gpu["grad_yN"]) * 2.0 ** 24
+    inc_emu = (emu["grad_y0"] - emu["grad_yN"]) * 2.0 ** 24
+    assert par.rel_err(inc_gpu, inc_emu) <= 5 * par.TOL_EMUL
 
 
 # ------------------------------------------------------------------ 64-row-tile kernels of 512-wide networks

