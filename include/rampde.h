@@ -147,6 +147,24 @@ int rampde_odeint_fwd(const rampde_velocity *vel, const float *theta, const floa
                       const rampde_policy *pol, void *ckpt, float *yN, void *workspace,
                       size_t workspace_bytes, void *hip_stream);
 
+/* rampde_odeint_fwd for callers that cannot allocate device memory or size a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and stream behaviour as rampde_odeint_fwd (the same kernels run), but the workspace is a static
+ * device array of RAMPDE_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until the
+ * process ends.  The call performs no hipMalloc / hipFree and creates no events (the optional timing
+ * facility does not record it).  The first call on each device looks the array's address up (that
+ * may load the library's code object): make it once before capturing.
+ *   - RAMPDE_EWORKSPACE, with nothing launched, if rampde_workspace_bytes(vel, B, N, tab, pol, 0)
+ *     exceeds RAMPDE_STATIC_SCRATCH_BYTES.  (Full-size dense workloads of the paper fit; the
+ *     128 x 64 x 32 x 32 convolutional one does not.)
+ *   - All calls on one GPU share that GPU's array, on whatever stream: calls that overlap in time on
+ *     one GPU race.  Nothing in the array has to survive from one call to the next, and nothing in it
+ *     is assumed to be zero at entry. */
+#define RAMPDE_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int rampde_odeint_fwd_static(const rampde_velocity *vel, const float *theta, const float *y0,
+                             int64_t B, const double *tgrid, int N, const rampde_tableau *tab,
+                             const rampde_policy *pol, void *ckpt, float *yN, void *hip_stream);
+
 /* Backward pass, Algorithm 2 (without the time-grid gradient: see rampde_odeint_bwd_tgrid).
  *   ckpt       dev, read: the trajectory written by rampde_odeint_fwd with the same arguments
  *   grad_yN    dev, B*d fp32: dL/dy_N (the terminal-cost gradient, formed by the caller)

@@ -83,6 +83,10 @@ def load_library():
     lib.rampde_odeint_fwd.argtypes = [C.POINTER(_Velocity), C.c_void_p, C.c_void_p, C.c_int64,
                                       C.POINTER(C.c_double), C.c_int, C.POINTER(_Tableau), C.POINTER(_Policy),
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.rampde_odeint_fwd_static.restype = C.c_int
+    lib.rampde_odeint_fwd_static.argtypes = [C.POINTER(_Velocity), C.c_void_p, C.c_void_p, C.c_int64,
+                                             C.POINTER(C.c_double), C.c_int, C.POINTER(_Tableau),
+                                             C.POINTER(_Policy), C.c_void_p, C.c_void_p, C.c_void_p]
     lib.rampde_odeint_bwd.restype = C.c_int
     lib.rampde_odeint_bwd.argtypes = [C.POINTER(_Velocity), C.c_void_p, C.c_int64, C.POINTER(C.c_double), C.c_int,
                                       C.POINTER(_Tableau), C.POINTER(_Policy), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -262,6 +266,31 @@ def rampde_odeint_fwd(vel: Velocity, theta: torch.Tensor, y0: torch.Tensor, tgri
     rc = lib.rampde_odeint_fwd(C.byref(vel.c), _ptr(theta), _ptr(y0), B, tg.ctypes.data_as(C.POINTER(C.c_double)), N,
                                C.byref(tab.c), C.byref(pc), _ptr(ckpt), _ptr(yN), _ptr(workspace),
                                workspace.numel(), _stream_ptr(stream))
+    if rc != OK:
+        raise RampdeError(rc, rampde_strerror(rc))
+    return yN, ckpt
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def rampde_odeint_fwd_static(vel: Velocity, theta: torch.Tensor, y0: torch.Tensor, tgrid, tab: Tableau, pol: Policy,
+                             ckpt: torch.Tensor, yN: torch.Tensor, stream=None):
+    """rampde_odeint_fwd on the library's static scratch array: the caller passes every output, nothing
+    is allocated here or in the library.  Raises RampdeError(EWORKSPACE) when the problem needs more
+    than STATIC_SCRATCH_BYTES of workspace."""
+    lib = load_library()
+    B = int(y0.shape[0])
+    tg = np.ascontiguousarray(np.asarray(tgrid, dtype=np.float64))
+    N = int(tg.shape[0]) - 1
+    _check_dev(theta, torch.float32, rampde_num_params(vel), "theta")
+    _check_dev(y0, torch.float32, B * vel.d, "y0")
+    _check_dev(ckpt, pol.torch_low, (N + 1) * B * vel.d, "ckpt")
+    _check_dev(yN, torch.float32, B * vel.d, "yN")
+    pc = pol.c
+    rc = lib.rampde_odeint_fwd_static(C.byref(vel.c), _ptr(theta), _ptr(y0), B,
+                                      tg.ctypes.data_as(C.POINTER(C.c_double)), N, C.byref(tab.c), C.byref(pc),
+                                      _ptr(ckpt), _ptr(yN), _stream_ptr(stream))
     if rc != OK:
         raise RampdeError(rc, rampde_strerror(rc))
     return yN, ckpt

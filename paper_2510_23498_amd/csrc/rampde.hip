@@ -1198,6 +1198,31 @@ static rampde_scaling resolve_scaling(const rampde_policy* pol) {
   return pol->low == RAMPDE_F16 ? RAMPDE_SCALE_DYNAMIC : RAMPDE_SCALE_NONE;
 }
 
+// ---------------------------------------------------------------- scratch of the entry point that allocates nothing
+// rampde_odeint_fwd_static keeps what rampde_odeint_fwd keeps in the caller's workspace (rounded weight
+// fragments, stage values, slopes, running sums) in this array.  Every GPU the library runs on holds its
+// own copy, at its own address, until the process ends.  In host code the array's NAME is only a handle
+// for hipGetSymbolAddress: the device address is looked up once per device and kept below, and only
+// that address is ever handed to kernels.
+constexpr size_t kStaticScratchBytes = RAMPDE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return RAMPDE_EUNSUPPORTED;
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr || ((uintptr_t)ptr & 255)) return RAMPDE_EWORKSPACE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return RAMPDE_OK;
+}
+
 }  // namespace rampde
 
 using namespace rampde;
@@ -1242,6 +1267,27 @@ int rampde_odeint_fwd(const rampde_velocity* vel, const float* theta, const floa
   Runner<BF16> r(p, workspace, st);
   r.use_fused = fused;
   return r.forward(theta, y0, tgrid, N, tab, pol, (uint16_t*)ckpt, yN);
+}
+
+int rampde_odeint_fwd_static(const rampde_velocity* vel, const float* theta, const float* y0, int64_t B,
+                             const double* tgrid, int N, const rampde_tableau* tab, const rampde_policy* pol,
+                             void* ckpt, float* yN, void* hip_stream) {
+  // size check first, on the host: nothing is launched for a problem the array cannot hold
+  int rc = check_common(vel, tgrid, N, tab, pol);
+  if (rc) return rc;
+  if (B < 1) return RAMPDE_EINVAL;
+  const Plan p = make_plan(vel, B, N, tab, pol, 0);
+  if (!p.ok) return RAMPDE_EINVAL;
+  if (p.total > kStaticScratchBytes) return RAMPDE_EWORKSPACE;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc) return rc;
+  // the timing facility creates events: not in a call that promises to allocate nothing
+  const bool timing = g_timing;
+  g_timing = false;
+  rc = rampde_odeint_fwd(vel, theta, y0, B, tgrid, N, tab, pol, ckpt, yN, ws, kStaticScratchBytes, hip_stream);
+  g_timing = timing;
+  return rc;
 }
 
 int rampde_odeint_bwd(const rampde_velocity* vel, const float* theta, int64_t B, const double* tgrid, int N,
