@@ -233,7 +233,7 @@ def main():
     }
 
     if not args.no_cpu:
-        default_steps = {"cfg1": cfg.N, "cfg2": cfg.N, "cfg3": 2, "cfg4": 1, "cfg5": 16}.get(cfg.name, 1)
+        default_steps = {"cfg1": cfg.N, "cfg2": cfg.N, "cfg3": 6, "cfg4": 1, "cfg5": 16}.get(cfg.name, 1)
         out["cpu_baseline"] = cpu_baseline(cfg, *inputs, args.cpu_steps or default_steps)
     del inputs
 
