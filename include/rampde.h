@@ -110,6 +110,13 @@ typedef struct {
   int row_tile;           /* dense networks: batch rows per workgroup of the row-tile kernels: 16, 32 or 64.
                              64 selects the kernels built for 512-wide networks (state width 128) where
                              they apply; values that do not apply fall back to the automatic choice  */
+  /* Scope of the adjoint scale within a batch (Alg. 2 is stated for one sample).  0: one scale S for the
+   * whole batch (the default).  G > 0: every G consecutive samples (the last group: the remainder) share a
+   * scale of their own -- initial value from the group's own max-norm, own overflow retries, own growth --
+   * and the group's share of dL/dtheta (and dL/dt) is unscaled with its own h / S before it is added to
+   * the other groups'.  Absent overflow and underflow the result is that of G = 0 up to fp32 summation
+   * order.  This one changes WHAT is computed, unlike the two fields above. */
+  int scale_group;
 } rampde_policy;
 
 typedef struct {
@@ -173,8 +180,12 @@ int rampde_odeint_fwd_static(const rampde_velocity *vel, const float *theta, con
  *   grad_y0    dev, B*d fp32, written: dL/dy_0
  *   grad_theta dev, P fp32, ACCUMULATED into (Alg. 2 starts g at the caller's dL/dtheta):
  *              zero it for a plain gradient
- *   scale_hist host or NULL, N+1 floats: [N] = S_N, [i] = accepted S_i
- *   stats      host or NULL
+ *   scale_hist host or NULL, N+1 floats: [N] = S_N, [i] = accepted S_i; with policy.scale_group = G in
+ *              (0, B): ceil(B / G) * (N+1) floats, one such row per group, in batch order
+ *   stats      host or NULL; with scale groups: retries summed, s_min / s_max over all groups, s_first /
+ *              s_last of the first group, status / failed_step of the worst group (the groups run one after
+ *              the other on the caller's stream and workspace; workspace size from rampde_workspace_bytes
+ *              with the same policy)
  * Returns RAMPDE_ESCALE if no finite scale was found within k_max attempts at some step
  * (outputs then undefined).  Under NONE_SAFE an overflow is not an error: grad_y0 and
  * grad_theta are filled with +inf and stats.status = 1. */

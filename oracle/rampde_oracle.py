@@ -335,13 +335,14 @@ class Policy:
     round_increment: bool = False    # literal Alg. 1: round sum_j b_j k_j to low before the fp32 add
     grow_raw_norm: bool = False      # literal Alg. 2 growth test on the unscaled norm
     naive_state: bool = False        # oracle-only: keep y and a in low precision (no fp32 accumulator)
+    scale_group: int = 0             # samples that share one adjoint scale; 0 = the whole batch (see odeint_bwd)
 
 
 @dataclass
 class BwdResult:
     grad_y0: np.ndarray
     grad_theta: np.ndarray
-    scale_hist: np.ndarray           # [N+1]: S_N at index N, accepted S_i at index i
+    scale_hist: np.ndarray           # [N+1]: S_N at index N, accepted S_i at index i ([groups, N+1] with scale groups)
     retries: int
     status: str                      # "ok" | "overflow_inf" | "scale_failed"
     failed_step: int = -1
@@ -425,6 +426,47 @@ def odeint_fwd(vel, theta, y0, tgrid, tableau, policy: Policy):
 
 def odeint_bwd(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad_yN,
                grad_theta_init=None, grad_ys=None, grad_t_init=None) -> BwdResult:
+    """Algorithm 2 on a batch, with the scope of the adjoint scale made explicit.
+
+    The paper states Alg. 2 for one sample: one adjoint vector, one scale S.  With a batch,
+    policy.scale_group = 0 treats the whole batch tensor as that vector (one S for all samples).
+    policy.scale_group = G > 0 applies Alg. 2 to every block of G consecutive samples (the last block:
+    the remainder) on its own: own S_N from the block's max-norm, own retries, own growth; the blocks
+    share theta, and each adds its h/S-unscaled share to the one gradient accumulator g (and t'), in
+    batch order.  Samples do not interact in the velocity, so without overflow or underflow both give
+    the same gradient up to the order of the fp32 sums.
+    """
+    B = np.shape(grad_yN)[0]
+    G = int(policy.scale_group)
+    if not 0 < G < B:
+        return _odeint_bwd_one_scale(vel, theta, tgrid, tableau, policy, ckpt, grad_yN, grad_theta_init, grad_ys,
+                                     grad_t_init)
+    ckpt = np.asarray(ckpt)
+    grad_yN = np.asarray(grad_yN)
+    g, tp = grad_theta_init, grad_t_init
+    a0, hists, retries = [], [], 0
+    for b0 in range(0, B, G):
+        rows = slice(b0, min(b0 + G, B))
+        res = _odeint_bwd_one_scale(vel, theta, tgrid, tableau, policy, ckpt[:, rows], grad_yN[rows], g,
+                                    None if grad_ys is None else np.asarray(grad_ys)[:, rows], tp)
+        retries += res.retries
+        hists.append(res.scale_hist)
+        if res.status == "scale_failed":
+            # (outputs are undefined after a failure: the groups that never ran are left as NaN)
+            part = np.full(np.shape(grad_yN), np.nan)
+            part[:rows.start] = np.concatenate(a0, axis=0) if a0 else part[:0]
+            part[rows] = res.grad_y0
+            return BwdResult(part, res.grad_theta, np.stack(hists), retries, res.status, res.failed_step)
+        if res.status == "overflow_inf":
+            return BwdResult(np.full(np.shape(grad_yN), np.inf), res.grad_theta, np.stack(hists), retries,
+                             res.status, res.failed_step)
+        a0.append(res.grad_y0)
+        g, tp = res.grad_theta, res.grad_t
+    return BwdResult(np.concatenate(a0, axis=0), g, np.stack(hists), retries, "ok", -1, tp)
+
+
+def _odeint_bwd_one_scale(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad_yN,
+                          grad_theta_init=None, grad_ys=None, grad_t_init=None) -> BwdResult:
     """Mixed-precision discrete adjoint with dynamic adjoint scaling (paper Algorithm 2).
 
     `grad_ys` (optional, [N+1, ...]) are per-step cotangents dL/dy_i of a running

@@ -43,7 +43,7 @@ class _Velocity(C.Structure):
 
 class _Policy(C.Structure):
     _fields_ = [("low", C.c_int), ("scaling", C.c_int), ("k_max", C.c_int), ("flags", C.c_uint),
-                ("step_group", C.c_int), ("row_tile", C.c_int)]
+                ("step_group", C.c_int), ("row_tile", C.c_int), ("scale_group", C.c_int)]
 
 
 class _Stats(C.Structure):
@@ -166,11 +166,12 @@ class Policy:
     flags: int = 0
     step_group: int = 0
     row_tile: int = 0
+    scale_group: int = 0
 
     @property
     def c(self):
         return _Policy(_LOW[self.low], _SCALING[self.scaling], int(self.k_max), int(self.flags),
-                       int(self.step_group), int(self.row_tile))
+                       int(self.step_group), int(self.row_tile), int(self.scale_group))
 
     @property
     def torch_low(self):
@@ -326,7 +327,10 @@ def rampde_odeint_bwd(vel: Velocity, theta: torch.Tensor, tgrid, tab: Tableau, p
         workspace = alloc_workspace(vel, B, N, tab, pol, True, grad_yN.device)
     pc = pol.c
     stats = _Stats()
-    hist = np.zeros(N + 1, dtype=np.float32) if want_info else None
+    G = int(pol.scale_group)
+    groups = (B + G - 1) // G if 0 < G < B else 1
+    # one row of N + 1 scales per scale group (a plain vector without groups)
+    hist = np.zeros(N + 1 if groups == 1 else (groups, N + 1), dtype=np.float32) if want_info else None
     hist_p = hist.ctypes.data_as(C.POINTER(C.c_float)) if want_info else None
     stats_p = C.byref(stats) if want_info else None
     if grad_t is not None:

@@ -88,6 +88,8 @@ struct FusedArgs {
   const float* y0;
   float* y;
   uint16_t* ckpt;
+  int64_t ckpt_stride;   // adjoint kernels: elements from one stored state to the next (R * d, or more when
+                         // the rows of this launch are a slice of a larger batch)
   int round_incr;        // bit 0: round sum_j b_j k_j to low before the fp32 add; bit 1: naive baseline,
                          // the state (y, and the adjoint a) is itself kept in low precision
   uint16_t* K;  // [s][R][dpad] slopes (used when they do not fit in LDS)
@@ -767,7 +769,6 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
   eng.wave = tid >> 6;
   const int lm = eng.lane & 15, lq = eng.lane >> 4;
   const int64_t row0 = (int64_t)blockIdx.x * TM;
-  const int64_t n_state = g.R * g.d;
   const int L = g.L, s = g.s, D = g.dpad;
   const float S = g.ctl->S;
   StageStore<MT> ks{lds.kl, g.k_in_lds != 0, g.K, D, g.stage_stride, row0, g.R};
@@ -809,7 +810,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
         for (int r = 0; r < 4; ++r) sa[r] = S * av[nt][mt][r];
         lamq[nt][mt] = pack4<T>(sa);
         bad = bad || any_nonfinite4<T>(lamq[nt][mt]);
-        yhat[nt][mt] = load4h(g.ckpt + (size_t)step * n_state, row0 + m, g.R, n, g.d);
+        yhat[nt][mt] = load4h(g.ckpt + (size_t)step * g.ckpt_stride, row0 + m, g.R, n, g.d);
       }
 
     // cotangent of the slope of stage j:  kbar_j = Q( b_j lambda + h sum_{l>j} a_lj zbar_l ),

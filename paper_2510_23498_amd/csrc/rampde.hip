@@ -391,6 +391,10 @@ static int hip_fail(hipError_t e, const char* where) {
 
 static inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
+__global__ void fill_u32(uint32_t* p, size_t n, uint32_t v) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
 __global__ void fill_zero_u32(uint32_t* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
@@ -469,8 +473,11 @@ struct Runner {
   char* ws;
   hipStream_t st;
   Ctl* ctl;
+  // elements from one stored state (and one running-cost cotangent) to the next: the rows of this pass
+  // may be a slice (a scale group) of the batch that the caller's buffers hold
+  int64_t step_elems;
   Runner(const Plan& plan, void* workspace, hipStream_t stream)
-      : p(plan), ws((char*)workspace), st(stream), ctl((Ctl*)((char*)workspace + plan.ctl)) {}
+      : p(plan), ws((char*)workspace), st(stream), ctl((Ctl*)((char*)workspace + plan.ctl)), step_elems(plan.n) {}
 
   uint16_t* u16(size_t off) const { return (uint16_t*)(ws + off); }
   float* f32(size_t off) const { return (float*)(ws + off); }
@@ -772,7 +779,7 @@ struct Runner {
     const float h = (float)(tgrid[i + 1] - tgrid[i]);
     Coefs taus{};
     if (recompute) {
-      stages(ckpt + (size_t)i * p.n, tgrid[i], h, tab, pol->low, 1, taus.v, ctl);
+      stages(ckpt + (size_t)i * step_elems, tgrid[i], h, tab, pol->low, 1, taus.v, ctl);
     } else {
       for (int j = 0; j < s; ++j) taus.v[j] = round_low_host((float)(tgrid[i] + tab->c[j] * (double)h), pol->low);
     }
@@ -1028,6 +1035,7 @@ struct Runner {
       write_steptab(tgrid, N, tab, pol->low);
       fa = fused_args(tab, N);
       fa.ckpt = const_cast<uint16_t*>(ckpt);
+      fa.ckpt_stride = step_elems;
       fa.ldk = p.ldk;
       fa.Rp = p.Rp;
       fa.ZBAR = u16(p.ZBAR);
@@ -1058,7 +1066,7 @@ struct Runner {
     float* gys_rows = nullptr;
     auto gys_at = [&](int i) -> const float* {
       if (!grad_ys) return nullptr;
-      const float* src = grad_ys + (size_t)i * p.n;
+      const float* src = grad_ys + (size_t)i * step_elems;
       if (!p.conv) return src;
       nchw_to_rows<<<blocks_for(p.n, 256), 256, 0, st>>>(src, gys_rows, p.R, p.d, HW);
       return gys_rows;
@@ -1095,7 +1103,7 @@ struct Runner {
           fa.a_out = ((groups - 1 - gi) % 2 == 0) ? grad_y0 : f32(p.a_alt);
           cur = fa.a_out;
           fa.gys = gys_at(hi);
-          fa.gys_stride = p.n;
+          fa.gys_stride = step_elems;
           fa.skip_recompute = 0;
           int rc = adjoint_step_fused(fa);
           if (rc) return rc;
@@ -1237,6 +1245,16 @@ int64_t rampde_num_params(const rampde_velocity* vel) {
 
 size_t rampde_workspace_bytes(const rampde_velocity* vel, int64_t B, int N, const rampde_tableau* tab,
                               const rampde_policy* pol, int is_backward) {
+  if (is_backward && pol && pol->scale_group > 0 && pol->scale_group < B) {
+    // the backward pass runs scale group by scale group on the same workspace: room for the largest
+    // (the groups have scale_group samples, the last one the remainder)
+    rampde_policy one = *pol;
+    one.scale_group = 0;
+    const size_t full = rampde_workspace_bytes(vel, pol->scale_group, N, tab, &one, 1);
+    const int64_t tail = B % pol->scale_group;
+    const size_t rest = tail ? rampde_workspace_bytes(vel, tail, N, tab, &one, 1) : 1;
+    return (full && rest) ? std::max(full, rest) : 0;
+  }
   Plan p = make_plan(vel, B, N, tab, pol, is_backward);
   if (!p.ok) return 0;
   size_t total = p.total;
@@ -1298,6 +1316,31 @@ int rampde_odeint_bwd(const rampde_velocity* vel, const float* theta, int64_t B,
                                  scale_hist, stats, workspace, workspace_bytes, hip_stream);
 }
 
+// one backward pass over rows that are the whole batch or one scale group of it
+static int backward_rows(const rampde_velocity* vel, const float* theta, int64_t B, int64_t step_elems,
+                         const double* tgrid, int N, const rampde_tableau* tab, const rampde_policy* pol,
+                         const void* ckpt, const float* grad_yN, const float* grad_ys, float* grad_y0,
+                         float* grad_theta, float* grad_t, float* scale_hist, rampde_stats* stats, void* workspace,
+                         size_t workspace_bytes, hipStream_t st) {
+  Plan p = make_plan(vel, B, N, tab, pol, 1, grad_t == nullptr);
+  if (!p.ok) return RAMPDE_EINVAL;
+  if (workspace_bytes < p.total || ((uintptr_t)workspace & 255)) return RAMPDE_EWORKSPACE;
+  const rampde_scaling sc = resolve_scaling(pol);
+  const bool fused = p.fused;
+  if (pol->low == RAMPDE_F16) {
+    Runner<F16> r(p, workspace, st);
+    r.use_fused = fused;
+    if (step_elems) r.step_elems = step_elems;
+    return r.backward(theta, tgrid, N, tab, pol, sc, (const uint16_t*)ckpt, grad_yN, grad_ys, grad_y0, grad_theta,
+                      grad_t, scale_hist, stats);
+  }
+  Runner<BF16> r(p, workspace, st);
+  r.use_fused = fused;
+  if (step_elems) r.step_elems = step_elems;
+  return r.backward(theta, tgrid, N, tab, pol, sc, (const uint16_t*)ckpt, grad_yN, grad_ys, grad_y0, grad_theta,
+                    grad_t, scale_hist, stats);
+}
+
 int rampde_odeint_bwd_tgrid(const rampde_velocity* vel, const float* theta, int64_t B, const double* tgrid, int N,
                             const rampde_tableau* tab, const rampde_policy* pol, const void* ckpt,
                             const float* grad_yN, const float* grad_ys, float* grad_y0, float* grad_theta,
@@ -1306,22 +1349,63 @@ int rampde_odeint_bwd_tgrid(const rampde_velocity* vel, const float* theta, int6
   int rc = check_common(vel, tgrid, N, tab, pol);
   if (rc) return rc;
   if (!theta || !ckpt || !grad_yN || !grad_y0 || !grad_theta || !workspace || B < 1) return RAMPDE_EINVAL;
-  Plan p = make_plan(vel, B, N, tab, pol, 1, grad_t == nullptr);
-  if (!p.ok) return RAMPDE_EINVAL;
-  if (workspace_bytes < p.total || ((uintptr_t)workspace & 255)) return RAMPDE_EWORKSPACE;
+  if (pol->scale_group < 0) return RAMPDE_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
-  const rampde_scaling sc = resolve_scaling(pol);
-  const bool fused = p.fused;
-  if (pol->low == RAMPDE_F16) {
-    Runner<F16> r(p, workspace, st);
-    r.use_fused = fused;
-    return r.backward(theta, tgrid, N, tab, pol, sc, (const uint16_t*)ckpt, grad_yN, grad_ys, grad_y0, grad_theta,
-                      grad_t, scale_hist, stats);
+  const int64_t G = pol->scale_group;
+  if (G == 0 || G >= B)
+    return backward_rows(vel, theta, B, 0, tgrid, N, tab, pol, ckpt, grad_yN, grad_ys, grad_y0, grad_theta, grad_t,
+                         scale_hist, stats, workspace, workspace_bytes, st);
+
+  // Scale groups (the batch-size-one setting of Alg. 2 carried over to a batch: G consecutive samples
+  // share one scale; each group has its own initial scale, overflow retries and growth, and its share
+  // of dL/dtheta is unscaled with its own h / S before it is added to the others').  The groups are
+  // independent adjoint problems that share theta: they run one after the other on the caller's
+  // stream and workspace, each on its slice of the caller's buffers.
+  rampde_policy one = *pol;
+  one.scale_group = 0;
+  Plan whole = make_plan(vel, B, N, tab, &one, 1, grad_t == nullptr);
+  if (!whole.ok) return RAMPDE_EINVAL;
+  const int64_t per_sample = whole.n / B;
+  const int64_t step_elems = whole.n;
+  const size_t low_bytes = 2;
+  rampde_stats all{};
+  all.failed_step = -1;
+  bool any_overflow = false;
+  // (the unscaled-safe variant reads its outcome back in any case: no extra synchronisation)
+  const bool want_stats = stats || resolve_scaling(pol) == RAMPDE_SCALE_NONE_SAFE;
+  int group = 0;
+  for (int64_t b0 = 0; b0 < B; b0 += G, ++group) {
+    const int64_t Bg = std::min<int64_t>(G, B - b0);
+    const int64_t off = b0 * per_sample;
+    rampde_stats gs{};
+    rc = backward_rows(vel, theta, Bg, step_elems, tgrid, N, tab, &one, (const char*)ckpt + (size_t)off * low_bytes,
+                       grad_yN + off, grad_ys ? grad_ys + off : nullptr, grad_y0 + off, grad_theta, grad_t,
+                       scale_hist ? scale_hist + (size_t)group * (N + 1) : nullptr, want_stats ? &gs : nullptr, workspace,
+                       workspace_bytes, st);
+    if (stats) {
+      if (group == 0) {
+        all = gs;
+      } else {
+        all.retries += gs.retries;
+        all.s_min = std::min(all.s_min, gs.s_min);
+        all.s_max = std::max(all.s_max, gs.s_max);
+        if (gs.status > all.status) {
+          all.status = gs.status;
+          all.failed_step = gs.failed_step;
+        }
+      }
+      *stats = all;
+    }
+    if (rc) return rc;
+    if (want_stats && gs.status == 1) any_overflow = true;
   }
-  Runner<BF16> r(p, workspace, st);
-  r.use_fused = fused;
-  return r.backward(theta, tgrid, N, tab, pol, sc, (const uint16_t*)ckpt, grad_yN, grad_ys, grad_y0, grad_theta,
-                    grad_t, scale_hist, stats);
+  if (any_overflow) {
+    // unscaled-safe variant: an overflow anywhere leaves +inf everywhere (the group's own pass has
+    // filled dL/dtheta and its own rows of dL/dy_0)
+    fill_u32<<<1024, 256, 0, st>>>((uint32_t*)grad_y0, (size_t)whole.n, 0x7f800000u);
+    HIP_TRY(hipGetLastError());
+  }
+  return RAMPDE_OK;
 }
 
 const char* rampde_strerror(int code) {

@@ -660,7 +660,6 @@ __global__ __launch_bounds__(64 * kWideWaves) void mlp_adjoint_wide(FusedArgs g)
   eng.setup();
   const int tid = threadIdx.x;
   const int64_t row0 = (int64_t)blockIdx.x * Sh::TM;
-  const int64_t n_state = g.R * D;
   const int L = g.L, s = g.s;
   const float S = g.ctl->S;
   const int step = g.step;
@@ -669,7 +668,7 @@ __global__ __launch_bounds__(64 * kWideWaves) void mlp_adjoint_wide(FusedArgs g)
   const int64_t set_off = (int64_t)(step % g.nsets) * g.set_stride;
   uint16_t* const ZT = g.ZT + set_off;
   uint16_t* const KBART = g.KBART + set_off;
-  const uint16_t* ck = g.ckpt + (size_t)step * n_state;
+  const uint16_t* ck = g.ckpt + (size_t)step * g.ckpt_stride;
   const int dense = pinned(g.dense_tableau);
   uint32_t nf = 0;  // exponent-field carries of every low-precision cotangent this lane formed
 

@@ -299,3 +299,93 @@ def test_raw_norm_growth_rule_differs_from_the_default(flags):
         np.testing.assert_array_equal(info.scale_hist.astype(np.float64), want)
         assert info.status == 0 and info.retries == expect_retries[gflag]
         assert torch.equal(gy0.cpu(), torch.from_numpy(aN))
+
+
+# ------------------------------------------------------------------ scale groups (policy.scale_group)
+def _group_inputs(cfg, spread):
+    """Inputs whose loss gradient differs from sample to sample by powers of two up to 2^-spread, so that
+    the groups start from different scales: the running-cost cotangents of sample b (added to the adjoint
+    at every step) are scaled by 2^-(b * spread // B); the terminal-cost gradient, which weighs all
+    samples alike, is made negligible beside them (the caller passes a cfg with a tiny grad_scale)."""
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    shape = (cfg.N + 1,) + tuple(np.shape(y0))
+    u = wl.uniforms(cfg.seed + 29, f"{cfg.name}.scale_groups.gys", int(np.prod(shape))).reshape(shape)
+    w = 2.0 ** -(np.arange(cfg.B) * spread // cfg.B)
+    gys = (0.05 * (u - 0.5) * w.reshape((1, cfg.B) + (1,) * (len(shape) - 2))).astype(np.float32)
+    return theta, y0, target, gys
+
+
+GROUP_CASES = [
+    # (workload, overrides, G, flags, row_tile): a group size that does not divide the batch; groups of one
+    # 64-row tile of the wide kernels; the per-layer kernels; the convolution path with one sample per group
+    ("cfg1", dict(name="groups_cfg1", B=70), 32, 0, 0),
+    ("cfg3", dict(name="groups_cfg3", B=200, N=4), 64, 0, 64),
+    ("cfg3", dict(name="groups_cfg3_tile", B=100, N=3), 48, 0, 16),
+    ("cfg2", dict(name="groups_cfg2_layer", B=90, N=4, low="f16", scaling="dynamic"), 40, 4, 0),
+    ("cfg4", dict(name="groups_conv", B=3, N=3, C=8, H=8, W=16), 1, 0, 0),
+]
+
+
+@pytest.mark.parametrize("base,kw,G,flags,row_tile", GROUP_CASES, ids=[c[1]["name"] for c in GROUP_CASES])
+def test_scale_groups_match_the_oracle_with_the_same_groups(base, kw, G, flags, row_tile):
+    cfg = wl.CONFIGS[base].with_(grad_scale=1e-12, **kw)
+    theta, y0, target, gys = _group_inputs(cfg, spread=24)
+    print(f"[case] scale groups {cfg.name} B={cfg.B} G={G} flags={flags} row_tile={row_tile}", flush=True)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul", flags={"scale_group": G}, grad_ys=gys)
+    assert emu["status"] == "ok"
+    groups = -(-cfg.B // G)
+    assert emu["scale_hist"].shape == (groups, cfg.N + 1)
+    assert len({tuple(r) for r in emu["scale_hist"]}) > 1, "the groups must not all share one scale history"
+    gpu = par.run_gpu(cfg, theta, y0, target, flags=flags, row_tile=row_tile, grad_ys=gys, scale_group=G,
+                      want_grad_t=True)
+    assert gpu["status"] == 0
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
+    assert gpu["retries"] == emu["retries"]
+    errs = par.compare(cfg, gpu, emu, par.TOL_EMUL, f"emulation oracle (scale groups of {G})")
+    errs["grad_t"] = par.rel_err(gpu["grad_t"], emu["grad_t"])
+    print("  vs emul:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert errs["grad_t"] <= 5 * par.TOL_EMUL
+    # one scale for the whole batch: the small samples' cotangents sink towards the subnormals and the
+    # result moves away from the fp64 gradient, which the grouped one stays close to
+    f64 = par.run_oracle(cfg, theta, y0, target, "f64", grad_ys=gys)
+    last = slice(-(cfg.B - (groups - 1) * G), None)
+    e_grp = par.rel_err(gpu["grad_y0"][last], f64["grad_y0"][last])
+    one = par.run_gpu(cfg, theta, y0, target, flags=flags, row_tile=row_tile, grad_ys=gys)
+    e_one = par.rel_err(one["grad_y0"][last], f64["grad_y0"][last])
+    print(f"  last group's dL/dy_0 vs fp64: own scale {e_grp:.2e}, batch-wide scale {e_one:.2e}", flush=True)
+    assert e_grp <= par.TOL_F64[cfg.low] and e_grp <= e_one * 1.5
+
+
+def test_scale_groups_retry_failure_and_overflow_are_per_group():
+    # the amplifying network of the mid-pass retry tests, two groups; every group retries on its own
+    cfg, theta, y0, target = _gain_case("cfg3", name="groups_retry", B=150, N=5, t1=0.09, gain=256.0, scaling="dynamic")
+    G = 80
+    print(f"[case] scale groups with retries {cfg.name} B={cfg.B} G={G}", flush=True)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul", flags={"scale_group": G})
+    assert emu["status"] == "ok" and emu["retries"] >= 4 and emu["scale_hist"].shape == (2, cfg.N + 1)
+    gpu = par.run_gpu(cfg, theta, y0, target, scale_group=G)
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
+    assert gpu["retries"] == emu["retries"] and gpu["status"] == 0
+    par.compare(cfg, gpu, emu, par.TOL_F64[cfg.low], "emulation oracle (amplifying network, scale groups)")
+    # k_max = 1: the first group fails
+    emu1 = par.run_oracle(cfg, theta, y0, target, "emul", k_max=1, flags={"scale_group": G})
+    gpu1 = par.run_gpu(cfg, theta, y0, target, k_max=1, expect_error=True, scale_group=G)
+    assert emu1["status"] == "scale_failed" and gpu1.get("error") == rb.ESCALE
+    assert gpu1["info"].failed_step == emu1["failed_step"] and gpu1["info"].status == 2
+    # unscaled-safe: an overflow in a group leaves +inf in ALL of dL/dy_0 and dL/dtheta
+    big = cfg.with_(grad_scale=1e3 * cfg.B * cfg.d, scaling="none_safe")
+    emu2 = par.run_oracle(big, theta, y0, target, "emul", flags={"scale_group": G})
+    gpu2 = par.run_gpu(big, theta, y0, target, scale_group=G)
+    assert emu2["status"] == "overflow_inf" and gpu2["status"] == 1
+    assert np.all(np.isposinf(gpu2["grad_y0"])) and np.all(np.isposinf(gpu2["grad_theta"]))
+
+
+def test_scale_group_sizes_that_cover_the_batch_are_the_default_path():
+    cfg = wl.CONFIGS["cfg1"].with_(name="groups_whole", B=40)
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    base = par.run_gpu(cfg, theta, y0, target)
+    for G in (40, 1000):
+        got = par.run_gpu(cfg, theta, y0, target, scale_group=G)
+        assert got["scale_hist"].shape == (cfg.N + 1,)
+        np.testing.assert_array_equal(got["grad_theta"], base["grad_theta"])
+        np.testing.assert_array_equal(got["grad_y0"], base["grad_y0"])

@@ -663,3 +663,120 @@ def test_round_increment_closed_form():
         yN, ck = orc.odeint_fwd(vel, theta, y0, tg, tab("heun"), pol)
         np.testing.assert_array_equal(yN, np.full((2, d), want))
         np.testing.assert_array_equal(ck[1], np.full((2, d), 1.0))   # the stored state is fp16 either way
+
+
+# ------------------------------------------------------------------ scale groups (scope of S within a batch)
+def test_scale_groups_closed_form_each_group_scales_by_its_own_norm():
+    # Zero velocity, constant adjoint: group g keeps S = 2^floor(-log2(u_L amax_g)) for the whole pass
+    # (default growth rule: S amax = 1536 > 1024 never grows).  Samples 1.5, 1.5 | 1.5 2^-6, 1.5 2^-6 | 12.
+    N, d = 4, 3
+    vel = orc.MLPVelocity((d, d), time_input=False, activation="identity")
+    theta = np.zeros(d * d + d)
+    y0 = np.full((5, d), 0.5)
+    tg = np.arange(N + 1) / N
+    aN = np.array([1.5, 1.5, 1.5 * 2.0 ** -6, 1.5 * 2.0 ** -6, 12.0])[:, None] * np.ones((5, d))
+    pol = orc.Policy(low="f16", scaling="dynamic", scale_group=2)
+    _, ck = orc.odeint_fwd(vel, theta, y0, tg, tab("euler"), pol)
+    res = orc.odeint_bwd(vel, theta, tg, tab("euler"), pol, ck, aN)
+    assert res.status == "ok" and res.retries == 0
+    want = np.array([2.0 ** 10, 2.0 ** 16, 2.0 ** 7])[:, None] * np.ones((3, N + 1))
+    np.testing.assert_array_equal(res.scale_hist, want)
+    np.testing.assert_array_equal(res.grad_y0, aN)
+    whole = orc.odeint_bwd(vel, theta, tg, tab("euler"), orc.Policy(low="f16", scaling="dynamic"), ck, aN)
+    np.testing.assert_array_equal(whole.scale_hist, np.full(N + 1, 2.0 ** 7))   # one S from the largest sample
+    # a group size that does not divide the batch, and one that covers it
+    for G, rows in ((4, 2), (5, None), (7, None)):
+        r = orc.odeint_bwd(vel, theta, tg, tab("euler"), orc.Policy(low="f16", scaling="dynamic", scale_group=G), ck, aN)
+        assert r.scale_hist.shape == ((N + 1,) if rows is None else (rows, N + 1))
+    r4 = orc.odeint_bwd(vel, theta, tg, tab("euler"), orc.Policy(low="f16", scaling="dynamic", scale_group=4), ck, aN)
+    np.testing.assert_array_equal(r4.scale_hist[:, 0], [2.0 ** 10, 2.0 ** 7])
+
+
+def test_scale_groups_overflow_retry_and_failure_are_local_to_a_group():
+    # f = tanh(128 y) (W1 = 128 I, W2 = I).  Sample A sits at y ~ 1e-5 (tanh' = 1): its cotangent picks up
+    # the gain 128, 1536 * 128 overflows fp16, two halvings make it fit (384 * 128 = 49152).  Sample B sits
+    # at y = 1 (tanh saturated, tanh' rounds to 0): its stage cotangent is zero, nothing overflows.
+    # Step 1 (first): A enters with 2^10, accepts 2^8, a_A = 1.5 + (h / 2^8) 49152 = 1.6875 (h = 2^-10);
+    # step 0: lambda = 432, 432 * 128 = 55296 fits: accepted at 2^8, a_A = 1.6875 + 0.2109375.
+    d = 3
+    vel = orc.MLPVelocity((d, d, d), time_input=False)
+    W1, W2 = 128.0 * np.eye(d), np.eye(d)
+    theta = np.concatenate([W1.ravel(), np.zeros(d), W2.ravel(), np.zeros(d)])
+    y0 = np.stack([np.full(d, 1e-5), np.full(d, 1.0)])
+    tg = np.array([0.0, 2.0 ** -10, 2.0 ** -9])
+    aN = np.full((2, d), 1.5)
+    pol = orc.Policy(low="f16", scaling="dynamic", scale_group=1)
+    _, ck = orc.odeint_fwd(vel, theta, y0, tg, tab("euler"), pol)
+    res = orc.odeint_bwd(vel, theta, tg, tab("euler"), pol, ck, aN)
+    assert res.status == "ok" and res.retries == 2
+    np.testing.assert_array_equal(res.scale_hist, [[2.0 ** 8, 2.0 ** 8, 2.0 ** 10], [2.0 ** 10] * 3])
+    np.testing.assert_array_equal(res.grad_y0, [[1.8984375] * d, [1.5] * d])
+    # one scale for the batch: B inherits A's halvings (same gradient here, nothing underflows)
+    whole = orc.odeint_bwd(vel, theta, tg, tab("euler"), orc.Policy(low="f16", scaling="dynamic"), ck, aN)
+    np.testing.assert_array_equal(whole.scale_hist, [2.0 ** 8, 2.0 ** 8, 2.0 ** 10])
+    np.testing.assert_array_equal(whole.grad_y0, res.grad_y0)
+    assert rel(whole.grad_theta, res.grad_theta) < 1e-6
+    # the gradient is that of the fp64 adjoint up to fp16 rounding of tanh'
+    ref_pol = orc.Policy(low="f64")
+    _, ck64 = orc.odeint_fwd(vel, theta, y0, tg, tab("euler"), ref_pol)
+    ref = orc.odeint_bwd(vel, theta, tg, tab("euler"), ref_pol, ck64, aN)
+    assert rel(res.grad_y0, ref.grad_y0) < 2e-3 and rel(res.grad_theta, ref.grad_theta) < 2e-3
+    # k_max = 1: A's group fails at the first step it meets; it is the first group, B's never runs
+    fail = orc.odeint_bwd(vel, theta, tg, tab("euler"), orc.Policy(low="f16", scaling="dynamic", k_max=1, scale_group=1),
+                          ck, aN)
+    assert fail.status == "scale_failed" and fail.failed_step == 1 and fail.scale_hist.shape == (1, 3)
+    # unscaled-safe: an overflow in one group leaves +inf everywhere
+    safe = orc.odeint_bwd(vel, theta, tg, tab("euler"), orc.Policy(low="f16", scaling="none_safe", scale_group=1), ck,
+                          aN * 1000.0)
+    assert safe.status == "overflow_inf" and np.all(np.isinf(safe.grad_theta)) and np.all(np.isinf(safe.grad_y0))
+
+
+@pytest.mark.parametrize("low", ["f16", "bf16"])
+def test_scale_groups_agree_with_one_scale_when_nothing_leaves_the_range(low):
+    # Samples do not interact; power-of-two scales commute with rounding inside the normal range.
+    cfg = wl.CONFIGS["cfg1"].with_(B=23)
+    vel = orc.MLPVelocity(cfg.widths)
+    theta = wl.make_theta(cfg).astype(np.float64)
+    y0 = wl.make_y0(cfg); tgt = wl.make_target(cfg); tg = cfg.tgrid()
+    gys = 0.01 * np.random.default_rng(5).standard_normal((cfg.N + 1,) + y0.shape)
+    outs = {}
+    for G in (0, 5):
+        pol = orc.Policy(low=low, scaling="dynamic", scale_group=G)
+        yN, ck = orc.odeint_fwd(vel, theta, y0, tg, tab("rk4"), pol)
+        outs[G] = orc.odeint_bwd(vel, theta, tg, tab("rk4"), pol, ck, yN - tgt, grad_ys=gys)
+        assert outs[G].status == "ok"
+    assert outs[5].scale_hist.shape == (5, cfg.N + 1)
+    tol = 1e-6 if low == "bf16" else 2e-4          # fp16: a few values cross into the subnormals under one S only
+    assert rel(outs[5].grad_y0, outs[0].grad_y0) < tol
+    assert rel(outs[5].grad_theta, outs[0].grad_theta) < tol
+    assert rel(outs[5].grad_t, outs[0].grad_t) < 10 * tol
+    # fp64 arithmetic: the split changes nothing but the order of the sums
+    pol0, pol5 = orc.Policy(low="f64"), orc.Policy(low="f64", scale_group=5)
+    yN, ck = orc.odeint_fwd(vel, theta, y0, tg, tab("rk4"), pol0)
+    r0 = orc.odeint_bwd(vel, theta, tg, tab("rk4"), pol0, ck, yN - tgt, grad_ys=gys)
+    r5 = orc.odeint_bwd(vel, theta, tg, tab("rk4"), pol5, ck, yN - tgt, grad_ys=gys)
+    assert rel(r5.grad_theta, r0.grad_theta) < 1e-13 and rel(r5.grad_t, r0.grad_t) < 1e-12
+    assert rel(r5.grad_y0, r0.grad_y0) < 1e-14     # (the matrix products see another batch size)
+
+
+def test_scale_groups_keep_small_samples_out_of_the_subnormals():
+    # Two samples whose loss gradients differ by 2^-30.  One S for both is set by the large one: the small
+    # sample's scaled cotangents are around 2^10 * 2^-30: deep in the fp16 subnormals, its gradient is
+    # mostly rounding.  With a scale of its own it is as accurate as the large one.
+    cfg = wl.CONFIGS["cfg1"].with_(B=2)
+    vel = orc.MLPVelocity(cfg.widths)
+    theta = wl.make_theta(cfg).astype(np.float64)
+    y0 = wl.make_y0(cfg); tg = cfg.tgrid()
+    aN = np.array([[0.7, -1.1], [0.9 * 2.0 ** -30, 0.6 * 2.0 ** -30]])
+    ref_pol = orc.Policy(low="f64")
+    _, ck64 = orc.odeint_fwd(vel, theta, y0, tg, tab("rk4"), ref_pol)
+    ref = orc.odeint_bwd(vel, theta, tg, tab("rk4"), ref_pol, ck64, aN)
+    err = {}
+    for G in (0, 1):
+        pol = orc.Policy(low="f16", scaling="dynamic", scale_group=G)
+        _, ck = orc.odeint_fwd(vel, theta, y0, tg, tab("rk4"), pol)
+        r = orc.odeint_bwd(vel, theta, tg, tab("rk4"), pol, ck, aN)
+        assert r.status == "ok"
+        inc, inc_ref = r.grad_y0[1] - aN[1], ref.grad_y0[1] - aN[1]
+        err[G] = rel(inc, inc_ref)
+    assert err[1] < 2e-2 and err[0] > 5 * err[1]
