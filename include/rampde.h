@@ -12,8 +12,8 @@
  *                       (paper Algorithm 2 and eq. (vjp); update formulas of Sec. 3).
  *
  * Conventions
- *   - "dev" pointers are device (HBM) pointers owned by the caller; "host" pointers are
- *     ordinary host memory.  The library allocates no device memory: all scratch comes
+ *   - "dev" pointers are device (HBM) pointers owned by the caller, 16-byte aligned (RAMPDE_EINVAL
+ *     otherwise); "host" pointers are ordinary host memory.  The library allocates no device memory: all scratch comes
  *     from the caller's workspace (size from rampde_workspace_bytes).
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*, may be NULL
  *     for the default stream).  rampde_odeint_fwd never synchronises.  rampde_odeint_bwd
@@ -115,7 +115,9 @@ typedef struct {
    * scale of their own -- initial value from the group's own max-norm, own overflow retries, own growth --
    * and the group's share of dL/dtheta (and dL/dt) is unscaled with its own h / S before it is added to
    * the other groups'.  Absent overflow and underflow the result is that of G = 0 up to fp32 summation
-   * order.  This one changes WHAT is computed, unlike the two fields above. */
+   * order.  G times the number of state elements of a sample must be a multiple of 8 (every group's
+   * slice of the caller's buffers starts 16-byte aligned; RAMPDE_EINVAL otherwise).  This field changes
+   * WHAT is computed, unlike the two above. */
   int scale_group;
 } rampde_policy;
 

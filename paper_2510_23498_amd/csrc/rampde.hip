@@ -27,6 +27,8 @@ namespace rampde {
 
 static inline int pad64(int x) { return (x + kPad - 1) / kPad * kPad; }
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+// the kernels read states, gradients and checkpoints with 16-byte vector loads
+static inline bool aligned16(const void* ptr) { return ((uintptr_t)ptr & 15) == 0; }
 
 // host-side rounding of a scalar to the low-precision format (stage times, paper Alg. 1:
 // the velocity sees its time argument in low precision)
@@ -1272,6 +1274,7 @@ int rampde_odeint_fwd(const rampde_velocity* vel, const float* theta, const floa
   int rc = check_common(vel, tgrid, N, tab, pol);
   if (rc) return rc;
   if (!theta || !y0 || !ckpt || !yN || !workspace || B < 1) return RAMPDE_EINVAL;
+  if (!aligned16(theta) || !aligned16(y0) || !aligned16(ckpt) || !aligned16(yN)) return RAMPDE_EINVAL;
   Plan p = make_plan(vel, B, N, tab, pol, 0);
   if (!p.ok) return RAMPDE_EINVAL;
   if (workspace_bytes < p.total || ((uintptr_t)workspace & 255)) return RAMPDE_EWORKSPACE;
@@ -1350,6 +1353,9 @@ int rampde_odeint_bwd_tgrid(const rampde_velocity* vel, const float* theta, int6
   if (rc) return rc;
   if (!theta || !ckpt || !grad_yN || !grad_y0 || !grad_theta || !workspace || B < 1) return RAMPDE_EINVAL;
   if (pol->scale_group < 0) return RAMPDE_EINVAL;
+  if (!aligned16(theta) || !aligned16(ckpt) || !aligned16(grad_yN) || !aligned16(grad_ys) || !aligned16(grad_y0) ||
+      !aligned16(grad_theta))
+    return RAMPDE_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
   const int64_t G = pol->scale_group;
   if (G == 0 || G >= B)
@@ -1367,6 +1373,7 @@ int rampde_odeint_bwd_tgrid(const rampde_velocity* vel, const float* theta, int6
   if (!whole.ok) return RAMPDE_EINVAL;
   const int64_t per_sample = whole.n / B;
   const int64_t step_elems = whole.n;
+  if ((G * per_sample) % 8) return RAMPDE_EINVAL;  // every group's slice must start 16-byte aligned
   const size_t low_bytes = 2;
   rampde_stats all{};
   all.failed_step = -1;

@@ -72,7 +72,7 @@ def _call_fwd(vel, tab, pol, tgrid, B=4, theta=1, y0=1, ckpt=1, yN=1, ws=1, ws_b
     lib = rb.load_library()
     tg = np.ascontiguousarray(np.asarray(tgrid, dtype=np.float64))
     pc = pol.c
-    p = lambda x: C.c_void_p(0x1000 * x) if x else None
+    p = lambda x: C.c_void_p(int(0x1000 * x)) if x else None
     return lib.rampde_odeint_fwd(C.byref(vel.c), p(theta), p(y0), B, tg.ctypes.data_as(C.POINTER(C.c_double)),
                                  len(tg) - 1, C.byref(tab.c), C.byref(pc), p(ckpt), p(yN), p(ws), ws_bytes, None)
 
@@ -84,6 +84,8 @@ def test_forward_rejects_bad_arguments_without_touching_the_device():
     assert _call_fwd(vel, tab, pol, grid, theta=0) == rb.EINVAL           # null pointer
     assert _call_fwd(vel, tab, pol, grid, ws=0) == rb.EINVAL
     assert _call_fwd(vel, tab, pol, grid, B=0) == rb.EINVAL
+    assert _call_fwd(vel, tab, pol, grid, y0=1.001) == rb.EINVAL          # device pointer not 16-byte aligned
+    assert _call_fwd(vel, tab, pol, grid, ckpt=1.002) == rb.EINVAL
     assert _call_fwd(vel, tab, pol, grid[::-1]) == rb.EINVAL              # decreasing grid
     assert _call_fwd(vel, tab, pol, [0.0, 0.5, 0.5, 1.0]) == rb.EINVAL    # not strictly increasing
     assert _call_fwd(vel, tab, pol, [0.0, np.nan, 1.0]) == rb.EINVAL
@@ -108,9 +110,9 @@ def test_backward_rejects_bad_arguments_without_touching_the_device():
     vel, tab, pol = _descr(cfg)
     tg = np.ascontiguousarray(cfg.tgrid())
     pc = pol.c
-    p = lambda x: C.c_void_p(0x1000 * x) if x else None
+    p = lambda x: C.c_void_p(int(0x1000 * x)) if x else None
 
-    def call(theta=1, ckpt=1, gyN=1, gy0=1, gth=1, ws=1, ws_bytes=1 << 40, N=cfg.N, B=4):
+    def call(theta=1, ckpt=1, gyN=1, gy0=1, gth=1, ws=1, ws_bytes=1 << 40, N=cfg.N, B=4, pc=pc):
         return lib.rampde_odeint_bwd(C.byref(vel.c), p(theta), B, tg.ctypes.data_as(C.POINTER(C.c_double)), N,
                                      C.byref(tab.c), C.byref(pc), p(ckpt), p(gyN), None, p(gy0), p(gth), None, None,
                                      p(ws), ws_bytes, None)
@@ -120,6 +122,12 @@ def test_backward_rejects_bad_arguments_without_touching_the_device():
     assert call(gth=0) == rb.EINVAL
     assert call(N=0) == rb.EINVAL
     assert call(ws_bytes=64) == rb.EWORKSPACE
+    assert call(gyN=1.001) == rb.EINVAL                                   # not 16-byte aligned
+    assert call(gy0=1.003) == rb.EINVAL
+    # scale groups: negative size; a group whose slice of the buffers would not start 16-byte aligned
+    # (cfg1 has 2 state elements per sample: 3 samples are 6 elements)
+    assert call(B=8, pc=rb.Policy(low="f16", scaling="dynamic", scale_group=-1).c) == rb.EINVAL
+    assert call(B=8, pc=rb.Policy(low="f16", scaling="dynamic", scale_group=3).c) == rb.EINVAL
 
 
 def test_error_strings():
