@@ -289,9 +289,32 @@ struct WideEngine {
     lane16 = (uint32_t)lane * 16u;
   }
   // request the first fragments of a hidden-shaped pass (contraction over the state: KS_S, else KS_H)
+  // A pass whose whole contraction fits the ring (over a state of 128: 8 steps; the split state-shaped
+  // pass: 16 single fragments) is requested in two parts: 5 of 8 steps (12 of 16 fragments) ahead, during
+  // the previous pass's epilogue, and the rest by the pass itself before its first matrix instruction
+  // -- the epilogue's own values and a full ring together are more registers than a wavefront has, and
+  // a fragment that is spilled has to be waited for right where it was requested (with these counts
+  // neither kernel spills).
+  static constexpr int KS_S_AHEAD = (Sh::KS_S <= PD) ? (5 * Sh::KS_S) / 8 : PD;
   template <bool FROM_STATE>
   __device__ __forceinline__ void preload_hidden(const WideW& W) {
-    wide_preload<2, PD>(ring, W, 2 * wave, lane16, FROM_STATE ? Sh::KS_S : Sh::KS_H, Sh::CT_H);
+    if constexpr (FROM_STATE && Sh::KS_S <= PD) {
+#pragma unroll
+      for (int u = 0; u < KS_S_AHEAD; ++u)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) ring[u][ct] = wide_frag(W, u * Sh::CT_H + 2 * wave + ct, lane16);
+    } else {
+      wide_preload<2, PD>(ring, W, 2 * wave, lane16, FROM_STATE ? Sh::KS_S : Sh::KS_H, Sh::CT_H);
+    }
+  }
+  template <bool FROM_STATE>
+  __device__ __forceinline__ void preload_hidden_rest(const WideW& W) {
+    if constexpr (FROM_STATE && Sh::KS_S <= PD) {
+#pragma unroll
+      for (int u = KS_S_AHEAD; u < Sh::KS_S; ++u)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) ring[u][ct] = wide_frag(W, u * Sh::CT_H + 2 * wave + ct, lane16);
+    }
   }
   // State-shaped passes.  D = 256: wavefront w owns column tile w and both row tiles.  D = 128 has
   // only 4 column tiles: wavefronts w and w + 4 share column tile w % 4 and SPLIT THE CONTRACTION
@@ -303,13 +326,41 @@ struct WideEngine {
   __device__ __forceinline__ int state_frag0() const { return kSplitK ? (wave >> 2) * KS_ST * Sh::CT_S + (wave & 3) : wave; }
   // (split contraction: a wavefront's 16 fragments fill the ring, slot u at ring[u % PD][u / PD], so the
   // pass has no refills and nothing in it waits for loads issued after this request)
+  static constexpr int KS_ST_AHEAD = kSplitK ? (3 * KS_ST) / 4 : PD;
+  __device__ __forceinline__ void preload_state_rest(const WideW& W) {
+    if constexpr (kSplitK) {
+#pragma unroll
+      for (int u = KS_ST_AHEAD; u < KS_ST; ++u) ring[u % PD][u / PD] = wide_frag(W, state_frag0() + u * Sh::CT_S, lane16);
+    }
+  }
   __device__ __forceinline__ void preload_state(const WideW& W) {
     if constexpr (kSplitK) {
       static_assert(KS_ST == 2 * PD, "the ring holds a state-shaped pass");
 #pragma unroll
-      for (int u = 0; u < KS_ST; ++u) ring[u % PD][u / PD] = wide_frag(W, state_frag0() + u * Sh::CT_S, lane16);
+      for (int u = 0; u < KS_ST_AHEAD; ++u) ring[u % PD][u / PD] = wide_frag(W, state_frag0() + u * Sh::CT_S, lane16);
     } else {
       wide_preload<1, PD>(ring, W, state_frag0(), lane16, KS_ST, Sh::CT_S);
+    }
+  }
+
+  // What a hidden-shaped pass requests for the pass after it: a state-shaped pass (state_next) or
+  // another hidden-shaped one over the hidden width.  ONE sequence of loads with selected fragment
+  // numbers -- two branches that fill different ring slots make the compiler keep ring slots in memory.
+  __device__ __forceinline__ void preload_after_hidden(const WideW& W, bool state_next) {
+    if constexpr (kSplitK) {
+      const int st0 = state_frag0();
+#pragma unroll
+      for (int u = 0; u < PD; ++u)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+          const int v = ct * PD + u;  // the state-shaped pass's step held by ring[u][ct]
+          const int frag = state_next ? st0 + v * Sh::CT_S : u * Sh::CT_H + 2 * wave + ct;
+          if (v < KS_ST_AHEAD) ring[u][ct] = wide_frag(W, frag, lane16);
+          else if (!state_next) ring[u][ct] = wide_frag(W, frag, lane16);
+        }
+    } else {
+      if (state_next) preload_state(W);
+      else preload_hidden<false>(W);
     }
   }
 
@@ -318,6 +369,7 @@ struct WideEngine {
                                              Tail tail) {
     constexpr int KS = FROM_STATE ? Sh::KS_S : Sh::KS_H;
     constexpr int ld = FROM_STATE ? Sh::ldz : Sh::ldp;
+    preload_hidden_rest<FROM_STATE>(W);
     f32x16 acc[2][2];
     {
       const int lh4 = 4 * fresh(lh);
@@ -351,6 +403,7 @@ struct WideEngine {
                                             Nxt nxt) {
     // pre(): the pass's global loads were issued at the end of the previous epilogue; this marks the point
     // (after the contraction) where they must be back
+    preload_state_rest(W);
     const int lh4 = 4 * fresh(lh);
     if constexpr (kSplitK) {
       const int kh = wave >> 2, ct = wave & 3;
@@ -487,10 +540,7 @@ __device__ __forceinline__ void wide_hidden_layers(WideEngine<T, HP, D>& eng, co
         if (live) *fm_word(goutT, g.ldk, kj, n_tile + 8 * q, goff) = pq;
       }
     };
-    auto nxt = [&]() {
-      if (next_is_last) eng.preload_state(Wnext);
-      else eng.template preload_hidden<false>(Wnext);
-    };
+    auto nxt = [&]() { eng.preload_after_hidden(Wnext, next_is_last); };
     auto tail = [&]() {
       if (next_is_last) state_loads();
     };
@@ -843,10 +893,7 @@ __global__ __launch_bounds__(64 * kWideWaves) void mlp_adjoint_wide(FusedArgs g)
           if (live) *fm_word(goutT, g.ldk, kj, n_tile + 8 * q, goff) = dq;
         }
       };
-      auto nxt_b = [&]() {
-        if (next_is_last) eng.preload_state(Wnext);
-        else eng.template preload_hidden<false>(Wnext);
-      };
+      auto nxt_b = [&]() { eng.preload_after_hidden(Wnext, next_is_last); };
       // (the last transposed hidden pass also fetches the adjoint for the slope cotangent that the
       // state-shaped pass after it forms)
       auto tail_b = [&]() {
