@@ -537,7 +537,9 @@ __device__ __forceinline__ void wide_hidden_layers(WideEngine<T, HP, D>& eng, co
         for (int r = 0; r < 4; ++r) v[r] = wide_tanh(acc[4 * q + r]);
         const uint2 pq = pack4<T>(v);
         lds_store_u2(orow + 8 * q, pq);
-        if (live) *fm_word(goutT, g.ldk, kj, n_tile + 8 * q, goff) = pq;
+        // (rows past the batch exist in the feature-group-major buffers and must hold zeros; storing
+        // without a branch keeps the 16 runs of this tile in one block for the scheduler)
+        if (KEEP) *fm_word(goutT, g.ldk, kj, n_tile + 8 * q, goff) = live ? pq : make_uint2(0u, 0u);
       }
     };
     auto nxt = [&]() { eng.preload_after_hidden(Wnext, next_is_last); };
@@ -869,11 +871,10 @@ __global__ __launch_bounds__(64 * kWideWaves) void mlp_adjoint_wide(FusedArgs g)
 #pragma unroll
           for (int rt = 0; rt < 2; ++rt) {
             const int m = rt * 32 + lrr;
-            const bool live = row0 + m < g.R;
             const uint32_t goff = eng.fm_off(g.ldk, m);
+            // (rows past the batch hold zeros in these buffers)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-              pf[ct][rt][q] = live ? *fm_word(actT, g.ldk, kj, (2 * eng.wave + ct) * 32 + 8 * q, goff) : make_uint2(0u, 0u);
+            for (int q = 0; q < 4; ++q) pf[ct][rt][q] = *fm_word(actT, g.ldk, kj, (2 * eng.wave + ct) * 32 + 8 * q, goff);
           }
       };
       auto epi_delta = [&](const f32x16& acc, int n_tile, int ct, int rt) {
@@ -890,7 +891,7 @@ __global__ __launch_bounds__(64 * kWideWaves) void mlp_adjoint_wide(FusedArgs g)
           const uint2 dq = pack4<T>(v);
           note_nonfinite<T>(nf, dq);
           lds_store_u2(orow + 8 * q, dq);
-          if (live) *fm_word(goutT, g.ldk, kj, n_tile + 8 * q, goff) = dq;
+          *fm_word(goutT, g.ldk, kj, n_tile + 8 * q, goff) = live ? dq : make_uint2(0u, 0u);
         }
       };
       auto nxt_b = [&]() { eng.preload_after_hidden(Wnext, next_is_last); };
