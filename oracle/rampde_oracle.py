@@ -292,6 +292,106 @@ class Conv2Velocity:
         return zbar.reshape(kbar.shape), dtheta, finite, taubar
 
 
+# 3x3 convolution, zero padding 1, stride 1 (NCHW), its transpose with respect to the input, and its
+# weight gradient, written out tap by tap from the definition
+def _conv3x3(x, Wt):
+    """out[b,o,y,x] = sum_{c,ky,kx} W[o,c,ky,kx] * xpad[b,c,y+ky,x+kx]."""
+    B, _, H, Wd = x.shape
+    xp = np.pad(x, ((0, 0), (0, 0), (1, 1), (1, 1)))
+    out = np.zeros((B, Wt.shape[0], H, Wd), dtype=np.float64)
+    for ky in range(3):
+        for kx in range(3):
+            out += np.einsum("oc,bchw->bohw", Wt[:, :, ky, kx], xp[:, :, ky:ky + H, kx:kx + Wd], optimize=True)
+    return out
+
+
+def _conv3x3_T(v, Wt):
+    """in[b,c,y,x] = sum_{o,ky,kx} W[o,c,ky,kx] * vpad[b,o,y-ky+2,x-kx+2]: the transpose of _conv3x3 in x."""
+    B, _, H, Wd = v.shape
+    dp = np.zeros((B, Wt.shape[1], H + 2, Wd + 2), dtype=np.float64)
+    for ky in range(3):
+        for kx in range(3):
+            dp[:, :, ky:ky + H, kx:kx + Wd] += np.einsum("oc,bohw->bchw", Wt[:, :, ky, kx], v, optimize=True)
+    return dp[:, :, 1:-1, 1:-1]
+
+
+def _conv3x3_dW(v, x):
+    """d<v, conv3x3(x, W)>/dW[o,c,ky,kx] = sum_{b,y,x} v[b,o,y,x] * xpad[b,c,y+ky,x+kx]."""
+    B, _, H, Wd = x.shape
+    xp = np.pad(x, ((0, 0), (0, 0), (1, 1), (1, 1)))
+    dW = np.zeros((v.shape[1], x.shape[1], 3, 3), dtype=np.float64)
+    for ky in range(3):
+        for kx in range(3):
+            dW[:, :, ky, kx] = np.einsum("bohw,bchw->oc", v, xp[:, :, ky:ky + H, kx:kx + Wd], optimize=True)
+    return dW
+
+
+class ParabolicConvVelocity:
+    """f(y; W, b) = -W^T N( relu( W y + b ) )   (paper Sec. 6.3, eq. (NODE_STL10); App. "parabolic").
+
+    W is a 3x3 convolution with C input and C output channels (zero padding 1), W^T its exact
+    transpose with the SAME weights, N the instance normalisation: per sample and channel, over the
+    H*W pixels, (r - mean) / sqrt(var + eps) with the biased variance and no affine parameters.
+    Weights and biases are piecewise constant in time (Sec. 6.3: constant on each time interval):
+    theta holds `n_intervals` blocks (W[C,C,3,3], b[C]); step i of an N-step grid uses block
+    i * n_intervals // N for all of its stages.  There is no explicit time input.
+
+    Rounding points in emulation mode (readings; the paper runs this block under autocast): the
+    post-ReLU activation, the normalised activation and the slope are rounded to `low`; the
+    convolution sums, the statistics (mean, variance, 1/sqrt) and the normalisation arithmetic are
+    fp32.  The VJP of N uses the stored (rounded) normalised activation and the fp32 statistics; the
+    ReLU mask is r > 0 of the stored activation; dn, du and zbar are rounded to `low`.
+    """
+
+    time_input = False
+
+    def __init__(self, C: int, H: int, W: int, n_intervals: int = 1, eps: float = 1e-5):
+        self.C, self.H, self.W = int(C), int(H), int(W)
+        self.n_intervals = int(n_intervals)
+        self.eps = float(eps)
+        self.block = self.C * self.C * 9 + self.C
+        self.n_params = self.n_intervals * self.block
+
+    def state_size(self):
+        return self.C * self.H * self.W
+
+    def step_slice(self, i: int, N: int) -> slice:
+        j = (i * self.n_intervals) // N
+        return slice(j * self.block, (j + 1) * self.block)
+
+    def _split(self, theta_blk):
+        wsz = self.C * self.C * 9
+        return theta_blk[:wsz].reshape(self.C, self.C, 3, 3), theta_blk[wsz:wsz + self.C]
+
+    def eval(self, theta_blk, z, tau, Q, R32):
+        Wt, b = self._split(theta_blk)
+        z4 = z.reshape(-1, self.C, self.H, self.W)
+        r = Q(R32(np.maximum(R32(_conv3x3(z4, Wt) + b[None, :, None, None]), 0.0)))
+        mu = R32(r.mean(axis=(2, 3), keepdims=True))
+        var = R32(((r - mu) ** 2).mean(axis=(2, 3), keepdims=True))
+        rstd = R32(1.0 / np.sqrt(var + self.eps))
+        n = Q(R32((r - mu) * rstd))
+        k = Q(R32(-_conv3x3_T(n, Wt)))
+        return k.reshape(z.shape), (z4, r, n, rstd)
+
+    def vjp(self, theta_blk, cache, kbar, Q, R32):
+        z4, r, n, rstd = cache
+        Wt, b = self._split(theta_blk)
+        kb4 = kbar.reshape(z4.shape)
+        dn = Q(R32(-_conv3x3(kb4, Wt)))
+        m1 = R32(dn.mean(axis=(2, 3), keepdims=True))
+        m2 = R32((dn * n).mean(axis=(2, 3), keepdims=True))
+        du = Q(R32(rstd * (dn - m1 - n * m2)) * (r > 0.0))
+        zbar = Q(R32(_conv3x3_T(du, Wt)))
+        dtheta = np.zeros(self.block, dtype=np.float64)
+        wsz = self.C * self.C * 9
+        # k = -W^T n is linear in W with "input" kbar and "output cotangent" n
+        dtheta[:wsz] = (_conv3x3_dW(du, z4) - _conv3x3_dW(n, kb4)).ravel()
+        dtheta[wsz:] = du.sum(axis=(0, 2, 3))
+        finite = bool(np.all(np.isfinite(dn))) and bool(np.all(np.isfinite(du))) and bool(np.all(np.isfinite(zbar)))
+        return zbar.reshape(kbar.shape), dtheta, finite, None
+
+
 class PolyDecayVelocity:
     """Scalar test problem of the paper's Example 3.1:  y' = -(th1 t^2 + th2 t + th3) y.
 
@@ -373,6 +473,12 @@ def initial_scale(amax: float, low: str) -> float:
 # --------------------------------------------------------------------------
 # Stage recursion shared by forward and backward recomputation
 # --------------------------------------------------------------------------
+def _step_theta(vel, theta_q, i, N):
+    """The parameters step i uses: all of them, or the step's block when the velocity's parameters are
+    piecewise constant in time (paper Sec. 6.3)."""
+    return theta_q[vel.step_slice(i, N)] if hasattr(vel, "step_slice") else theta_q
+
+
 def _stages(vel, theta_q, yhat, t_i, h, tab_A, tab_c, Q, R32):
     """Stage inputs z_j, times tau_j, slopes k_j of one explicit RK step (Phi's inside)."""
     s = len(tab_c)
@@ -411,7 +517,7 @@ def odeint_fwd(vel, theta, y0, tgrid, tableau, policy: Policy):
     for i in range(N):
         h = float(R32(tgrid[i + 1] - tgrid[i]))
         yhat = ckpt[i]
-        ks, _ = _stages(vel, theta_q, yhat, tgrid[i], h, A, c, Q, R32)
+        ks, _ = _stages(vel, _step_theta(vel, theta_q, i, N), yhat, tgrid[i], h, A, c, Q, R32)
         incr = np.zeros_like(y)
         for j in range(len(b)):
             incr = incr + b[j] * ks[j]
@@ -517,7 +623,8 @@ def _odeint_bwd_one_scale(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad
     for i in range(N - 1, -1, -1):
         h = float(R32(tgrid[i + 1] - tgrid[i]))
         yhat = flat(ckpt[i])
-        ks, caches = _stages(vel, theta_q, yhat, tgrid[i], h, A, c, Q, R32)   # recompute
+        th_i = _step_theta(vel, theta_q, i, N)
+        ks, caches = _stages(vel, th_i, yhat, tgrid[i], h, A, c, Q, R32)   # recompute
 
         k_used = 0
         k_lim = policy.k_max if dynamic else 1
@@ -527,7 +634,7 @@ def _odeint_bwd_one_scale(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad
             finite = bool(np.all(np.isfinite(lam)))
             zbars = [None] * s
             taubars = [0.0] * s
-            dth = np.zeros(vel.n_params)
+            dth = np.zeros(len(th_i))
             for j in range(s - 1, -1, -1):
                 kb = b[j] * lam
                 for l in range(j + 1, s):
@@ -535,7 +642,7 @@ def _odeint_bwd_one_scale(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad
                         kb = kb + h * A[l][j] * zbars[l]
                 kb = Q(R32(kb))                                        # R9a
                 finite = finite and bool(np.all(np.isfinite(kb)))
-                zbars[j], dth_j, fin_j, taubars[j] = vel.vjp(theta_q, caches[j], kb, Q, R32)   # R9b, R9c
+                zbars[j], dth_j, fin_j, taubars[j] = vel.vjp(th_i, caches[j], kb, Q, R32)   # R9b, R9c
                 finite = finite and fin_j
                 dth = dth + dth_j
             if finite or not check:
@@ -582,7 +689,12 @@ def _odeint_bwd_one_scale(vel, theta, tgrid, tableau, policy: Policy, ckpt, grad
         a = R32(a_new)
         if policy.naive_state:
             a = Q(a)
-        g = R32(g + hs * R32(dth))
+        if hasattr(vel, "step_slice"):
+            # parameters that are piecewise constant in time: the step's gradient goes to its own block
+            blk = vel.step_slice(i, N)
+            g[blk] = R32(g[blk] + hs * R32(dth))
+        else:
+            g = R32(g + hs * R32(dth))
         if dynamic and k_used == 1:
             amax = float(np.max(np.abs(a))) if a.size else 0.0
             test = amax if policy.grow_raw_norm else S * amax

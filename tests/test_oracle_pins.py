@@ -780,3 +780,154 @@ def test_scale_groups_keep_small_samples_out_of_the_subnormals():
         inc, inc_ref = r.grad_y0[1] - aN[1], ref.grad_y0[1] - aN[1]
         err[G] = rel(inc, inc_ref)
     assert err[1] < 2e-2 and err[0] > 5 * err[1]
+
+
+# ------------------------------------------------------------------ parabolic convolution block (Sec. 6.3)
+def _parabolic_direct(z, Wt, b, eps):
+    """-W^T N(relu(W z + b)) from the definitions, with explicit loops (tiny sizes only)."""
+    B, C, H, W = z.shape
+    u = np.zeros((B, C, H, W))
+    for n in range(B):
+        for o in range(C):
+            for yy in range(H):
+                for xx in range(W):
+                    acc = b[o]
+                    for c in range(C):
+                        for ky in range(3):
+                            for kx in range(3):
+                                iy, ix = yy + ky - 1, xx + kx - 1
+                                if 0 <= iy < H and 0 <= ix < W:
+                                    acc += Wt[o, c, ky, kx] * z[n, c, iy, ix]
+                    u[n, o, yy, xx] = acc
+    r = np.where(u > 0, u, 0.0)
+    nrm = np.zeros_like(r)
+    for n in range(B):
+        for o in range(C):
+            m = sum(r[n, o].ravel()) / (H * W)
+            v = sum((r[n, o].ravel() - m) ** 2) / (H * W)
+            nrm[n, o] = (r[n, o] - m) / math.sqrt(v + eps)
+    # transpose of the convolution: scatter every output pixel back through the same taps
+    k = np.zeros((B, C, H, W))
+    for n in range(B):
+        for o in range(C):
+            for yy in range(H):
+                for xx in range(W):
+                    for c in range(C):
+                        for ky in range(3):
+                            for kx in range(3):
+                                iy, ix = yy + ky - 1, xx + kx - 1
+                                if 0 <= iy < H and 0 <= ix < W:
+                                    k[n, c, iy, ix] -= Wt[o, c, ky, kx] * nrm[n, o, yy, xx]
+    return k, nrm
+
+
+def test_parabolic_block_matches_direct_definition():
+    rng = np.random.default_rng(31)
+    B, C, H, W = 2, 3, 4, 3
+    vel = orc.ParabolicConvVelocity(C, H, W)
+    theta = rng.normal(size=vel.n_params) * 0.5
+    z = rng.normal(size=(B, C, H, W))
+    Q, R32 = orc.make_quantisers("f64")
+    k, cache = vel.eval(theta, z.reshape(B, -1), 0.0, Q, R32)
+    Wt, b = vel._split(theta)
+    want, nrm = _parabolic_direct(z, Wt, b, vel.eps)
+    assert rel(k, want.reshape(B, -1)) < 1e-13
+    # the normalised activation has zero mean and variance var / (var + eps) per sample and channel
+    n = cache[2]
+    assert np.max(np.abs(n.mean(axis=(2, 3)))) < 1e-13
+    var_r = cache[1].var(axis=(2, 3))
+    assert np.allclose(n.var(axis=(2, 3)), var_r / (var_r + vel.eps), rtol=1e-12)
+
+
+def test_parabolic_transpose_shares_the_weights():
+    # <W x, v> = <x, W^T v> for the pair the block uses, and the weight gradient is the derivative of that form
+    rng = np.random.default_rng(32)
+    B, C, H, W = 2, 3, 5, 4
+    Wt = rng.normal(size=(C, C, 3, 3))
+    x = rng.normal(size=(B, C, H, W)); v = rng.normal(size=(B, C, H, W))
+    lhs = np.sum(orc._conv3x3(x, Wt) * v)
+    assert abs(lhs - np.sum(x * orc._conv3x3_T(v, Wt))) < 1e-12 * abs(lhs)
+    dW = orc._conv3x3_dW(v, x)
+    E = rng.normal(size=Wt.shape)
+    assert abs(np.sum(dW * E) - np.sum(orc._conv3x3(x, E) * v)) < 1e-12 * abs(np.sum(dW * E))
+
+
+def test_parabolic_without_norm_scale_is_dissipative_direction():
+    # the structure behind the block's stability (App., "parabolic"): with b = 0 the un-normalised velocity
+    # -W^T relu(W y) satisfies <y, f> = -<W y, relu(W y)> <= 0; the normalisation divides each channel by a
+    # positive number, which keeps the sign of every channel's contribution when its mean is removed from
+    # the pairing: <W y - 0, N(r)> = sum_c rstd_c <u_c, r_c - mean_c>, and <u_c, r_c> >= 0.
+    rng = np.random.default_rng(33)
+    B, C, H, W = 1, 2, 4, 4
+    vel = orc.ParabolicConvVelocity(C, H, W)
+    theta = np.concatenate([rng.normal(size=C * C * 9), np.zeros(C)])
+    z = rng.normal(size=(B, C * H * W))
+    Q, R32 = orc.make_quantisers("f64")
+    k, (z4, r, n, rstd) = vel.eval(theta, z, 0.0, Q, R32)
+    Wt, _ = vel._split(theta)
+    u = orc._conv3x3(z4, Wt)
+    # <y, f> = -<W y, n>, computed two ways
+    assert abs(np.sum(z * k) + np.sum(u * n)) < 1e-12 * abs(np.sum(u * n))
+    # n = rstd (r - mean(r)): per channel
+    mu = r.mean(axis=(2, 3), keepdims=True)
+    assert rel(n, rstd * (r - mu)) < 1e-13
+
+
+@pytest.mark.parametrize("name,n_int", [("rk4", 1), ("rk4", 2), ("heun", 4), ("euler", 2)])
+def test_parabolic_gradients_match_finite_differences(name, n_int):
+    rng = np.random.default_rng(34)
+    B, C, H, W = 2, 2, 3, 4
+    vel = orc.ParabolicConvVelocity(C, H, W, n_intervals=n_int)
+    theta = rng.normal(size=vel.n_params) * 0.5
+    y0 = rng.normal(size=(B, C * H * W))
+    tg = np.linspace(0.0, 0.6, 5)
+    target = rng.normal(size=y0.shape)
+    # (pre-activations stay away from the ReLU kink for this seed at the FD step: checked by the tolerance)
+    _fd_check(vel, theta, y0, tg, tab(name), target, step=1e-6, tol=5e-6)
+
+
+def test_parabolic_piecewise_constant_weights_use_the_steps_own_block():
+    # with 2 blocks on a 4-step grid, steps 0-1 read block 0 and steps 2-3 block 1: the result equals two
+    # consecutive 2-step solves with constant weights, and each block's gradient is that sub-solve's
+    rng = np.random.default_rng(35)
+    B, C, H, W = 2, 2, 3, 3
+    vel2 = orc.ParabolicConvVelocity(C, H, W, n_intervals=2)
+    vel1 = orc.ParabolicConvVelocity(C, H, W, n_intervals=1)
+    theta = rng.normal(size=vel2.n_params) * 0.5
+    y0 = rng.normal(size=(B, C * H * W))
+    tg = np.linspace(0.0, 0.8, 5)
+    pol = orc.Policy(low="f64")
+    yN, ck = orc.odeint_fwd(vel2, theta, y0, tg, tab("rk4"), pol)
+    ymid, ck_a = orc.odeint_fwd(vel1, theta[:vel1.n_params], y0, tg[:3], tab("rk4"), pol)
+    yend, ck_b = orc.odeint_fwd(vel1, theta[vel1.n_params:], ymid, tg[2:], tab("rk4"), pol)
+    assert rel(yN, yend) < 1e-14 and rel(ck[2], ymid) < 1e-14
+    gN = rng.normal(size=yN.shape)
+    res = orc.odeint_bwd(vel2, theta, tg, tab("rk4"), pol, ck, gN)
+    rb = orc.odeint_bwd(vel1, theta[vel1.n_params:], tg[2:], tab("rk4"), pol, ck_b, gN)
+    ra = orc.odeint_bwd(vel1, theta[:vel1.n_params], tg[:3], tab("rk4"), pol, ck_a, rb.grad_y0)
+    assert rel(res.grad_y0, ra.grad_y0) < 1e-13
+    assert rel(res.grad_theta[:vel1.n_params], ra.grad_theta) < 1e-13
+    assert rel(res.grad_theta[vel1.n_params:], rb.grad_theta) < 1e-13
+
+
+# (the ReLU mask is a discontinuous factor of the gradient: a pre-activation that rounding moves across zero
+# flips a mask bit, so the gradient bounds are looser than for the smooth tanh networks)
+@pytest.mark.parametrize("low,tol", [("f16", 2e-2), ("bf16", 1.5e-1)])
+def test_parabolic_emulation_is_close_to_fp64(low, tol):
+    rng = np.random.default_rng(36)
+    B, C, H, W = 2, 8, 8, 8
+    vel = orc.ParabolicConvVelocity(C, H, W, n_intervals=2)
+    theta = np.concatenate([np.concatenate([rng.normal(size=C * C * 9) * (2.0 / (C * 9)) ** 0.5, rng.normal(size=C) * 0.1])
+                            for _ in range(2)])
+    y0 = rng.normal(size=(B, C * H * W))
+    tg = np.linspace(0.0, 1.0, 5)
+    gN = rng.normal(size=y0.shape) * 1e-3
+    out = {}
+    for lw in ("f64", low):
+        pol = orc.Policy(low=lw, scaling="dynamic")
+        yN, ck = orc.odeint_fwd(vel, theta, y0, tg, tab("rk4"), pol)
+        out[lw] = (yN, orc.odeint_bwd(vel, theta, tg, tab("rk4"), pol, ck, gN))
+    assert rel(out[low][0], out["f64"][0]) < (2e-2 if low == "f16" else 5e-2)
+    assert rel(out[low][1].grad_y0, out["f64"][1].grad_y0) < tol
+    assert rel(out[low][1].grad_theta, out["f64"][1].grad_theta) < tol
+    assert out[low][1].status == "ok"
