@@ -35,11 +35,12 @@
  *              layer 1 has in_1 = d + 1 when time_input is set (time column LAST).
  *       CONV2: W1[C][C+time_input][3][3], b1[C], W2[C][C+time_input][3][3], b2[C]
  *              (time channel LAST); zero padding 1, stride 1.
- *     Activation is tanh after every layer but the last.
+ *       PARABOLIC: for each piece q = 0 .. n_intervals-1: W_q[C][C][3][3], b_q[C].
+ *     Activation is tanh after every layer but the last (MLP, CONV2); ReLU in PARABOLIC.
  *   - State layout at the boundary (y0, yN, grad_yN, grad_y0, grad_ys), fp32:
- *       MLP [B][d];  CONV2 NCHW [B][C][H][W].
+ *       MLP [B][d];  CONV2 and PARABOLIC NCHW [B][C][H][W].
  *   - Checkpoint layout (ckpt, written by fwd, read by bwd; element type = policy.low):
- *       MLP [N+1][B][d];  CONV2 channels-last [N+1][B][H][W][C].
+ *       MLP [N+1][B][d];  CONV2 and PARABOLIC channels-last [N+1][B][H][W][C].
  */
 #ifndef RAMPDE_H
 #define RAMPDE_H
@@ -61,7 +62,14 @@ typedef enum {
   RAMPDE_SCALE_AUTO = 3       /* F32/BF16 -> NONE, F16 -> DYNAMIC                          */
 } rampde_scaling;
 
-typedef enum { RAMPDE_VEL_MLP = 0, RAMPDE_VEL_CONV2 = 1 } rampde_vel_kind;
+/* Velocity kinds.  PARABOLIC is the convolution block of the paper's image classifier,
+ * f(y) = -W^T N(relu(W y + b))  (Sec. 6.3, eq. (NODE_STL10)): W a 3x3 convolution with C input and C
+ * output channels (zero padding 1), W^T its exact transpose with the same weights, N the instance
+ * normalisation (per sample and channel over the H*W pixels, biased variance, eps = 1e-5, no affine
+ * parameters; statistics and arithmetic in fp32, result rounded to `low`).  No time input; instead the
+ * parameters are piecewise constant in time: step i of an N-step grid uses piece i * n_intervals / N
+ * (integer division) for all of its stages. */
+typedef enum { RAMPDE_VEL_MLP = 0, RAMPDE_VEL_CONV2 = 1, RAMPDE_VEL_PARABOLIC = 2 } rampde_vel_kind;
 
 typedef enum {
   RAMPDE_OK = 0,
@@ -94,8 +102,9 @@ typedef struct {
   rampde_vel_kind kind;
   int n_layers;      /* MLP: number of linear layers (>= 1)                           */
   const int *widths; /* MLP: n_layers + 1 entries, widths[0] = widths[n_layers] = d   */
-  int C, H, W;       /* CONV2: channels and spatial size; kernel 3x3, padding 1      */
-  int time_input;    /* 1: append t as last input column (MLP, layer 1) / channel (each conv) */
+  int C, H, W;       /* CONV2, PARABOLIC: channels and spatial size; kernel 3x3, padding 1 */
+  int time_input;    /* 1: append t as last input column (MLP, layer 1) / channel (each conv); PARABOLIC: 0 */
+  int n_intervals;   /* PARABOLIC: pieces of the piecewise-constant parameters (0 or 1: constant in time) */
 } rampde_velocity;
 
 typedef struct {

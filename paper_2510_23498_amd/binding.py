@@ -18,7 +18,7 @@ from .build import LIB_PATH
 
 F32, F16, BF16 = 0, 1, 2
 SCALE_NONE, SCALE_NONE_SAFE, SCALE_DYNAMIC, SCALE_AUTO = 0, 1, 2, 3
-VEL_MLP, VEL_CONV2 = 0, 1
+VEL_MLP, VEL_CONV2, VEL_PARABOLIC = 0, 1, 2
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, ESCALE, EHIP = 0, 1, 2, 3, 4, 5
 _LOW = {"f32": F32, "f16": F16, "bf16": BF16}
 _SCALING = {"none": SCALE_NONE, "none_safe": SCALE_NONE_SAFE, "dynamic": SCALE_DYNAMIC, "auto": SCALE_AUTO}
@@ -38,7 +38,7 @@ class _Tableau(C.Structure):
 
 class _Velocity(C.Structure):
     _fields_ = [("kind", C.c_int), ("n_layers", C.c_int), ("widths", C.POINTER(C.c_int)),
-                ("C", C.c_int), ("H", C.c_int), ("W", C.c_int), ("time_input", C.c_int)]
+                ("C", C.c_int), ("H", C.c_int), ("W", C.c_int), ("time_input", C.c_int), ("n_intervals", C.c_int)]
 
 
 class _Policy(C.Structure):
@@ -113,14 +113,16 @@ class Velocity:
     """Host-side velocity descriptor (mirrors rampde_velocity)."""
 
     def __init__(self, kind: str, widths: Sequence[int] = (), C_: int = 0, H: int = 0, W: int = 0,
-                 time_input: bool = True):
+                 time_input: bool = True, n_intervals: int = 0):
         self.kind = kind
+        self.n_intervals = int(n_intervals)
         self.widths = tuple(int(w) for w in widths)
         self.C, self.H, self.W = int(C_), int(H), int(W)
         self.time_input = bool(time_input)
         self._warr = (C.c_int * max(1, len(self.widths)))(*self.widths) if self.widths else None
         self.c = _Velocity()
-        self.c.kind = VEL_MLP if kind == "mlp" else VEL_CONV2
+        self.c.kind = {"mlp": VEL_MLP, "conv2": VEL_CONV2, "parabolic": VEL_PARABOLIC}[kind]
+        self.c.n_intervals = self.n_intervals
         self.c.n_layers = len(self.widths) - 1 if kind == "mlp" else 2
         self.c.widths = C.cast(self._warr, C.POINTER(C.c_int)) if self._warr is not None else None
         self.c.C, self.c.H, self.c.W = self.C, self.H, self.W
@@ -133,6 +135,10 @@ class Velocity:
     @staticmethod
     def conv2(C_, H, W, time_input=True):
         return Velocity("conv2", C_=C_, H=H, W=W, time_input=time_input)
+
+    @staticmethod
+    def parabolic(C_, H, W, n_intervals=1):
+        return Velocity("parabolic", C_=C_, H=H, W=W, time_input=False, n_intervals=n_intervals)
 
     @property
     def d(self):

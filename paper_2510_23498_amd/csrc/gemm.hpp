@@ -29,7 +29,8 @@ struct GemmNT {
   const float* bias;           // [N] fp32 (already rounded to low) or null
   const float* wt;             // time weights: MLP [N]; conv [9][N]; or null
   float tau;                   // stage time, already rounded to low
-  int act_tanh;                // apply tanh before rounding
+  int act_tanh;                // activation applied before rounding: 0 none, 1 tanh, 2 ReLU
+  int negate;                  // store the negated result (the -W^T of the parabolic block, Sec. 6.3)
   const uint16_t* dact; int ldd;  // stored activation for the factor (1 - act^2), or null
   Ctl* ctl;                    // may be null (forward pass)
   int detect;                  // raise ctl->nonfinite if any output is inf/nan
@@ -199,7 +200,9 @@ __global__ __launch_bounds__(256) void gemm_nt(GemmNT g) {
               v += tv;
             }
           }
-          if (g.act_tanh) v = act_tanh(v);
+          if (g.act_tanh == 1) v = act_tanh(v);
+          else if (g.act_tanh == 2) v = fmaxf(v, 0.f);
+          if (g.negate) v = -v;
           if (g.dact) {
             float av = Low<T>::to_f32(g.dact[(size_t)m * g.ldd + n]);
             v = v * (1.f - av * av);

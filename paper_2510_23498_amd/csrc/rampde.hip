@@ -22,6 +22,7 @@
 #include "wide.hpp"
 #include "gemm.hpp"
 #include "conv.hpp"
+#include "norm.hpp"
 
 namespace rampde {
 
@@ -61,6 +62,13 @@ struct Layer {
 struct Plan {
   bool ok = false;
   bool conv = false;
+  // parabolic block -W^T N(relu(W y + b)) (Sec. 6.3): one convolution used forward and transposed, an
+  // instance normalisation between them, parameters piecewise constant over n_intervals pieces of the grid
+  bool parabolic = false;
+  int n_intervals = 1;
+  int64_t Pblk = 0;                  // parameters of one piece
+  size_t nstat = 0, nstat_vjp = 0, npart = 0;  // statistics [stage][B][Cpad][2], VJP means, chunk sums
+  int norm_chunks = 1, norm_rpc = 0;
   int L = 0;
   int s = 0;
   int64_t R = 0;     // rows: B (dense) or B*H*W (conv)
@@ -147,6 +155,26 @@ static bool build_layers(const rampde_velocity* vel, Plan& p, int hidden_pad = k
       off += y.out;
       p.layers.push_back(y);
     }
+  } else if (vel->kind == RAMPDE_VEL_PARABOLIC) {
+    if (vel->C < 1 || vel->C > 4096 || vel->H < 1 || vel->W < 1 || vel->H > 4096 || vel->W > 4096) return false;
+    if (vel->n_intervals < 0 || vel->n_intervals > 65536 || vel->time_input) return false;
+    p.conv = true;
+    p.parabolic = true;
+    p.n_intervals = vel->n_intervals > 0 ? vel->n_intervals : 1;
+    p.L = 1;
+    p.d = vel->C;
+    p.H = vel->H;
+    p.Wd = vel->W;
+    Layer y{};
+    y.out = y.in = y.in_full = vel->C;
+    y.has_time = 0;
+    y.Npad = y.Kpad = pad64(vel->C);
+    y.ldw = 9 * y.Kpad;
+    y.theta_w = 0;
+    y.theta_b = (size_t)vel->C * vel->C * 9;
+    p.layers.push_back(y);
+    p.Pblk = (int64_t)y.theta_b + vel->C;
+    off = (size_t)p.Pblk * p.n_intervals;
   } else {
     return false;
   }
@@ -333,10 +361,27 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
     p.Z = take((size_t)sbuf * p.R * p.dpad * 2);
     p.K = take((size_t)p.s * p.R * p.dpad * 2);
     for (int l = 0; l + 1 < p.L; ++l) p.ACT.push_back(take((size_t)sbuf * p.R * p.layers[l].Npad * 2));
+    if (p.parabolic) {
+      // ACT[0] = post-ReLU activation r, ACT[1] = normalised activation n; per-stage statistics
+      const Layer& y = p.layers[0];
+      const int64_t HW = (int64_t)p.H * p.Wd, Bn = p.R / HW;
+      for (int q = 0; q < 2; ++q) p.ACT.push_back(take((size_t)sbuf * p.R * y.Npad * 2));
+      p.nstat = take(sizeof(float) * 2 * (size_t)sbuf * Bn * y.Npad);
+      p.nstat_vjp = take(sizeof(float) * 2 * (size_t)Bn * y.Npad);
+      // pixel chunks of the statistics sums: enough workgroups to fill the device, at least 256 pixels each
+      const int64_t base = (int64_t)(y.Npad / 64) * Bn;
+      int64_t chunks = std::max<int64_t>(1, std::min<int64_t>(16, (2 * device_compute_units() + base - 1) / base));
+      int64_t rpc = std::max<int64_t>(256, ((HW + chunks - 1) / chunks + 31) / 32 * 32);
+      p.norm_rpc = (int)rpc;
+      p.norm_chunks = (int)((HW + rpc - 1) / rpc);
+      p.npart = take(sizeof(float) * 2 * (size_t)p.norm_chunks * Bn * y.Npad);
+    }
     if (is_backward) {
       p.KBAR = take((size_t)p.s * p.R * p.dpad * 2);
       p.ZBAR = take((size_t)p.s * p.R * p.dpad * 2);
       for (int l = 0; l + 1 < p.L; ++l) p.DELTA.push_back(take((size_t)p.s * p.R * p.layers[l].Npad * 2));
+      if (p.parabolic)  // DELTA[0] = cotangent of n, DELTA[1] = cotangent of the pre-activation
+        for (int q = 0; q < 2; ++q) p.DELTA.push_back(take((size_t)p.s * p.R * p.layers[0].Npad * 2));
       if (conv_wgrad_applies(p)) {
         // every (K-chunk, 64 x 64 channel block) accumulates its 9 tap blocks over all steps in a
         // copy of its own; one workgroup per compute unit (its LDS holds one), at least 4 k-steps
@@ -508,7 +553,7 @@ struct Runner {
 
   void launch_nt(const GemmNT& g) {
     TimeScope ts(RAMPDE_K_VELOCITY_GEMM, 2.0 * g.M * (double)g.N * g.K, st);
-    if (p.conv && conv_tile_applies(g.Cpad, g.N, g.H, g.Wd, g.M)) {
+    if (p.conv && !p.parabolic && conv_tile_applies(g.Cpad, g.N, g.H, g.Wd, g.M)) {
       // persistent: one workgroup per CU (its LDS holds the layer's weights), tiles of 256 pixels
       const int ntiles = (int)(g.M / CT_TILE);
       conv3x3_tile<T, 8><<<std::min(ntiles, device_compute_units()), 512, conv_tile_lds_bytes(g.Wd), st>>>(g);
@@ -526,6 +571,73 @@ struct Runner {
       gemm_nt<T, 1, 1, false><<<grid, 256, 0, st>>>(g);
     }
   }
+
+  // ---- parabolic block (Sec. 6.3): instance-normalisation statistics of stage buffer jb, then the
+  // elementwise part; vjp: the two means of the normalisation's cotangent formula
+  void norm_stats(const uint16_t* X, const uint16_t* Nrm, float* stat, bool vjp, Ctl* c) {
+    const Layer& y = p.layers[0];
+    const int64_t HW = (int64_t)p.H * p.Wd, Bn = p.R / HW;
+    NormPartial a{};
+    a.X = X; a.Nrm = Nrm; a.ld = y.Npad; a.Cpad = y.Npad; a.B = (int)Bn; a.HW = HW;
+    a.rows_per_chunk = p.norm_rpc; a.part = f32(p.npart); a.ctl = c;
+    dim3 grid(y.Npad / 64, (unsigned)Bn, p.norm_chunks);
+    const int64_t n = Bn * y.Npad;
+    if (vjp) {
+      instnorm_partial<T, true><<<grid, 256, 0, st>>>(a);
+      instnorm_finalize<true><<<blocks_for(n, 256), 256, 0, st>>>(f32(p.npart), p.norm_chunks, n, 1.f / (float)HW, kNormEps, stat, c);
+    } else {
+      instnorm_partial<T, false><<<grid, 256, 0, st>>>(a);
+      instnorm_finalize<false><<<blocks_for(n, 256), 256, 0, st>>>(f32(p.npart), p.norm_chunks, n, 1.f / (float)HW, kNormEps, stat, c);
+    }
+  }
+  float* norm_stat_of(int jb) const {
+    const int64_t Bn = p.R / ((int64_t)p.H * p.Wd);
+    return f32(p.nstat) + 2 * (size_t)jb * Bn * p.layers[0].Npad;
+  }
+  // k_j = -W^T N(relu(W z_j + b)) from the stage input z (stage buffers jb)
+  void parabolic_eval(const uint16_t* z, int j, int jb, Ctl* c) {
+    const Layer& y = p.layers[0];
+    uint16_t* r = u16(p.ACT[0]) + (size_t)jb * p.R * y.Npad;
+    uint16_t* nrm = u16(p.ACT[1]) + (size_t)jb * p.R * y.Npad;
+    GemmNT g{};
+    g.A = z; g.lda = y.Kpad; g.W = u16(y.Wp); g.ldw = y.ldw; g.C = r; g.ldc = y.Npad;
+    g.M = (int)p.R; g.N = y.Npad; g.K = y.ldw; g.bias = f32(y.bias_f); g.act_tanh = 2; g.ctl = c;
+    g.H = p.H; g.Wd = p.Wd; g.Cpad = y.Kpad;
+    launch_nt(g);
+    norm_stats(r, nullptr, norm_stat_of(jb), false, c);
+    NormApply a{};
+    a.X = r; a.Out = nrm; a.ld = y.Npad; a.Cpad = y.Npad; a.HW = (int64_t)p.H * p.Wd; a.rows = p.R;
+    a.stat = norm_stat_of(jb); a.ctl = c;
+    instnorm_apply<T, false><<<stream_blocks(p.R * (y.Npad / 8)), 256, 0, st>>>(a);
+    GemmNT t{};
+    t.A = nrm; t.lda = y.Npad; t.W = u16(y.WTp); t.ldw = 9 * y.Npad; t.C = u16(p.K) + (size_t)j * p.stage_stride; t.ldc = y.Kpad;
+    t.M = (int)p.R; t.N = y.Kpad; t.K = t.ldw; t.negate = 1; t.ctl = c; t.H = p.H; t.Wd = p.Wd; t.Cpad = y.Npad;
+    launch_nt(t);
+  }
+  // cotangent chain of stage j through the block: kbar -> dn -> du -> zbar (eq. (vjp))
+  void parabolic_vjp(const uint16_t* kbar, int j, int detect) {
+    const Layer& y = p.layers[0];
+    const size_t so = (size_t)j * p.R * y.Npad;
+    uint16_t* dn = u16(p.DELTA[0]) + so;
+    uint16_t* du = u16(p.DELTA[1]) + so;
+    GemmNT g{};
+    g.A = kbar; g.lda = y.Kpad; g.W = u16(y.Wp); g.ldw = y.ldw; g.C = dn; g.ldc = y.Npad;
+    g.M = (int)p.R; g.N = y.Npad; g.K = y.ldw; g.negate = 1; g.ctl = ctl; g.detect = detect;
+    g.H = p.H; g.Wd = p.Wd; g.Cpad = y.Kpad;
+    launch_nt(g);
+    norm_stats(dn, u16(p.ACT[1]) + so, f32(p.nstat_vjp), true, ctl);
+    NormApply a{};
+    a.X = dn; a.Nrm = u16(p.ACT[1]) + so; a.Rl = u16(p.ACT[0]) + so; a.Out = du; a.ld = y.Npad; a.Cpad = y.Npad;
+    a.HW = (int64_t)p.H * p.Wd; a.rows = p.R; a.stat = norm_stat_of(j); a.stat_vjp = f32(p.nstat_vjp); a.ctl = ctl;
+    a.detect = detect;
+    instnorm_apply<T, true><<<stream_blocks(p.R * (y.Npad / 8)), 256, 0, st>>>(a);
+    GemmNT t{};
+    t.A = du; t.lda = y.Npad; t.W = u16(y.WTp); t.ldw = 9 * y.Npad; t.C = u16(p.ZBAR) + (size_t)j * p.stage_stride; t.ldc = y.Kpad;
+    t.M = (int)p.R; t.N = y.Kpad; t.K = t.ldw; t.ctl = ctl; t.detect = detect; t.H = p.H; t.Wd = p.Wd; t.Cpad = y.Npad;
+    launch_nt(t);
+  }
+  // piece of the piecewise-constant parameters that step i uses
+  int piece_of(int i, int N) const { return (int)(((int64_t)i * p.n_intervals) / N); }
 
   // stage inputs, stage times and slopes of one step (the inside of Phi), from checkpoint ck.
   // keep != 0: every stage keeps its own input / activation buffers (backward recomputation).
@@ -546,6 +658,10 @@ struct Runner {
       const float tau = round_low_host((float)(t_i + tab->c[j] * (double)h), low);
       if (taus_out) taus_out[j] = tau;
       const uint16_t* in = z;
+      if (p.parabolic) {
+        parabolic_eval(z, j, jb, c);
+        continue;
+      }
       for (int l = 0; l < p.L; ++l) {
         const Layer& y = p.layers[l];
         GemmNT g{};
@@ -754,9 +870,14 @@ struct Runner {
     }
     Coefs bw{};
     for (int j = 0; j < p.s; ++j) bw.v[j] = (float)tab->b[j];
+    int piece = 0;
     for (int i = 0; i < N; ++i) {
       const float h = (float)(tgrid[i + 1] - tgrid[i]);
       const uint16_t* ck = ckpt + (size_t)i * p.n;
+      if (p.parabolic && piece_of(i, N) != piece) {
+        piece = piece_of(i, N);
+        cast_weights(theta + (size_t)piece * p.Pblk);
+      }
       stages(ck, tgrid[i], h, tab, pol->low, 0, nullptr, nullptr);
       // bytes per state element: read y (4) + s slopes (2 each) + write y (4) + write checkpoint (2)
       TimeScope ts(RAMPDE_K_COMBINE_STORE, (double)p.n * (10.0 + 2.0 * p.s), st);
@@ -798,6 +919,10 @@ struct Runner {
                                                                          (float)tab->b[j], acol, h, kbar, p.dpad, p.R,
                                                                          ctl, detect);
       const uint16_t* delta = kbar;
+      if (p.parabolic) {
+        parabolic_vjp(kbar, j, detect);
+        continue;
+      }
       for (int l = p.L - 1; l >= 0; --l) {
         const Layer& y = p.layers[l];
         GemmNT g{};
@@ -861,15 +986,24 @@ struct Runner {
   // parameter gradient of one accepted step: contraction over all stages and rows at once,
   // scaled by h / S_step and accumulated in fp32 (paper Sec. 3, update of g)
   void param_grads(float h, const Coefs& taus, float* grad_theta, const Coefs& cs, float* tpart_i) {
+    // (grad_theta: the gradient of the parameters this step used -- the step's piece when they are piecewise constant)
     const int s = p.s;
     const int64_t rows = (int64_t)s * p.R;
-    for (int l = 0; l < p.L; ++l) {
-      const Layer& y = p.layers[l];
+    // parabolic block: the one weight tensor gets two terms, pass 0: dW += du^T z (and db), pass 1:
+    // dW -= n^T kbar (the slope -W^T n is linear in W with "input" kbar and "output cotangent" n)
+    const int passes = p.parabolic ? 2 : p.L;
+    for (int l = 0; l < passes; ++l) {
+      const Layer& y = p.layers[p.parabolic ? 0 : l];
       GemmTN g{};
       g.A = (l == p.L - 1) ? u16(p.KBAR) : u16(p.DELTA[l]);
       g.lda = y.Npad;
       g.B = (l == 0) ? u16(p.Z) : u16(p.ACT[l - 1]);
       g.ldb = y.Kpad;
+      if (p.parabolic) {
+        g.A = l == 0 ? u16(p.DELTA[1]) : u16(p.ACT[1]);
+        g.B = l == 0 ? u16(p.Z) : u16(p.KBAR);
+        if (l == 1) h = -h;
+      }
       g.rows = rows;
       if (conv_wgrad_applies(p)) {
         // all 9 taps of a 64 x 64 channel block per workgroup
@@ -879,7 +1013,7 @@ struct Runner {
         c.rows_per_split = y.cw_per;
         c.part = f32(y.cw_part);
         c.h = h; c.ctl = ctl; c.H = p.H; c.Wd = p.Wd;
-        c.want_sums = true;
+        c.want_sums = !(p.parabolic && l == 1);
         c.Na = y.out;
         c.R = p.R;
         for (int j = 0; j < kMaxStages; ++j) {
@@ -930,6 +1064,7 @@ struct Runner {
             gemm_tn<T, false><<<grid, 256, 0, st>>>(g);
         }
       }
+      if (p.parabolic && l == 1) continue;
       // bias and time-weight gradients
       int rpb = (int)((rows + 255) / 256);
       if (rpb < 64) rpb = 64;
@@ -1022,7 +1157,23 @@ struct Runner {
       for (auto& y : p.layers)
         fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + y.cw_part),
                                             (size_t)y.cw_splits * (y.Npad / 64) * (y.Kpad / 64) * CW_SLOT);
-    if (!use_fused) cast_weights(theta);
+    // piecewise-constant parameters: the piece whose rounded weights are in the workspace and whose
+    // private gradient copies are being filled (-1: none yet)
+    int piece = -1;
+    auto flush_piece = [&](int q) {
+      // fold the private copies into the piece's gradient, then clear them -- both skipped once a chain
+      // has been rejected, so that the retry continues on the sums of the piece's accepted steps
+      if (!conv_wgrad_applies(p)) return;
+      const Layer& y = p.layers[0];
+      float* gq = grad_theta + (size_t)q * p.Pblk;
+      const int64_t n = (int64_t)y.out * y.in * 9 + (int64_t)y.out * 10;
+      conv_wgrad_reduce<<<blocks_for(n, 256), 256, 0, st>>>(gq + y.theta_w, y.in_full * 9, f32(y.cw_part), y.cw_splits,
+                                                            y.Npad / 64, y.Kpad / 64, y.out, y.in, gq + y.theta_b, nullptr,
+                                                            y.in_full * 9, ctl);
+      fill_zero_unless_poisoned<<<1024, 256, 0, st>>>((uint32_t*)(ws + y.cw_part),
+                                                      (size_t)y.cw_splits * (y.Npad / 64) * (y.Kpad / 64) * CW_SLOT, ctl);
+    };
+    if (!use_fused && !p.parabolic) cast_weights(theta);
     SideStream& side = SideStream::get();
     if (use_fused && p.overlap_wgrad) {
       int rc = side.prepare(N);
@@ -1138,7 +1289,19 @@ struct Runner {
             param_grads_fused(i, h, taus, st);
           }
         } else {
-          backward_step(i, tgrid, tab, pol, ckpt, a, gys_at(i), grad_theta, dynamic, detect,
+          float* g_i = grad_theta;
+          if (p.parabolic) {
+            const int q = piece_of(i, N);
+            if (q != piece) {
+              // (after a rejected chain the loop re-enters inside a piece whose copies are still being
+              // filled: then only the weights are rounded again)
+              if (piece >= 0 && i != from) flush_piece(piece);
+              cast_weights(theta + (size_t)q * p.Pblk);
+              piece = q;
+            }
+            g_i = grad_theta + (size_t)q * p.Pblk;
+          }
+          backward_step(i, tgrid, tab, pol, ckpt, a, gys_at(i), g_i, dynamic, detect,
                         i == from ? recompute_first : true, grad_t ? f32(p.tpart) + 2 * (size_t)i : nullptr);
         }
       }
@@ -1148,7 +1311,10 @@ struct Runner {
         reduce_partial_gradients<<<blocks_for(p.P, 256), 256, 0, st>>>(grad_theta, f32(p.gpart), p.P, p.ksplits, ctl);
       }
       if (grad_t) fold_time_sums<<<blocks_for(N + 1, 256), 256, 0, st>>>(grad_t, f32(p.tpart), N, ctl);
-      if (conv_wgrad_applies(p))
+      if (p.parabolic) {
+        flush_piece(piece);
+        piece = -1;  // (a retry starts by rounding the weights of its piece again)
+      } else if (conv_wgrad_applies(p))
         for (auto& y : p.layers) {
           const int64_t n = (int64_t)y.out * y.in * 9 + (int64_t)y.out * 10;
           conv_wgrad_reduce<<<blocks_for(n, 256), 256, 0, st>>>(
@@ -1353,6 +1519,8 @@ int rampde_odeint_bwd_tgrid(const rampde_velocity* vel, const float* theta, int6
   if (rc) return rc;
   if (!theta || !ckpt || !grad_yN || !grad_y0 || !grad_theta || !workspace || B < 1) return RAMPDE_EINVAL;
   if (pol->scale_group < 0) return RAMPDE_EINVAL;
+  // (the parabolic block has no time input and step-wise constant parameters: no time-grid gradient is formed)
+  if (grad_t && vel->kind == RAMPDE_VEL_PARABOLIC) return RAMPDE_EUNSUPPORTED;
   if (!aligned16(theta) || !aligned16(ckpt) || !aligned16(grad_yN) || !aligned16(grad_ys) || !aligned16(grad_y0) ||
       !aligned16(grad_theta))
     return RAMPDE_EINVAL;

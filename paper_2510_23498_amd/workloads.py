@@ -105,7 +105,7 @@ TABLEAUX: Dict[str, Tableau] = {
 @dataclass(frozen=True)
 class Config:
     name: str
-    kind: str  # "mlp" or "conv2"
+    kind: str  # "mlp", "conv2" or "parabolic"
     B: int
     low: str  # "f16" | "bf16"
     tableau: str
@@ -113,9 +113,10 @@ class Config:
     t0: float
     t1: float
     widths: Tuple[int, ...] = ()  # mlp: (d, hidden..., d); the time column is implicit
-    C: int = 0  # conv2
+    C: int = 0  # conv2, parabolic
     H: int = 0
     W: int = 0
+    n_intervals: int = 1  # parabolic: pieces of the piecewise-constant parameters
     loss: str = "half_sse"  # "half_sse" | "mse" | "mean_sq"
     grad_scale: float = 1.0
     scaling: str = "auto"  # "none" | "dynamic" | "auto"
@@ -134,6 +135,8 @@ class Config:
         if self.kind == "mlp":
             return sum((self.widths[l] + (1 if l == 0 else 0)) * self.widths[l + 1] + self.widths[l + 1]
                        for l in range(len(self.widths) - 1))
+        if self.kind == "parabolic":
+            return self.n_intervals * (self.C * self.C * 9 + self.C)
         return 2 * (self.C * (self.C + 1) * 9 + self.C)
 
     def tgrid(self) -> np.ndarray:
@@ -155,6 +158,10 @@ CONFIGS: Dict[str, Config] = {
                    C=64, H=32, W=32, loss="mean_sq"),
     "cfg5": Config("cfg5", "mlp", B=1024, low="f16", tableau="rk4", N=256, t0=0.0, t1=1.0,
                    widths=(256, 1024, 1024, 256), loss="mse"),
+    # the middle neural-ODE block of the paper's image classifier (Sec. 6.3): 256 channels, 64 x 64
+    # pixels, batch 16, four RK4 steps with weights that are constant on each step
+    "parab": Config("parab", "parabolic", B=16, low="f16", tableau="rk4", N=4, t0=0.0, t1=1.0,
+                    C=256, H=64, W=64, n_intervals=4, loss="mean_sq"),
 }
 
 
@@ -176,6 +183,10 @@ def theta_layout(cfg: Config) -> List[Tuple[str, Tuple[int, ...], int]]:
         for l, (o, i) in enumerate(mlp_layer_shapes(cfg.widths)):
             out.append((f"W{l + 1}", (o, i), off)); off += o * i
             out.append((f"b{l + 1}", (o,), off)); off += o
+    elif cfg.kind == "parabolic":
+        for q in range(cfg.n_intervals):
+            out.append((f"W{q + 1}", (cfg.C, cfg.C, 3, 3), off)); off += cfg.C * cfg.C * 9
+            out.append((f"b{q + 1}", (cfg.C,), off)); off += cfg.C
     else:
         for l in range(2):
             shp = (cfg.C, cfg.C + 1, 3, 3)
@@ -194,6 +205,8 @@ def make_theta(cfg: Config, bias_std: float = 0.0) -> np.ndarray:
 
     MLP: W ~ N(0, 1/fan_in), fan_in counting the time column; b = 0.
     Conv: He-normal, std = sqrt(2/fan_in), fan_in = (C+1)*9; b = 0.
+    Parabolic block: W ~ N(0, 1/fan_in), fan_in = 9 C (the normalised activation has unit variance and
+    W^T W then has O(1) gain, so the state neither dies nor blows up over t in [0,1]); b = 0.
     `bias_std` > 0 draws non-zero biases (used by tests so that the bias path
     cannot be wrong unnoticed).
     """
@@ -202,7 +215,7 @@ def make_theta(cfg: Config, bias_std: float = 0.0) -> np.ndarray:
         cnt = int(np.prod(shp))
         if name.startswith("W"):
             fan_in = int(np.prod(shp[1:]))
-            std = (1.0 / fan_in) ** 0.5 if cfg.kind == "mlp" else (2.0 / fan_in) ** 0.5
+            std = (2.0 / fan_in) ** 0.5 if cfg.kind == "conv2" else (1.0 / fan_in) ** 0.5
             theta[off:off + cnt] = normals(cfg.seed, f"{cfg.name}.theta.{name}", (cnt,), std)
         elif bias_std > 0.0:
             theta[off:off + cnt] = normals(cfg.seed, f"{cfg.name}.theta.{name}", (cnt,), bias_std)

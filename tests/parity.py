@@ -54,6 +54,8 @@ def oracle_velocity(cfg: wl.Config):
     from oracle import rampde_oracle as orc
     if cfg.kind == "mlp":
         return orc.MLPVelocity(cfg.widths, time_input=True)
+    if cfg.kind == "parabolic":
+        return orc.ParabolicConvVelocity(cfg.C, cfg.H, cfg.W, n_intervals=cfg.n_intervals)
     return orc.Conv2Velocity(cfg.C, cfg.H, cfg.W, time_input=True)
 
 
@@ -108,6 +110,8 @@ def gpu_descriptors(cfg: wl.Config, scaling: str = None, k_max: int = 16, flags:
     from paper_2510_23498_amd import binding as rb
     if cfg.kind == "mlp":
         vel = rb.Velocity.mlp(cfg.widths, time_input=True)
+    elif cfg.kind == "parabolic":
+        vel = rb.Velocity.parabolic(cfg.C, cfg.H, cfg.W, n_intervals=cfg.n_intervals)
     else:
         vel = rb.Velocity.conv2(cfg.C, cfg.H, cfg.W, time_input=True)
     t = wl.TABLEAUX[cfg.tableau]
