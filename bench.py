@@ -7,7 +7,8 @@ Algorithm 2).  Metric: batch * RK-steps per second = B * N / (t_fwd + t_bwd).
 
 Prints ONE JSON line.  The headline (`value`, `roofline`, `cpu_baseline`) is the largest dense
 workload, cfg3 (fp16, batch 16384, 512-wide, 64 RK4 steps, dynamic adjoint scaling); `all_configs`
-holds one record per synthetic workload (cfg1, cfg2, cfg3, cfg4, cfg5 under RK4 / Heun / Euler)
+holds one record per synthetic workload (cfg1, cfg2, cfg3, cfg4, cfg5 under RK4 / Heun / Euler, and
+"parab": the parabolic convolution block of the paper's Sec. 6.3 at 256 channels, 64 x 64 pixels, batch 16)
 measured the same way with fewer passes.
 
 `roofline` is measured in a second, instrumented run of the same K passes (HIP events around
@@ -32,7 +33,7 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0}   # MI355X dense matrix peak
 PEAK_HBM_GBS = 8000.0
 HEADLINE = "cfg3"
 ALL_CONFIGS = [("cfg1", None), ("cfg2", None), ("cfg3", None), ("cfg4", None),
-               ("cfg5", "rk4"), ("cfg5", "heun"), ("cfg5", "euler")]
+               ("cfg5", "rk4"), ("cfg5", "heun"), ("cfg5", "euler"), ("parab", None)]
 # evaluations of the velocity per forward evaluation that a kernel class performs
 CLASS_EVALS = {"fused_forward": 1.0, "fused_adjoint_step": 2.0, "wgrad_gemm": 1.0, "velocity_gemm": 3.0}
 
@@ -43,6 +44,8 @@ def macs_per_row(cfg):
     if cfg.kind == "mlp":
         w = cfg.widths
         return sum((w[l] + (1 if l == 0 else 0)) * w[l + 1] for l in range(len(w) - 1))
+    if cfg.kind == "parabolic":
+        return 2 * cfg.C * 9 * cfg.C     # the convolution and its transpose
     return 2 * (cfg.C + 1) * 9 * cfg.C
 
 
