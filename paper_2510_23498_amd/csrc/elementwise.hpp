@@ -272,14 +272,24 @@ __global__ void adjoint_update(float* __restrict__ a, int d, const uint16_t* __r
 }
 
 // end of a step: record S_i, decide growth   (paper Alg. 2, doubling rule)
-__global__ void scale_grow(Ctl* ctl, float* scale_hist, int step, int p_bits, int dynamic, int raw_norm) {
+// (slots: per-workgroup maxima of |a| written by adjoint_update_v8 instead of one atomic per workgroup on
+// a single address -- a thousand of those cost as much as a third of that kernel's streaming time;
+// folded here by the workgroup's threads, launched with 256 threads)
+__global__ void scale_grow(Ctl* ctl, float* scale_hist, int step, int p_bits, int dynamic, int raw_norm,
+                           const unsigned* __restrict__ slots, int nslots) {
   if (ctl->poison) return;
+  unsigned bits = 0;
+  for (int i = threadIdx.x; i < nslots; i += blockDim.x) bits = slots[i] > bits ? slots[i] : bits;
+  block_amax(bits, &ctl->amax_bits);
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  __threadfence();
   float S = ctl->S;
   scale_hist[step] = S;
   ctl->s_min = fminf(ctl->s_min, S);
   ctl->s_max = fmaxf(ctl->s_max, S);
   if (dynamic && ctl->attempt == 1) {
-    float amax = __builtin_bit_cast(float, ctl->amax_bits);
+    float amax = __builtin_bit_cast(float, atomicMax(&ctl->amax_bits, 0u));
     float test = raw_norm ? amax : S * amax;
     if (test <= ldexpf(1.f, p_bits - 1) && S < ldexpf(1.f, 126)) ctl->S = 2.f * S;
   }
@@ -562,40 +572,74 @@ template <class T>
 __global__ __launch_bounds__(256) void adjoint_update_v8(float* __restrict__ a, int d,
                                                          const uint16_t* __restrict__ zbar, int64_t stage_stride, int s,
                                                          float h, const float* __restrict__ gys_i, int ld, int64_t R,
-                                                         Ctl* ctl, int naive) {
-  if (ctl->poison) return;
+                                                         Ctl* ctl, int naive, unsigned* __restrict__ slots) {
   const int gpr = d >> 3;
   const int64_t G = R * gpr;
-  const float hs = h / ctl->S;
   unsigned bits = 0;
-  for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < G; g += (int64_t)gridDim.x * blockDim.x) {
+  // The streaming loads of a thread's first group are requested BEFORE the control block is looked at:
+  // the rejected-chain flag and the scale are one more memory round trip, which would otherwise sit in
+  // front of every load of a kernel that runs for a few tens of microseconds.  Nothing is stored before
+  // the flag is known.
+  int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  u16x8 zq[kMaxStages];
+  float av[8];
+  auto request = [&](int64_t gi) {
+    const int64_t r = gi / gpr;
+    const int c = (int)(gi - r * gpr) << 3;
+#pragma unroll
+    for (int j = 0; j < kMaxStages; ++j)
+      if (j < s) zq[j] = *reinterpret_cast<const u16x8*>(zbar + j * stage_stride + r * ld + c);
+    load8f(a + r * d + c, av);
+  };
+  if (g < G) request(g);
+  const int poison = ctl->poison;
+  const float hs = h / ctl->S;
+  if (poison) return;
+  for (; g < G;) {
     const int64_t r = g / gpr;
     const int c = (int)(g - r * gpr) << 3;
-    float da[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, zj[8], av[8];
-    for (int j = 0; j < s; ++j) {
-      unpack8<T>(*reinterpret_cast<const u16x8*>(zbar + j * stage_stride + r * ld + c), zj);
+    float da[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, zj[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) da[e] += zj[e];
-    }
-    load8f(a + r * d + c, av);
+    for (int j = 0; j < kMaxStages; ++j)
+      if (j < s) {
+        unpack8<T>(zq[j], zj);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) da[e] += zj[e];
+      }
+    float out[8];
     if (gys_i) {
       float gy[8];
       load8f(gys_i + r * d + c, gy);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) av[e] = fmaf(hs, da[e], av[e]) + gy[e];
+      for (int e = 0; e < 8; ++e) out[e] = fmaf(hs, da[e], av[e]) + gy[e];
     } else {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) av[e] = fmaf(hs, da[e], av[e]);
+      for (int e = 0; e < 8; ++e) out[e] = fmaf(hs, da[e], av[e]);
     }
-    if (naive) unpack8<T>(pack8<T>(av), av);
-    store8f(a + r * d + c, av);
+    if (naive) unpack8<T>(pack8<T>(out), out);
+    const int64_t gn = g + (int64_t)gridDim.x * blockDim.x;
+    if (gn < G) request(gn);  // (a different group: no overlap with the store below)
+    store8f(a + r * d + c, out);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const unsigned bb = __builtin_bit_cast(unsigned, fabsf(av[e]));
+      const unsigned bb = __builtin_bit_cast(unsigned, fabsf(out[e]));
       bits = bb > bits ? bb : bits;
     }
+    g = gn;
   }
-  block_amax(bits, &ctl->amax_bits);
+  // the workgroup's maximum goes to its own slot (folded by scale_grow)
+  for (int o = 32; o > 0; o >>= 1) {
+    const unsigned other = __shfl_xor(bits, o);
+    bits = bits > other ? bits : other;
+  }
+  __shared__ unsigned wmax[4];
+  if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = bits;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned m = wmax[0];
+    for (int i = 1; i < 4; ++i) m = wmax[i] > m ? wmax[i] : m;
+    slots[blockIdx.x] = m;
+  }
 }
 
 }  // namespace rampde

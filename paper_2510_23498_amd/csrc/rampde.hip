@@ -92,6 +92,7 @@ struct Plan {
   size_t lds_bytes = 0;
   size_t steptab = 0, a_alt = 0, bsum = 0;
   size_t tpart = 0;                 // [N][2] fp32 per-step sums of the time-grid gradient
+  size_t amax_slots = 0;            // [4096] per-workgroup maxima of |a| (per-layer path)
   int nparam = 0, wt_off = 0;
   bool k_in_lds = false;
   bool overlap_wgrad = false;       // narrow nets: 4-wave adjoint kernel + parameter gradients on a helper stream
@@ -401,6 +402,7 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
     }
   }
   if (is_backward) p.tpart = take(sizeof(float) * 2 * (size_t)N);
+  if (is_backward) p.amax_slots = take(sizeof(unsigned) * 4096);  // per-workgroup maxima of the streaming adjoint update
   p.total = off;
   p.ok = true;
   return p;
@@ -968,19 +970,23 @@ struct Runner {
       time_grid_terms<T><<<stream_blocks(p.n, 1024), 256, 0, st>>>(a, p.d, u16(p.K), u16(p.ZBAR), p.stage_stride, s, bw,
                                                                    am, h, p.dpad, p.R, ctl, tpart_i);
     }
-    param_grads(h, taus, grad_theta, cs, tpart_i);
+    // (the fp32 update of a comes before the parameter gradients, which do not read it: the stage
+    // cotangents it streams are then still in the last-level cache)
+    int nslots = 0;
     {
       // bytes per state element: read a (4) + s stage cotangents (2 each) + write a (4)
       TimeScope ts(RAMPDE_K_ADJOINT_UPDATE, (double)p.n * (8.0 + 2.0 * s), st);
-      if (vec8())
-        adjoint_update_v8<T><<<stream_blocks(p.n / 8, 1024), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, s, h, gys_i,
-                                                                    p.dpad, p.R, ctl, naive);
-      else
+      if (vec8()) {
+        nslots = (int)stream_blocks(p.n / 8);  // (at most 4096: the size of the slot array)
+        adjoint_update_v8<T><<<nslots, 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, s, h, gys_i, p.dpad, p.R, ctl,
+                                                     naive, (unsigned*)(ws + p.amax_slots));
+      } else
         adjoint_update<T><<<blocks_for(p.n, 256), 256, 0, st>>>(a, p.d, u16(p.ZBAR), p.stage_stride, s, h, gys_i,
                                                                p.dpad, p.R, ctl, naive);
     }
-    scale_grow<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), i, Low<T>::p_bits, dynamic,
-                                (pol->flags & RAMPDE_GROW_RAW_NORM) ? 1 : 0);
+    scale_grow<<<1, 256, 0, st>>>(ctl, f32(p.scale_hist), i, Low<T>::p_bits, dynamic,
+                                  (pol->flags & RAMPDE_GROW_RAW_NORM) ? 1 : 0, (const unsigned*)(ws + p.amax_slots), nslots);
+    param_grads(h, taus, grad_theta, cs, tpart_i);
   }
 
   // parameter gradient of one accepted step: contraction over all stages and rows at once,
