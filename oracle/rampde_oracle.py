@@ -392,6 +392,67 @@ class ParabolicConvVelocity:
         return zbar.reshape(kbar.shape), dtheta, finite, None
 
 
+class CNFVelocity:
+    """Augmented state of a continuous normalising flow (paper Sec. 6.1):  y = [z; l],
+
+        dz/dt = v(t, z),      dl/dt = -tr(dv/dz),
+
+    with the trace formed analytically (the paper replaces the stochastic estimator by the direct
+    trace).  The velocity is one hidden layer, v = W2 tanh(W1 [z; t] + b1) + b2 -- the summed-tanh-units
+    form of the paper's CNF velocity with the weights given directly instead of through a hypernetwork --
+    for which   tr(dv/dz) = sum_h c_h (1 - a_h^2),   c_h = sum_i W2[i,h] W1[h,i],   a = tanh(.).
+    theta layout: that of MLPVelocity((d, H, d)): W1[H, d+1] (time column last), b1[H], W2[d, H], b2[d].
+    The state has d + 1 columns; the velocity does not depend on l.
+
+    Rounding points in emulation mode: those of the MLP (activation, slope) plus: c_h and the trace sum
+    are fp32 (from the rounded weights and the rounded activation), dl/dt is rounded to `low` like the
+    other slope entries; in the VJP the cotangent of the activation gets the extra term 2 kbar_l c_h a_h
+    inside the fp32 sum before the tanh' factor and the rounding.
+    """
+
+    time_input = True
+
+    def __init__(self, d: int, H: int):
+        self.d, self.H = int(d), int(H)
+        self.mlp = MLPVelocity((self.d, self.H, self.d), time_input=True)
+        self.n_params = self.mlp.n_params
+
+    def state_size(self):
+        return self.d + 1
+
+    def eval(self, theta_q, y, tau, Q, R32):
+        (W1, wt, b1), (W2, _, b2) = self.mlp.split(theta_q)
+        z = y[:, :self.d]
+        a = Q(R32(np.tanh(R32(z @ W1.T + tau * wt + b1))))
+        v = Q(R32(a @ W2.T + b2))
+        c = R32(np.einsum("ih,hi->h", W2, W1))
+        ldot = Q(R32(-((1.0 - a * a) @ c)))
+        return np.concatenate([v, ldot[:, None]], axis=1), (z, a, c, tau)
+
+    def vjp(self, theta_q, cache, kbar, Q, R32):
+        z, a, c, tau = cache
+        (W1, wt, b1), (W2, _, b2) = self.mlp.split(theta_q)
+        (o1, i1, w1off, b1off), (o2, i2, w2off, b2off) = self.mlp.shapes
+        kz, kl = kbar[:, :self.d], kbar[:, self.d]
+        dtheta = np.zeros(self.n_params, dtype=np.float64)
+        s = kl @ (1.0 - a * a)                       # cotangent of -c_h (batch sums)
+        dW2 = kz.T @ a - W1.T * s[None, :]
+        dtheta[w2off:w2off + o2 * i2] = dW2.ravel()
+        dtheta[b2off:b2off + o2] = kz.sum(axis=0)
+        back = R32(kz @ W2 + 2.0 * kl[:, None] * (c[None, :] * a))
+        d1 = Q(R32(back * (1.0 - a * a)))
+        dW1 = np.zeros((o1, i1))
+        dW1[:, :self.d] = d1.T @ z - W2.T * s[:, None]
+        colsum = d1.sum(axis=0)
+        dW1[:, -1] = colsum * tau
+        dtheta[w1off:w1off + o1 * i1] = dW1.ravel()
+        dtheta[b1off:b1off + o1] = colsum
+        zbar = Q(R32(d1 @ W1))
+        finite = bool(np.all(np.isfinite(d1))) and bool(np.all(np.isfinite(zbar)))
+        ybar = np.concatenate([zbar, np.zeros((len(zbar), 1))], axis=1)
+        return ybar, dtheta, finite, float(colsum @ wt)
+
+
 class PolyDecayVelocity:
     """Scalar test problem of the paper's Example 3.1:  y' = -(th1 t^2 + th2 t + th3) y.
 

@@ -931,3 +931,113 @@ def test_parabolic_emulation_is_close_to_fp64(low, tol):
     assert rel(out[low][1].grad_y0, out["f64"][1].grad_y0) < tol
     assert rel(out[low][1].grad_theta, out["f64"][1].grad_theta) < tol
     assert out[low][1].status == "ok"
+
+
+# ------------------------------------------------------------------ CNF augmented state with exact trace (Sec. 6.1)
+def test_cnf_trace_row_is_minus_the_jacobian_trace():
+    # dl/dt against the trace of a finite-difference Jacobian of the velocity part
+    rng = np.random.default_rng(41)
+    d, H, B = 3, 7, 4
+    vel = orc.CNFVelocity(d, H)
+    theta = rng.normal(size=vel.n_params) * 0.7
+    y = rng.normal(size=(B, d + 1))
+    Q, R32 = orc.make_quantisers("f64")
+    k, _ = vel.eval(theta, y, 0.3, Q, R32)
+    eps = 1e-6
+    tr = np.zeros(B)
+    for i in range(d):
+        e = np.zeros_like(y); e[:, i] = eps
+        kp, _ = vel.eval(theta, y + e, 0.3, Q, R32)
+        km, _ = vel.eval(theta, y - e, 0.3, Q, R32)
+        tr += (kp[:, i] - km[:, i]) / (2 * eps)
+    assert np.max(np.abs(k[:, d] + tr)) < 1e-8
+    # the velocity part is the plain one-hidden-layer network and ignores l
+    mk, _ = vel.mlp.eval(theta, y[:, :d], 0.3, Q, R32)
+    assert rel(k[:, :d], mk) < 1e-14
+    y2 = y.copy(); y2[:, d] += 5.0
+    k2, _ = vel.eval(theta, y2, 0.3, Q, R32)
+    assert np.array_equal(k, k2)
+
+
+def test_cnf_log_density_of_a_linear_flow_closed_form():
+    # tanh replaced by its linearisation at small arguments: for tiny weights W1 the flow is z' ~ W2 W1 z and
+    # l(T) ~ -T tr(W2 W1): the change-of-variables term of a linear map (closed form), to first order in |W1|
+    rng = np.random.default_rng(42)
+    d, H = 2, 5
+    vel = orc.CNFVelocity(d, H)
+    (o1, i1, w1off, b1off), (o2, i2, w2off, b2off) = vel.mlp.shapes
+    theta = np.zeros(vel.n_params)
+    W1 = rng.normal(size=(H, d)) * 1e-4
+    W2 = rng.normal(size=(d, H))
+    th1 = np.zeros((H, d + 1)); th1[:, :d] = W1
+    theta[w1off:w1off + o1 * i1] = th1.ravel()
+    theta[w2off:w2off + o2 * i2] = W2.ravel()
+    y0 = np.concatenate([rng.normal(size=(3, d)), np.zeros((3, 1))], axis=1)
+    tg = np.linspace(0.0, 1.0, 9)
+    yN, _ = orc.odeint_fwd(vel, theta, y0, tg, tab("rk4"), orc.Policy(low="f64"))
+    want = -np.trace(W2 @ W1)
+    assert np.allclose(yN[:, d], want, rtol=1e-6, atol=1e-12)
+
+
+@pytest.mark.parametrize("name", ["euler", "rk4", "kutta3"])
+def test_cnf_gradients_match_finite_differences(name):
+    rng = np.random.default_rng(43)
+    d, H, B = 2, 5, 3
+    vel = orc.CNFVelocity(d, H)
+    theta = rng.normal(size=vel.n_params) * 0.6
+    y0 = np.concatenate([rng.normal(size=(B, d)), np.zeros((B, 1))], axis=1)
+    tg = np.array([0.0, 0.25, 0.6, 1.0])
+    target = rng.normal(size=y0.shape)          # the loss weighs z(T) and l(T): both cotangents are exercised
+    pol = orc.Policy(low="f64")
+
+    def loss(th, y):
+        yN, _ = orc.odeint_fwd(vel, th, y, tg, tab(name), pol)
+        return 0.5 * np.sum((yN - target) ** 2)
+
+    yN, ck = orc.odeint_fwd(vel, theta, y0, tg, tab(name), pol)
+    res = orc.odeint_bwd(vel, theta, tg, tab(name), pol, ck, yN - target)
+    step = 1e-6
+    g_fd = np.zeros_like(theta)
+    for p in range(theta.size):
+        e = np.zeros_like(theta); e[p] = step
+        g_fd[p] = (loss(theta + e, y0) - loss(theta - e, y0)) / (2 * step)
+    a_fd = np.zeros_like(y0)
+    for idx in np.ndindex(*y0.shape):
+        e = np.zeros_like(y0); e[idx] = step
+        a_fd[idx] = (loss(theta, y0 + e) - loss(theta, y0 - e)) / (2 * step)
+    assert rel(res.grad_theta, g_fd) < 5e-6, rel(res.grad_theta, g_fd)
+    assert rel(res.grad_y0, a_fd) < 5e-6, rel(res.grad_y0, a_fd)
+    # dL/dl(0) = dL/dl(T): the velocity does not depend on l
+    assert np.allclose(res.grad_y0[:, d], (yN - target)[:, d], rtol=1e-12)
+    # the time-grid gradient of this velocity, against finite differences in every grid point
+    t_fd = np.zeros_like(tg)
+    for m in range(len(tg)):
+        e = np.zeros_like(tg); e[m] = step
+
+        def lt(tt):
+            yN2, _ = orc.odeint_fwd(vel, theta, y0, tt, tab(name), pol)
+            return 0.5 * np.sum((yN2 - target) ** 2)
+        t_fd[m] = (lt(tg + e) - lt(tg - e)) / (2 * step)
+    assert rel(res.grad_t, t_fd) < 5e-6, rel(res.grad_t, t_fd)
+
+
+@pytest.mark.parametrize("low,tol", [("f16", 2e-2), ("bf16", 5e-2)])
+def test_cnf_emulation_is_close_to_fp64(low, tol):
+    rng = np.random.default_rng(44)
+    d, H, B = 7, 64, 16
+    vel = orc.CNFVelocity(d, H)
+    theta = np.zeros(vel.n_params)
+    (o1, i1, w1off, b1off), (o2, i2, w2off, b2off) = vel.mlp.shapes
+    theta[w1off:w1off + o1 * i1] = rng.normal(size=o1 * i1) / np.sqrt(i1)
+    theta[w2off:w2off + o2 * i2] = rng.normal(size=o2 * i2) / np.sqrt(i2)
+    y0 = np.concatenate([rng.normal(size=(B, d)), np.zeros((B, 1))], axis=1)
+    tg = np.linspace(0.0, 1.0, 9)
+    gN = rng.normal(size=y0.shape) * 1e-2
+    out = {}
+    for lw in ("f64", low):
+        pol = orc.Policy(low=lw, scaling="dynamic")
+        yN, ck = orc.odeint_fwd(vel, theta, y0, tg, tab("rk4"), pol)
+        out[lw] = (yN, orc.odeint_bwd(vel, theta, tg, tab("rk4"), pol, ck, gN))
+    assert rel(out[low][0], out["f64"][0]) < tol
+    assert rel(out[low][1].grad_y0, out["f64"][1].grad_y0) < tol
+    assert rel(out[low][1].grad_theta, out["f64"][1].grad_theta) < tol
