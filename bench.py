@@ -33,7 +33,7 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0}   # MI355X dense matrix peak
 PEAK_HBM_GBS = 8000.0
 HEADLINE = "cfg3"
 ALL_CONFIGS = [("cfg1", None), ("cfg2", None), ("cfg3", None), ("cfg4", None),
-               ("cfg5", "rk4"), ("cfg5", "heun"), ("cfg5", "euler"), ("parab", None)]
+               ("cfg5", "rk4"), ("cfg5", "heun"), ("cfg5", "euler"), ("parab", None), ("cnf", None)]
 # evaluations of the velocity per forward evaluation that a kernel class performs
 CLASS_EVALS = {"fused_forward": 1.0, "fused_adjoint_step": 2.0, "wgrad_gemm": 1.0, "velocity_gemm": 3.0}
 
@@ -41,7 +41,7 @@ CLASS_EVALS = {"fused_forward": 1.0, "fused_adjoint_step": 2.0, "wgrad_gemm": 1.
 def macs_per_row(cfg):
     """Multiply-accumulates of one velocity evaluation per batch row (MLP) or per pixel (conv),
     unpadded, time column / time channel included."""
-    if cfg.kind == "mlp":
+    if cfg.kind in ("mlp", "cnf"):
         w = cfg.widths
         return sum((w[l] + (1 if l == 0 else 0)) * w[l + 1] for l in range(len(w) - 1))
     if cfg.kind == "parabolic":
@@ -50,11 +50,11 @@ def macs_per_row(cfg):
 
 
 def rows_of(cfg):
-    return cfg.B if cfg.kind == "mlp" else cfg.B * cfg.H * cfg.W
+    return cfg.B if cfg.kind in ("mlp", "cnf") else cfg.B * cfg.H * cfg.W
 
 
 def describe(cfg, wl, extra=""):
-    shape = list(cfg.widths) if cfg.kind == "mlp" else [cfg.C, cfg.H, cfg.W]
+    shape = list(cfg.widths) if cfg.kind in ("mlp", "cnf") else [cfg.C, cfg.H, cfg.W]
     return (f"{cfg.name}: {cfg.kind} B={cfg.B} widths={shape} {cfg.tableau} N={cfg.N} t=[{cfg.t0},{cfg.t1}] "
             f"low={cfg.low} scaling={wl.resolve_scaling(cfg)}" + extra)
 

@@ -38,9 +38,9 @@
  *       PARABOLIC: for each piece q = 0 .. n_intervals-1: W_q[C][C][3][3], b_q[C].
  *     Activation is tanh after every layer but the last (MLP, CONV2); ReLU in PARABOLIC.
  *   - State layout at the boundary (y0, yN, grad_yN, grad_y0, grad_ys), fp32:
- *       MLP [B][d];  CONV2 and PARABOLIC NCHW [B][C][H][W].
+ *       MLP [B][d];  CNF [B][d+1] (l last);  CONV2 and PARABOLIC NCHW [B][C][H][W].
  *   - Checkpoint layout (ckpt, written by fwd, read by bwd; element type = policy.low):
- *       MLP [N+1][B][d];  CONV2 and PARABOLIC channels-last [N+1][B][H][W][C].
+ *       MLP [N+1][B][d];  CNF [N+1][B][d+1];  CONV2 and PARABOLIC channels-last [N+1][B][H][W][C].
  */
 #ifndef RAMPDE_H
 #define RAMPDE_H
@@ -68,8 +68,12 @@ typedef enum {
  * normalisation (per sample and channel over the H*W pixels, biased variance, eps = 1e-5, no affine
  * parameters; statistics and arithmetic in fp32, result rounded to `low`).  No time input; instead the
  * parameters are piecewise constant in time: step i of an N-step grid uses piece i * n_intervals / N
- * (integer division) for all of its stages. */
-typedef enum { RAMPDE_VEL_MLP = 0, RAMPDE_VEL_CONV2 = 1, RAMPDE_VEL_PARABOLIC = 2 } rampde_vel_kind;
+ * (integer division) for all of its stages.
+ * CNF is the augmented state of a continuous normalising flow (Sec. 6.1): y = [z; l] with d + 1 columns,
+ * dz/dt = v(t, z) = W2 tanh(W1 [z; t] + b1) + b2 (n_layers = 2, widths = {d, H, d}), dl/dt = -tr(dv/dz)
+ * formed analytically (sum_h c_h (1 - a_h^2), c_h = sum_i W2[i,h] W1[h,i], in fp32 from the rounded
+ * weights and activations, rounded to `low` like the other slope entries).  theta is that of the MLP. */
+typedef enum { RAMPDE_VEL_MLP = 0, RAMPDE_VEL_CONV2 = 1, RAMPDE_VEL_PARABOLIC = 2, RAMPDE_VEL_CNF = 3 } rampde_vel_kind;
 
 typedef enum {
   RAMPDE_OK = 0,

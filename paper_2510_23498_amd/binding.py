@@ -18,7 +18,7 @@ from .build import LIB_PATH
 
 F32, F16, BF16 = 0, 1, 2
 SCALE_NONE, SCALE_NONE_SAFE, SCALE_DYNAMIC, SCALE_AUTO = 0, 1, 2, 3
-VEL_MLP, VEL_CONV2, VEL_PARABOLIC = 0, 1, 2
+VEL_MLP, VEL_CONV2, VEL_PARABOLIC, VEL_CNF = 0, 1, 2, 3
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, ESCALE, EHIP = 0, 1, 2, 3, 4, 5
 _LOW = {"f32": F32, "f16": F16, "bf16": BF16}
 _SCALING = {"none": SCALE_NONE, "none_safe": SCALE_NONE_SAFE, "dynamic": SCALE_DYNAMIC, "auto": SCALE_AUTO}
@@ -121,9 +121,9 @@ class Velocity:
         self.time_input = bool(time_input)
         self._warr = (C.c_int * max(1, len(self.widths)))(*self.widths) if self.widths else None
         self.c = _Velocity()
-        self.c.kind = {"mlp": VEL_MLP, "conv2": VEL_CONV2, "parabolic": VEL_PARABOLIC}[kind]
+        self.c.kind = {"mlp": VEL_MLP, "conv2": VEL_CONV2, "parabolic": VEL_PARABOLIC, "cnf": VEL_CNF}[kind]
         self.c.n_intervals = self.n_intervals
-        self.c.n_layers = len(self.widths) - 1 if kind == "mlp" else 2
+        self.c.n_layers = len(self.widths) - 1 if kind in ("mlp", "cnf") else 2
         self.c.widths = C.cast(self._warr, C.POINTER(C.c_int)) if self._warr is not None else None
         self.c.C, self.c.H, self.c.W = self.C, self.H, self.W
         self.c.time_input = 1 if self.time_input else 0
@@ -137,17 +137,28 @@ class Velocity:
         return Velocity("conv2", C_=C_, H=H, W=W, time_input=time_input)
 
     @staticmethod
+    def cnf(d, H, time_input=True):
+        """state [z; l] of d + 1 columns; velocity d -> H -> d with the exact trace row"""
+        return Velocity("cnf", widths=(d, H, d), time_input=time_input)
+
+    @staticmethod
     def parabolic(C_, H, W, n_intervals=1):
         return Velocity("parabolic", C_=C_, H=H, W=W, time_input=False, n_intervals=n_intervals)
 
     @property
     def d(self):
+        if self.kind == "cnf":
+            return self.widths[0] + 1
         return self.widths[0] if self.kind == "mlp" else self.C * self.H * self.W
 
     def state_shape(self, B):
+        if self.kind == "cnf":
+            return (B, self.widths[0] + 1)
         return (B, self.widths[0]) if self.kind == "mlp" else (B, self.C, self.H, self.W)
 
     def ckpt_shape(self, B, N):
+        if self.kind == "cnf":
+            return (N + 1, B, self.widths[0] + 1)
         return (N + 1, B, self.widths[0]) if self.kind == "mlp" else (N + 1, B, self.H, self.W, self.C)
 
 

@@ -31,6 +31,9 @@ struct GemmNT {
   float tau;                   // stage time, already rounded to low
   int act_tanh;                // activation applied before rounding: 0 none, 1 tanh, 2 ReLU
   int negate;                  // store the negated result (the -W^T of the parabolic block, Sec. 6.3)
+  // exact-trace row of a normalising-flow state (Sec. 6.1): with dact, the activation's cotangent gets the
+  // term 2 kbar_l[m] c[n] act[m][n] before the tanh' factor (tr_kl: the l column of the slope cotangent)
+  const float* tr_c; const uint16_t* tr_kl; int tr_ld;
   const uint16_t* dact; int ldd;  // stored activation for the factor (1 - act^2), or null
   Ctl* ctl;                    // may be null (forward pass)
   int detect;                  // raise ctl->nonfinite if any output is inf/nan
@@ -205,6 +208,7 @@ __global__ __launch_bounds__(256) void gemm_nt(GemmNT g) {
           if (g.negate) v = -v;
           if (g.dact) {
             float av = Low<T>::to_f32(g.dact[(size_t)m * g.ldd + n]);
+            if (g.tr_c) v = fmaf(2.f * g.tr_c[n] * av, Low<T>::to_f32(g.tr_kl[(size_t)m * g.tr_ld]), v);
             v = v * (1.f - av * av);
           }
           uint16_t q = Low<T>::from_f32(v);

@@ -23,6 +23,7 @@
 #include "gemm.hpp"
 #include "conv.hpp"
 #include "norm.hpp"
+#include "cnf.hpp"
 
 namespace rampde {
 
@@ -65,6 +66,10 @@ struct Plan {
   // parabolic block -W^T N(relu(W y + b)) (Sec. 6.3): one convolution used forward and transposed, an
   // instance normalisation between them, parameters piecewise constant over n_intervals pieces of the grid
   bool parabolic = false;
+  // normalising-flow state [z; l] with the exact trace row (Sec. 6.1): the one-hidden-layer velocity on the
+  // dense per-layer kernels, state width d + 1
+  bool cnf = false;
+  size_t cnf_c = 0, cnf_s = 0;       // c_h and the per-step sums s_h, fp32 [Hpad]
   int n_intervals = 1;
   int64_t Pblk = 0;                  // parameters of one piece
   size_t nstat = 0, nstat_vjp = 0, npart = 0;  // statistics [stage][B][Cpad][2], VJP means, chunk sums
@@ -110,8 +115,9 @@ struct Plan {
 static bool build_layers(const rampde_velocity* vel, Plan& p, int hidden_pad = kPad) {
   if (!vel) return false;
   size_t off = 0;
-  if (vel->kind == RAMPDE_VEL_MLP) {
+  if (vel->kind == RAMPDE_VEL_MLP || vel->kind == RAMPDE_VEL_CNF) {
     if (vel->n_layers < 1 || vel->n_layers > 16 || !vel->widths) return false;
+    if (vel->kind == RAMPDE_VEL_CNF && vel->n_layers != 2) return false;
     p.L = vel->n_layers;
     for (int l = 0; l <= p.L; ++l)
       if (vel->widths[l] < 1 || vel->widths[l] > 16384) return false;
@@ -133,6 +139,13 @@ static bool build_layers(const rampde_velocity* vel, Plan& p, int hidden_pad = k
       y.theta_b = off;
       off += y.out;
       p.layers.push_back(y);
+    }
+    if (vel->kind == RAMPDE_VEL_CNF) {
+      // the state carries one more column (l) than the velocity reads or writes: it meets zero weights
+      p.cnf = true;
+      p.d = vel->widths[0] + 1;
+      p.layers[0].Kpad = p.layers[0].ldw = pad64(p.d);
+      p.layers[1].Npad = pad64(p.d);
     }
   } else if (vel->kind == RAMPDE_VEL_CONV2) {
     if (vel->C < 1 || vel->C > 4096 || vel->H < 1 || vel->W < 1 || vel->H > 4096 || vel->W > 4096) return false;
@@ -303,6 +316,10 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
       p.a_rows = p.y_rows;
       p.gys_rows = take(sizeof(float) * (size_t)p.n);
     }
+  }
+  if (p.cnf) {
+    p.cnf_c = take(sizeof(float) * p.layers[0].Npad);
+    p.cnf_s = take(sizeof(float) * p.layers[0].Npad);
   }
   if (p.fused) {
     // row-tile-persistent kernels: slopes / stage cotangents only when they do not fit in LDS;
@@ -544,6 +561,11 @@ struct Runner {
                                                  u16(y.Wp), u16(y.WTp), f32(y.bias_f), f32(y.wt_f), y.Npad, y.Kpad);
       }
     }
+    if (p.cnf) {
+      const Layer &y0 = p.layers[0], &y1 = p.layers[1];
+      cnf_trace_coef<T><<<blocks_for(y0.Npad, 256), 256, 0, st>>>(u16(y0.Wp), y0.Kpad, u16(y1.Wp), y1.Kpad, y0.in, y0.out,
+                                                                 y0.Npad, f32(p.cnf_c));
+    }
   }
 
   // the convolution tile kernel keeps a layer's weights in LDS: more than the default limit
@@ -693,6 +715,10 @@ struct Runner {
         launch_nt(g);
         in = out;
       }
+      if (p.cnf)  // dl/dt = -tr(dv/dz) into the l column of the slope
+        cnf_trace_row<T><<<blocks_for(p.R, 4), 256, 0, st>>>(u16(p.ACT[0]) + (size_t)jb * p.R * p.layers[0].Npad,
+                                                             p.layers[0].Npad, f32(p.cnf_c), p.R,
+                                                             u16(p.K) + (size_t)j * p.stage_stride, p.dpad, p.d - 1, c);
     }
   }
 
@@ -946,6 +972,11 @@ struct Runner {
         if (l > 0) {
           g.dact = u16(p.ACT[l - 1]) + (size_t)j * p.R * y.Kpad;
           g.ldd = y.Kpad;
+          if (p.cnf) {
+            g.tr_c = f32(p.cnf_c);
+            g.tr_kl = kbar + (p.d - 1);
+            g.tr_ld = p.dpad;
+          }
         }
         g.ctl = ctl;
         g.detect = detect;
@@ -1083,6 +1114,18 @@ struct Runner {
       else
         column_sums<T, false><<<cgrid, 256, 0, st>>>(g.A, y.Npad, p.R, s, y.out, taus, h, gb, gwt, y.in_full, p.H,
                                                      p.Wd, rpb, ctl, y.has_time ? f32(y.wt_f) : nullptr, cs, tpart_i);
+    }
+    if (p.cnf) {
+      // the trace row's share of dW1 and dW2: s_h = sum over stages and rows of kbar_l (1 - a_h^2)
+      const Layer &y0 = p.layers[0], &y1 = p.layers[1];
+      fill_zero_u32<<<1, 256, 0, st>>>((uint32_t*)(ws + p.cnf_s), (size_t)y0.Npad);
+      int rpb = (int)((rows + 255) / 256);
+      if (rpb < 64) rpb = 64;
+      dim3 sgrid(y0.Npad / 64, blocks_for(rows, rpb));
+      cnf_trace_sums<T><<<sgrid, 256, 0, st>>>(u16(p.ACT[0]), y0.Npad, u16(p.KBAR), p.dpad, p.d - 1, rows, rpb, f32(p.cnf_s), ctl);
+      cnf_trace_grad<T><<<blocks_for((int64_t)y0.out * y0.in, 256), 256, 0, st>>>(
+          f32(p.cnf_s), u16(y0.Wp), y0.Kpad, u16(y1.Wp), y1.Kpad, y0.in, y0.out, h, ctl, grad_theta + y0.theta_w, y0.in_full,
+          grad_theta + y1.theta_w, y1.in_full);
     }
   }
 

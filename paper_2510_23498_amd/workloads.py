@@ -105,7 +105,7 @@ TABLEAUX: Dict[str, Tableau] = {
 @dataclass(frozen=True)
 class Config:
     name: str
-    kind: str  # "mlp", "conv2" or "parabolic"
+    kind: str  # "mlp", "conv2", "parabolic" or "cnf" (widths = (d, H, d); the state has d + 1 columns)
     B: int
     low: str  # "f16" | "bf16"
     tableau: str
@@ -124,15 +124,19 @@ class Config:
 
     @property
     def d(self) -> int:
+        if self.kind == "cnf":
+            return self.widths[0] + 1
         return self.widths[0] if self.kind == "mlp" else self.C * self.H * self.W
 
     @property
     def state_shape(self) -> Tuple[int, ...]:
+        if self.kind == "cnf":
+            return (self.B, self.widths[0] + 1)
         return (self.B, self.widths[0]) if self.kind == "mlp" else (self.B, self.C, self.H, self.W)
 
     @property
     def n_params(self) -> int:
-        if self.kind == "mlp":
+        if self.kind in ("mlp", "cnf"):
             return sum((self.widths[l] + (1 if l == 0 else 0)) * self.widths[l + 1] + self.widths[l + 1]
                        for l in range(len(self.widths) - 1))
         if self.kind == "parabolic":
@@ -158,6 +162,10 @@ CONFIGS: Dict[str, Config] = {
                    C=64, H=32, W=32, loss="mean_sq"),
     "cfg5": Config("cfg5", "mlp", B=1024, low="f16", tableau="rk4", N=256, t0=0.0, t1=1.0,
                    widths=(256, 1024, 1024, 256), loss="mse"),
+    # normalising-flow state [z; l] with the exact trace row (Sec. 6.1), at the sizes of the paper's second
+    # generative workload (Sec. 6.2): 63 features + time = 64 network inputs, width 1024, batch 512, 16 RK4 steps
+    "cnf": Config("cnf", "cnf", B=512, low="f16", tableau="rk4", N=16, t0=0.0, t1=1.0,
+                  widths=(63, 1024, 63), loss="half_sse", grad_scale=1e-3),
     # the middle neural-ODE block of the paper's image classifier (Sec. 6.3): 256 channels, 64 x 64
     # pixels, batch 16, four RK4 steps with weights that are constant on each step
     "parab": Config("parab", "parabolic", B=16, low="f16", tableau="rk4", N=4, t0=0.0, t1=1.0,
@@ -179,7 +187,7 @@ def theta_layout(cfg: Config) -> List[Tuple[str, Tuple[int, ...], int]]:
     """
     out: List[Tuple[str, Tuple[int, ...], int]] = []
     off = 0
-    if cfg.kind == "mlp":
+    if cfg.kind in ("mlp", "cnf"):
         for l, (o, i) in enumerate(mlp_layer_shapes(cfg.widths)):
             out.append((f"W{l + 1}", (o, i), off)); off += o * i
             out.append((f"b{l + 1}", (o,), off)); off += o

@@ -54,6 +54,8 @@ def oracle_velocity(cfg: wl.Config):
     from oracle import rampde_oracle as orc
     if cfg.kind == "mlp":
         return orc.MLPVelocity(cfg.widths, time_input=True)
+    if cfg.kind == "cnf":
+        return orc.CNFVelocity(cfg.widths[0], cfg.widths[1])
     if cfg.kind == "parabolic":
         return orc.ParabolicConvVelocity(cfg.C, cfg.H, cfg.W, n_intervals=cfg.n_intervals)
     return orc.Conv2Velocity(cfg.C, cfg.H, cfg.W, time_input=True)
@@ -110,6 +112,8 @@ def gpu_descriptors(cfg: wl.Config, scaling: str = None, k_max: int = 16, flags:
     from paper_2510_23498_amd import binding as rb
     if cfg.kind == "mlp":
         vel = rb.Velocity.mlp(cfg.widths, time_input=True)
+    elif cfg.kind == "cnf":
+        vel = rb.Velocity.cnf(cfg.widths[0], cfg.widths[1])
     elif cfg.kind == "parabolic":
         vel = rb.Velocity.parabolic(cfg.C, cfg.H, cfg.W, n_intervals=cfg.n_intervals)
     else:
@@ -123,7 +127,7 @@ def gpu_descriptors(cfg: wl.Config, scaling: str = None, k_max: int = 16, flags:
 
 def ckpt_to_boundary_layout(cfg: wl.Config, ckpt_np: np.ndarray) -> np.ndarray:
     """Library checkpoint layout -> [N+1, B, (state)] in the boundary (NCHW) element order."""
-    if cfg.kind == "mlp":
+    if cfg.kind in ("mlp", "cnf"):
         return ckpt_np
     return np.ascontiguousarray(np.transpose(ckpt_np, (0, 1, 4, 2, 3)))
 

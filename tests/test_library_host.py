@@ -37,6 +37,8 @@ def test_library_exports_every_declared_symbol():
 def _descr(cfg, **kw):
     if cfg.kind == "mlp":
         vel = rb.Velocity.mlp(cfg.widths)
+    elif cfg.kind == "cnf":
+        vel = rb.Velocity.cnf(cfg.widths[0], cfg.widths[1])
     elif cfg.kind == "parabolic":
         vel = rb.Velocity.parabolic(cfg.C, cfg.H, cfg.W, n_intervals=cfg.n_intervals)
     else:
