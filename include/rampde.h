@@ -123,6 +123,10 @@ typedef struct {
   int row_tile;           /* dense networks: batch rows per workgroup of the row-tile kernels: 16, 32 or 64.
                              64 selects the kernels built for 512-wide networks (state width 128) where
                              they apply; values that do not apply fall back to the automatic choice  */
+  int wgrad_tile;         /* dense networks, row-tile kernels, one launch per adjoint step: which kernel forms the
+                             parameter gradients.  128: workgroups with a 128 x 128 block of dW_l; 256: wavefronts
+                             with a 128 x 128 block each, operands streamed through LDS by direct loads (built for
+                             long batch contractions).  0: chosen by the contraction length (stages x batch rows) */
   /* Scope of the adjoint scale within a batch (Alg. 2 is stated for one sample).  0: one scale S for the
    * whole batch (the default).  G > 0: every G consecutive samples (the last group: the remainder) share a
    * scale of their own -- initial value from the group's own max-norm, own overflow retries, own growth --
@@ -130,7 +134,7 @@ typedef struct {
    * the other groups'.  Absent overflow and underflow the result is that of G = 0 up to fp32 summation
    * order.  G times the number of state elements of a sample must be a multiple of 8 (every group's
    * slice of the caller's buffers starts 16-byte aligned; RAMPDE_EINVAL otherwise).  This field changes
-   * WHAT is computed, unlike the two above. */
+   * WHAT is computed, unlike the three above. */
   int scale_group;
 } rampde_policy;
 

@@ -43,7 +43,7 @@ class _Velocity(C.Structure):
 
 class _Policy(C.Structure):
     _fields_ = [("low", C.c_int), ("scaling", C.c_int), ("k_max", C.c_int), ("flags", C.c_uint),
-                ("step_group", C.c_int), ("row_tile", C.c_int), ("scale_group", C.c_int)]
+                ("step_group", C.c_int), ("row_tile", C.c_int), ("wgrad_tile", C.c_int), ("scale_group", C.c_int)]
 
 
 class _Stats(C.Structure):
@@ -184,11 +184,12 @@ class Policy:
     step_group: int = 0
     row_tile: int = 0
     scale_group: int = 0
+    wgrad_tile: int = 0
 
     @property
     def c(self):
         return _Policy(_LOW[self.low], _SCALING[self.scaling], int(self.k_max), int(self.flags),
-                       int(self.step_group), int(self.row_tile), int(self.scale_group))
+                       int(self.step_group), int(self.row_tile), int(self.wgrad_tile), int(self.scale_group))
 
     @property
     def torch_low(self):

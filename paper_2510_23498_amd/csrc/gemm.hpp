@@ -846,15 +846,15 @@ __global__ __launch_bounds__(256, 2) __attribute__((amdgpu_num_vgpr(104))) void 
   const int fg = tid >> 3, oct = tid & 7;
   u16x8 ra[WG_STAGES][4], rb[WG_STAGES][4];
   // feature groups beyond the padded extent read group 0 instead and are masked in the epilogue
-  const uint16_t* pa0 = y.DT + ((size_t)((a0 + fg * 4 < y.NaPad) ? a0 / 4 + fg : 0) * g.ldk + oct * 8) * 4;
-  const uint16_t* pb0 = y.AT + ((size_t)((b0 + fg * 4 < y.NbPad) ? b0 / 4 + fg : 0) * g.ldk + oct * 8) * 4;
+  const uint16_t* pa0 = y.DT + ((size_t)((a0 + fg * 4 < y.NaPad) ? a0 / 4 + fg : 0) * g.ldk + oct * 2) * 4;
+  const uint16_t* pb0 = y.AT + ((size_t)((b0 + fg * 4 < y.NbPad) ? b0 / 4 + fg : 0) * g.ldk + oct * 2) * 4;
   const int nsteps = (int)((k_end - k_begin) / BK);
   auto load_tiles = [&](u16x8 (&qa)[4], u16x8 (&qb)[4], int step) {
     const int64_t k0 = k_begin + (int64_t)(step < nsteps ? step : nsteps - 1) * BK;  // clamped: branch-free
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      qa[i] = *reinterpret_cast<const u16x8*>(pa0 + k0 * 4 + i * 8);  // k = 2i, 2i+1
-      qb[i] = *reinterpret_cast<const u16x8*>(pb0 + k0 * 4 + i * 8);
+      qa[i] = *reinterpret_cast<const u16x8*>(pa0 + k0 * 4 + i * 64);  // k = 16 i + 2 oct, + 1
+      qb[i] = *reinterpret_cast<const u16x8*>(pb0 + k0 * 4 + i * 64);
     }
   };
   // r[i] = (k = 2i: f0 f1 f2 f3, k = 2i + 1: f0 f1 f2 f3); row of feature f = 8 consecutive k.
@@ -1039,8 +1039,8 @@ __global__ __launch_bounds__(256, 2) void wgrad_feature_major_steps(WgradArgs g)
   constexpr int WG_STAGES = 2;
   const int fg = tid >> 3, oct = tid & 7;
   u16x8 ra[WG_STAGES][4], rb[WG_STAGES][4];
-  const uint16_t* pa0 = y.DT + ((size_t)((a0 + fg * 4 < y.NaPad) ? a0 / 4 + fg : 0) * g.ldk + oct * 8) * 4;
-  const uint16_t* pb0 = y.AT + ((size_t)((b0 + fg * 4 < y.NbPad) ? b0 / 4 + fg : 0) * g.ldk + oct * 8) * 4;
+  const uint16_t* pa0 = y.DT + ((size_t)((a0 + fg * 4 < y.NaPad) ? a0 / 4 + fg : 0) * g.ldk + oct * 2) * 4;
+  const uint16_t* pb0 = y.AT + ((size_t)((b0 + fg * 4 < y.NbPad) ? b0 / 4 + fg : 0) * g.ldk + oct * 2) * 4;
   const int nk = (int)((k_end - k_begin) / BK);  // k-steps per step
   const int total = nk * g.nsteps;
   // position of the next tile to load: (step number it within the launch, k-step kk, buffer set)
@@ -1049,8 +1049,8 @@ __global__ __launch_bounds__(256, 2) void wgrad_feature_major_steps(WgradArgs g)
     const int64_t off = (int64_t)ld_set * g.set_stride + (k_begin + (int64_t)ld_kk * BK) * 4;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      qa[i] = *reinterpret_cast<const u16x8*>(pa0 + off + i * 8);
-      qb[i] = *reinterpret_cast<const u16x8*>(pb0 + off + i * 8);
+      qa[i] = *reinterpret_cast<const u16x8*>(pa0 + off + i * 64);
+      qb[i] = *reinterpret_cast<const u16x8*>(pb0 + off + i * 64);
     }
     // advance, staying on the last tile once it is reached (the extra loads of the pipeline tail)
     const bool last = (ld_it == g.nsteps - 1) && (ld_kk == nk - 1);

@@ -21,6 +21,7 @@
 #include "fused_launch.hpp"
 #include "wide.hpp"
 #include "gemm.hpp"
+#include "wgrad_slab.hpp"
 #include "conv.hpp"
 #include "norm.hpp"
 #include "cnf.hpp"
@@ -103,6 +104,7 @@ struct Plan {
   bool overlap_wgrad = false;       // narrow nets: 4-wave adjoint kernel + parameter gradients on a helper stream
   int64_t Rp = 0, ldk = 0;          // feature-major buffers: k = stage * Rp + row
   int ksplits = 1, kchunk = 64;     // K-chunks of the parameter-gradient contraction
+  bool wgrad_slab = false;          // per-step parameter gradients by the 128 x 128-per-wavefront kernel
   size_t gpart = 0;                 // ksplits copies of the gradient vector
   size_t ZT = 0, KBART = 0;
   size_t fm_stride = 0;             // distance between the sets of feature-group-major buffers
@@ -348,12 +350,23 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
         }
       }
       {
+        // Long contractions (one launch per step, kernel not sharing the CUs): the kernel whose
+        // wavefronts own 128 x 128 blocks and stream the operands through LDS without registers.
+        const int want_tile = pol ? pol->wgrad_tile : 0;
+        p.wgrad_slab = !p.overlap_wgrad && p.step_group <= 1 && (want_tile == 256 || (want_tile != 128 && p.ldk >= kSlabMinK));
         int tiles = 0;
-        for (auto& y : p.layers) tiles += ((y.Npad + 127) / 128) * ((y.Kpad + 127) / 128);
+        for (auto& y : p.layers) {
+          if (p.wgrad_slab) {
+            const SlabShape sh = slab_shape(y.Npad, y.Kpad);
+            tiles += ((y.Npad + slab_tile_a(sh) - 1) / slab_tile_a(sh)) * ((y.Kpad + slab_tile_b(sh) - 1) / slab_tile_b(sh));
+          } else {
+            tiles += ((y.Npad + 127) / 128) * ((y.Kpad + 127) / 128);
+          }
+        }
         // K-chunks: as many workgroups as are resident at once (two per CU; one when the kernel
-        // shares the CUs with the adjoint kernel) and no more -- a second, partial round of
-        // workgroups costs more than it spreads --, but at least 256 k per chunk
-        const int resident = device_compute_units() * (p.overlap_wgrad ? 1 : 2);
+        // shares the CUs with the adjoint kernel or needs a CU's whole LDS) and no more -- a second,
+        // partial round of workgroups costs more than it spreads --, but at least 256 k per chunk
+        const int resident = device_compute_units() * ((p.overlap_wgrad || p.wgrad_slab) ? 1 : 2);
         int64_t ks = std::max(1, resident / tiles);
         // (a group of steps multiplies a workgroup's k-steps: chunks can be shorter)
         const int64_t min_chunk = p.step_group > 1 ? 128 : 256;
@@ -1173,6 +1186,25 @@ struct Runner {
       flops += 2.0 * (double)p.ldk * y.Npad * y.Kpad * std::max(1, nsteps);
     }
     w.ntiles = blk;
+    if (p.wgrad_slab && nsteps == 0) {
+      SlabArgs sa{};
+      sa.w = w;
+      blk = 0;
+      for (int l = 0; l < p.L; ++l) {
+        WgradLayer& d = sa.w.layer[l];
+        const SlabShape sh = slab_shape(d.NaPad, d.NbPad);
+        sa.shape[l] = sh;
+        d.tiles_a = (d.NaPad + slab_tile_a(sh) - 1) / slab_tile_a(sh);
+        d.tiles_b = (d.NbPad + slab_tile_b(sh) - 1) / slab_tile_b(sh);
+        d.tile0 = blk;
+        blk += d.tiles_a * d.tiles_b;
+      }
+      sa.w.ntiles = blk;
+      const int grid = (blk * w.ksplits + 7) / 8 * 8;
+      TimeScope ts(RAMPDE_K_WGRAD_GEMM, flops, stream);
+      wgrad_slab<T><<<grid, 256, kSlabLdsBytes, stream>>>(sa);
+      return;
+    }
     const int grid = (blk * w.ksplits + 7) / 8 * 8;  // a multiple of the XCD count: see the kernel's block mapping
     TimeScope ts(RAMPDE_K_WGRAD_GEMM, flops, stream);
     if (nsteps > 0)
@@ -1190,6 +1222,9 @@ struct Runner {
     const int k_max = pol->k_max > 0 ? pol->k_max : 16;
     const int HW = p.H * p.Wd;
     if (p.conv) HIP_TRY(allow_conv_tile_lds());
+    if (p.wgrad_slab)  // (its ring of operand slabs takes most of a CU's LDS)
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_slab<T>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  kSlabLdsBytes));
     if (conv_wgrad_applies(p)) {
       const int lds = (int)conv_wgrad_lds_bytes(p.Wd);
       HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false, CW_MAXI_LO>),

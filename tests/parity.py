@@ -108,7 +108,7 @@ def run_oracle_rows(cfg: wl.Config, theta, y0, target, rows, mode: str):
 
 # ------------------------------------------------------------------ HIP side
 def gpu_descriptors(cfg: wl.Config, scaling: str = None, k_max: int = 16, flags: int = 0, step_group: int = 0,
-                    row_tile: int = 0, scale_group: int = 0):
+                    row_tile: int = 0, scale_group: int = 0, wgrad_tile: int = 0):
     from paper_2510_23498_amd import binding as rb
     if cfg.kind == "mlp":
         vel = rb.Velocity.mlp(cfg.widths, time_input=True)
@@ -121,7 +121,7 @@ def gpu_descriptors(cfg: wl.Config, scaling: str = None, k_max: int = 16, flags:
     t = wl.TABLEAUX[cfg.tableau]
     tab = rb.Tableau(t.A, t.b, t.c)
     pol = rb.Policy(low=cfg.low, scaling=scaling or wl.resolve_scaling(cfg), k_max=k_max, flags=flags,
-                    step_group=step_group, row_tile=row_tile, scale_group=scale_group)
+                    step_group=step_group, row_tile=row_tile, scale_group=scale_group, wgrad_tile=wgrad_tile)
     return vel, tab, pol
 
 
@@ -134,10 +134,10 @@ def ckpt_to_boundary_layout(cfg: wl.Config, ckpt_np: np.ndarray) -> np.ndarray:
 
 def run_gpu(cfg: wl.Config, theta, y0, target, scaling: str = None, k_max: int = 16, flags: int = 0,
             grad_ys=None, expect_error: bool = False, want_grad_t: bool = False, tgrid=None, step_group: int = 0,
-            row_tile: int = 0, scale_group: int = 0):
+            row_tile: int = 0, scale_group: int = 0, wgrad_tile: int = 0):
     import torch
     from paper_2510_23498_amd import binding as rb
-    vel, tab, pol = gpu_descriptors(cfg, scaling, k_max, flags, step_group, row_tile, scale_group)
+    vel, tab, pol = gpu_descriptors(cfg, scaling, k_max, flags, step_group, row_tile, scale_group, wgrad_tile)
     dev = torch.device("cuda:0")
     th = torch.from_numpy(theta).to(dev)
     y0d = torch.from_numpy(np.ascontiguousarray(y0)).to(dev)

@@ -20,11 +20,12 @@ PER_LAYER = 4  # policy flag: one kernel per layer instead of the row-tile-persi
 PATHS = pytest.mark.parametrize("flags", [0, PER_LAYER], ids=["tile", "layer"])
 
 
-def _both(cfg, bias_std=0.0, scaling=None, tol_emul=par.TOL_EMUL, flags=0, row_tile=0, grad_ys=None):
+def _both(cfg, bias_std=0.0, scaling=None, tol_emul=par.TOL_EMUL, flags=0, row_tile=0, grad_ys=None, wgrad_tile=0):
     theta, y0, target = par.make_inputs(cfg, bias_std=bias_std)
     print(f"[case] {cfg.name} kind={cfg.kind} B={cfg.B} N={cfg.N} low={cfg.low} tab={cfg.tableau} flags={flags} "
-          f"row_tile={row_tile}", flush=True)
-    gpu = par.run_gpu(cfg, theta, y0, target, scaling=scaling, flags=flags, row_tile=row_tile, grad_ys=grad_ys)
+          f"row_tile={row_tile} wgrad_tile={wgrad_tile}", flush=True)
+    gpu = par.run_gpu(cfg, theta, y0, target, scaling=scaling, flags=flags, row_tile=row_tile, grad_ys=grad_ys,
+                      wgrad_tile=wgrad_tile)
     if grad_ys is not None:
         emu = par.run_oracle(cfg, theta, y0, target, "emul", scaling=scaling, grad_ys=grad_ys.astype(np.float64))
         par.compare(cfg, gpu, emu, tol_emul, "emulation oracle")
@@ -138,6 +139,38 @@ def test_wide_kernels_depths_tableaux_precisions(tab, low, widths):
     # that 16 stage evaluations of 4 layers accumulate to about 1e-3 in the 2-norm.  The 16-, 32- and
     # 64-row kernels give bit-identical results on this case, so it is not a property of one kernel.
     _both(cfg, bias_std=0.1, row_tile=64, tol_emul=2e-3 if low == "bf16" else par.TOL_EMUL)
+
+
+# ------------------------------------------------------------------ parameter gradients: 128 x 128 block per wavefront
+@pytest.mark.parametrize("B", [200, 65, 1])
+def test_slab_parameter_gradient_kernel_cfg3_shape(B):
+    # the kernel that the full-size cfg3 takes by its contraction length, requested at batches the oracle
+    # handles: K-chunks shorter than its ring of k-steps, a ragged tail, a single row
+    _both(wl.CONFIGS["cfg3"].with_(name=f"slab{B}", B=B, N=3), bias_std=0.1, row_tile=64, wgrad_tile=256)
+
+
+@pytest.mark.parametrize("tab,low,widths,row_tile", [
+    ("heun", "f16", (128, 512, 128), 64), ("kutta3", "bf16", (128, 512, 512, 128), 64),
+    ("euler", "f16", (128, 400, 512, 300, 500, 128), 64),      # hidden widths that are no multiple of 128
+    ("rk4", "f16", (64, 1024, 1024, 64), 0), ("rk4", "f16", (38, 302, 700, 38), 0)])  # 8-wave row-tile kernels; widths that are no multiple of 4
+def test_slab_parameter_gradient_kernel_shapes(tab, low, widths, row_tile):
+    # every arrangement of the four wavefronts (2 x 2, 4 x 1, 1 x 4), masked feature groups, rows with
+    # and without a time column, both precisions
+    cfg = wl.CONFIGS["cfg3"].with_(name=f"slab{tab}{low}{len(widths)}", B=150, N=3, tableau=tab, low=low, widths=widths,
+                                   scaling="dynamic", grad_scale=1.0 if low == "bf16" else 1e-6)
+    _both(cfg, bias_std=0.1, row_tile=row_tile, wgrad_tile=256, tol_emul=2e-3 if low == "bf16" else par.TOL_EMUL)
+
+
+def test_slab_parameter_gradient_kernel_by_contraction_length():
+    # chosen without being asked for: 4 stages x 2048 rows = 8192 k
+    cfg = wl.CONFIGS["cfg3"].with_(name="slabauto", B=2048, N=2)
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    gpu = par.run_gpu(cfg, theta, y0, target, row_tile=64)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul")
+    par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle", tol_max=par.TOL_EMUL_MAX[cfg.low])
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
+    small = par.run_gpu(cfg, theta, y0, target, row_tile=64, wgrad_tile=128)
+    assert par.rel_err(gpu["grad_theta"], small["grad_theta"]) < 1e-5
 
 
 def test_wide_kernels_running_cost_and_literal_flags():
