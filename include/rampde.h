@@ -119,7 +119,10 @@ typedef struct {
   /* Launch-shape choices; 0 = let the library choose.  They change how the work is cut into
    * kernels, never what is computed (results agree to fp32 summation order). */
   int step_group;         /* dense networks, fixed scale (SCALE_NONE): cap on the adjoint steps that one
-                             launch runs (default: as many as about 4 GiB of workspace hold, at most 64) */
+                             launch runs (default: as many as about 4 GiB of workspace hold, at most 64).
+                             With overflow detection the adjoint runs step by step; where wgrad_tile = 256
+                             applies this is the number of accepted steps whose parameter gradients one launch
+                             forms (default: as many as keep their buffers in the memory-side cache) */
   int row_tile;           /* dense networks: batch rows per workgroup of the row-tile kernels: 16, 32 or 64.
                              64 selects the kernels built for 512-wide networks (state width 128) where
                              they apply; values that do not apply fall back to the automatic choice  */

@@ -105,6 +105,7 @@ struct Plan {
   int64_t Rp = 0, ldk = 0;          // feature-major buffers: k = stage * Rp + row
   int ksplits = 1, kchunk = 64;     // K-chunks of the parameter-gradient contraction
   bool wgrad_slab = false;          // per-step parameter gradients by the 128 x 128-per-wavefront kernel
+  int wgrad_group = 1;              // ... of this many adjoint steps per launch (each step has a buffer set of its own)
   size_t gpart = 0;                 // ksplits copies of the gradient vector
   size_t ZT = 0, KBART = 0;
   size_t fm_stride = 0;             // distance between the sets of feature-group-major buffers
@@ -333,14 +334,14 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
       p.ZBAR = take((size_t)p.s * p.R * p.dpad * 2);
       p.Rp = (p.R + 63) / 64 * 64;
       p.ldk = (int64_t)p.s * p.Rp;
+      size_t per_set = 2 * (size_t)p.dpad * p.ldk * 2;
+      for (int l = 0; l + 1 < p.L; ++l) per_set += 2 * (size_t)p.layers[l].Npad * p.ldk * 2;
+      const int64_t fit = (int64_t)((size_t(4) << 30) / per_set);  // buffer sets in about 4 GiB
       {
         // Without overflow detection nothing is decided between steps: a launch of the adjoint
         // kernel then runs a group of steps (the adjoint stays in registers) and the parameter
         // gradients of the whole group are one contraction.  Every step of a group needs its own
         // set of buffers; groups are as long as about 4 GiB of sets allow.
-        size_t per_set = 2 * (size_t)p.dpad * p.ldk * 2;
-        for (int l = 0; l + 1 < p.L; ++l) per_set += 2 * (size_t)p.layers[l].Npad * p.ldk * 2;
-        const int64_t fit = (int64_t)((size_t(4) << 30) / per_set);
         const int64_t want_group = (pol && pol->step_group > 0) ? pol->step_group : kMaxWgradSteps;
         const int64_t cap = std::min<int64_t>(want_group, std::min<int64_t>(fit, kMaxWgradSteps));
         if (pol && resolve_scaling(pol) == RAMPDE_SCALE_NONE && cap >= 2) {
@@ -352,8 +353,21 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
       {
         // Long contractions (one launch per step, kernel not sharing the CUs): the kernel whose
         // wavefronts own 128 x 128 blocks and stream the operands through LDS without registers.
+        // The adjoint kernel runs step by step under overflow detection (a step must be accepted before the
+        // next one starts), but the parameter gradients of several accepted steps can be ONE contraction over
+        // their buffer sets: one pass over the private gradient copies per group instead of one per step.
+        // That pays as long as the group's buffer sets are still in the memory-side cache when they are read
+        // (about half of its 256 MB is left to them); the headline workload's set is larger than that.
         const int want_tile = pol ? pol->wgrad_tile : 0;
-        p.wgrad_slab = !p.overlap_wgrad && p.step_group <= 1 && (want_tile == 256 || (want_tile != 128 && p.ldk >= kSlabMinK));
+        const int64_t cached = std::max<int64_t>(1, (int64_t)((size_t(128) << 20) / per_set));
+        const int64_t want = (pol && pol->step_group > 0) ? pol->step_group : cached;
+        const int64_t group = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, fit), std::min<int64_t>(N, kMaxWgradSteps)));
+        p.wgrad_slab = !p.overlap_wgrad && p.step_group <= 1 &&
+                       (want_tile == 256 || (want_tile != 128 && group * p.ldk >= kSlabMinK));
+        if (p.wgrad_slab) {
+          p.wgrad_group = (int)group;
+          p.nsets = p.wgrad_group;
+        }
         int tiles = 0;
         for (auto& y : p.layers) {
           if (p.wgrad_slab) {
@@ -1147,7 +1161,8 @@ struct Runner {
   // step - 1, ..., step - nsteps + 1 in one launch, h and taus from the step table
   void param_grads_fused(int step, float h, const Coefs& taus, hipStream_t stream, int nsteps = 0) {
     float* grad_theta = f32(p.gpart);  // copy 0; chunk c adds into copy c
-    const size_t set = nsteps > 0 ? 0 : (size_t)(step % p.nsets) * p.fm_stride;
+    // (the kernels that take several steps per launch find a step's buffer set themselves)
+    const size_t set = (nsteps > 0 || p.wgrad_slab) ? 0 : (size_t)(step % p.nsets) * p.fm_stride;
     WgradArgs w{};
     w.L = p.L;
     w.ksplits = p.ksplits;
@@ -1186,9 +1201,10 @@ struct Runner {
       flops += 2.0 * (double)p.ldk * y.Npad * y.Kpad * std::max(1, nsteps);
     }
     w.ntiles = blk;
-    if (p.wgrad_slab && nsteps == 0) {
+    if (p.wgrad_slab) {
       SlabArgs sa{};
       sa.w = w;
+      sa.w.nsteps = std::max(1, nsteps);
       blk = 0;
       for (int l = 0; l < p.L; ++l) {
         WgradLayer& d = sa.w.layer[l];
@@ -1202,7 +1218,10 @@ struct Runner {
       sa.w.ntiles = blk;
       const int grid = (blk * w.ksplits + 7) / 8 * 8;
       TimeScope ts(RAMPDE_K_WGRAD_GEMM, flops, stream);
-      wgrad_slab<T><<<grid, 256, kSlabLdsBytes, stream>>>(sa);
+      if (sa.w.nsteps > 1)
+        wgrad_slab<T, true><<<grid, 256, kSlabLdsBytes, stream>>>(sa);
+      else
+        wgrad_slab<T, false><<<grid, 256, kSlabLdsBytes, stream>>>(sa);
       return;
     }
     const int grid = (blk * w.ksplits + 7) / 8 * 8;  // a multiple of the XCD count: see the kernel's block mapping
@@ -1223,8 +1242,8 @@ struct Runner {
     const int HW = p.H * p.Wd;
     if (p.conv) HIP_TRY(allow_conv_tile_lds());
     if (p.wgrad_slab)  // (its ring of operand slabs takes most of a CU's LDS)
-      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_slab<T>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  kSlabLdsBytes));
+      for (const void* f : {reinterpret_cast<const void*>(&wgrad_slab<T, false>), reinterpret_cast<const void*>(&wgrad_slab<T, true>)})
+        HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kSlabLdsBytes));
     if (conv_wgrad_applies(p)) {
       const int lds = (int)conv_wgrad_lds_bytes(p.Wd);
       HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false, CW_MAXI_LO>),
@@ -1348,6 +1367,7 @@ struct Runner {
           hi -= n;
         }
       }
+      int pending_hi = -1, pending_n = 0;  // steps whose parameter gradients wait for their group's launch
       for (int i = (use_fused && p.step_group > 1) ? -1 : from; i >= 0; --i) {
         if (use_fused) {
           // this set was last read by the parameter-gradient kernel of step i + 2
@@ -1369,6 +1389,16 @@ struct Runner {
             HIP_TRY(hipStreamWaitEvent(side.stream, side.adjoint_done(i), 0));
             param_grads_fused(i, h, taus, side.stream);
             HIP_TRY(hipEventRecord(side.wgrad_done(i), side.stream));
+          } else if (p.wgrad_slab) {
+            // groups of steps per launch; a group ends early at step 0.  After a rejected chain the launch
+            // that holds the rejected step takes the accepted steps before it, and the loop re-enters with
+            // a group that starts at the rejected step.
+            if (pending_n == 0) pending_hi = i;
+            ++pending_n;
+            if (pending_n == p.wgrad_group || i == 0) {
+              param_grads_fused(pending_hi, 0.f, Coefs{}, st, pending_n);
+              pending_n = 0;
+            }
           } else {
             param_grads_fused(i, h, taus, st);
           }

@@ -395,3 +395,17 @@ def test_fixed_scale_many_steps_default_group_length():
     print("  vs emul:", {k: f"{v:.2e}" for k, v in e.items()}, f"dL/dt {et:.2e}", flush=True)
     assert et <= par.TOL_EMUL
     np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])
+
+
+@pytest.mark.parametrize("group", [1, 2, 4])
+def test_slab_parameter_gradient_groups_of_steps_nonuniform_grid(group):
+    # 7 steps in groups of 1, 2 and 4 (the last group is cut short at step 0); on a non-uniform grid h_i / S_i
+    # differs from step to step, so the rescaling of the running sums at step boundaries is exercised
+    cfg = wl.CONFIGS["cfg3"].with_(name=f"slabgrp{group}", B=100, N=7)
+    tg = _nonuniform_grid(cfg.N, t1=2.0, seed=5)
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    gpu = par.run_gpu(cfg, theta, y0, target, row_tile=64, wgrad_tile=256, step_group=group, tgrid=tg, want_grad_t=True)
+    emu = par.run_oracle(cfg, theta, y0, target, "emul", tgrid=tg)
+    par.compare(cfg, gpu, emu, par.TOL_EMUL, "emulation oracle", tol_max=par.TOL_EMUL_MAX[cfg.low])
+    assert par.rel_err(gpu["grad_t"], emu["grad_t"]) <= par.TOL_EMUL
+    np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), emu["scale_hist"])

@@ -198,8 +198,13 @@ MULTI_WG = [
 
 
 @pytest.mark.parametrize("base,kw", MULTI_WG, ids=[k["name"] for _, k in MULTI_WG])
-@pytest.mark.parametrize("flags,row_tile", [(0, 0), (rb.PER_LAYER_KERNELS, 0), (0, 64)], ids=["tile", "layer", "wide"])
-def test_retry_in_the_middle_of_the_pass_many_workgroups(base, kw, flags, row_tile):
+@pytest.mark.parametrize("flags,row_tile,wgrad_tile,step_group",
+                         [(0, 0, 0, 0), (rb.PER_LAYER_KERNELS, 0, 0, 0), (0, 64, 0, 0), (0, 64, 256, 0), (0, 64, 256, 3),
+                          (0, 64, 256, 1)],
+                         ids=["tile", "layer", "wide", "wide-groups-of-4", "wide-groups-of-3", "wide-groups-of-1"])
+def test_retry_in_the_middle_of_the_pass_many_workgroups(base, kw, flags, row_tile, wgrad_tile, step_group):
+    # (wgrad_tile = 256: the parameter gradients of a group of accepted steps are one launch; a rejected
+    # step cuts its group short and the next group starts with it)
     if base == "cfg4" and (flags or row_tile):
         pytest.skip("the convolution has one path")
     if base == "cfg2" and row_tile:
@@ -210,7 +215,7 @@ def test_retry_in_the_middle_of_the_pass_many_workgroups(base, kw, flags, row_ti
     hist = emu["scale_hist"]
     assert emu["status"] == "ok" and emu["retries"] >= 3
     assert np.sum(hist[:-1] < hist[1:]) >= 2, "the scale must drop at more than one step"
-    gpu = par.run_gpu(cfg, theta, y0, target, flags=flags, row_tile=row_tile)
+    gpu = par.run_gpu(cfg, theta, y0, target, flags=flags, row_tile=row_tile, wgrad_tile=wgrad_tile, step_group=step_group)
     assert gpu["status"] == 0
     np.testing.assert_array_equal(gpu["scale_hist"].astype(np.float64), hist)
     assert gpu["retries"] == emu["retries"]
