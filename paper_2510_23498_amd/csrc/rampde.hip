@@ -362,7 +362,10 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
         const int64_t cached = std::max<int64_t>(1, (int64_t)((size_t(128) << 20) / per_set));
         const int64_t want = (pol && pol->step_group > 0) ? pol->step_group : cached;
         const int64_t group = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, fit), std::min<int64_t>(N, kMaxWgradSteps)));
-        p.wgrad_slab = !p.overlap_wgrad && p.step_group <= 1 &&
+        // (the kernel addresses a lane's part of an operand tensor by a 32-bit byte offset)
+        bool offsets_fit = (size_t)p.dpad * p.ldk * 2 < (size_t(1) << 32);
+        for (auto& y : p.layers) offsets_fit = offsets_fit && (size_t)std::max(y.Npad, y.Kpad) * p.ldk * 2 < (size_t(1) << 32);
+        p.wgrad_slab = !p.overlap_wgrad && p.step_group <= 1 && offsets_fit &&
                        (want_tile == 256 || (want_tile != 128 && group * p.ldk >= kSlabMinK));
         if (p.wgrad_slab) {
           p.wgrad_group = (int)group;
