@@ -22,6 +22,7 @@
 #include "wide.hpp"
 #include "gemm.hpp"
 #include "wgrad_slab.hpp"
+#include "gemm_slab.hpp"
 #include "conv.hpp"
 #include "norm.hpp"
 #include "cnf.hpp"
@@ -600,6 +601,9 @@ struct Runner {
 
   // the convolution tile kernel keeps a layer's weights in LDS: more than the default limit
   hipError_t allow_conv_tile_lds() {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_slab<T, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kNtSlabLdsBytes);
+    if (e != hipSuccess) return e;
     if (p.Wd < 8 || p.Wd > 64) return hipSuccess;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3x3_tile<T, 8>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_tile_lds_bytes(p.Wd));
@@ -611,6 +615,10 @@ struct Runner {
       // persistent: one workgroup per CU (its LDS holds the layer's weights), tiles of 256 pixels
       const int ntiles = (int)(g.M / CT_TILE);
       conv3x3_tile<T, 8><<<std::min(ntiles, device_compute_units()), 512, conv_tile_lds_bytes(g.Wd), st>>>(g);
+    } else if (p.conv && gemm_nt_slab_applies(g, true)) {
+      // wide convolutions (the parabolic block): 256 x 256 workgroup tiles fed by direct global->LDS loads
+      dim3 grid(blocks_for(g.M, 256), g.N / 256);
+      gemm_nt_slab<T, true><<<grid, 256, kNtSlabLdsBytes, st>>>(g);
     } else if (p.conv) {
       dim3 grid(blocks_for(g.M, 128), g.N / 64);
       gemm_nt<T, 2, 1, true><<<grid, 256, 0, st>>>(g);

@@ -92,6 +92,18 @@ def test_parabolic_single_euler_step_is_tight(low):
           strict=True)
 
 
+@pytest.mark.parametrize("low,B,H,W", [("f16", 65, 8, 8), ("bf16", 16, 16, 16)])
+def test_parabolic_wide_convolution_kernel_single_euler_step_is_tight(low, B, H, W):
+    # 256 channels and >= 4096 pixels: the convolutions take the kernel with 256 x 256 workgroup tiles; image
+    # borders inside a tile (four 8 x 8 images per tile), a last tile that is cut short (65 images)
+    _case(BASE.with_(name=f"pbwide{low}", B=B, C=256, H=H, W=W, N=1, n_intervals=1, tableau="euler", t1=0.25, low=low),
+          strict=True)
+
+
+def test_parabolic_wide_convolution_kernel_rk4_two_pieces():
+    _case(BASE.with_(name="pbwiderk4", B=16, C=256, H=16, W=16, N=2, n_intervals=2, t1=0.25))
+
+
 def test_parabolic_all_positive_preactivations_one_rk4_step_is_tight():
     _case(BASE.with_(name="pbpos", B=3, C=64, H=16, W=16, N=1, n_intervals=1, t1=0.25), positive=True, strict=True)
 
