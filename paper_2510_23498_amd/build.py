@@ -39,7 +39,7 @@ def _compile(args):
 
 # headers each translation unit includes (directly or not), for the incremental mode
 _DEPS = {
-    "rampde.hip": ("common.hpp", "elementwise.hpp", "fused.hpp", "fused_launch.hpp", "wide.hpp", "gemm.hpp", "wgrad_slab.hpp", "gemm_slab.hpp", "conv.hpp", "norm.hpp",
+    "rampde.hip": ("common.hpp", "elementwise.hpp", "fused.hpp", "fused_launch.hpp", "wide.hpp", "gemm.hpp", "wgrad_slab.hpp", "gemm_slab.hpp", "conv_wgrad_tr.hpp", "conv.hpp", "norm.hpp",
                    os.path.join("..", "..", "include", "rampde.h")),
     "fused_inst.hip": ("common.hpp", "fused.hpp", "fused_launch.hpp"),
     "wide_inst.hip": ("common.hpp", "fused.hpp", "fused_launch.hpp", "wide.hpp"),

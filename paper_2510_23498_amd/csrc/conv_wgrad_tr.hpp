@@ -1,0 +1,290 @@
+// Weight gradient of a 3x3 convolution with many channels (multiples of 128: the parabolic block of the paper's
+// Sec. 6.3), one term of the update of g in Sec. 3:
+//   dW[co][ci][tap] += scale * sum_k delta[k][co] * x[k + dy W + dx][ci] * [pixel (y+dy, x+dx) inside]
+// over the rows k (pixels of all samples and stages, channels-last) of one K-chunk.
+//
+// Both operands are stored with the contraction index (the pixel) as the SLOW one, while a matrix instruction wants
+// 8 consecutive k per lane.  Here the rows go to LDS exactly as they are in memory (direct global->LDS loads: no
+// registers, no LDS store instructions) and the transposing LDS read of gfx950 (64 bits, 16-bit elements) builds
+// the fragments: within 16 lanes, lane s supplies the address of 4 consecutive channels of row s / 4 (channel
+// group s % 4), and lane j receives the 4 rows of channel j -- 4 consecutive k of one channel (checked on the
+// device with an index pattern).  Two such reads are the 8 k of a 32x32x16 fragment.
+//
+// Work split: a workgroup owns 128 output channels x 128 input channels x the three taps of one dy; its four
+// wavefronts take 32 input channels each (192 accumulator registers: 4 co blocks x 3 dx).  Per k-step of 16 pixels
+// a wavefront reads 4 cotangent fragments and 3 input fragments (the dx shifts are row offsets of the same line;
+// a zero row before and after the line stands for the pixels off the line) for 12 matrix instructions.  A step of
+// the pipeline is one image line: cotangent line l and input line l + dy (skipped when that line is off the image)
+// in a ring of 16 / (W / 16) slots; explicit vmcnt waits (every wavefront issues the same number of loads per
+// line), one barrier per line.  The 16-byte pieces of a row are permuted (XOR of the 32-channel block number
+// with the row number mod 4) so that the four rows a transposing read touches fall into different banks.
+//
+// Needs W in {16, 32, 64}, channel counts that are multiples of 128, no time channel.  Bias gradient: sums of the
+// cotangent over k by one extra matrix instruction against a fragment of ones (wavefront w: channel block w), the
+// k-steps dealt out among the dy = 0 workgroups.  Every (K-chunk, workgroup tile) accumulates into a private fp32 copy
+// over the backward pass (plain read-modify-write), summed at the end: the result does not depend on the order in
+// which workgroups finish.
+#pragma once
+#include "gemm.hpp"
+
+namespace rampde {
+
+struct ConvWgradTr {
+  const uint16_t* A; int lda;   // [rows, >= 128 gridDim.x] cotangents of the layer's output
+  const uint16_t* B; int ldb;   // [rows, >= 128 gridDim.y / 3] the layer's input
+  int64_t lines;                // image lines over all stages and samples: rows / W
+  int lines_per_split;
+  float* part;                  // [gridDim.z][gridDim.x][gridDim.y][CT_SLOT] fp32
+  float h;                      // scale = h / ctl->S_step
+  const Ctl* ctl;
+  int H;
+  bool want_sums;               // also db[co] += scale * sum_k delta[k][co]
+};
+
+// floats of a workgroup's private copy: 12 (co block, dx) accumulator blocks of 4096 in register order, then the
+// 128 cotangent sums
+constexpr int CT_SLOT = 12 * 4096 + 128;
+constexpr size_t conv_wgrad_tr_lds_bytes(int W) { return (size_t)(16 / (W / 16)) * (2 * W + 2) * 256; }
+
+template <class T, int W16>
+__global__ __launch_bounds__(256, 1) void conv_wgrad_tr(ConvWgradTr g) {
+  if (g.ctl->poison) return;
+  constexpr int W = 16 * W16, NS = 16 / W16, PERL = 2 * W16;
+  constexpr int GB = W * 256, SLOT = (2 * W + 2) * 256;  // cotangent line, then the input line with its two zero rows
+  typedef __attribute__((address_space(3))) uint8_t lds_u8;
+  typedef short v4s __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) v4s lds_v4s;
+  extern __shared__ __attribute__((aligned(16))) uint8_t cwt_smem[];
+  lds_u8* ring = (lds_u8*)cwt_smem;
+  const uint32_t ring_base = (uint32_t)(uintptr_t)ring;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int a0 = blockIdx.x * 128;
+  const int bt = blockIdx.y / 3, dy = (int)(blockIdx.y % 3) - 1, b0 = bt * 128;
+  const int64_t l_begin = (int64_t)blockIdx.z * g.lines_per_split;
+  int64_t l_end = l_begin + g.lines_per_split;
+  if (l_end > g.lines) l_end = g.lines;
+  if (l_begin >= l_end) return;
+  const int nl = (int)(l_end - l_begin);
+
+  // the zero rows before and after the input line of every slot (never overwritten)
+  for (int i = tid; i < NS * 32; i += 256) {
+    const int s = i >> 5, which = (i >> 4) & 1, piece = i & 15;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    *reinterpret_cast<__attribute__((address_space(3))) u32x4*>(ring + s * SLOT + GB + (which ? (W + 1) * 256 : 0) + piece * 16) =
+        u32x4{0u, 0u, 0u, 0u};
+  }
+  __syncthreads();
+
+  // ---- loader role.  Wave-load i of this wavefront: pixels 4 j .. 4 j + 3 of the line, j = wave * W16 + i; lane / 16
+  // is the pixel, lane % 16 the 16-byte slot, which holds piece  slot ^ (4 * key)  with key = (LDS row) % 4.
+  const int lr = lane >> 4, sp = lane & 15;
+  const int pg = sp ^ (lr << 2);               // cotangent: LDS row = pixel
+  const int px = sp ^ (((lr + 1) & 3) << 2);   // input: LDS row = pixel + 1
+  const uint16_t* gsrc = g.A + ((size_t)l_begin * W + 4 * wave * W16 + lr) * g.lda + a0 + pg * 8;
+  const uint16_t* xsrc = g.B + ((size_t)l_begin * W + 4 * wave * W16 + lr) * g.ldb + b0 + px * 8;
+  int ld_n = 0, ld_y = (int)(l_begin % g.H), wslot = 0;
+  auto issue = [&]() {
+    lds_u8* slot = ring + wslot * SLOT;
+    wslot = (wslot + 1 == NS) ? 0 : wslot + 1;
+    // input line l + dy; where it is off the image the step is not multiplied: any line inside the tensor will do
+    const int yy = ld_y + dy;
+    const int64_t xoff = (yy >= 0 && yy < g.H) ? (int64_t)dy * W * g.ldb : 0;
+#pragma unroll
+    for (int i = 0; i < W16; ++i)
+      __builtin_amdgcn_global_load_lds(gsrc + (size_t)4 * i * g.lda,
+                                       (__attribute__((address_space(3))) void*)(slot + (wave * W16 + i) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < W16; ++i)
+      __builtin_amdgcn_global_load_lds(xsrc + xoff + (size_t)4 * i * g.ldb,
+                                       (__attribute__((address_space(3))) void*)(slot + GB + 256 + (wave * W16 + i) * 1024), 16, 0, 0);
+    // advance, staying on the last line once it is reached (the extra loads of the pipeline tail stay in bounds)
+    if (ld_n + 1 < nl) {
+      ++ld_n;
+      gsrc += (size_t)W * g.lda;
+      xsrc += (size_t)W * g.ldb;
+      ld_y = (ld_y + 1 == g.H) ? 0 : ld_y + 1;
+    }
+  };
+
+  // ---- consumer role.  Lane = 32 kg + 16 g2 + s: k-octet kg, channel half g2 of a 32-channel block, s = 4 sr + sc
+  // supplies row sr, channel group sc of a transposing read.
+  const int kg = lane >> 5, g2 = (lane >> 4) & 1, s = lane & 15, sr = s >> 2, sc = s & 3;
+  const int inrow = (2 * g2 + (sc >> 1)) * 16 + 8 * (sc & 1);
+  int goff[4], xoffs[3], xrows[3];
+#pragma unroll
+  for (int a = 0; a < 4; ++a) goff[a] = (8 * kg + sr) * 256 + ((a ^ sr) * 64) + inrow;
+#pragma unroll
+  for (int d = 0; d < 3; ++d) {
+    xoffs[d] = GB + ((wave ^ ((sr + d) & 3)) * 64) + inrow;   // in the zero row before the line
+    xrows[d] = (8 * kg + sr + d) * 256;
+  }
+  // The transposing reads are written as assembly: the compiler, which cannot tell such a read from the slots that
+  // direct loads still in flight are filling, would wait for ALL of them (vmcnt(0)) before each.  It does not
+  // count these reads either: read_done() is the wait before their results are used.
+  // read_done() is the wait before their results are used; the results pass through it as operands, so that nothing
+  // that reads them can be placed before it.
+  auto tr2 = [&](uint32_t p, v4s& lo, v4s& hi) {
+    // rows r .. r + 3 and r + 4 .. r + 7: the 8 consecutive k of this lane's channel
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(p));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:1024" : "=v"(hi) : "v"(p));
+  };
+  auto read_done = [&](v4s (&r)[14]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]), "+v"(r[8]),
+                   "+v"(r[9]), "+v"(r[10]), "+v"(r[11]), "+v"(r[12]), "+v"(r[13]));
+  };
+  auto frag = [&](const v4s (&r)[14], int i) -> u16x8 {
+    return __builtin_bit_cast(u16x8, __builtin_shufflevector(r[2 * i], r[2 * i + 1], 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  // fragments 0..3: cotangent blocks, 4..6: input at dx = -1, 0, +1
+  // (xrow: 1 on a line whose input line l + dy is inside the image, else 0: all reads then go to the zero row)
+  auto read_frags = [&](uint32_t slot, int ks, int xrow, v4s (&r)[14]) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) tr2(slot + goff[a] + ks * 16 * 256, r[2 * a], r[2 * a + 1]);
+#pragma unroll
+    for (int d = 0; d < 3; ++d) {
+      const uint32_t p = slot + xoffs[d] + xrow * (xrows[d] + ks * 16 * 256);
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r[8 + 2 * d]) : "v"(p));
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r[9 + 2 * d]) : "v"(p + xrow * 1024));
+    }
+  };
+  f32x16 acc[12], sacc;
+#pragma unroll
+  for (int j = 0; j < 12; ++j)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[j][q] = 0.f;
+#pragma unroll
+  for (int q = 0; q < 16; ++q) sacc[q] = 0.f;
+  u16x8 ones;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ones[i] = Low<T>::from_f32(1.f);
+  // cotangent sums: wavefront w forms those of the 32-channel block w; the k-steps are dealt out among the dy = 0
+  // workgroups of this (co block, K-chunk)
+  const bool sums = g.want_sums && dy == 0;
+  const int sum_period = (int)(gridDim.y / 3);
+  const int soff = (8 * kg + sr) * 256 + ((wave ^ sr) * 64) + inrow;
+  int sum_phase = 0;
+  auto wait_vm = [&](auto cnt) {
+    constexpr int c = decltype(cnt)::value;
+    static_assert(c < 64, "vmcnt field");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (c & 15) | ((c >> 4) << 14));  // vmcnt only
+  };
+
+  // Pipeline: lines n + 1 .. n + NS - 2 are in LDS or on their way while line n is multiplied.
+#pragma unroll
+  for (int u = 0; u < NS - 1; ++u) issue();
+  int rslot = 0, c_y = (int)(l_begin % g.H);
+  for (int n = 0; n < nl; ++n) {
+    wait_vm(std::integral_constant<int, (NS - 2) * PERL>{});
+    __builtin_amdgcn_s_barrier();  // everyone's part of line n is in LDS; everyone is done reading line n - 1
+    __builtin_amdgcn_sched_barrier(0);
+    issue();
+    __builtin_amdgcn_sched_barrier(0);
+    const uint32_t slot = ring_base + rslot * SLOT;
+    rslot = (rslot + 1 == NS) ? 0 : rslot + 1;
+    const int yy = c_y + dy;
+    c_y = (c_y + 1 == g.H) ? 0 : c_y + 1;
+    // input line off the image: multiply by zeros (this lane's columns of the zero row are read for every k),
+    // which keeps the loop free of branches around the accumulators
+    const int xrow = (yy >= 0 && yy < g.H) ? 1 : 0;
+    v4s raw[2][14];
+    read_frags(slot, 0, xrow, raw[0]);
+#pragma unroll
+    for (int ks = 0; ks < W16; ++ks) {
+      read_done(raw[ks & 1]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks + 1 < W16) read_frags(slot, ks + 1, xrow, raw[(ks + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);  // (the reads are issued first: the matrix instructions cover their latency)
+      u16x8 fb[3];
+#pragma unroll
+      for (int d = 0; d < 3; ++d) fb[d] = frag(raw[ks & 1], 4 + d);
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const u16x8 fa = frag(raw[ks & 1], a);
+#pragma unroll
+        for (int d = 0; d < 3; ++d) acc[a * 3 + d] = Low<T>::mfma32(fa, fb[d], acc[a * 3 + d]);
+      }
+      if (sums) {
+        if (sum_phase == bt) {
+          v4s lo, hi;
+          tr2(slot + soff + ks * 16 * 256, lo, hi);
+          asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lo), "+v"(hi));
+          const u16x8 fs = __builtin_bit_cast(u16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+          sacc = Low<T>::mfma32(fs, ones, sacc);
+        }
+        sum_phase = (sum_phase + 1 == sum_period) ? 0 : sum_phase + 1;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the tail's extra loads
+
+  // ---- epilogue: plain read-modify-write, the slot belongs to this workgroup for the whole backward pass.  Its layout
+  // follows the accumulator registers: float4 number ((j * 4 + q / 4) * 256 + thread), j = 3 a + dx + 1, holds rows (co)
+  // 32 a + 8 (q / 4) + 4 (lane / 32) + 0..3 of column (ci) 32 wave + lane % 32.
+  const float scale = g.h / g.ctl->S_step;
+  float* slotf = g.part + ((size_t)(blockIdx.z * gridDim.x + blockIdx.x) * gridDim.y + blockIdx.y) * CT_SLOT;
+  float4* slot4 = reinterpret_cast<float4*>(slotf);
+#pragma unroll
+  for (int j0 = 0; j0 < 12; j0 += 3) {
+    float4 old[3][4];
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) old[t][q4] = slot4[((j0 + t) * 4 + q4) * 256 + tid];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        float4 v = old[t][q4];
+        v.x = fmaf(scale, acc[j0 + t][q4 * 4 + 0], v.x);
+        v.y = fmaf(scale, acc[j0 + t][q4 * 4 + 1], v.y);
+        v.z = fmaf(scale, acc[j0 + t][q4 * 4 + 2], v.z);
+        v.w = fmaf(scale, acc[j0 + t][q4 * 4 + 3], v.w);
+        slot4[((j0 + t) * 4 + q4) * 256 + tid] = v;
+      }
+  }
+  if (sums && (lane & 31) == 0) {
+    // column 0 of the sums block: rows 8 (q / 4) + 4 (lane / 32) + q % 4
+    float* tail = slotf + 12 * 4096 + wave * 32;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      float* d = tail + 8 * (q >> 2) + 4 * kg + (q & 3);
+      *d = fmaf(scale, sacc[q], *d);
+    }
+  }
+}
+
+// dW[co][ci][tap] and db[co] += sum over K-chunks of the private copies (end of the backward pass, or of a piece of
+// piecewise-constant weights).  tiles_a, tiles_b: 128-channel blocks of the output / input channels.
+__global__ void conv_wgrad_tr_reduce(float* __restrict__ G, int ldg, const float* __restrict__ part, int splits,
+                                     int tiles_a, int tiles_b, int Na, int Nb, float* __restrict__ gb, const Ctl* ctl) {
+  if (ctl->poison) return;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t nW = (int64_t)Na * Nb * 9;
+  if (i >= nW + Na) return;
+  const size_t per_split = (size_t)tiles_a * tiles_b * 3 * CT_SLOT;
+  if (i >= nW) {
+    if (!gb) return;
+    const int na = (int)(i - nW);
+    float acc = 0.f;
+    for (int c = 0; c < splits; ++c)
+      for (int b = 0; b < tiles_b; ++b)
+        acc += part[c * per_split + ((size_t)(na >> 7) * tiles_b * 3 + b * 3 + 1) * CT_SLOT + 12 * 4096 + (na & 127)];
+    gb[na] += acc;
+    return;
+  }
+  const int nb = (int)(i % Nb), t = (int)((i / Nb) % 9), na = (int)(i / ((int64_t)Nb * 9));
+  // (position of element (co, ci, tap) in a workgroup's copy: see the epilogue of conv_wgrad_tr)
+  const int a = (na & 127) >> 5, r = na & 31, wave = (nb & 127) >> 5, c = nb & 31;
+  const int thread = wave * 64 + ((r >> 2) & 1) * 32 + c;
+  const int j = a * 3 + t % 3;
+  const size_t in_tile = ((size_t)(j * 4 + (r >> 3)) * 256 + thread) * 4 + (r & 3);
+  const size_t tile = ((size_t)(na >> 7) * tiles_b + (nb >> 7)) * 3 + t / 3;
+  float acc = 0.f;
+  for (int c2 = 0; c2 < splits; ++c2) acc += part[c2 * per_split + tile * CT_SLOT + in_tile];
+  G[(size_t)na * ldg + (size_t)nb * 9 + t] += acc;
+}
+
+}  // namespace rampde

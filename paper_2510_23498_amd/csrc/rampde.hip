@@ -23,6 +23,7 @@
 #include "gemm.hpp"
 #include "wgrad_slab.hpp"
 #include "gemm_slab.hpp"
+#include "conv_wgrad_tr.hpp"
 #include "conv.hpp"
 #include "norm.hpp"
 #include "cnf.hpp"
@@ -60,6 +61,7 @@ struct Layer {
   // all-taps convolution weight gradient: K-chunk length, chunk count, the chunks' private copies
   int cw_per = 0, cw_splits = 0;
   size_t cw_part = 0;
+  size_t cw_floats = 0;  // fp32 elements of all the copies
 };
 
 struct Plan {
@@ -105,6 +107,7 @@ struct Plan {
   bool overlap_wgrad = false;       // narrow nets: 4-wave adjoint kernel + parameter gradients on a helper stream
   int64_t Rp = 0, ldk = 0;          // feature-major buffers: k = stage * Rp + row
   int ksplits = 1, kchunk = 64;     // K-chunks of the parameter-gradient contraction
+  bool cw_blocks = false;           // convolutions: keep the weight-gradient kernel with 64 x 64 channel blocks (policy.wgrad_tile = 64)
   bool wgrad_slab = false;          // per-step parameter gradients by the 128 x 128-per-wavefront kernel
   int wgrad_group = 1;              // ... of this many adjoint steps per launch (each step has a buffer set of its own)
   size_t gpart = 0;                 // ksplits copies of the gradient vector
@@ -206,6 +209,7 @@ struct Plan;
 // the all-taps convolution weight-gradient kernel: image lines of a multiple of 8 pixels, at most
 // 64, and whole 128-row k-steps within a stage
 static bool conv_wgrad_applies(const Plan& p);
+static bool conv_wgrad_tr_applies(const Plan& p);
 // compute units of the current device (256 on MI355X; also the answer when no device is visible,
 // e.g. a workspace query on a host without a GPU)
 static int device_compute_units() {
@@ -232,6 +236,7 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
   if (!build_layers(vel, p, allow_fused ? 256 : kPad)) return p;
   if (B < 1 || N < 1 || !tab || tab->s < 1 || tab->s > kMaxStages) return p;
   p.s = tab->s;
+  p.cw_blocks = pol && pol->wgrad_tile == 64;
   p.R = p.conv ? B * (int64_t)p.H * p.Wd : B;
   if (p.R > (int64_t)1 << 30) return p;
   p.n = p.R * p.d;
@@ -437,6 +442,19 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
         // each: fewer, longer chunks keep the read-modify-write of the copies and the pipeline
         // fill small against the multiplication
         const int64_t rows = (int64_t)p.s * p.R;
+        if (conv_wgrad_tr_applies(p)) {
+          // many channels: (128 x 128 channels, one dy) per workgroup, K-chunks of whole image lines, one workgroup per
+          // compute unit
+          Layer& y = p.layers[0];
+          const int tiles = (y.Npad / 128) * (y.Kpad / 128) * 3;
+          const int64_t lines = rows / p.Wd;
+          const int64_t want = std::max<int64_t>(1, device_compute_units() / tiles);
+          const int64_t per = std::max<int64_t>((lines + want - 1) / want, std::min<int64_t>(lines, 4 * (64 / p.Wd)));
+          y.cw_per = (int)per;
+          y.cw_splits = (int)((lines + per - 1) / per);
+          y.cw_floats = (size_t)y.cw_splits * tiles * CT_SLOT;
+          y.cw_part = take(sizeof(float) * y.cw_floats);
+        } else
         for (auto& y : p.layers) {
           const int tiles = (y.Npad / 64) * (y.Kpad / 64);
           const int64_t want = std::max<int64_t>(1, device_compute_units() / tiles);
@@ -444,7 +462,8 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
           if (per < 4 * CW_KS) per = 4 * CW_KS;
           y.cw_per = (int)per;
           y.cw_splits = (int)((rows + per - 1) / per);
-          y.cw_part = take(sizeof(float) * (size_t)y.cw_splits * tiles * CW_SLOT);
+          y.cw_floats = (size_t)y.cw_splits * tiles * CW_SLOT;
+          y.cw_part = take(sizeof(float) * y.cw_floats);
         }
       }
     }
@@ -457,6 +476,12 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
 }
 
 static bool conv_wgrad_applies(const Plan& p) { return p.conv && !p.fused && p.Wd % 8 == 0 && p.Wd <= 64 && p.R % CW_KS == 0; }
+// (the kernel built on transposing LDS reads: the parabolic block's one layer, channel counts in multiples of 128)
+static bool conv_wgrad_tr_applies(const Plan& p) {
+  return conv_wgrad_applies(p) && p.parabolic && !p.cw_blocks &&
+         (p.Wd == 16 || p.Wd == 32 || p.Wd == 64) && p.layers[0].Npad % 128 == 0 && p.layers[0].Kpad % 128 == 0 &&
+         !p.layers[0].has_time;
+}
 
 static int check_common(const rampde_velocity* vel, const double* tgrid, int N, const rampde_tableau* tab,
                         const rampde_policy* pol) {
@@ -1080,7 +1105,22 @@ struct Runner {
         if (l == 1) h = -h;
       }
       g.rows = rows;
-      if (conv_wgrad_applies(p)) {
+      if (conv_wgrad_tr_applies(p)) {
+        ConvWgradTr c{};
+        c.A = g.A; c.lda = g.lda; c.B = g.B; c.ldb = g.ldb;
+        c.lines = rows / p.Wd;
+        c.lines_per_split = y.cw_per;
+        c.part = f32(y.cw_part);
+        c.h = h; c.ctl = ctl; c.H = p.H;
+        c.want_sums = l == 0;
+        dim3 cgrid(y.Npad / 128, y.Kpad / 128 * 3, y.cw_splits);
+        TimeScope ts(RAMPDE_K_WGRAD_GEMM, 2.0 * rows * (double)y.Npad * y.Kpad * 9, st);
+        const size_t lds = conv_wgrad_tr_lds_bytes(p.Wd);
+        if (p.Wd == 16) conv_wgrad_tr<T, 1><<<cgrid, 256, lds, st>>>(c);
+        else if (p.Wd == 32) conv_wgrad_tr<T, 2><<<cgrid, 256, lds, st>>>(c);
+        else conv_wgrad_tr<T, 4><<<cgrid, 256, lds, st>>>(c);
+        continue;  // (bias gradient included)
+      } else if (conv_wgrad_applies(p)) {
         // all 9 taps of a 64 x 64 channel block per workgroup
         ConvWgrad c{};
         c.A = g.A; c.lda = g.lda; c.B = g.B; c.ldb = g.ldb;
@@ -1255,7 +1295,11 @@ struct Runner {
     if (p.wgrad_slab)  // (its ring of operand slabs takes most of a CU's LDS)
       for (const void* f : {reinterpret_cast<const void*>(&wgrad_slab<T, false>), reinterpret_cast<const void*>(&wgrad_slab<T, true>)})
         HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kSlabLdsBytes));
-    if (conv_wgrad_applies(p)) {
+    if (conv_wgrad_tr_applies(p)) {
+      for (const void* f : {reinterpret_cast<const void*>(&conv_wgrad_tr<T, 1>), reinterpret_cast<const void*>(&conv_wgrad_tr<T, 2>),
+                            reinterpret_cast<const void*>(&conv_wgrad_tr<T, 4>)})
+        HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_wgrad_tr_lds_bytes(64)));
+    } else if (conv_wgrad_applies(p)) {
       const int lds = (int)conv_wgrad_lds_bytes(p.Wd);
       HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false, CW_MAXI_LO>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));
@@ -1269,8 +1313,7 @@ struct Runner {
     ctl_reset<<<1, 1, 0, st>>>(ctl, f32(p.scale_hist), N);
     if (conv_wgrad_applies(p))
       for (auto& y : p.layers)
-        fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + y.cw_part),
-                                            (size_t)y.cw_splits * (y.Npad / 64) * (y.Kpad / 64) * CW_SLOT);
+        if (y.cw_floats) fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + y.cw_part), y.cw_floats);
     // piecewise-constant parameters: the piece whose rounded weights are in the workspace and whose
     // private gradient copies are being filled (-1: none yet)
     int piece = -1;
@@ -1281,11 +1324,14 @@ struct Runner {
       const Layer& y = p.layers[0];
       float* gq = grad_theta + (size_t)q * p.Pblk;
       const int64_t n = (int64_t)y.out * y.in * 9 + (int64_t)y.out * 10;
-      conv_wgrad_reduce<<<blocks_for(n, 256), 256, 0, st>>>(gq + y.theta_w, y.in_full * 9, f32(y.cw_part), y.cw_splits,
-                                                            y.Npad / 64, y.Kpad / 64, y.out, y.in, gq + y.theta_b, nullptr,
-                                                            y.in_full * 9, ctl);
-      fill_zero_unless_poisoned<<<1024, 256, 0, st>>>((uint32_t*)(ws + y.cw_part),
-                                                      (size_t)y.cw_splits * (y.Npad / 64) * (y.Kpad / 64) * CW_SLOT, ctl);
+      if (conv_wgrad_tr_applies(p))
+        conv_wgrad_tr_reduce<<<blocks_for(n, 256), 256, 0, st>>>(gq + y.theta_w, y.in_full * 9, f32(y.cw_part), y.cw_splits,
+                                                                 y.Npad / 128, y.Kpad / 128, y.out, y.in, gq + y.theta_b, ctl);
+      else
+        conv_wgrad_reduce<<<blocks_for(n, 256), 256, 0, st>>>(gq + y.theta_w, y.in_full * 9, f32(y.cw_part), y.cw_splits,
+                                                              y.Npad / 64, y.Kpad / 64, y.out, y.in, gq + y.theta_b, nullptr,
+                                                              y.in_full * 9, ctl);
+      fill_zero_unless_poisoned<<<1024, 256, 0, st>>>((uint32_t*)(ws + y.cw_part), y.cw_floats, ctl);
     };
     if (!use_fused && !p.parabolic) cast_weights(theta);
     SideStream& side = SideStream::get();

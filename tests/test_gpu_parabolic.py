@@ -50,14 +50,14 @@ def _all_positive(cfg, theta):
     return theta
 
 
-def _case(cfg, bias_std=0.1, scaling=None, scale_group=0, positive=False, strict=False):
+def _case(cfg, bias_std=0.1, scaling=None, scale_group=0, positive=False, strict=False, wgrad_tile=0):
     theta, y0, target = par.make_inputs(cfg, bias_std=bias_std)
     if positive:
         theta = _all_positive(cfg, theta)
     print(f"[case] {cfg.name} C={cfg.C} {cfg.H}x{cfg.W} B={cfg.B} N={cfg.N} pieces={cfg.n_intervals} low={cfg.low} "
           f"tab={cfg.tableau}", flush=True)
     flags = dict(scale_group=scale_group) if scale_group else None
-    gpu = par.run_gpu(cfg, theta, y0, target, scaling=scaling, scale_group=scale_group)
+    gpu = par.run_gpu(cfg, theta, y0, target, scaling=scaling, scale_group=scale_group, wgrad_tile=wgrad_tile)
     emu = par.run_oracle(cfg, theta, y0, target, "emul", scaling=scaling, flags=flags)
     f64 = par.run_oracle(cfg, theta, y0, target, "f64")
     sens = {k: 0.0 for k in ("yN", "ckpt", "grad_y0", "grad_theta")} if strict else \
@@ -104,6 +104,18 @@ def test_parabolic_wide_convolution_kernel_rk4_two_pieces():
     _case(BASE.with_(name="pbwiderk4", B=16, C=256, H=16, W=16, N=2, n_intervals=2, t1=0.25))
 
 
+# Weight gradients with channel counts in multiples of 128 and 16, 32 or 64 pixels per image line take the kernel built on
+# transposing LDS reads (the cases above with 256 channels and 16 x 16 images among them); policy.wgrad_tile = 64 keeps
+# the kernel with 64 x 64 channel blocks.  One Euler step: the same stage input on both sides, everything to 1e-3.
+@pytest.mark.parametrize("C,B,H,W,wgrad_tile", [(256, 4, 16, 16, 64), (128, 3, 8, 32, 0), (128, 1, 24, 64, 0),
+                                                (128, 5, 16, 16, 0)])
+def test_parabolic_weight_gradient_kernels_single_euler_step_is_tight(C, B, H, W, wgrad_tile):
+    # (128 channels: one channel block, three workgroups per K-chunk, so that chunks of a few image lines occur,
+    # which start and end inside images; 5 images of 16 lines: a last chunk that is cut short)
+    _case(BASE.with_(name=f"pbwg{C}x{H}x{W}", B=B, C=C, H=H, W=W, N=1, n_intervals=1, tableau="euler", t1=0.25),
+          strict=True, wgrad_tile=wgrad_tile)
+
+
 def test_parabolic_all_positive_preactivations_one_rk4_step_is_tight():
     _case(BASE.with_(name="pbpos", B=3, C=64, H=16, W=16, N=1, n_intervals=1, t1=0.25), positive=True, strict=True)
 
@@ -133,10 +145,12 @@ def test_parabolic_many_pixel_chunks_in_the_statistics():
     _case(BASE.with_(name="pbhw", B=1, C=64, H=64, W=64, N=1, n_intervals=1, tableau="heun"))
 
 
-def test_parabolic_retry_inside_a_piece_keeps_the_pieces_gradient():
+@pytest.mark.parametrize("C,H,W", [(64, 8, 8), (128, 16, 16)])
+def test_parabolic_retry_inside_a_piece_keeps_the_pieces_gradient(C, H, W):
     # a terminal gradient large enough that the first scale overflows in the chain: S is halved, the step is
     # redone, and the gradient of the piece that was being accumulated is continued, not lost
-    cfg = BASE.with_(name="pbretry", B=2, C=64, H=8, W=8, N=4, n_intervals=2, grad_scale=1.0)
+    # (128 channels, 16 pixels per line: the weight-gradient kernel built on transposing LDS reads)
+    cfg = BASE.with_(name="pbretry" if C == 64 else f"pbretry{C}", B=2, C=C, H=H, W=W, N=4, n_intervals=2, grad_scale=1.0)
     theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
     theta = (theta * np.float32(12.0)).astype(np.float32)      # cotangents grow backward through W^T W
     gpu = par.run_gpu(cfg, theta, y0, target, scaling="dynamic")
