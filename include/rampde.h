@@ -132,7 +132,9 @@ typedef struct {
                              long batch contractions).  0: chosen by the contraction length (stages x batch rows).
                              PARABOLIC with channel counts in multiples of 128 and W in {16, 32, 64}: 64 keeps the
                              convolution weight-gradient kernel with 64 x 64 channel blocks per workgroup instead of
-                             the one with 128 x 128 x 3-tap blocks built on transposing LDS reads (the default there) */
+                             the one with 128 x 128 x 3-tap blocks built on transposing LDS reads (the default there),
+                             and the convolution kernel that fetches an input slab per tap instead of the one that
+                             stages the input by image lines */
   /* Scope of the adjoint scale within a batch (Alg. 2 is stated for one sample).  0: one scale S for the
    * whole batch (the default).  G > 0: every G consecutive samples (the last group: the remainder) share a
    * scale of their own -- initial value from the group's own max-norm, own overflow retries, own growth --

@@ -30,11 +30,13 @@
 namespace rampde {
 
 struct ConvWgradTr {
-  const uint16_t* A; int lda;   // [rows, >= 128 gridDim.x] cotangents of the layer's output
-  const uint16_t* B; int ldb;   // [rows, >= 128 gridDim.y / 3] the layer's input
+  const uint16_t* A; int lda;   // [rows, >= 128 tiles_a] cotangents of the layer's output
+  const uint16_t* B; int ldb;   // [rows, >= 128 tiles_b] the layer's input
   int64_t lines;                // image lines over all stages and samples: rows / W
   int lines_per_split;
-  float* part;                  // [gridDim.z][gridDim.x][gridDim.y][CT_SLOT] fp32
+  float* part;                  // [splits][tiles_a][3 tiles_b][CT_SLOT] fp32
+  int tiles_a, tiles_b;         // 128-channel blocks of the output / input channels
+  int splits;                   // K-chunks
   float h;                      // scale = h / ctl->S_step
   const Ctl* ctl;
   int H;
@@ -58,9 +60,17 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_tr(ConvWgradTr g) {
   lds_u8* ring = (lds_u8*)cwt_smem;
   const uint32_t ring_base = (uint32_t)(uintptr_t)ring;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int a0 = blockIdx.x * 128;
-  const int bt = blockIdx.y / 3, dy = (int)(blockIdx.y % 3) - 1, b0 = bt * 128;
-  const int64_t l_begin = (int64_t)blockIdx.z * g.lines_per_split;
+  // One-dimensional grid.  The 3 tiles_b workgroups that share an output-channel block and a K-chunk (a group: they read
+  // the same cotangent lines, and input lines one apart) run on one XCD -- workgroup L is dispatched to XCD L % 8 --
+  // so that its L2 fetches those lines from memory once: group number = 8 * (L / 8 / group size) + L % 8.
+  const int gsize = 3 * g.tiles_b;
+  const int wg_n = (int)(blockIdx.x >> 3);
+  const int grp = 8 * (wg_n / gsize) + (int)(blockIdx.x & 7), tile = wg_n % gsize;
+  if (grp >= g.tiles_a * g.splits) return;
+  const int at = grp % g.tiles_a, chunk = grp / g.tiles_a;
+  const int a0 = at * 128;
+  const int bt = tile / 3, dy = tile % 3 - 1, b0 = bt * 128;
+  const int64_t l_begin = (int64_t)chunk * g.lines_per_split;
   int64_t l_end = l_begin + g.lines_per_split;
   if (l_end > g.lines) l_end = g.lines;
   if (l_begin >= l_end) return;
@@ -161,7 +171,7 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_tr(ConvWgradTr g) {
   // cotangent sums: wavefront w forms those of the 32-channel block w; the k-steps are dealt out among the dy = 0
   // workgroups of this (co block, K-chunk)
   const bool sums = g.want_sums && dy == 0;
-  const int sum_period = (int)(gridDim.y / 3);
+  const int sum_period = g.tiles_b;
   const int soff = (8 * kg + sr) * 256 + ((wave ^ sr) * 64) + inrow;
   int sum_phase = 0;
   auto wait_vm = [&](auto cnt) {
@@ -223,7 +233,7 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_tr(ConvWgradTr g) {
   // follows the accumulator registers: float4 number ((j * 4 + q / 4) * 256 + thread), j = 3 a + dx + 1, holds rows (co)
   // 32 a + 8 (q / 4) + 4 (lane / 32) + 0..3 of column (ci) 32 wave + lane % 32.
   const float scale = g.h / g.ctl->S_step;
-  float* slotf = g.part + ((size_t)(blockIdx.z * gridDim.x + blockIdx.x) * gridDim.y + blockIdx.y) * CT_SLOT;
+  float* slotf = g.part + ((size_t)(chunk * g.tiles_a + at) * gsize + tile) * CT_SLOT;
   float4* slot4 = reinterpret_cast<float4*>(slotf);
 #pragma unroll
   for (int j0 = 0; j0 < 12; j0 += 3) {

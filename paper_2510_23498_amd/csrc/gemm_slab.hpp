@@ -199,4 +199,220 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_slab(GemmNT g) {
   if (g.detect) raise_if_any(bad, g.ctl);
 }
 
+
+// ---- The same convolution with the input staged by image lines (W in {16, 32, 64} pixels per line, 256 / W lines per
+// tile, image heights that are multiples of that).  gemm_nt_slab fetches a 256 x 64-byte slab of shifted input rows for
+// every tap: nine passes over the same pixels.  Here a block of 32 input channels of the tile's lines and of the line
+// above and below (zeros where that line is off the image), with a zero pixel before and after every line, is brought
+// into LDS ONCE and serves all nine taps as row offsets; only the weight slabs (256 output channels x 32 input
+// channels of one tap) stream per k-step, through a ring of four slots.  The input blocks alternate between two
+// buffers: block c + 1 is requested when block c's first tap is multiplied.  Fill traffic per k-step: 18.8 KB
+// instead of 32 KB.  Fragment reads, permutation of the 16-byte pieces (XOR with bits of the LDS row number),
+// accumulators and epilogue as in gemm_nt_slab.
+template <int W16>
+struct NtLines {
+  static constexpr int W = 16 * W16, LT = 256 / W;
+  static constexpr int ROWS = (LT + 2) * (W + 2);     // LDS rows (pixels) of an input block
+  static constexpr int XB = ROWS * 64;                // bytes of an input block (32 channels)
+  static constexpr int NJ = (LT + 2) * W16;           // its 1 KB wave-loads (16 pixels each)
+  static constexpr int XL = (NJ + 3) / 4;             // ... per wavefront (the last ones may be repeated)
+  static constexpr int NS = 4, WB = 256 * 64;         // ring of weight slabs
+  static constexpr int LDS = 2 * XB + NS * WB;
+};
+
+inline bool conv_nt_lines_applies(const GemmNT& g) {
+  if (!(g.Wd == 16 || g.Wd == 32 || g.Wd == 64)) return false;
+  return g.N % 256 == 0 && g.M >= 4096 && !g.wt && !g.dact && !g.tr_c && g.Cpad % 32 == 0 && g.K == 9 * g.Cpad &&
+         g.H % (256 / g.Wd) == 0 && g.M % 256 == 0;
+}
+
+template <class T, int W16>
+__global__ __launch_bounds__(256, 1) void conv_nt_lines(GemmNT g) {
+  if (g.ctl && g.ctl->poison) return;
+  typedef NtLines<W16> P;
+  constexpr int W = P::W, LT = P::LT, NS = P::NS, PERW = 4;
+  typedef __attribute__((address_space(3))) uint8_t lds_u8;
+  extern __shared__ __attribute__((aligned(16))) uint8_t ntl_smem[];
+  lds_u8* xbuf = (lds_u8*)ntl_smem;            // two input blocks
+  lds_u8* ring = xbuf + 2 * P::XB;             // NS weight slabs
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int frow = lane & 31, oct = lane >> 5;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int64_t m0 = (int64_t)blockIdx.x * 256;
+  const int n0 = blockIdx.y * 256;
+  const int KC = g.Cpad / 32, KT = 9 * KC;
+
+  // the zero pixels before and after every line of both input blocks (never overwritten)
+  for (int i = tid; i < 2 * (LT + 2) * 2 * 4; i += 256) {
+    const int piece = i & 3, side = (i >> 2) & 1, line = (i >> 3) % (LT + 2), buf = (i >> 3) / (LT + 2);
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    *reinterpret_cast<__attribute__((address_space(3))) u32x4*>(xbuf + buf * P::XB + (line * (W + 2) + (side ? W + 1 : 0)) * 64 + piece * 16) =
+        u32x4{0u, 0u, 0u, 0u};
+  }
+  __syncthreads();
+
+  // ---- loader role.  Weight slab: wave-load i of this wavefront = rows 64 * wave + 16 * i + lane / 4; lane % 4 is the
+  // 16-byte slot, which holds piece  slot ^ ((row >> 2) & 3).
+  const int lrow = lane >> 2;
+  const uint16_t* wp[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = 64 * wave + 16 * i + lrow;
+    wp[i] = g.W + (size_t)(n0 + r) * g.ldw + (((lane & 3) ^ ((lrow >> 2) & 3))) * 8;
+  }
+  // Input block: wave-load j = (LDS line j / W16, pixels 16 (j % W16) ..); LDS line i holds the tile's line i - 1.
+  const int64_t line0 = m0 / W;                       // the tile's first line (lines over all samples)
+  const int y0 = (int)(line0 % g.H);                  // ... within its image (the tile's lines are in one image)
+  const uintptr_t zeros = (uintptr_t)g_nt_slab_zeros;
+  uintptr_t xsrc[P::XL];   // this lane's 16 bytes of channel block 0, or the zero buffer
+  int xdst[P::XL];         // LDS offset of the wave-load within an input block
+  bool xlive[P::XL];
+#pragma unroll
+  for (int i = 0; i < P::XL; ++i) {
+    const int j = (wave * P::XL + i < P::NJ) ? wave * P::XL + i : P::NJ - 1;
+    const int li = j / W16, x = 16 * (j % W16) + lrow;
+    const int pr = li * (W + 2) + 1 + x;
+    const int piece = (lane & 3) ^ ((pr >> 2) & 3);
+    const int yy = y0 - 1 + li;
+    xlive[i] = yy >= 0 && yy < g.H;
+    xsrc[i] = xlive[i] ? (uintptr_t)(g.A + ((size_t)(line0 - 1 + li) * W + x) * g.lda + piece * 8) : zeros + (lane & 3) * 16;
+    xdst[i] = (li * (W + 2) + 1 + 16 * (j % W16)) * 64;
+  }
+  auto issue_x = [&](int c) {
+    lds_u8* dst = xbuf + (c & 1) * P::XB;
+#pragma unroll
+    for (int i = 0; i < P::XL; ++i)
+      __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint16_t*>(xsrc[i] + (xlive[i] ? (uintptr_t)c * 64 : 0)),
+                                       (__attribute__((address_space(3))) void*)(dst + xdst[i]), 16, 0, 0);
+  };
+  int wslot = 0, ld_kt = 0, ld_tap = 0, ld_c0 = 0;
+  auto issue_w = [&]() {
+    lds_u8* slot = ring + wslot * P::WB;
+    wslot = (wslot + 1 == NS) ? 0 : wslot + 1;
+    const int64_t wk = (int64_t)ld_tap * g.Cpad + ld_c0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds(wp[i] + wk, (__attribute__((address_space(3))) void*)(slot + (64 * wave + 16 * i) * 64), 16, 0, 0);
+    // advance, staying on the last k-step once it is reached (the extra loads of the pipeline tail stay in bounds)
+    const bool more = ld_kt + 1 < KT;
+    ld_kt += more ? 1 : 0;
+    const int t1 = ld_tap + (more ? 1 : 0);
+    const bool wrap = t1 == 9;
+    ld_tap = wrap ? 0 : t1;
+    ld_c0 += wrap ? 32 : 0;
+  };
+
+  // ---- consumer role.  Input fragment of 32-pixel block a: pixel p = 128 wm + 32 a + lane % 32 of the tile, LDS row
+  // (p / W + 1 + dy) (W + 2) + p % W + 1 + dx; weight fragment: row 128 wn + 32 a + lane % 32 of the slab.
+  int pr0[4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    const int p = 128 * wm + 32 * a + frow;
+    pr0[a] = (p / W + 1) * (W + 2) + p % W + 1;
+  }
+  int rdw[2];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) rdw[kk] = frow * 64 + (((2 * kk + oct) ^ ((frow >> 2) & 3)) * 16);
+  int rslot = 0, rd_tap = 0, rd_c = 0;   // position of the next k-step to read
+  auto read_frags = [&](u16x8 (&fa)[2][4], u16x8 (&fb)[2][4]) {
+    const lds_u8* slot = ring + rslot * P::WB;
+    rslot = (rslot + 1 == NS) ? 0 : rslot + 1;
+    const lds_u8* xb = xbuf + (rd_c & 1) * P::XB;
+    const int shift = (rd_tap / 3 - 1) * (W + 2) + (rd_tap % 3 - 1);
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const int pr = pr0[a] + shift, key = (pr >> 2) & 3;
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        fa[kk][a] = *reinterpret_cast<const __attribute__((address_space(3))) u16x8*>(xb + pr * 64 + (((2 * kk + oct) ^ key) * 16));
+        fb[kk][a] = *reinterpret_cast<const __attribute__((address_space(3))) u16x8*>(slot + (wn * 128 + a * 32) * 64 + rdw[kk]);
+      }
+    }
+    // (past the end: stays on the last k-step, whose copy is never multiplied)
+    const bool more = rd_c * 9 + rd_tap + 1 < KT;
+    const int t1 = rd_tap + (more ? 1 : 0);
+    rd_c += (t1 == 9) ? 1 : 0;
+    rd_tap = (t1 == 9) ? 0 : t1;
+  };
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.f;
+  auto wait_vm = [&](auto cnt) {
+    constexpr int c = decltype(cnt)::value;
+    static_assert(c < 64, "vmcnt field");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (c & 15) | ((c >> 4) << 14));  // vmcnt only
+  };
+  auto mma = [&](const u16x8 (&fa)[2][4], const u16x8 (&fb)[2][4]) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = Low<T>::mfma32(fa[kk][a], fb[kk][b], acc[a][b]);
+  };
+
+  // Pipeline: weight slabs st + 1 .. st + NS - 2 are in LDS or on their way while k-step st is multiplied; the fragments
+  // of k-step st + 1 are read in the shadow of the matrix instructions of st.  Loads complete in the order of their issue,
+  // so a wait that leaves only the weight loads of the later k-steps outstanding also covers an input block requested
+  // before them (and waits a little longer than needed where one was requested after them).
+  u16x8 fa[2][2][4], fb[2][2][4];
+  issue_x(0);
+#pragma unroll
+  for (int u = 0; u < NS - 1; ++u) issue_w();
+  wait_vm(std::integral_constant<int, (NS - 2) * PERW>{});
+  __builtin_amdgcn_s_barrier();
+  read_frags(fa[0], fb[0]);
+  int st_tap = 0, st_c = 0;  // position of the k-step being multiplied
+  auto k_step = [&](u16x8 (&ca)[2][4], u16x8 (&cb)[2][4], u16x8 (&na)[2][4], u16x8 (&nb)[2][4]) {
+    wait_vm(std::integral_constant<int, (NS - 3) * PERW>{});
+    __builtin_amdgcn_s_barrier();  // everyone's part of k-step st + 1 is in LDS; everyone is done reading k-step st
+    __builtin_amdgcn_sched_barrier(0);
+    // (the other input buffer was last read for the last tap of block c - 1, one k-step ago)
+    if (st_tap == 0 && st_c + 1 < KC) issue_x(st_c + 1);
+    issue_w();
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(na, nb);
+    __builtin_amdgcn_sched_barrier(0);  // (the reads are issued first: the matrix instructions cover their latency)
+    mma(ca, cb);
+    __builtin_amdgcn_sched_barrier(0);
+    st_c += (st_tap == 8) ? 1 : 0;
+    st_tap = (st_tap == 8) ? 0 : st_tap + 1;
+  };
+  int st = 0;
+  for (; st + 2 <= KT; st += 2) {
+    k_step(fa[0], fb[0], fa[1], fb[1]);
+    k_step(fa[1], fb[1], fa[0], fb[0]);
+  }
+  if (st < KT) k_step(fa[0], fb[0], fa[1], fb[1]);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the tail's extra loads
+
+  // ---- epilogue: accumulator lane layout of a 32x32 block: column = lane % 32, row = 8 (q / 4) + 4 (lane / 32) + q % 4
+  bool bad = false;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const int n = n0 + wn * 128 + b * 32 + frow;
+    const float bv = g.bias ? g.bias[n] : 0.f;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const int64_t mb = m0 + wm * 128 + a * 32 + 4 * oct;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int64_t m = mb + 8 * (q >> 2) + (q & 3);
+        float v = acc[a][b][q] + bv;
+        if (g.act_tanh == 1) v = act_tanh(v);
+        else if (g.act_tanh == 2) v = fmaxf(v, 0.f);
+        if (g.negate) v = -v;
+        const uint16_t qv = Low<T>::from_f32(v);
+        bad = bad || Low<T>::nonfinite(qv);
+        g.C[(size_t)m * g.ldc + n] = qv;
+      }
+    }
+  }
+  if (g.detect) raise_if_any(bad, g.ctl);
+}
+
 }  // namespace rampde

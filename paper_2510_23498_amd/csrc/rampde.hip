@@ -446,9 +446,12 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
           // many channels: (128 x 128 channels, one dy) per workgroup, K-chunks of whole image lines, one workgroup per
           // compute unit
           Layer& y = p.layers[0];
-          const int tiles = (y.Npad / 128) * (y.Kpad / 128) * 3;
+          const int tiles_a = y.Npad / 128, gsize = y.Kpad / 128 * 3, tiles = tiles_a * gsize;
           const int64_t lines = rows / p.Wd;
-          const int64_t want = std::max<int64_t>(1, device_compute_units() / tiles);
+          // (a group -- the workgroups of one output-channel block and K-chunk -- runs on one XCD: as many whole groups
+          // as an XCD's compute units hold)
+          const int per_xcd = std::max(1, device_compute_units() / 8 / gsize);
+          const int64_t want = std::max<int64_t>(1, 8 * per_xcd / tiles_a);
           const int64_t per = std::max<int64_t>((lines + want - 1) / want, std::min<int64_t>(lines, 4 * (64 / p.Wd)));
           y.cw_per = (int)per;
           y.cw_splits = (int)((lines + per - 1) / per);
@@ -629,6 +632,11 @@ struct Runner {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_slab<T, true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kNtSlabLdsBytes);
     if (e != hipSuccess) return e;
+    for (const void* f : {reinterpret_cast<const void*>(&conv_nt_lines<T, 1>), reinterpret_cast<const void*>(&conv_nt_lines<T, 2>),
+                          reinterpret_cast<const void*>(&conv_nt_lines<T, 4>)}) {
+      e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, NtLines<4>::LDS);
+      if (e != hipSuccess) return e;
+    }
     if (p.Wd < 8 || p.Wd > 64) return hipSuccess;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3x3_tile<T, 8>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_tile_lds_bytes(p.Wd));
@@ -640,6 +648,12 @@ struct Runner {
       // persistent: one workgroup per CU (its LDS holds the layer's weights), tiles of 256 pixels
       const int ntiles = (int)(g.M / CT_TILE);
       conv3x3_tile<T, 8><<<std::min(ntiles, device_compute_units()), 512, conv_tile_lds_bytes(g.Wd), st>>>(g);
+    } else if (p.conv && !p.cw_blocks && conv_nt_lines_applies(g)) {
+      // ... with the input staged by image lines: a block of input channels serves all nine taps from LDS
+      dim3 grid(g.M / 256, g.N / 256);
+      if (g.Wd == 16) conv_nt_lines<T, 1><<<grid, 256, NtLines<1>::LDS, st>>>(g);
+      else if (g.Wd == 32) conv_nt_lines<T, 2><<<grid, 256, NtLines<2>::LDS, st>>>(g);
+      else conv_nt_lines<T, 4><<<grid, 256, NtLines<4>::LDS, st>>>(g);
     } else if (p.conv && gemm_nt_slab_applies(g, true)) {
       // wide convolutions (the parabolic block): 256 x 256 workgroup tiles fed by direct global->LDS loads
       dim3 grid(blocks_for(g.M, 256), g.N / 256);
@@ -1113,7 +1127,9 @@ struct Runner {
         c.part = f32(y.cw_part);
         c.h = h; c.ctl = ctl; c.H = p.H;
         c.want_sums = l == 0;
-        dim3 cgrid(y.Npad / 128, y.Kpad / 128 * 3, y.cw_splits);
+        c.tiles_a = y.Npad / 128; c.tiles_b = y.Kpad / 128; c.splits = y.cw_splits;
+        const int groups = c.tiles_a * c.splits;
+        dim3 cgrid(8 * 3 * c.tiles_b * ((groups + 7) / 8));
         TimeScope ts(RAMPDE_K_WGRAD_GEMM, 2.0 * rows * (double)y.Npad * y.Kpad * 9, st);
         const size_t lds = conv_wgrad_tr_lds_bytes(p.Wd);
         if (p.Wd == 16) conv_wgrad_tr<T, 1><<<cgrid, 256, lds, st>>>(c);
