@@ -174,72 +174,92 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_slab(GemmNT g) {
 
   // ---- epilogue: accumulator lane layout of a 32x32 block: column = lane % 32, row = 8 (q / 4) + 4 (lane / 32) + q % 4
   bool bad = false;
+  // (the choice of activation and sign is made once, around straight-line code: with one wavefront per SIMD nothing
+  // hides a branch per element)
+  auto convert = [&](auto act_c, auto neg_c) {
+    constexpr int ACT = decltype(act_c)::value;
+    constexpr bool NEG = decltype(neg_c)::value != 0;
 #pragma unroll
-  for (int b = 0; b < 4; ++b) {
-    const int n = n0 + wn * 128 + b * 32 + frow;
-    const float bv = g.bias ? g.bias[n] : 0.f;
+    for (int b = 0; b < 4; ++b) {
+      const int n = n0 + wn * 128 + b * 32 + frow;
+      const float bv = g.bias ? g.bias[n] : 0.f;
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      const int64_t mb = m0 + wm * 128 + a * 32 + 4 * oct;
+      for (int a = 0; a < 4; ++a) {
+        const int64_t mb = m0 + wm * 128 + a * 32 + 4 * oct;
 #pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const int64_t m = mb + 8 * (q >> 2) + (q & 3);
-        if (m < g.M) {
+        for (int q = 0; q < 16; ++q) {
+          const int64_t m = mb + 8 * (q >> 2) + (q & 3);
           float v = acc[a][b][q] + bv;
-          if (g.act_tanh == 1) v = act_tanh(v);
-          else if (g.act_tanh == 2) v = fmaxf(v, 0.f);
-          if (g.negate) v = -v;
+          if (ACT == 1) v = act_tanh(v);
+          else if (ACT == 2) v = fmaxf(v, 0.f);
+          if (NEG) v = -v;
           const uint16_t qv = Low<T>::from_f32(v);
-          bad = bad || Low<T>::nonfinite(qv);
-          g.C[(size_t)m * g.ldc + n] = qv;
+          if (m < g.M) {
+            bad |= Low<T>::nonfinite(qv);
+            g.C[(size_t)m * g.ldc + n] = qv;
+          }
         }
       }
     }
+  };
+  typedef std::integral_constant<int, 0> c0;
+  typedef std::integral_constant<int, 1> c1;
+  typedef std::integral_constant<int, 2> c2;
+  if (g.negate) {
+    if (g.act_tanh == 1) convert(c1{}, c1{});
+    else if (g.act_tanh == 2) convert(c2{}, c1{});
+    else convert(c0{}, c1{});
+  } else {
+    if (g.act_tanh == 1) convert(c1{}, c0{});
+    else if (g.act_tanh == 2) convert(c2{}, c0{});
+    else convert(c0{}, c0{});
   }
   if (g.detect) raise_if_any(bad, g.ctl);
 }
 
 
-// ---- The same convolution with the input staged by image lines (W in {16, 32, 64} pixels per line, 256 / W lines per
+// ---- The same convolution with the input staged by image lines (W in {16, 32, 64} pixels per line, 512 / W lines per
 // tile, image heights that are multiples of that).  gemm_nt_slab fetches a 256 x 64-byte slab of shifted input rows for
 // every tap: nine passes over the same pixels.  Here a block of 32 input channels of the tile's lines and of the line
 // above and below (zeros where that line is off the image), with a zero pixel before and after every line, is brought
-// into LDS ONCE and serves all nine taps as row offsets; only the weight slabs (256 output channels x 32 input
+// into LDS ONCE and serves all nine taps as row offsets; only the weight slabs (128 output channels x 32 input
 // channels of one tap) stream per k-step, through a ring of four slots.  The input blocks alternate between two
-// buffers: block c + 1 is requested when block c's first tap is multiplied.  Fill traffic per k-step: 18.8 KB
-// instead of 32 KB.  Fragment reads, permutation of the 16-byte pieces (XOR with bits of the LDS row number),
-// accumulators and epilogue as in gemm_nt_slab.
+// buffers: block c + 1 is requested when block c's first tap is multiplied.  A workgroup owns 512 pixels x 128 output
+// channels (a wavefront: 128 x 128): all compute units of an XCD pull the same weight slabs from its L2 at the same
+// time, and half as many weight bytes per pixel is what this shape is for.  Fill traffic per k-step and workgroup:
+// 12.7 KB (gemm_nt_slab: 32 KB).  Fragment reads, permutation of the 16-byte pieces (XOR with bits of the LDS row
+// number), accumulators and epilogue as in gemm_nt_slab.
 template <int W16>
 struct NtLines {
-  static constexpr int W = 16 * W16, LT = 256 / W;
+  static constexpr int W = 16 * W16, LT = 512 / W;
   static constexpr int ROWS = (LT + 2) * (W + 2);     // LDS rows (pixels) of an input block
   static constexpr int XB = ROWS * 64;                // bytes of an input block (32 channels)
   static constexpr int NJ = (LT + 2) * W16;           // its 1 KB wave-loads (16 pixels each)
   static constexpr int XL = (NJ + 3) / 4;             // ... per wavefront (the last ones may be repeated)
-  static constexpr int NS = 4, WB = 256 * 64;         // ring of weight slabs
-  static constexpr int LDS = 2 * XB + NS * WB;
+  static constexpr int NS = 4, WB = 128 * 64;         // ring of weight slabs
+  static constexpr int EP = 272;                      // epilogue: pitch (bytes) of a staged output row of 128 channels
+  static constexpr int LDS = (2 * XB + NS * WB > 4 * 128 * EP) ? 2 * XB + NS * WB : 4 * 128 * EP;
 };
 
 inline bool conv_nt_lines_applies(const GemmNT& g) {
   if (!(g.Wd == 16 || g.Wd == 32 || g.Wd == 64)) return false;
-  return g.N % 256 == 0 && g.M >= 4096 && !g.wt && !g.dact && !g.tr_c && g.Cpad % 32 == 0 && g.K == 9 * g.Cpad &&
-         g.H % (256 / g.Wd) == 0 && g.M % 256 == 0;
+  return g.N % 128 == 0 && g.M >= 4096 && !g.wt && !g.dact && !g.tr_c && g.Cpad % 32 == 0 && g.K == 9 * g.Cpad &&
+         g.H % (512 / g.Wd) == 0 && g.M % 512 == 0;
 }
 
 template <class T, int W16>
 __global__ __launch_bounds__(256, 1) void conv_nt_lines(GemmNT g) {
   if (g.ctl && g.ctl->poison) return;
   typedef NtLines<W16> P;
-  constexpr int W = P::W, LT = P::LT, NS = P::NS, PERW = 4;
+  constexpr int W = P::W, LT = P::LT, NS = P::NS, PERW = 2;
   typedef __attribute__((address_space(3))) uint8_t lds_u8;
   extern __shared__ __attribute__((aligned(16))) uint8_t ntl_smem[];
   lds_u8* xbuf = (lds_u8*)ntl_smem;            // two input blocks
   lds_u8* ring = xbuf + 2 * P::XB;             // NS weight slabs
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int frow = lane & 31, oct = lane >> 5;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int64_t m0 = (int64_t)blockIdx.x * 256;
-  const int n0 = blockIdx.y * 256;
+  const int64_t m0 = (int64_t)blockIdx.x * 512;
+  const int n0 = blockIdx.y * 128;
   const int KC = g.Cpad / 32, KT = 9 * KC;
 
   // the zero pixels before and after every line of both input blocks (never overwritten)
@@ -251,13 +271,13 @@ __global__ __launch_bounds__(256, 1) void conv_nt_lines(GemmNT g) {
   }
   __syncthreads();
 
-  // ---- loader role.  Weight slab: wave-load i of this wavefront = rows 64 * wave + 16 * i + lane / 4; lane % 4 is the
+  // ---- loader role.  Weight slab: wave-load i of this wavefront = rows 32 * wave + 16 * i + lane / 4; lane % 4 is the
   // 16-byte slot, which holds piece  slot ^ ((row >> 2) & 3).
   const int lrow = lane >> 2;
-  const uint16_t* wp[4];
+  const uint16_t* wp[2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = 64 * wave + 16 * i + lrow;
+  for (int i = 0; i < 2; ++i) {
+    const int r = 32 * wave + 16 * i + lrow;
     wp[i] = g.W + (size_t)(n0 + r) * g.ldw + (((lane & 3) ^ ((lrow >> 2) & 3))) * 8;
   }
   // Input block: wave-load j = (LDS line j / W16, pixels 16 (j % W16) ..); LDS line i holds the tile's line i - 1.
@@ -291,8 +311,8 @@ __global__ __launch_bounds__(256, 1) void conv_nt_lines(GemmNT g) {
     wslot = (wslot + 1 == NS) ? 0 : wslot + 1;
     const int64_t wk = (int64_t)ld_tap * g.Cpad + ld_c0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_global_load_lds(wp[i] + wk, (__attribute__((address_space(3))) void*)(slot + (64 * wave + 16 * i) * 64), 16, 0, 0);
+    for (int i = 0; i < 2; ++i)
+      __builtin_amdgcn_global_load_lds(wp[i] + wk, (__attribute__((address_space(3))) void*)(slot + (32 * wave + 16 * i) * 64), 16, 0, 0);
     // advance, staying on the last k-step once it is reached (the extra loads of the pipeline tail stay in bounds)
     const bool more = ld_kt + 1 < KT;
     ld_kt += more ? 1 : 0;
@@ -302,12 +322,12 @@ __global__ __launch_bounds__(256, 1) void conv_nt_lines(GemmNT g) {
     ld_c0 += wrap ? 32 : 0;
   };
 
-  // ---- consumer role.  Input fragment of 32-pixel block a: pixel p = 128 wm + 32 a + lane % 32 of the tile, LDS row
-  // (p / W + 1 + dy) (W + 2) + p % W + 1 + dx; weight fragment: row 128 wn + 32 a + lane % 32 of the slab.
+  // ---- consumer role.  Input fragment of 32-pixel block a: pixel p = 128 wave + 32 a + lane % 32 of the tile, LDS row
+  // (p / W + 1 + dy) (W + 2) + p % W + 1 + dx; weight fragment: row 32 a + lane % 32 of the slab.
   int pr0[4];
 #pragma unroll
   for (int a = 0; a < 4; ++a) {
-    const int p = 128 * wm + 32 * a + frow;
+    const int p = 128 * wave + 32 * a + frow;
     pr0[a] = (p / W + 1) * (W + 2) + p % W + 1;
   }
   int rdw[2];
@@ -319,15 +339,15 @@ __global__ __launch_bounds__(256, 1) void conv_nt_lines(GemmNT g) {
     rslot = (rslot + 1 == NS) ? 0 : rslot + 1;
     const lds_u8* xb = xbuf + (rd_c & 1) * P::XB;
     const int shift = (rd_tap / 3 - 1) * (W + 2) + (rd_tap % 3 - 1);
+    // (in the order in which the matrix instructions use them)
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      const int pr = pr0[a] + shift, key = (pr >> 2) & 3;
+    for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
+      for (int a = 0; a < 4; ++a) {
+        const int pr = pr0[a] + shift, key = (pr >> 2) & 3;
         fa[kk][a] = *reinterpret_cast<const __attribute__((address_space(3))) u16x8*>(xb + pr * 64 + (((2 * kk + oct) ^ key) * 16));
-        fb[kk][a] = *reinterpret_cast<const __attribute__((address_space(3))) u16x8*>(slot + (wn * 128 + a * 32) * 64 + rdw[kk]);
+        fb[kk][a] = *reinterpret_cast<const __attribute__((address_space(3))) u16x8*>(slot + a * 32 * 64 + rdw[kk]);
       }
-    }
     // (past the end: stays on the last k-step, whose copy is never multiplied)
     const bool more = rd_c * 9 + rd_tap + 1 < KT;
     const int t1 = rd_tap + (more ? 1 : 0);
@@ -346,13 +366,14 @@ __global__ __launch_bounds__(256, 1) void conv_nt_lines(GemmNT g) {
     static_assert(c < 64, "vmcnt field");
     __builtin_amdgcn_s_waitcnt(0x0F70 | (c & 15) | ((c >> 4) << 14));  // vmcnt only
   };
-  auto mma = [&](const u16x8 (&fa)[2][4], const u16x8 (&fb)[2][4]) {
+  // matrix instructions [I0, I1) of a k-step's 32, in the order (kk, a, b)
+  auto mma = [&](auto first, auto last, const u16x8 (&fa)[2][4], const u16x8 (&fb)[2][4]) {
+    constexpr int I0 = decltype(first)::value, I1 = decltype(last)::value;
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-      for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = Low<T>::mfma32(fa[kk][a], fb[kk][b], acc[a][b]);
+    for (int i = I0; i < I1; ++i) {
+      const int kk = i >> 4, a = (i >> 2) & 3, b = i & 3;
+      acc[a][b] = Low<T>::mfma32(fa[kk][a], fb[kk][b], acc[a][b]);
+    }
   };
 
   // Pipeline: weight slabs st + 1 .. st + NS - 2 are in LDS or on their way while k-step st is multiplied; the fragments
@@ -368,16 +389,28 @@ __global__ __launch_bounds__(256, 1) void conv_nt_lines(GemmNT g) {
   read_frags(fa[0], fb[0]);
   int st_tap = 0, st_c = 0;  // position of the k-step being multiplied
   auto k_step = [&](u16x8 (&ca)[2][4], u16x8 (&cb)[2][4], u16x8 (&na)[2][4], u16x8 (&nb)[2][4]) {
+    // One wavefront per SIMD: whatever it issues between two matrix instructions runs beside them, whatever it issues in
+    // a block of its own leaves the matrix unit idle.  The first quarter of the k-step's matrix instructions goes out
+    // before the wait (the unit works on them while this wavefront waits for the slab and the others); the address
+    // arithmetic, the requests and the fragment reads of the next k-step are placed between the rest.
+    mma(std::integral_constant<int, 0>{}, std::integral_constant<int, 8>{}, ca, cb);
+    __builtin_amdgcn_sched_barrier(0);
     wait_vm(std::integral_constant<int, (NS - 3) * PERW>{});
     __builtin_amdgcn_s_barrier();  // everyone's part of k-step st + 1 is in LDS; everyone is done reading k-step st
     __builtin_amdgcn_sched_barrier(0);
     // (the other input buffer was last read for the last tap of block c - 1, one k-step ago)
     if (st_tap == 0 && st_c + 1 < KC) issue_x(st_c + 1);
-    issue_w();
     __builtin_amdgcn_sched_barrier(0);
     read_frags(na, nb);
-    __builtin_amdgcn_sched_barrier(0);  // (the reads are issued first: the matrix instructions cover their latency)
-    mma(ca, cb);
+    issue_w();
+    mma(std::integral_constant<int, 8>{}, std::integral_constant<int, 32>{}, ca, cb);
+#pragma unroll
+    for (int i = 0; i < 24; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one matrix instruction
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one fragment read
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // at most one request
+      __builtin_amdgcn_sched_group_barrier(0x006, 5, 0);   // vector / scalar arithmetic
+    }
     __builtin_amdgcn_sched_barrier(0);
     st_c += (st_tap == 8) ? 1 : 0;
     st_tap = (st_tap == 8) ? 0 : st_tap + 1;
@@ -390,26 +423,58 @@ __global__ __launch_bounds__(256, 1) void conv_nt_lines(GemmNT g) {
   if (st < KT) k_step(fa[0], fb[0], fa[1], fb[1]);
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the tail's extra loads
 
-  // ---- epilogue: accumulator lane layout of a 32x32 block: column = lane % 32, row = 8 (q / 4) + 4 (lane / 32) + q % 4
+  // ---- epilogue: accumulator lane layout of a 32x32 block: column = lane % 32, row = 8 (q / 4) + 4 (lane / 32) + q % 4.
+  // Storing from that layout is 256 two-byte store instructions per wavefront (a quarter of the kernel's time when it
+  // was done so): the rounded block goes through LDS instead -- every wavefront has a region of its own, rows of
+  // 128 channels with a pitch of 272 bytes -- and leaves as 16-byte stores of whole 256-byte row segments.
+  __builtin_amdgcn_s_barrier();  // everyone is done reading the operand buffers
+  lds_u8* stage = (lds_u8*)ntl_smem + wave * (128 * P::EP);
   bool bad = false;
+  // (the choice of activation and sign is made once, around straight-line code: taken per element it was a branch per
+  // element, and with one wavefront per SIMD nothing hides a branch)
+  auto convert = [&](auto act_c, auto neg_c) {
+    constexpr int ACT = decltype(act_c)::value;
+    constexpr bool NEG = decltype(neg_c)::value != 0;
 #pragma unroll
-  for (int b = 0; b < 4; ++b) {
-    const int n = n0 + wn * 128 + b * 32 + frow;
-    const float bv = g.bias ? g.bias[n] : 0.f;
+    for (int b = 0; b < 4; ++b) {
+      const int n = n0 + b * 32 + frow;
+      const float bv = g.bias ? g.bias[n] : 0.f;
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      const int64_t mb = m0 + wm * 128 + a * 32 + 4 * oct;
+      for (int a = 0; a < 4; ++a) {
 #pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const int64_t m = mb + 8 * (q >> 2) + (q & 3);
-        float v = acc[a][b][q] + bv;
-        if (g.act_tanh == 1) v = act_tanh(v);
-        else if (g.act_tanh == 2) v = fmaxf(v, 0.f);
-        if (g.negate) v = -v;
-        const uint16_t qv = Low<T>::from_f32(v);
-        bad = bad || Low<T>::nonfinite(qv);
-        g.C[(size_t)m * g.ldc + n] = qv;
+        for (int q = 0; q < 16; ++q) {
+          const int ml = a * 32 + 4 * oct + 8 * (q >> 2) + (q & 3);
+          float v = acc[a][b][q] + bv;
+          if (ACT == 1) v = act_tanh(v);
+          else if (ACT == 2) v = fmaxf(v, 0.f);
+          if (NEG) v = -v;
+          const uint16_t qv = Low<T>::from_f32(v);
+          bad |= Low<T>::nonfinite(qv);
+          *reinterpret_cast<__attribute__((address_space(3))) uint16_t*>(stage + ml * P::EP + (b * 32 + frow) * 2) = qv;
+        }
       }
+    }
+  };
+  typedef std::integral_constant<int, 0> c0;
+  typedef std::integral_constant<int, 1> c1;
+  typedef std::integral_constant<int, 2> c2;
+  if (g.negate) {
+    if (g.act_tanh == 1) convert(c1{}, c1{});
+    else if (g.act_tanh == 2) convert(c2{}, c1{});
+    else convert(c0{}, c1{});
+  } else {
+    if (g.act_tanh == 1) convert(c1{}, c0{});
+    else if (g.act_tanh == 2) convert(c2{}, c0{});
+    else convert(c0{}, c0{});
+  }
+  {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const int er = lane >> 4, ep = lane & 15;
+    uint16_t* crow = g.C + (size_t)(m0 + wave * 128 + er) * g.ldc + n0 + ep * 8;
+#pragma unroll 8
+    for (int i = 0; i < 32; ++i) {
+      const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(stage + (4 * i + er) * P::EP + ep * 16);
+      *reinterpret_cast<u32x4*>(crow + (size_t)4 * i * g.ldc) = v;
     }
   }
   if (g.detect) raise_if_any(bad, g.ctl);

@@ -650,7 +650,7 @@ struct Runner {
       conv3x3_tile<T, 8><<<std::min(ntiles, device_compute_units()), 512, conv_tile_lds_bytes(g.Wd), st>>>(g);
     } else if (p.conv && !p.cw_blocks && conv_nt_lines_applies(g)) {
       // ... with the input staged by image lines: a block of input channels serves all nine taps from LDS
-      dim3 grid(g.M / 256, g.N / 256);
+      dim3 grid(g.M / 512, g.N / 128);
       if (g.Wd == 16) conv_nt_lines<T, 1><<<grid, 256, NtLines<1>::LDS, st>>>(g);
       else if (g.Wd == 32) conv_nt_lines<T, 2><<<grid, 256, NtLines<2>::LDS, st>>>(g);
       else conv_nt_lines<T, 4><<<grid, 256, NtLines<4>::LDS, st>>>(g);

@@ -100,9 +100,9 @@ def test_parabolic_wide_convolution_kernel_single_euler_step_is_tight(low, B, H,
           strict=True)
 
 
-@pytest.mark.parametrize("B,H,W,wgrad_tile", [(4, 32, 32, 0), (1, 64, 64, 0), (2, 32, 64, 0), (16, 16, 16, 64)])
+@pytest.mark.parametrize("B,H,W,wgrad_tile", [(4, 32, 32, 0), (1, 64, 64, 0), (2, 32, 64, 0), (8, 32, 16, 0), (4, 32, 32, 64)])
 def test_parabolic_line_staged_convolution_kernel_single_euler_step_is_tight(B, H, W, wgrad_tile):
-    # 256 channels, >= 4096 pixels, 16 / 32 / 64 pixels per line and image heights that are multiples of 256 / W: the
+    # 256 channels, >= 4096 pixels, 16 / 32 / 64 pixels per line and image heights that are multiples of 512 / W: the
     # convolutions take the kernel that stages the input by image lines (several tiles per image: tiles at the top, in
     # the middle and at the bottom of an image); policy.wgrad_tile = 64 keeps the kernel that fetches a slab per tap
     _case(BASE.with_(name=f"pblines{H}x{W}", B=B, C=256, H=H, W=W, N=1, n_intervals=1, tableau="euler", t1=0.25),
