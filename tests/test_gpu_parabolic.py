@@ -109,6 +109,12 @@ def test_parabolic_line_staged_convolution_kernel_single_euler_step_is_tight(B, 
           strict=True, wgrad_tile=wgrad_tile)
 
 
+def test_parabolic_benchmark_shape_single_euler_step_is_tight():
+    # the shape the benchmark times (256 channels, 64 x 64 images, batch 16: 128 convolution tiles on each half of the
+    # output channels, 20 K-chunks of 205 image lines in the weight gradient), one Euler step, everything to 1e-3
+    _case(BASE.with_(name="pbfull", N=1, n_intervals=1, tableau="euler", t1=0.25), strict=True)
+
+
 def test_parabolic_wide_convolution_kernel_rk4_two_pieces():
     _case(BASE.with_(name="pbwiderk4", B=16, C=256, H=16, W=16, N=2, n_intervals=2, t1=0.25))
 
