@@ -148,15 +148,25 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_tr(ConvWgradTr g) {
   };
   // fragments 0..3: cotangent blocks, 4..6: input at dx = -1, 0, +1
   // (xrow: 1 on a line whose input line l + dy is inside the image, else 0: all reads then go to the zero row)
-  auto read_frags = [&](uint32_t slot, int ks, int xrow, v4s (&r)[14]) {
-#pragma unroll
-    for (int a = 0; a < 4; ++a) tr2(slot + goff[a] + ks * 16 * 256, r[2 * a], r[2 * a + 1]);
-#pragma unroll
-    for (int d = 0; d < 3; ++d) {
+  auto read_frag = [&](uint32_t slot, int ks, int xrow, v4s (&r)[14], auto which) {
+    constexpr int i = decltype(which)::value;
+    if constexpr (i < 4) {
+      tr2(slot + goff[i] + ks * 16 * 256, r[2 * i], r[2 * i + 1]);
+    } else {
+      constexpr int d = i - 4;
       const uint32_t p = slot + xoffs[d] + xrow * (xrows[d] + ks * 16 * 256);
       asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r[8 + 2 * d]) : "v"(p));
       asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r[9 + 2 * d]) : "v"(p + xrow * 1024));
     }
+  };
+  auto read_frags = [&](uint32_t slot, int ks, int xrow, v4s (&r)[14]) {
+    read_frag(slot, ks, xrow, r, std::integral_constant<int, 0>{});
+    read_frag(slot, ks, xrow, r, std::integral_constant<int, 1>{});
+    read_frag(slot, ks, xrow, r, std::integral_constant<int, 2>{});
+    read_frag(slot, ks, xrow, r, std::integral_constant<int, 3>{});
+    read_frag(slot, ks, xrow, r, std::integral_constant<int, 4>{});
+    read_frag(slot, ks, xrow, r, std::integral_constant<int, 5>{});
+    read_frag(slot, ks, xrow, r, std::integral_constant<int, 6>{});
   };
   f32x16 acc[12], sacc;
 #pragma unroll
@@ -180,39 +190,88 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_tr(ConvWgradTr g) {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (c & 15) | ((c >> 4) << 14));  // vmcnt only
   };
 
-  // Pipeline: lines n + 1 .. n + NS - 2 are in LDS or on their way while line n is multiplied.
+  // Pipeline: lines n + 1 .. n + NS - 2 are in LDS or on their way while line n is multiplied.  The wait for line n + 1
+  // and the workgroup's barrier sit in the MIDDLE of line n's last k-step, behind half of its matrix instructions (the
+  // matrix unit works on those while the wavefront waits), and the first fragments of line n + 1 are read behind the
+  // other half: with one wavefront per SIMD a wait at the head of every line left the matrix unit idle for its length.
+  auto mma_read = [&](auto which, const u16x8 (&fa)[4], const u16x8 (&fb)[3], bool rd, uint32_t rslot_addr, int rks, int rxrow,
+                      v4s (&rto)[14]) {
+    constexpr int i = decltype(which)::value;
+    constexpr int a = i / 3, d = i % 3;
+    acc[a * 3 + d] = Low<T>::mfma32(fa[a], fb[d], acc[a * 3 + d]);
+    if constexpr (i < 7) {
+      if (rd) read_frag(rslot_addr, rks, rxrow, rto, which);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto valid_line = [&](int y) { const int yy = y + dy; return (yy >= 0 && yy < g.H) ? 1 : 0; };
 #pragma unroll
   for (int u = 0; u < NS - 1; ++u) issue();
+  wait_vm(std::integral_constant<int, (NS - 2) * PERL>{});
+  __builtin_amdgcn_s_barrier();
   int rslot = 0, c_y = (int)(l_begin % g.H);
-  for (int n = 0; n < nl; ++n) {
-    wait_vm(std::integral_constant<int, (NS - 2) * PERL>{});
-    __builtin_amdgcn_s_barrier();  // everyone's part of line n is in LDS; everyone is done reading line n - 1
-    __builtin_amdgcn_sched_barrier(0);
-    issue();
-    __builtin_amdgcn_sched_barrier(0);
+  // input line off the image: multiply by zeros (this lane's columns of the zero row are read for every k), which keeps
+  // the loop free of branches around the accumulators
+  int xrow = valid_line(c_y);
+  v4s raw[2][14];
+  read_frags(ring_base, 0, xrow, raw[0]);
+  // (par: which of the two fragment register sets the line's first k-step uses -- with one k-step per line, W = 16,
+  // the sets alternate from line to line, and the lines are taken in pairs)
+  auto do_line = [&](auto par) {
+    constexpr int PAR = decltype(par)::value;
     const uint32_t slot = ring_base + rslot * SLOT;
     rslot = (rslot + 1 == NS) ? 0 : rslot + 1;
-    const int yy = c_y + dy;
     c_y = (c_y + 1 == g.H) ? 0 : c_y + 1;
-    // input line off the image: multiply by zeros (this lane's columns of the zero row are read for every k),
-    // which keeps the loop free of branches around the accumulators
-    const int xrow = (yy >= 0 && yy < g.H) ? 1 : 0;
-    v4s raw[2][14];
-    read_frags(slot, 0, xrow, raw[0]);
+    const uint32_t slot_next = ring_base + rslot * SLOT;
+    const int xrow_next = valid_line(c_y);
 #pragma unroll
     for (int ks = 0; ks < W16; ++ks) {
-      read_done(raw[ks & 1]);
+      v4s (&cur)[14] = raw[(PAR + ks) & 1];
+      v4s (&nxt)[14] = raw[(PAR + ks + 1) & 1];
+      read_done(cur);
       __builtin_amdgcn_sched_barrier(0);
-      if (ks + 1 < W16) read_frags(slot, ks + 1, xrow, raw[(ks + 1) & 1]);
-      __builtin_amdgcn_sched_barrier(0);  // (the reads are issued first: the matrix instructions cover their latency)
-      u16x8 fb[3];
+      // A wavefront issues a transposing read about every 10 ns (measured: 200 bytes per ns and compute unit with one
+      // wavefront per SIMD), as long as a matrix instruction takes: the two reads of a fragment of the next k-step go
+      // out behind each of seven matrix instructions of this one.
+      u16x8 fa[4], fb[3];
 #pragma unroll
-      for (int d = 0; d < 3; ++d) fb[d] = frag(raw[ks & 1], 4 + d);
+      for (int a = 0; a < 4; ++a) fa[a] = frag(cur, a);
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const u16x8 fa = frag(raw[ks & 1], a);
-#pragma unroll
-        for (int d = 0; d < 3; ++d) acc[a * 3 + d] = Low<T>::mfma32(fa, fb[d], acc[a * 3 + d]);
+      for (int d = 0; d < 3; ++d) fb[d] = frag(cur, 4 + d);
+      if (ks + 1 < W16) {
+        mma_read(std::integral_constant<int, 0>{}, fa, fb, true, slot, ks + 1, xrow, nxt);
+        mma_read(std::integral_constant<int, 1>{}, fa, fb, true, slot, ks + 1, xrow, nxt);
+        mma_read(std::integral_constant<int, 2>{}, fa, fb, true, slot, ks + 1, xrow, nxt);
+        mma_read(std::integral_constant<int, 3>{}, fa, fb, true, slot, ks + 1, xrow, nxt);
+        mma_read(std::integral_constant<int, 4>{}, fa, fb, true, slot, ks + 1, xrow, nxt);
+        mma_read(std::integral_constant<int, 5>{}, fa, fb, true, slot, ks + 1, xrow, nxt);
+        mma_read(std::integral_constant<int, 6>{}, fa, fb, true, slot, ks + 1, xrow, nxt);
+        mma_read(std::integral_constant<int, 7>{}, fa, fb, false, slot, 0, 0, nxt);
+        mma_read(std::integral_constant<int, 8>{}, fa, fb, false, slot, 0, 0, nxt);
+        mma_read(std::integral_constant<int, 9>{}, fa, fb, false, slot, 0, 0, nxt);
+        mma_read(std::integral_constant<int, 10>{}, fa, fb, false, slot, 0, 0, nxt);
+        mma_read(std::integral_constant<int, 11>{}, fa, fb, false, slot, 0, 0, nxt);
+      } else {
+        // last k-step of the line: matrix instructions 7..11 first (they take no reads with them) ...
+        mma_read(std::integral_constant<int, 7>{}, fa, fb, false, slot, 0, 0, nxt);
+        mma_read(std::integral_constant<int, 8>{}, fa, fb, false, slot, 0, 0, nxt);
+        mma_read(std::integral_constant<int, 9>{}, fa, fb, false, slot, 0, 0, nxt);
+        mma_read(std::integral_constant<int, 10>{}, fa, fb, false, slot, 0, 0, nxt);
+        mma_read(std::integral_constant<int, 11>{}, fa, fb, false, slot, 0, 0, nxt);
+        // ... then line n + 1 (past the chunk's end: a repeated copy of its last line, read but never multiplied) ...
+        wait_vm(std::integral_constant<int, (NS - 3) * PERL>{});
+        __builtin_amdgcn_s_barrier();  // everyone's part of line n + 1 is in LDS; everyone is done reading line n - 1
+        __builtin_amdgcn_sched_barrier(0);
+        issue();                       // line n + NS - 1 into the slot of line n - 1
+        __builtin_amdgcn_sched_barrier(0);
+        // ... and its first fragments behind matrix instructions 0..6
+        mma_read(std::integral_constant<int, 0>{}, fa, fb, true, slot_next, 0, xrow_next, nxt);
+        mma_read(std::integral_constant<int, 1>{}, fa, fb, true, slot_next, 0, xrow_next, nxt);
+        mma_read(std::integral_constant<int, 2>{}, fa, fb, true, slot_next, 0, xrow_next, nxt);
+        mma_read(std::integral_constant<int, 3>{}, fa, fb, true, slot_next, 0, xrow_next, nxt);
+        mma_read(std::integral_constant<int, 4>{}, fa, fb, true, slot_next, 0, xrow_next, nxt);
+        mma_read(std::integral_constant<int, 5>{}, fa, fb, true, slot_next, 0, xrow_next, nxt);
+        mma_read(std::integral_constant<int, 6>{}, fa, fb, true, slot_next, 0, xrow_next, nxt);
       }
       if (sums) {
         if (sum_phase == bt) {
@@ -225,6 +284,13 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_tr(ConvWgradTr g) {
         sum_phase = (sum_phase + 1 == sum_period) ? 0 : sum_phase + 1;
       }
       __builtin_amdgcn_sched_barrier(0);
+    }
+    xrow = xrow_next;
+  };
+  for (int n = 0; n < nl; n += (W16 == 1 ? 2 : 1)) {
+    do_line(std::integral_constant<int, 0>{});
+    if constexpr (W16 == 1) {
+      if (n + 1 < nl) do_line(std::integral_constant<int, 1>{});
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the tail's extra loads
