@@ -130,7 +130,7 @@ typedef struct {
                              parameter gradients.  128: workgroups with a 128 x 128 block of dW_l; 256: wavefronts
                              with a 128 x 128 block each, operands streamed through LDS by direct loads (built for
                              long batch contractions).  0: chosen by the contraction length (stages x batch rows).
-                             PARABOLIC with channel counts in multiples of 128 and W in {16, 32, 64}: 64 keeps the
+                             Convolutions with 64 channels, or PARABOLIC with channel counts in multiples of 128, and W in {16, 32, 64}: 64 keeps the
                              convolution weight-gradient kernel with 64 x 64 channel blocks per workgroup instead of
                              the one with 128 x 128 x 3-tap blocks built on transposing LDS reads (the default there),
                              and the convolution kernel that fetches an input slab per tap instead of the one that

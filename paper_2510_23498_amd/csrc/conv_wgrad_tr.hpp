@@ -363,4 +363,335 @@ __global__ void conv_wgrad_tr_reduce(float* __restrict__ G, int ldg, const float
   G[(size_t)na * ldg + (size_t)nb * 9 + t] += acc;
 }
 
+
+// ---- The same design for 64 x 64 channels (the two-convolution velocity with a time channel): a drop-in for conv_wgrad
+// (same argument structure, same layout of the private copies and of their tail of bias / time-channel sums, so
+// conv_wgrad_reduce serves both).  One workgroup per K-chunk; its four wavefronts own the quadrants 32 co x 32 ci with all
+// nine taps (144 accumulator registers): per k-step of 16 pixels one cotangent fragment and nine input fragments (three
+// lines x three dx) for nine matrix instructions.  LDS holds a ring of 512 / W image lines (cotangent line + input line
+// with a zero pixel at both ends; row = 64 channels = 128 bytes, the two 64-byte halves of a row swapped on every other
+// pair of rows against bank conflicts); a pipeline step is 64 pixels (64 / W lines); lines arrive in groups of a step,
+// six groups ahead.  The loaded range is the chunk's lines plus one line before and after (input halo).
+// Bias and time-channel sums (and the time cotangent sums of the time-grid gradient): the wavefronts of the first input
+// block multiply the cotangent fragment with a 0/1 fragment built in registers -- column t < 9: [pixel + tap t inside],
+// column 9: ones -- into one more accumulator block, which is folded into fp32 sums with the stage's time factors
+// whenever the stage changes (a K-chunk can span stages).
+template <class T, bool TS, int W16>
+__global__ __launch_bounds__(256, 1) void conv_wgrad_tr64(ConvWgrad g) {
+  if (g.ctl->poison) return;
+  constexpr int W = 16 * W16, LPS = 4 / W16, NL = 32 / W16;   // lines per step, lines in the ring
+  constexpr int GB = W * 128, LSLOT = (2 * W + 2) * 128;      // cotangent line, then the input line with its zero rows
+  constexpr int NG = NL / LPS;                                 // groups in the ring (8)
+  constexpr int AHEAD = NG - 1;                                // groups requested ahead of the step being multiplied
+  constexpr int D = (LPS == 1) ? 2 : 1;                        // step j needs the groups up to j + D
+  typedef __attribute__((address_space(3))) uint8_t lds_u8;
+  typedef short v4s __attribute__((ext_vector_type(4)));
+  extern __shared__ __attribute__((aligned(16))) uint8_t cwt64_smem[];
+  lds_u8* ring = (lds_u8*)cwt64_smem;
+  const uint32_t ring_base = (uint32_t)(uintptr_t)ring;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int64_t total_lines = g.rows / W;
+  const int64_t c0 = (int64_t)blockIdx.z * (g.rows_per_split / W);
+  int64_t c1 = c0 + g.rows_per_split / W;
+  if (c1 > total_lines) c1 = total_lines;
+  if (c0 >= c1) return;
+  const int nl = (int)(c1 - c0);
+  const int nsteps = (nl + LPS - 1) / LPS;
+  const int lines_per_stage = (int)(g.R / W);
+
+  // the zero rows before and after the input line of every ring slot (never overwritten)
+  for (int i = tid; i < NL * 16; i += 256) {
+    const int sl = i >> 4, which = (i >> 3) & 1, piece = i & 7;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    *reinterpret_cast<__attribute__((address_space(3))) u32x4*>(ring + sl * LSLOT + GB + (which ? (W + 1) * 128 : 0) + piece * 16) =
+        u32x4{0u, 0u, 0u, 0u};
+  }
+  __syncthreads();
+
+  // ---- loader role.  A group = LPS loaded lines = 64 pixels of cotangent + 64 of input = 16 wave-loads of 8 rows; this
+  // wavefront's four: u = 4 wave + i -> (operand u / 8, pixels 8 (u % 8) .. of the group).  Loaded line lam is line
+  // c0 - 1 + lam (clamped into the tensor: the two halo lines are only used where they are inside the image).
+  const int lr = lane >> 3, sp = lane & 7;
+  int ld_line[4], ld_px[4], ld_dst[4];
+  const uint16_t* ld_src[4];
+  int ld_ldx[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int u = 4 * wave + i, op = u >> 3, px = 8 * (u & 7) + lr;   // pixel within the group
+    ld_line[i] = px / W;
+    ld_px[i] = px % W;
+    const int prow = op ? ld_px[i] + 1 : ld_px[i];                    // LDS row of the lane's pixel
+    const int piece = sp ^ (((prow >> 1) & 1) << 2);
+    ld_src[i] = (op ? g.B : g.A) + piece * 8;
+    ld_ldx[i] = op ? g.ldb : g.lda;
+    ld_dst[i] = (op ? GB + 128 : 0) + (8 * (u & 7) % W) * 128;        // (+ the line's slot)
+  }
+  int ld_group = 0;
+  auto issue = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int lam = ld_group * LPS + ld_line[i];
+      int64_t line = c0 - 1 + lam;
+      line = line < 0 ? 0 : (line >= total_lines ? total_lines - 1 : line);
+      const int slot = lam % NL;
+      __builtin_amdgcn_global_load_lds(ld_src[i] + ((size_t)line * W + ld_px[i]) * ld_ldx[i],
+                                       (__attribute__((address_space(3))) void*)(ring + slot * LSLOT + ld_dst[i]), 16, 0, 0);
+    }
+    ++ld_group;
+  };
+
+  // ---- consumer role.  Lane = 32 kg + 16 g2 + s, s = 4 sr + sc: see conv_wgrad_tr.
+  const int kg = lane >> 5, g2 = (lane >> 4) & 1, sfrag = lane & 15, sr = sfrag >> 2, sc = sfrag & 3;
+  const int incol = 32 * g2 + 8 * sc;
+  const int goff = (8 * kg + sr) * 128 + ((wm ^ ((sr >> 1) & 1)) * 64) + incol;
+  int xcol[3], xrow[3];
+#pragma unroll
+  for (int d = 0; d < 3; ++d) {
+    xcol[d] = GB + ((wn ^ (((sr + d) >> 1) & 1)) * 64) + incol;   // in the zero row before the line
+    xrow[d] = (8 * kg + sr + d) * 128;
+  }
+  auto tr1 = [&](uint32_t p, v4s& v) { asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v) : "v"(p)); };
+  // fragments of a k-step: 0 = cotangent, 1 + 3 dyv + dxv = input of tap (dyv, dxv); two reads each
+  // what a k-step needs to know of its image line: LDS positions of the cotangent line and of the three input lines,
+  // which of those are inside the image, the on / off word of this lane's column of the sums block
+  struct LineCtx {
+    uint32_t gline, xline[3];
+    int vy[3];
+    uint32_t mbase;
+  };
+  auto read_frag = [&](auto which, const LineCtx& c, int ks, v4s (&r)[20]) {
+    constexpr int i = decltype(which)::value;
+    if constexpr (i == 0) {
+      const uint32_t p = c.gline + goff + ks * 16 * 128;
+      tr1(p, r[0]);
+      tr1(p + 512, r[1]);
+    } else {
+      constexpr int dyv = (i - 1) / 3, dxv = (i - 1) % 3;
+      // (input line off the image: this lane's columns of the zero row, for every k)
+      const uint32_t p = c.xline[dyv] + xcol[dxv] + c.vy[dyv] * (xrow[dxv] + ks * 16 * 128);
+      tr1(p, r[2 * i]);
+      tr1(p + c.vy[dyv] * 512, r[2 * i + 1]);
+    }
+  };
+  auto read_done = [&](v4s (&r)[20]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]), "+v"(r[8]),
+                   "+v"(r[9]));
+    asm volatile("" : "+v"(r[10]), "+v"(r[11]), "+v"(r[12]), "+v"(r[13]), "+v"(r[14]), "+v"(r[15]), "+v"(r[16]), "+v"(r[17]),
+                      "+v"(r[18]), "+v"(r[19]));
+  };
+  auto frag = [&](const v4s (&r)[20], int i) -> u16x8 {
+    return __builtin_bit_cast(u16x8, __builtin_shufflevector(r[2 * i], r[2 * i + 1], 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  f32x16 acc[9], am;
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[t][q] = 0.f;
+#pragma unroll
+  for (int q = 0; q < 16; ++q) am[q] = 0.f;
+  // sums: column n = lane % 32 of the extra block is tap n (n < 9) or the plain sum (n = 9)
+  const bool sums = g.want_sums && wn == 0;
+  const int ncol = lane & 31;
+  const uint32_t one2 = (uint32_t)Low<T>::from_f32(1.f) * 0x10001u;
+  const int vsel = ncol < 9 ? ncol / 3 : (ncol == 9 ? 3 : 4);           // bit of the validity word that switches the column on
+  const bool edge_l = ncol < 9 && ncol % 3 == 0 && kg == 0;             // dx = -1: pixel 0 of the line is off
+  const bool edge_r = ncol < 9 && ncol % 3 == 2 && kg == 1;             // dx = +1: pixel W - 1 of the line is off
+  float s_tau[16], s_one[16], s_c[16];   // tau-, un- and c_j-weighted sums of this lane's column
+#pragma unroll
+  for (int q = 0; q < 16; ++q) s_tau[q] = s_one[q] = s_c[q] = 0.f;
+  // (image row and stage of the line being multiplied are stepped from line to line: no division in the loop)
+  int cur_stage = (int)(c0 / lines_per_stage);
+  int stage_end_m = (int)((int64_t)(cur_stage + 1) * lines_per_stage - c0);   // first line (chunk-relative) of the next stage
+
+  auto flush_sums = [&]() {
+    float tau = 0.f, cj = 0.f;
+#pragma unroll
+    for (int q = 0; q < kMaxStages; ++q) {
+      tau = (q == cur_stage) ? g.taus[q] : tau;
+      cj = (q == cur_stage) ? g.cs[q] : cj;
+    }
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      s_tau[q] = fmaf(tau, am[q], s_tau[q]);
+      s_one[q] += am[q];
+      if (TS) s_c[q] = fmaf(cj, am[q], s_c[q]);
+      am[q] = 0.f;
+    }
+  };
+  auto wait_vm = [&](auto cnt) {
+    constexpr int c = decltype(cnt)::value;
+    static_assert(c < 64, "vmcnt field");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (c & 15) | ((c >> 4) << 14));  // vmcnt only
+  };
+
+  // (image row and stage are stepped from line to line: no division in the loop)
+  int y_ctx = (int)(c0 % g.H);   // image row of the next line that gets a context (lines are taken in order)
+  auto make_ctx = [&](int m) -> LineCtx {
+    LineCtx c;
+    const int lam = m + 1;      // cotangent line c0 + m = loaded line m + 1
+    c.gline = ring_base + (lam % NL) * LSLOT;
+    c.xline[0] = ring_base + ((lam - 1) % NL) * LSLOT;
+    c.xline[1] = c.gline;
+    c.xline[2] = ring_base + ((lam + 1) % NL) * LSLOT;
+    c.vy[0] = y_ctx > 0 ? 1 : 0;
+    c.vy[1] = 1;
+    c.vy[2] = y_ctx < g.H - 1 ? 1 : 0;
+    const uint32_t vword = (uint32_t)(c.vy[0] | 2 | (c.vy[2] << 2) | 8);
+    c.mbase = ((vword >> vsel) & 1u) ? one2 : 0u;
+    y_ctx = (y_ctx + 1 == g.H) ? 0 : y_ctx + 1;
+    return c;
+  };
+  auto read_all = [&](const LineCtx& c, int ks, v4s (&r)[20]) {
+    read_frag(std::integral_constant<int, 0>{}, c, ks, r);
+    read_frag(std::integral_constant<int, 1>{}, c, ks, r);
+    read_frag(std::integral_constant<int, 2>{}, c, ks, r);
+    read_frag(std::integral_constant<int, 3>{}, c, ks, r);
+    read_frag(std::integral_constant<int, 4>{}, c, ks, r);
+    read_frag(std::integral_constant<int, 5>{}, c, ks, r);
+    read_frag(std::integral_constant<int, 6>{}, c, ks, r);
+    read_frag(std::integral_constant<int, 7>{}, c, ks, r);
+    read_frag(std::integral_constant<int, 8>{}, c, ks, r);
+    read_frag(std::integral_constant<int, 9>{}, c, ks, r);
+  };
+
+  // Pipeline: step j multiplies cotangent lines [LPS j, LPS (j + 1)) of the chunk = loaded lines + 1, four k-steps, and
+  // needs the loaded groups up to j + D.  With one wavefront per SIMD nothing runs beside a wait or a block of reads, so:
+  // the fragments of k-step i + 1 are read between the matrix instructions of k-step i (also from line to line and from
+  // step to step), and the wait for step j + 1's groups, the barrier and the request of group j + AHEAD sit behind the
+  // first five matrix instructions of step j's last k-step.  Group j + AHEAD takes the ring position of group j - 1,
+  // whose lines step j - 1 was the last to read.
+#pragma unroll
+  for (int u = 0; u < AHEAD; ++u) issue();
+  wait_vm(std::integral_constant<int, (AHEAD - 2 - D) * 4>{});
+  __builtin_amdgcn_s_barrier();
+  v4s raw[2][20];
+  LineCtx cur = make_ctx(0);
+  read_all(cur, 0, raw[0]);
+  for (int j = 0; j < nsteps; ++j) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int li = i / W16, ks = i % W16;
+      const int m = j * LPS + li;
+      const bool live = m < nl;            // (uniform: a chunk's last step may be cut short)
+      // the k-step after this one
+      const int nks = (i + 1) % W16;
+      LineCtx nxt = cur;
+      if (nks == 0) nxt = make_ctx(i == 3 ? (j + 1) * LPS : m + 1);
+      v4s (&rc)[20] = raw[i & 1];
+      v4s (&rn)[20] = raw[(i + 1) & 1];
+      read_done(rc);
+      if (ks == 0 && sums && m >= stage_end_m && live) {
+        flush_sums();
+        ++cur_stage;
+        stage_end_m += lines_per_stage;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // (a k-step past the chunk's end multiplies zeros: no branch around the accumulators)
+      u16x8 fa = frag(rc, 0);
+      if (!live) fa = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      u16x8 fb[9];
+#pragma unroll
+      for (int t = 0; t < 9; ++t) fb[t] = frag(rc, 1 + t);
+      auto mm = [&](auto which) {
+        constexpr int t = decltype(which)::value;
+        acc[t] = Low<T>::mfma32(fa, fb[t], acc[t]);
+      };
+      auto rd = [&](auto which) { read_frag(which, nxt, nks, rn); };
+      typedef std::integral_constant<int, 0> I0; typedef std::integral_constant<int, 1> I1;
+      typedef std::integral_constant<int, 2> I2; typedef std::integral_constant<int, 3> I3;
+      typedef std::integral_constant<int, 4> I4; typedef std::integral_constant<int, 5> I5;
+      typedef std::integral_constant<int, 6> I6; typedef std::integral_constant<int, 7> I7;
+      typedef std::integral_constant<int, 8> I8; typedef std::integral_constant<int, 9> I9;
+#define CWT64_FENCE __builtin_amdgcn_sched_barrier(0)
+      if (i < 3) {
+        // every matrix instruction takes the reads of a fragment of the next k-step with it
+        mm(I0{}); rd(I0{}); rd(I1{}); CWT64_FENCE;
+        mm(I1{}); rd(I2{}); CWT64_FENCE;
+        mm(I2{}); rd(I3{}); CWT64_FENCE;
+        mm(I3{}); rd(I4{}); CWT64_FENCE;
+        mm(I4{}); rd(I5{}); CWT64_FENCE;
+        mm(I5{}); rd(I6{}); CWT64_FENCE;
+        mm(I6{}); rd(I7{}); CWT64_FENCE;
+        mm(I7{}); rd(I8{}); CWT64_FENCE;
+        mm(I8{}); rd(I9{}); CWT64_FENCE;
+      } else {
+        mm(I0{}); mm(I1{}); mm(I2{}); mm(I3{}); mm(I4{});
+        CWT64_FENCE;
+        wait_vm(std::integral_constant<int, (AHEAD - 2 - D) * 4>{});
+        __builtin_amdgcn_s_barrier();   // everyone's part of step j + 1's groups is in LDS; everyone is done with step j - 1
+        CWT64_FENCE;
+        issue();
+        CWT64_FENCE;
+        mm(I5{}); rd(I0{}); rd(I1{}); rd(I2{}); CWT64_FENCE;
+        mm(I6{}); rd(I3{}); rd(I4{}); rd(I5{}); CWT64_FENCE;
+        mm(I7{}); rd(I6{}); rd(I7{}); CWT64_FENCE;
+        mm(I8{}); rd(I8{}); rd(I9{}); CWT64_FENCE;
+      }
+#undef CWT64_FENCE
+      if (sums) {
+        // this lane's 8 pixels of the k-step against its column's tap: all on, except the line's first / last pixel
+        uint32_t mk[4] = {cur.mbase, cur.mbase, cur.mbase, cur.mbase};
+        if (edge_l && ks == 0) mk[0] &= 0xffff0000u;
+        if (edge_r && ks == W16 - 1) mk[3] &= 0x0000ffffu;
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        am = Low<T>::mfma32(fa, __builtin_bit_cast(u16x8, u32x4{mk[0], mk[1], mk[2], mk[3]}), am);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      cur = nxt;
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the requests past the chunk's end
+
+  const float scale = g.h / g.ctl->S_step;
+  float* slotf = g.part + (size_t)blockIdx.z * CW_SLOT;
+  if (g.want_sums) {
+    float p0 = 0.f, p1 = 0.f;
+    if (sums) {
+      flush_sums();
+      // column n of block wm: rows (co) 32 wm + 8 (q / 4) + 4 (lane / 32) + q % 4; tail entry 0 = bias, 1 + t = tap t
+      if (ncol <= 9) {
+        const int e = ncol == 9 ? 0 : 1 + ncol;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const int co = 32 * wm + 8 * (q >> 2) + 4 * kg + (q & 3);
+          float* d = slotf + 9 * 4096 + co * 16 + e;
+          *d = fmaf(scale, ncol == 9 ? s_one[q] : s_tau[q], *d);
+          if (TS && ncol < 9 && co < g.Na) {
+            const float wv = g.wt[ncol * g.ldwt + co];
+            p0 = fmaf(wv, s_one[q] - s_c[q], p0);
+            p1 = fmaf(wv, s_c[q], p1);
+          }
+        }
+      }
+    }
+    if (TS) block_sum2(scale * p0, scale * p1, g.tpart);
+  }
+  // plain read-modify-write in conv_wgrad's layout: float4 number ((tap * 4 + q / 4) * 256 + thread) holds rows (co)
+  // 32 wm + 8 (q / 4) + 4 (lane / 32) + 0..3 of column (ci) 32 wn + lane % 32
+  float4* slot = reinterpret_cast<float4*>(slotf);
+#pragma unroll
+  for (int t0 = 0; t0 < 9; t0 += 3) {
+    float4 old[3][4];
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) old[t][q4] = slot[((t0 + t) * 4 + q4) * 256 + tid];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        float4 v = old[t][q4];
+        v.x = fmaf(scale, acc[t0 + t][q4 * 4 + 0], v.x);
+        v.y = fmaf(scale, acc[t0 + t][q4 * 4 + 1], v.y);
+        v.z = fmaf(scale, acc[t0 + t][q4 * 4 + 2], v.z);
+        v.w = fmaf(scale, acc[t0 + t][q4 * 4 + 3], v.w);
+        slot[((t0 + t) * 4 + q4) * 256 + tid] = v;
+      }
+  }
+}
+constexpr size_t conv_wgrad_tr64_lds_bytes(int W) { return (size_t)(512 / W) * (2 * W + 2) * 128; }
+
 }  // namespace rampde

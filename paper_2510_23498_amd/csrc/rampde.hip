@@ -210,6 +210,7 @@ struct Plan;
 // 64, and whole 128-row k-steps within a stage
 static bool conv_wgrad_applies(const Plan& p);
 static bool conv_wgrad_tr_applies(const Plan& p);
+static bool conv_wgrad_tr64_applies(const Plan& p, const Layer& y);
 // compute units of the current device (256 on MI355X; also the answer when no device is visible,
 // e.g. a workspace query on a host without a GPU)
 static int device_compute_units() {
@@ -479,6 +480,10 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
 }
 
 static bool conv_wgrad_applies(const Plan& p) { return p.conv && !p.fused && p.Wd % 8 == 0 && p.Wd <= 64 && p.R % CW_KS == 0; }
+// (64 x 64 channels, 16 / 32 / 64 pixels per line: conv_wgrad's drop-in built on transposing LDS reads)
+static bool conv_wgrad_tr64_applies(const Plan& p, const Layer& y) {
+  return conv_wgrad_applies(p) && !p.cw_blocks && y.Npad == 64 && y.Kpad == 64 && (p.Wd == 16 || p.Wd == 32 || p.Wd == 64);
+}
 // (the kernel built on transposing LDS reads: the parabolic block's one layer, channel counts in multiples of 128)
 static bool conv_wgrad_tr_applies(const Plan& p) {
   return conv_wgrad_applies(p) && p.parabolic && !p.cw_blocks &&
@@ -1158,7 +1163,20 @@ struct Runner {
         TimeScope ts(RAMPDE_K_WGRAD_GEMM, 2.0 * rows * (double)y.Npad * y.Kpad * 9, st);
         const size_t lds = conv_wgrad_lds_bytes(p.Wd);
         const bool tsum = c.tpart && c.wt;
-        if (p.Wd <= 32) {
+        if (conv_wgrad_tr64_applies(p, y)) {
+          // 64 x 64 channels: the kernel built on transposing LDS reads (same private copies)
+          const size_t l64 = conv_wgrad_tr64_lds_bytes(p.Wd);
+          if (p.Wd == 16) {
+            if (tsum) conv_wgrad_tr64<T, true, 1><<<cgrid, 256, l64, st>>>(c);
+            else conv_wgrad_tr64<T, false, 1><<<cgrid, 256, l64, st>>>(c);
+          } else if (p.Wd == 32) {
+            if (tsum) conv_wgrad_tr64<T, true, 2><<<cgrid, 256, l64, st>>>(c);
+            else conv_wgrad_tr64<T, false, 2><<<cgrid, 256, l64, st>>>(c);
+          } else {
+            if (tsum) conv_wgrad_tr64<T, true, 4><<<cgrid, 256, l64, st>>>(c);
+            else conv_wgrad_tr64<T, false, 4><<<cgrid, 256, l64, st>>>(c);
+          }
+        } else if (p.Wd <= 32) {
           if (tsum) conv_wgrad<T, true, CW_MAXI_LO><<<cgrid, 256, lds, st>>>(c);
           else conv_wgrad<T, false, CW_MAXI_LO><<<cgrid, 256, lds, st>>>(c);
         } else {
@@ -1316,6 +1334,11 @@ struct Runner {
                             reinterpret_cast<const void*>(&conv_wgrad_tr<T, 4>)})
         HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_wgrad_tr_lds_bytes(64)));
     } else if (conv_wgrad_applies(p)) {
+      if (conv_wgrad_tr64_applies(p, p.layers[0]))
+        for (const void* f : {reinterpret_cast<const void*>(&conv_wgrad_tr64<T, false, 1>), reinterpret_cast<const void*>(&conv_wgrad_tr64<T, true, 1>),
+                              reinterpret_cast<const void*>(&conv_wgrad_tr64<T, false, 2>), reinterpret_cast<const void*>(&conv_wgrad_tr64<T, true, 2>),
+                              reinterpret_cast<const void*>(&conv_wgrad_tr64<T, false, 4>), reinterpret_cast<const void*>(&conv_wgrad_tr64<T, true, 4>)})
+          HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)conv_wgrad_tr64_lds_bytes(16)));
       const int lds = (int)conv_wgrad_lds_bytes(p.Wd);
       HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wgrad<T, false, CW_MAXI_LO>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));

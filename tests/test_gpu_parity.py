@@ -199,6 +199,15 @@ def test_conv_weight_gradient_all_taps_kernel(C, H, W, B):
     _both(cfg, bias_std=0.1)
 
 
+@pytest.mark.parametrize("H,W,B,wgrad_tile", [(16, 16, 3, 0), (8, 64, 2, 0), (20, 32, 3, 0), (32, 32, 2, 64)])
+def test_conv_weight_gradient_64_channels_transposing_reads(H, W, B, wgrad_tile):
+    # 64 channels and 16 / 32 / 64 pixels per line: the weight gradient (with the bias and time-channel sums) takes
+    # the kernel built on transposing LDS reads -- K-chunks that start and end inside images (20 lines per image),
+    # stage boundaries inside a chunk; policy.wgrad_tile = 64 keeps the kernel that transposes in registers
+    cfg = wl.CONFIGS["cfg4"].with_(name=f"convtr{H}x{W}", B=B, N=2, C=64, H=H, W=W, tableau="kutta3")
+    _both(cfg, bias_std=0.1, wgrad_tile=wgrad_tile)
+
+
 def test_conv_small_odd_geometry():
     cfg = wl.CONFIGS["cfg4"].with_(name="convodd", B=2, N=2, C=5, H=7, W=6, tableau="kutta3")
     _both(cfg, bias_std=0.1)
@@ -267,7 +276,8 @@ def test_time_grid_gradient_small_mlp_all_tableaux(tab, flags):
     _time_grid_case(cfg, flags=flags)
 
 
-@pytest.mark.parametrize("C,H,W,B,tab", [(64, 32, 32, 2, "rk4"), (5, 7, 6, 2, "kutta3"), (70, 4, 8, 4, "heun"),
+@pytest.mark.parametrize("C,H,W,B,tab", [(64, 32, 32, 2, "rk4"), (64, 16, 16, 3, "heun"), (64, 4, 64, 2, "kutta3"),
+                                          (5, 7, 6, 2, "kutta3"), (70, 4, 8, 4, "heun"),
                                           (70, 4, 8, 3, "heun"), (8, 16, 24, 1, "kutta3")])
 def test_time_grid_gradient_conv(C, H, W, B, tab):
     # both convolutions carry a time channel; all-taps weight-gradient kernel and the generic one (W = 6)
