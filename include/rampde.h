@@ -233,7 +233,8 @@ int rampde_odeint_bwd(const rampde_velocity *vel, const float *theta, int64_t B,
  *   as the state and parameter cotangents, summed in fp32 and not rounded to 16 bits,
  *   t'_i += (h/S)(dt - dh) - Phi^T a_{i+1},   t'_{i+1} += (h/S) dh + Phi^T a_{i+1},
  * Phi = sum_j b_j k_j from the low-precision slopes, a_{i+1} the fp32 adjoint before the step's
- * update.  Sums over the batch use fp32 atomics: the result is reproducible to rounding only. */
+ * update.  Sums over the batch: every workgroup writes a slot of its own and a one-workgroup kernel folds a launch's
+ * slots in a fixed order (no floating-point atomics): two calls on the same inputs give the same bits. */
 int rampde_odeint_bwd_tgrid(const rampde_velocity *vel, const float *theta, int64_t B,
                             const double *tgrid, int N, const rampde_tableau *tab,
                             const rampde_policy *pol, const void *ckpt, const float *grad_yN,

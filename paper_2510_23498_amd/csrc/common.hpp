@@ -119,8 +119,9 @@ __device__ inline void block_amax(unsigned bits, unsigned* dst) {
   }
 }
 
-// Block-wide sums of two per-thread values, then one atomicAdd each per workgroup (dst[0], dst[1]).
-// (Must be reached by every thread of the workgroup.)
+// Block-wide sums of two per-thread values, stored to dst[0], dst[1]: the workgroup's slot of a launch-wide table that
+// a one-workgroup kernel folds in a fixed order afterwards (fold_time_slots), so that the result does not depend on
+// the order in which workgroups finish.  (Must be reached by every thread of the workgroup.)
 __device__ inline void block_sum2(float a, float b, float* dst) {
   for (int o = 32; o > 0; o >>= 1) {
     a += __shfl_xor(a, o);
@@ -141,8 +142,8 @@ __device__ inline void block_sum2(float a, float b, float* dst) {
       s0 += wsum[i][0];
       s1 += wsum[i][1];
     }
-    unsafeAtomicAdd(dst, s0);
-    unsafeAtomicAdd(dst + 1, s1);
+    dst[0] = s0;
+    dst[1] = s1;
   }
 }
 

@@ -666,7 +666,7 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_tr64(ConvWgrad g) {
         }
       }
     }
-    if (TS) block_sum2(scale * p0, scale * p1, g.tpart);
+    if (TS) block_sum2(scale * p0, scale * p1, g.tpart + 2 * (size_t)blockIdx.z);
   }
   // plain read-modify-write in conv_wgrad's layout: float4 number ((tap * 4 + q / 4) * 256 + thread) holds rows (co)
   // 32 wm + 8 (q / 4) + 4 (lane / 32) + 0..3 of column (ci) 32 wn + lane % 32

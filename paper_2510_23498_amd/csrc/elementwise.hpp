@@ -386,9 +386,10 @@ __global__ __launch_bounds__(256) void column_sums(const uint16_t* __restrict__ 
         p0 += __shfl_xor(p0, o);
         p1 += __shfl_xor(p1, o);
       }
-      if (tx == 0) {
-        unsafeAtomicAdd(&tpart[0], scale * p0);
-        unsafeAtomicAdd(&tpart[1], scale * p1);
+      if (tx == 0) {  // (this workgroup's slot of the launch's table: see fold_time_slots)
+        float* slot = tpart + 2 * ((size_t)blockIdx.y * gridDim.x + blockIdx.x);
+        slot[0] = scale * p0;
+        slot[1] = scale * p1;
       }
     }
   }
@@ -431,7 +432,38 @@ __global__ __launch_bounds__(256) void time_grid_terms(const float* __restrict__
     }
   }
   const float hs = h / ctl->S_step;
-  block_sum2(-hs * dz - pa, fmaf(hs, dz, pa), tpart);
+  block_sum2(-hs * dz - pa, fmaf(hs, dz, pa), tpart + 2 * (size_t)blockIdx.x);
+}
+
+// Per-workgroup slots of the time-grid sums -> the per-step sums, in a fixed order: workgroup b of this kernel takes the
+// slots [b * per_step, (b + 1) * per_step) (pairs) and adds their sum to dst[2 (step0 - b)], dst[2 (step0 - b) + 1];
+// thread t sums the slots t, t + 256, ... and the 256 partial sums are added up in order.  The slots are cleared for
+// the next launch (the kernels that fill them write only the slots of the workgroups that have something to add).
+__global__ __launch_bounds__(256) void fold_time_slots(float* __restrict__ slots, int per_step, float* __restrict__ dst, int step0,
+                                                       const Ctl* ctl) {
+  if (ctl->poison) return;
+  __shared__ float part[256][2];
+  float* base = slots + 2 * (size_t)blockIdx.x * per_step;
+  float s0 = 0.f, s1 = 0.f;
+  for (int i = threadIdx.x; i < per_step; i += 256) {
+    s0 += base[2 * i];
+    s1 += base[2 * i + 1];
+    base[2 * i] = 0.f;
+    base[2 * i + 1] = 0.f;
+  }
+  part[threadIdx.x][0] = s0;
+  part[threadIdx.x][1] = s1;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float a = 0.f, b = 0.f;
+    for (int i = 0; i < 256; ++i) {
+      a += part[i][0];
+      b += part[i][1];
+    }
+    float* d = dst + 2 * (size_t)(step0 - (int)blockIdx.x);
+    d[0] += a;
+    d[1] += b;
+  }
 }
 
 // NONE_SAFE outcome: overflow => gradients are +inf

@@ -121,6 +121,8 @@ struct FusedArgs {
   int detect, dynamic, raw_norm, skip_recompute;
   // time-grid gradient (paper Sec. 3, update lines of t'): null, or [N][2] fp32 per-step sums
   //   tpart[i][0] = (h/S)(dt - dh) - Phi^T a_{i+1},   tpart[i][1] = (h/S) dh + Phi^T a_{i+1}
+  // (here: the launch's table of per-workgroup slots, [step of the launch][workgroup][2], folded into the per-step
+  // sums by fold_time_slots after the launch)
   // added to by every workgroup; folded into dL/dt once the steps are accepted
   float* tpart;
 };
@@ -1026,7 +1028,7 @@ __global__ __launch_bounds__(64 * NW) void mlp_adjoint_step(FusedArgs g) {
     // ---- a <- a + (h / S) sum_j zbar_j (+ running-cost cotangent), fp32; max |a| after the last step
     bits = 0;
     const float hs = h / S;
-    if (want_t) block_sum2(fmaf(hs, t_dt - t_dh, -t_phia), fmaf(hs, t_dh, t_phia), g.tpart + 2 * (size_t)step);
+    if (want_t) block_sum2(fmaf(hs, t_dt - t_dh, -t_phia), fmaf(hs, t_dh, t_phia), g.tpart + 2 * ((size_t)it * gridDim.x + blockIdx.x));
 #pragma unroll
     for (int nt = 0; nt < NTS; ++nt)
 #pragma unroll

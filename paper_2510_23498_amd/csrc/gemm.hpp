@@ -384,7 +384,7 @@ struct ConvWgrad {
   // taubar_j = sum_{k, co, tap} delta[k][co] * wt[tap][co] * [tap inside]; the step's sums get
   //   tpart[0] += scale * sum_j (1 - c_j) taubar_j,   tpart[1] += scale * sum_j c_j taubar_j
   const float* wt; int ldwt;    // rounded time-channel weights [9][ldwt], or null
-  float* tpart;                 // or null
+  float* tpart;                 // or null: the launch's table of per-workgroup slots (fold_time_slots)
   float cs[kMaxStages];         // c_j
 };
 
@@ -666,7 +666,7 @@ __global__ __launch_bounds__(256) void conv_wgrad(ConvWgrad g) {
           p1 = fmaf(wv, sum_c[t], p1);
         }
       }
-      block_sum2(scale * p0, scale * p1, g.tpart);
+      block_sum2(scale * p0, scale * p1, g.tpart + 2 * (((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x));
     }
   }
   // plain read-modify-write: the slot belongs to this workgroup for the whole backward pass.  Its

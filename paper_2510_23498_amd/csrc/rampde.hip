@@ -101,6 +101,7 @@ struct Plan {
   size_t lds_bytes = 0;
   size_t steptab = 0, a_alt = 0, bsum = 0;
   size_t tpart = 0;                 // [N][2] fp32 per-step sums of the time-grid gradient
+  size_t tslots = 0;                // per-workgroup slots of the launch that is adding to them (kTimeSlotPairs pairs)
   size_t amax_slots = 0;            // [4096] per-workgroup maxima of |a| (per-layer path)
   int nparam = 0, wt_off = 0;
   bool k_in_lds = false;
@@ -209,6 +210,10 @@ struct Plan;
 // the all-taps convolution weight-gradient kernel: image lines of a multiple of 8 pixels, at most
 // 64, and whole 128-row k-steps within a stage
 static bool conv_wgrad_applies(const Plan& p);
+// Time-grid gradient: every workgroup that adds to a step's sums writes a slot of its own, and a one-workgroup kernel
+// folds the launch's slots in a fixed order (no floating-point atomics: the result does not depend on the order in
+// which workgroups finish).  Slots of one launch: workgroups x steps of the launch.
+constexpr size_t kTimeSlotPairs = size_t(1) << 19;
 static bool conv_wgrad_tr_applies(const Plan& p);
 static bool conv_wgrad_tr64_applies(const Plan& p, const Layer& y);
 // compute units of the current device (256 on MI355X; also the answer when no device is visible,
@@ -473,6 +478,7 @@ static Plan make_plan(const rampde_velocity* vel, int64_t B, int N, const rampde
     }
   }
   if (is_backward) p.tpart = take(sizeof(float) * 2 * (size_t)N);
+  if (is_backward) p.tslots = take(sizeof(float) * 2 * (size_t)kTimeSlotPairs);
   if (is_backward) p.amax_slots = take(sizeof(unsigned) * 4096);  // per-workgroup maxima of the streaming adjoint update
   p.total = off;
   p.ok = true;
@@ -959,8 +965,19 @@ struct Runner {
   }
 
   int adjoint_step_fused(const FusedArgs& a) {
-    TimeScope ts(RAMPDE_K_FUSED_ADJOINT_STEP, step_flops() * p.s * (a.skip_recompute ? 1.0 : 2.0) * a.nsteps, st);
-    return launch_fused(true, a);
+    int rc;
+    {
+      TimeScope ts(RAMPDE_K_FUSED_ADJOINT_STEP, step_flops() * p.s * (a.skip_recompute ? 1.0 : 2.0) * a.nsteps, st);
+      rc = launch_fused(true, a);
+    }
+    if (rc) return rc;
+    if (a.tpart) {
+      // the launch's per-workgroup slots of the time-grid sums -> the per-step sums (steps a.step, a.step - 1, ...)
+      const int grid = blocks_for(p.R, 16 * p.MT);
+      if ((size_t)grid * a.nsteps > kTimeSlotPairs) return RAMPDE_EUNSUPPORTED;
+      fold_time_slots<<<a.nsteps, 256, 0, st>>>(a.tpart, grid, f32(p.tpart), a.step, ctl);
+    }
+    return RAMPDE_OK;
   }
 
   int forward(const float* theta, const float* y0, const double* tgrid, int N, const rampde_tableau* tab,
@@ -1080,8 +1097,10 @@ struct Runner {
         bw.v[j] = (float)tab->b[j];
         for (int l = 0; l < j; ++l) am.v[j * kMaxStages + l] = (float)tab->A[j * s + l];
       }
-      time_grid_terms<T><<<stream_blocks(p.n, 1024), 256, 0, st>>>(a, p.d, u16(p.K), u16(p.ZBAR), p.stage_stride, s, bw,
-                                                                   am, h, p.dpad, p.R, ctl, tpart_i);
+      const int tg_blocks = stream_blocks(p.n, 1024);
+      time_grid_terms<T><<<tg_blocks, 256, 0, st>>>(a, p.d, u16(p.K), u16(p.ZBAR), p.stage_stride, s, bw,
+                                                    am, h, p.dpad, p.R, ctl, f32(p.tslots));
+      fold_time_slots<<<1, 256, 0, st>>>(f32(p.tslots), tg_blocks, tpart_i, 0, ctl);
     }
     // (the fp32 update of a comes before the parameter gradients, which do not read it: the stage
     // cotangents it streams are then still in the last-level cache)
@@ -1158,7 +1177,7 @@ struct Runner {
         }
         c.wt = y.has_time ? f32(y.wt_f) : nullptr;
         c.ldwt = y.Npad;
-        c.tpart = tpart_i;
+        c.tpart = tpart_i ? f32(p.tslots) : nullptr;
         dim3 cgrid(y.Npad / 64, y.Kpad / 64, y.cw_splits);
         TimeScope ts(RAMPDE_K_WGRAD_GEMM, 2.0 * rows * (double)y.Npad * y.Kpad * 9, st);
         const size_t lds = conv_wgrad_lds_bytes(p.Wd);
@@ -1183,6 +1202,7 @@ struct Runner {
           if (tsum) conv_wgrad<T, true, CW_MAXI_HI><<<cgrid, 256, lds, st>>>(c);
           else conv_wgrad<T, false, CW_MAXI_HI><<<cgrid, 256, lds, st>>>(c);
         }
+        if (tsum) fold_time_slots<<<1, 256, 0, st>>>(f32(p.tslots), (int)(cgrid.x * cgrid.y * cgrid.z), tpart_i, 0, ctl);
         continue;  // (bias and time-channel gradients included)
       } else {
         // split the contraction so that about 1024 workgroups are in flight
@@ -1220,12 +1240,14 @@ struct Runner {
       dim3 cgrid(y.Npad / 64, blocks_for(rows, rpb));
       float* gb = grad_theta + y.theta_b;
       float* gwt = y.has_time ? grad_theta + y.theta_w + (p.conv ? (size_t)y.in * 9 : (size_t)y.in) : nullptr;
+      float* tsl = tpart_i ? f32(p.tslots) : nullptr;
       if (p.conv)
         column_sums<T, true><<<cgrid, 256, 0, st>>>(g.A, y.Npad, p.R, s, y.out, taus, h, gb, gwt, y.in_full * 9, p.H,
-                                                    p.Wd, rpb, ctl, y.has_time ? f32(y.wt_f) : nullptr, cs, tpart_i);
+                                                    p.Wd, rpb, ctl, y.has_time ? f32(y.wt_f) : nullptr, cs, tsl);
       else
         column_sums<T, false><<<cgrid, 256, 0, st>>>(g.A, y.Npad, p.R, s, y.out, taus, h, gb, gwt, y.in_full, p.H,
-                                                     p.Wd, rpb, ctl, y.has_time ? f32(y.wt_f) : nullptr, cs, tpart_i);
+                                                     p.Wd, rpb, ctl, y.has_time ? f32(y.wt_f) : nullptr, cs, tsl);
+      if (tsl && y.has_time) fold_time_slots<<<1, 256, 0, st>>>(tsl, (int)(cgrid.x * cgrid.y), tpart_i, 0, ctl);
     }
     if (p.cnf) {
       // the trace row's share of dW1 and dW2: s_h = sum over stages and rows of kbar_l (1 - a_h^2)
@@ -1322,6 +1344,7 @@ struct Runner {
                float* grad_y0, float* grad_theta, float* grad_t, float* scale_hist, rampde_stats* stats) {
     const int dynamic = scaling == RAMPDE_SCALE_DYNAMIC;
     if (grad_t) fill_zero_u32<<<1, 256, 0, st>>>((uint32_t*)(ws + p.tpart), 2 * (size_t)N);
+    if (grad_t) fill_zero_u32<<<256, 256, 0, st>>>((uint32_t*)(ws + p.tslots), 2 * kTimeSlotPairs);
     const int detect = dynamic || scaling == RAMPDE_SCALE_NONE_SAFE;
     const int k_max = pol->k_max > 0 ? pol->k_max : 16;
     const int HW = p.H * p.Wd;
@@ -1400,7 +1423,7 @@ struct Runner {
       fa.nsets = p.nsets;
       fa.set_stride = (int64_t)(p.fm_stride / 2);
       fa.nsteps = 1;
-      fa.tpart = grad_t ? f32(p.tpart) : nullptr;
+      fa.tpart = grad_t ? f32(p.tslots) : nullptr;
       fa.round_incr = (pol->flags & RAMPDE_NAIVE_STATE) ? 2 : 0;
       fill_zero_u32<<<1024, 256, 0, st>>>((uint32_t*)(ws + p.gpart), (size_t)p.ksplits * p.P);
       if (p.Rp != p.R) {

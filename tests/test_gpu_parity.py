@@ -285,6 +285,23 @@ def test_time_grid_gradient_conv(C, H, W, B, tab):
     _time_grid_case(cfg)
 
 
+@pytest.mark.parametrize("kind", ["mlp", "mlp_per_layer", "conv"])
+def test_time_grid_gradient_is_reproducible_bit_for_bit(kind):
+    # the batch sums of dL/dt are folded from per-workgroup slots in a fixed order (no floating-point atomics): two
+    # runs on the same inputs give the same bits, with hundreds of workgroups adding to every step's sums
+    if kind == "conv":
+        cfg = wl.CONFIGS["cfg4"].with_(name="dtrep_conv", B=4, N=3, C=64, H=32, W=32)
+        flags = 0
+    else:
+        cfg = wl.CONFIGS["cfg2"].with_(name="dtrep_mlp", B=4000, N=4)
+        flags = 4 if kind == "mlp_per_layer" else 0
+    theta, y0, target = par.make_inputs(cfg)
+    a = par.run_gpu(cfg, theta, y0, target, want_grad_t=True, flags=flags)
+    b = par.run_gpu(cfg, theta, y0, target, want_grad_t=True, flags=flags)
+    assert np.all(np.isfinite(a["grad_t"])) and np.linalg.norm(a["grad_t"]) > 0
+    np.testing.assert_array_equal(a["grad_t"], b["grad_t"])
+
+
 def test_time_grid_gradient_cfg1_and_running_cost():
     _time_grid_case(wl.CONFIGS["cfg1"])
     cfg = wl.CONFIGS["cfg1"].with_(name="dtrun", B=64, N=4, widths=(6, 32, 6))
