@@ -14,6 +14,7 @@
 //   instnorm_finalize  folds the chunks: (mean, rstd) forward, (mean(dn), mean(dn * n)) backward;
 //   instnorm_apply / instnorm_apply_vjp   the elementwise part, 8 channels (16 bytes) per thread.
 #pragma once
+#include <algorithm>
 #include "common.hpp"
 
 namespace rampde {
@@ -116,37 +117,62 @@ struct NormApply {
   int detect;
 };
 
+// grid (row blocks, B); a workgroup of gcols * rpi <= 256 threads (gcols = min(Cpad / 8, 256) channel groups x rpi rows per
+// iteration): a thread keeps its channel group, so the sample's statistics of its 8 channels are loaded once, and the
+// loop over rows is three 16-byte loads, the arithmetic and one 16-byte store, without index divisions.
+inline int instnorm_apply_threads(int Cpad) {
+  const int gcols = std::min(Cpad / 8, 256);
+  return gcols * (256 / gcols);
+}
 template <class T, bool VJP>
 __global__ __launch_bounds__(256) void instnorm_apply(NormApply g) {
   if (g.ctl && g.ctl->poison) return;
   const int gpr = g.Cpad >> 3;  // groups of 8 channels per row
-  const int64_t total = g.rows * gpr;
+  const int gcols = gpr < 256 ? gpr : 256;
+  const int rpi = (int)blockDim.x / gcols;
+  const int rr = (int)threadIdx.x / gcols;
+  const int Bn = (int)(g.rows / g.HW);
   bool bad = false;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t row = i / gpr;
-    const int c0 = (int)(i - row * gpr) * 8;
-    const int64_t b = row / g.HW;
-    const size_t at = (size_t)row * g.ld + c0;
-    const float* st = g.stat + ((size_t)b * g.Cpad + c0) * 2;
-    const u16x8 x = *reinterpret_cast<const u16x8*>(g.X + at);
-    u16x8 o;
-    if (VJP) {
-      const float* sv = g.stat_vjp + ((size_t)b * g.Cpad + c0) * 2;
-      const u16x8 n = *reinterpret_cast<const u16x8*>(g.Nrm + at);
-      const u16x8 r = *reinterpret_cast<const u16x8*>(g.Rl + at);
+  for (int b = blockIdx.y; b < Bn; b += gridDim.y)   // (one sample per workgroup row, unless the grid's y extent is short of B)
+  for (int cg = (int)threadIdx.x % gcols; cg < gpr; cg += gcols) {
+    const int c0 = cg * 8;
+    float st[16], sv[16];
+    const float4* sp = reinterpret_cast<const float4*>(g.stat + ((size_t)b * g.Cpad + c0) * 2);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float dn = Low<T>::to_f32(x[e]), nv = Low<T>::to_f32(n[e]);
-        float v = st[2 * e + 1] * (dn - sv[2 * e] - nv * sv[2 * e + 1]);
-        if (!(Low<T>::to_f32(r[e]) > 0.f)) v = 0.f;  // ReLU mask of the stored activation
-        o[e] = Low<T>::from_f32(v);
-        bad = bad || Low<T>::nonfinite(o[e]);
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = Low<T>::from_f32((Low<T>::to_f32(x[e]) - st[2 * e]) * st[2 * e + 1]);
+    for (int q = 0; q < 4; ++q) {
+      const float4 v = sp[q];
+      st[4 * q] = v.x; st[4 * q + 1] = v.y; st[4 * q + 2] = v.z; st[4 * q + 3] = v.w;
     }
-    *reinterpret_cast<u16x8*>(g.Out + at) = o;
+    if (VJP) {
+      const float4* vp = reinterpret_cast<const float4*>(g.stat_vjp + ((size_t)b * g.Cpad + c0) * 2);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 v = vp[q];
+        sv[4 * q] = v.x; sv[4 * q + 1] = v.y; sv[4 * q + 2] = v.z; sv[4 * q + 3] = v.w;
+      }
+    }
+    const size_t base = (size_t)b * g.HW * g.ld + c0;
+    for (int64_t r = (int64_t)blockIdx.x * rpi + rr; r < g.HW; r += (int64_t)gridDim.x * rpi) {
+      const size_t at = base + (size_t)r * g.ld;
+      const u16x8 x = *reinterpret_cast<const u16x8*>(g.X + at);
+      u16x8 o;
+      if (VJP) {
+        const u16x8 n = *reinterpret_cast<const u16x8*>(g.Nrm + at);
+        const u16x8 rl = *reinterpret_cast<const u16x8*>(g.Rl + at);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float dn = Low<T>::to_f32(x[e]), nv = Low<T>::to_f32(n[e]);
+          float v = st[2 * e + 1] * (dn - sv[2 * e] - nv * sv[2 * e + 1]);
+          if (!(Low<T>::to_f32(rl[e]) > 0.f)) v = 0.f;  // ReLU mask of the stored activation
+          o[e] = Low<T>::from_f32(v);
+          bad |= Low<T>::nonfinite(o[e]);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = Low<T>::from_f32((Low<T>::to_f32(x[e]) - st[2 * e]) * st[2 * e + 1]);
+      }
+      *reinterpret_cast<u16x8*>(g.Out + at) = o;
+    }
   }
   if (VJP && g.detect) raise_if_any(bad, g.ctl);
 }

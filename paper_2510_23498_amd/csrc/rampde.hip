@@ -707,6 +707,13 @@ struct Runner {
     return f32(p.nstat) + 2 * (size_t)jb * Bn * p.layers[0].Npad;
   }
   // k_j = -W^T N(relu(W z_j + b)) from the stage input z (stage buffers jb)
+  // row blocks x samples of the normalisation's elementwise kernels: about 8 workgroups per compute unit
+  dim3 norm_apply_grid(int Cpad) const {
+    const int64_t Bn = p.R / ((int64_t)p.H * p.Wd), HW = (int64_t)p.H * p.Wd;
+    const int rpi = instnorm_apply_threads(Cpad) / std::min(Cpad / 8, 256);
+    const int64_t want = std::max<int64_t>(1, (8 * (int64_t)device_compute_units() + Bn - 1) / Bn);
+    return dim3((unsigned)std::max<int64_t>(1, std::min<int64_t>(want, (HW + rpi - 1) / rpi)), (unsigned)std::min<int64_t>(Bn, 65535));
+  }
   void parabolic_eval(const uint16_t* z, int j, int jb, Ctl* c) {
     const Layer& y = p.layers[0];
     uint16_t* r = u16(p.ACT[0]) + (size_t)jb * p.R * y.Npad;
@@ -720,7 +727,7 @@ struct Runner {
     NormApply a{};
     a.X = r; a.Out = nrm; a.ld = y.Npad; a.Cpad = y.Npad; a.HW = (int64_t)p.H * p.Wd; a.rows = p.R;
     a.stat = norm_stat_of(jb); a.ctl = c;
-    instnorm_apply<T, false><<<stream_blocks(p.R * (y.Npad / 8)), 256, 0, st>>>(a);
+    instnorm_apply<T, false><<<norm_apply_grid(y.Npad), instnorm_apply_threads(y.Npad), 0, st>>>(a);
     GemmNT t{};
     t.A = nrm; t.lda = y.Npad; t.W = u16(y.WTp); t.ldw = 9 * y.Npad; t.C = u16(p.K) + (size_t)j * p.stage_stride; t.ldc = y.Kpad;
     t.M = (int)p.R; t.N = y.Kpad; t.K = t.ldw; t.negate = 1; t.ctl = c; t.H = p.H; t.Wd = p.Wd; t.Cpad = y.Npad;
@@ -742,7 +749,7 @@ struct Runner {
     a.X = dn; a.Nrm = u16(p.ACT[1]) + so; a.Rl = u16(p.ACT[0]) + so; a.Out = du; a.ld = y.Npad; a.Cpad = y.Npad;
     a.HW = (int64_t)p.H * p.Wd; a.rows = p.R; a.stat = norm_stat_of(j); a.stat_vjp = f32(p.nstat_vjp); a.ctl = ctl;
     a.detect = detect;
-    instnorm_apply<T, true><<<stream_blocks(p.R * (y.Npad / 8)), 256, 0, st>>>(a);
+    instnorm_apply<T, true><<<norm_apply_grid(y.Npad), instnorm_apply_threads(y.Npad), 0, st>>>(a);
     GemmNT t{};
     t.A = du; t.lda = y.Npad; t.W = u16(y.WTp); t.ldw = 9 * y.Npad; t.C = u16(p.ZBAR) + (size_t)j * p.stage_stride; t.ldc = y.Kpad;
     t.M = (int)p.R; t.N = y.Kpad; t.K = t.ldw; t.ctl = ctl; t.detect = detect; t.H = p.H; t.Wd = p.Wd; t.Cpad = y.Npad;
