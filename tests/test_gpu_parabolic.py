@@ -109,6 +109,12 @@ def test_parabolic_line_staged_convolution_kernel_single_euler_step_is_tight(B, 
           strict=True, wgrad_tile=wgrad_tile)
 
 
+def test_parabolic_line_staged_and_transposing_kernels_bf16():
+    # the bf16 instantiations of the line-staged convolution and of the transposing-read weight gradient
+    _case(BASE.with_(name="pblinesbf16", B=4, C=256, H=32, W=32, N=1, n_intervals=1, tableau="euler", t1=0.25, low="bf16"),
+          strict=True)
+
+
 def test_parabolic_benchmark_shape_single_euler_step_is_tight():
     # the shape the benchmark times (256 channels, 64 x 64 images, batch 16: 128 convolution tiles on each half of the
     # output channels, 20 K-chunks of 205 image lines in the weight gradient), one Euler step, everything to 1e-3

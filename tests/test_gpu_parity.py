@@ -208,6 +208,19 @@ def test_conv_weight_gradient_64_channels_transposing_reads(H, W, B, wgrad_tile)
     _both(cfg, bias_std=0.1, wgrad_tile=wgrad_tile)
 
 
+def test_conv_weight_gradient_64_channels_transposing_reads_bf16():
+    cfg = wl.CONFIGS["cfg4"].with_(name="convtrbf16", B=3, N=2, C=64, H=16, W=32, tableau="kutta3", low="bf16")
+    # bf16 at contraction length 9 * 65: the device sums the products in fp32, the oracle in fp64 with one rounding,
+    # and the two land on different sides of a bf16 rounding boundary often enough for 1e-3 (grad_y0, which no
+    # weight-gradient kernel touches, is the largest: 1.9e-3); same bound as for the 512-wide bf16 networks above
+    gpu, _, _ = _both(cfg, bias_std=0.1, tol_emul=2e-3)
+    # the two weight-gradient kernels contract the same rounded operands: they agree to fp32 summation order
+    theta, y0, target = par.make_inputs(cfg, bias_std=0.1)
+    old = par.run_gpu(cfg, theta, y0, target, wgrad_tile=64)
+    assert par.rel_err(gpu["grad_theta"], old["grad_theta"]) <= 1e-5
+    np.testing.assert_array_equal(gpu["grad_y0"], old["grad_y0"])
+
+
 def test_conv_small_odd_geometry():
     cfg = wl.CONFIGS["cfg4"].with_(name="convodd", B=2, N=2, C=5, H=7, W=6, tableau="kutta3")
     _both(cfg, bias_std=0.1)
