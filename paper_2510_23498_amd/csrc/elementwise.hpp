@@ -3,6 +3,7 @@
 // adjoint-side kernels: scale-and-round, overflow detection, fp32 adjoint update and
 // the scale state machine (paper Algorithm 2).
 #pragma once
+#include <algorithm>
 #include "common.hpp"
 
 namespace rampde {
@@ -57,25 +58,35 @@ __global__ void cast_conv_layer(const float* __restrict__ W, const float* __rest
   }
 }
 
-// fp32 NCHW <-> channels-last [B*H*W][C]
-__global__ void nchw_to_rows(const float* __restrict__ src, float* __restrict__ dst, int64_t P, int C, int HW) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // index into dst
-  if (i >= P * C) return;
-  int64_t p = i / C;
-  int c = (int)(i % C);
-  int64_t bimg = p / HW, pix = p % HW;
-  dst[i] = src[(bimg * C + c) * HW + pix];
+// fp32 NCHW <-> channels-last [B*H*W][C]: per sample a transposition [rows][cols] -> [cols][rows] through LDS tiles of
+// 32 x 32 (both the reads and the writes are runs of 128 bytes).  grid (cols / 32, rows / 32, samples), 32 x 8 threads.
+// fill_inf: write +inf instead once a cotangent chain has been rejected (ctl may be null otherwise).
+__global__ __launch_bounds__(256) void transpose_samples(const float* __restrict__ src, float* __restrict__ dst, int rows,
+                                                         int cols, int nsamples, const Ctl* ctl, int fill_inf) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x, ty = threadIdx.y;
+  const bool inf = fill_inf && ctl->poison;
+  for (int b = blockIdx.z; b < nsamples; b += gridDim.z) {
+    const float* s = src + (size_t)b * rows * cols;
+    float* d = dst + (size_t)b * rows * cols;
+    const int c = blockIdx.x * 32 + tx;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int r = blockIdx.y * 32 + ty + 8 * k;
+      tile[ty + 8 * k][tx] = (r < rows && c < cols) ? s[(size_t)r * cols + c] : 0.f;
+    }
+    __syncthreads();
+    const int oc = blockIdx.y * 32 + tx;   // column of the output = row of the input
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int orow = blockIdx.x * 32 + ty + 8 * k;
+      if (orow < cols && oc < rows) d[(size_t)orow * rows + oc] = inf ? __builtin_inff() : tile[tx][ty + 8 * k];
+    }
+    __syncthreads();
+  }
 }
-__global__ void rows_to_nchw(const float* __restrict__ src, float* __restrict__ dst, int64_t P, int C, int HW,
-                             const Ctl* ctl, int fill_inf) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // index into dst (NCHW)
-  if (i >= P * C) return;
-  int64_t pix = i % HW;
-  int c = (int)((i / HW) % C);
-  int64_t bimg = i / ((int64_t)HW * C);
-  float v = src[(bimg * HW + pix) * C + c];
-  if (fill_inf && ctl->poison) v = __builtin_inff();
-  dst[i] = v;
+inline dim3 transpose_grid(int rows, int cols, int64_t nsamples) {
+  return dim3((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32), (unsigned)std::min<int64_t>(nsamples, 65535));
 }
 
 // y <- y0 (fp32), ckpt[0] <- Q(y0)     (paper Alg. 1: initialisation and first stored state)

@@ -707,6 +707,15 @@ struct Runner {
     return f32(p.nstat) + 2 * (size_t)jb * Bn * p.layers[0].Npad;
   }
   // k_j = -W^T N(relu(W z_j + b)) from the stage input z (stage buffers jb)
+  // caller's NCHW fp32 <-> channels-last rows (per sample: [C][H W] <-> [H W][C])
+  void to_rows(const float* nchw, float* rows) {
+    const int HW = p.H * p.Wd;
+    transpose_samples<<<transpose_grid(p.d, HW, p.R / HW), dim3(32, 8), 0, st>>>(nchw, rows, p.d, HW, (int)(p.R / HW), nullptr, 0);
+  }
+  void to_nchw(const float* rows, float* nchw) {
+    const int HW = p.H * p.Wd;
+    transpose_samples<<<transpose_grid(HW, p.d, p.R / HW), dim3(32, 8), 0, st>>>(rows, nchw, HW, p.d, (int)(p.R / HW), nullptr, 0);
+  }
   // row blocks x samples of the normalisation's elementwise kernels: about 8 workgroups per compute unit
   dim3 norm_apply_grid(int Cpad) const {
     const int64_t Bn = p.R / ((int64_t)p.H * p.Wd), HW = (int64_t)p.H * p.Wd;
@@ -997,7 +1006,7 @@ struct Runner {
     float* y = yN;
     if (p.conv) {
       y = f32(p.y_rows);
-      nchw_to_rows<<<blocks_for(p.n, 256), 256, 0, st>>>(y0, y, p.R, p.d, p.H * p.Wd);
+      to_rows(y0, y);
       init_state<T><<<blocks_for(p.n, 256), 256, 0, st>>>(y, y, ckpt, p.n, 0, naive);
     } else {
       init_state<T><<<blocks_for(p.n, 256), 256, 0, st>>>(y0, y, ckpt, p.n, 1, naive);
@@ -1022,7 +1031,7 @@ struct Runner {
         combine_store<T><<<blocks_for(p.n, 256), 256, 0, st>>>(y, u16(p.K), p.stage_stride, p.s, bw, h, incr_mode,
                                                               ckpt + (size_t)(i + 1) * p.n, p.d, p.dpad, p.R);
     }
-    if (p.conv) rows_to_nchw<<<blocks_for(p.n, 256), 256, 0, st>>>(y, yN, p.R, p.d, p.H * p.Wd, nullptr, 0);
+    if (p.conv) to_nchw(y, yN);
     HIP_TRY(hipGetLastError());
     return RAMPDE_OK;
   }
@@ -1450,13 +1459,13 @@ struct Runner {
       if (!grad_ys) return nullptr;
       const float* src = grad_ys + (size_t)i * step_elems;
       if (!p.conv) return src;
-      nchw_to_rows<<<blocks_for(p.n, 256), 256, 0, st>>>(src, gys_rows, p.R, p.d, HW);
+      to_rows(src, gys_rows);
       return gys_rows;
     };
     if (p.conv) {
       a = f32(p.a_rows);
       gys_rows = f32(p.gys_rows);
-      nchw_to_rows<<<blocks_for(p.n, 256), 256, 0, st>>>(grad_yN, a, p.R, p.d, HW);
+      to_rows(grad_yN, a);
       init_adjoint<<<stream_blocks(p.n, 512), 256, 0, st>>>(a, gys_at(N), a, p.n, ctl, 0, naive_low);
     } else {
       init_adjoint<<<stream_blocks(p.n, 512), 256, 0, st>>>(grad_yN, gys_at(N), a, p.n, ctl, 1, naive_low);
@@ -1587,7 +1596,7 @@ struct Runner {
         fill_inf_if_poisoned<<<blocks_for(p.P, 256), 256, 0, st>>>(grad_theta, p.P, ctl);
       }
     }
-    if (p.conv) rows_to_nchw<<<blocks_for(p.n, 256), 256, 0, st>>>(a, grad_y0, p.R, p.d, HW, nullptr, 0);
+    if (p.conv) to_nchw(a, grad_y0);
     HIP_TRY(hipGetLastError());
     std::vector<float> hist;
     if (scale_hist || stats) {
