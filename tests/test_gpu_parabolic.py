@@ -109,6 +109,13 @@ def test_parabolic_line_staged_convolution_kernel_single_euler_step_is_tight(B, 
           strict=True, wgrad_tile=wgrad_tile)
 
 
+@pytest.mark.parametrize("C,B,H,W", [(128, 4, 32, 32), (384, 4, 32, 32)])
+def test_parabolic_line_staged_and_transposing_kernels_other_channel_counts(C, B, H, W):
+    # 128 channels: one block of output channels in both kernels; 384: three blocks each way (nine weight-gradient
+    # workgroups per K-chunk and output-channel block, fewer whole groups per XCD than compute units)
+    _case(BASE.with_(name=f"pbch{C}", B=B, C=C, H=H, W=W, N=1, n_intervals=1, tableau="euler", t1=0.25), strict=True)
+
+
 def test_parabolic_line_staged_and_transposing_kernels_bf16():
     # the bf16 instantiations of the line-staged convolution and of the transposing-read weight gradient
     _case(BASE.with_(name="pblinesbf16", B=4, C=256, H=32, W=32, N=1, n_intervals=1, tableau="euler", t1=0.25, low="bf16"),
